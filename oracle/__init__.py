@@ -1,0 +1,156 @@
+"""ctypes front end of the CPU oracle (test infrastructure, never used by the product path).
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this package.
+It compiles oracle/rannc_dp_oracle.c with gcc on first use and wraps its entry points with
+numpy arrays.  Nothing here is shared with the HIP path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rannc_dp_oracle.c")
+_LIB = os.path.join(_HERE, "librannc_dp_oracle.so")
+INF = np.iinfo(np.int64).max
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle shared library (gcc -O2 -fopenmp)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _p(a, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        i32, i64, u8 = C.c_int32, C.c_int64, C.c_uint8
+        pi32, pi64, pu8 = C.POINTER(i32), C.POINTER(i64), C.POINTER(u8)
+        L.rannc_oracle_prefix.argtypes = [i32, pi64, pi64]
+        L.rannc_oracle_prefix.restype = C.c_int
+        L.rannc_oracle_table_entries.argtypes = [i32, i32]
+        L.rannc_oracle_table_entries.restype = C.c_size_t
+        L.rannc_oracle_tables.argtypes = [i32, i32, pi64, pi64, pi64, i64, pi64, pu8]
+        L.rannc_oracle_tables.restype = C.c_int
+        L.rannc_oracle_dp.argtypes = [i32, i32, i32, pi64, pu8, pi64, pi32, pi32, i32]
+        L.rannc_oracle_dp.restype = C.c_int
+        L.rannc_oracle_select.argtypes = [i32, i32, i32, pi64, pi64, pi32]
+        L.rannc_oracle_select.restype = C.c_int
+        L.rannc_oracle_traceback.argtypes = [i32, i32, i32, pi32, pi32, i32, pi32, pi32]
+        L.rannc_oracle_traceback.restype = C.c_int
+        L.rannc_oracle_est_iter_ns.argtypes = [i64, i32, i32]
+        L.rannc_oracle_est_iter_ns.restype = i64
+        L.rannc_oracle_max_threads.argtypes = []
+        L.rannc_oracle_max_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def _chk(rc, what):
+    if rc != 0:
+        raise OracleError(f"{what}: oracle error {rc}")
+
+
+def max_threads() -> int:
+    return int(lib().rannc_oracle_max_threads())
+
+
+def prefix(x) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.int64)
+    X = np.empty(x.shape[0] + 1, dtype=np.int64)
+    _chk(lib().rannc_oracle_prefix(x.shape[0], _p(x, C.c_int64), _p(X, C.c_int64)), "prefix")
+    return X
+
+
+def tables(T, P, A, D: int, M: int):
+    """cost (int64) and fit (uint8), packed as ((j*(j-1)/2 + i)*D + (r-1))."""
+    N = T.shape[0] - 1
+    n = lib().rannc_oracle_table_entries(N, D)
+    cost = np.empty(n, dtype=np.int64)
+    fit = np.empty(n, dtype=np.uint8)
+    _chk(lib().rannc_oracle_tables(N, D, _p(T, C.c_int64), _p(P, C.c_int64), _p(A, C.c_int64),
+                                   int(M), _p(cost, C.c_int64), _p(fit, C.c_uint8)), "tables")
+    return cost, fit
+
+
+def table_index(j, i, r, D):
+    return (j * (j - 1) // 2 + i) * D + (r - 1)
+
+
+def dp(N: int, D: int, n_levels: int, cost, fit, n_threads: int = 1):
+    shape = (n_levels + 1, N + 1, D + 1)
+    V = np.empty(shape, dtype=np.int64)
+    ai = np.empty(shape, dtype=np.int32)
+    ad = np.empty(shape, dtype=np.int32)
+    _chk(lib().rannc_oracle_dp(N, D, n_levels, _p(cost, C.c_int64), _p(fit, C.c_uint8),
+                               _p(V, C.c_int64), _p(ai, C.c_int32), _p(ad, C.c_int32),
+                               int(n_threads)), "dp")
+    return V, ai, ad
+
+
+def select(V):
+    n_levels, N, D = V.shape[0] - 1, V.shape[1] - 1, V.shape[2] - 1
+    opt = C.c_int64()
+    ns = C.c_int32()
+    _chk(lib().rannc_oracle_select(N, D, n_levels, _p(V, C.c_int64), C.byref(opt), C.byref(ns)),
+         "select")
+    return int(opt.value), int(ns.value)
+
+
+def traceback(ai, ad, n_stages: int, max_slots: int):
+    N, D = ai.shape[1] - 1, ai.shape[2] - 1
+    se = np.empty(max_slots, dtype=np.int32)
+    rp = np.empty(max_slots, dtype=np.int32)
+    _chk(lib().rannc_oracle_traceback(N, D, n_stages, _p(ai, C.c_int32), _p(ad, C.c_int32),
+                                      max_slots, _p(se, C.c_int32), _p(rp, C.c_int32)),
+         "traceback")
+    return se, rp
+
+
+def est_iter_ns(opt: int, n_stages: int, MB: int) -> int:
+    return int(lib().rannc_oracle_est_iter_ns(int(opt), int(n_stages), int(MB)))
+
+
+def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=None):
+    """Whole path for one problem dict (see the input generator module for its keys).
+
+    Returns a dict with opt, n_stages, est_iter_ns, stage_end[S], replicas[S] and, with
+    keep_tables, T/P/A, cost, fit, V, arg_i, arg_d.  max_levels bounds the number of levels
+    computed (used only to time a bounded sample of a large search)."""
+    t, p, a = problem["time_ns"], problem["param_bytes"], problem["act_bytes"]
+    N = int(t.shape[0])
+    D, S = int(problem["n_devices"]), int(problem["max_stages"])
+    MB, M = int(problem["n_microbatches"]), int(problem["mem_capacity"])
+    if D < 1 or S < 1 or MB < 1 or M < 0:
+        raise OracleError("bad scalar argument")
+    T, P, A = prefix(t), prefix(p), prefix(a)
+    cost, fit = tables(T, P, A, D, M)
+    n_levels = min(S, N, D)
+    if max_levels is not None:
+        n_levels = min(n_levels, int(max_levels))
+    V, ai, ad = dp(N, D, n_levels, cost, fit, n_threads)
+    opt, ns = select(V)
+    se, rp = traceback(ai, ad, ns, S)
+    out = {"opt": opt, "n_stages": ns, "est_iter_ns": est_iter_ns(opt, ns, MB),
+           "stage_end": se, "replicas": rp, "n_levels": n_levels}
+    if keep_tables:
+        out.update(T=T, P=P, A=A, cost=cost, fit=fit, V=V, arg_i=ai, arg_d=ad)
+    return out

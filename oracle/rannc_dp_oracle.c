@@ -1,0 +1,207 @@
+/*
+ * CPU oracle for the stage-level partition search of RaNNC (Sec. III-C, Algorithm 1).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, obviously-correct reference that the
+ * tests, the smoke check and the benchmark's cpu_baseline leg compare the HIP path against.
+ * It shares no code with the HIP path and the product never calls it.
+ *
+ * What it computes (all values int64, no floating point):
+ *
+ *   blocks k = 1..N with time t_k, persistent bytes p_k, per-microbatch transient bytes a_k;
+ *   prefix sums T, P, A (T[0] = 0);
+ *   a stage holding blocks i+1..j with r replicas (Sec. III-C: consecutive blocks
+ *   b_{i-1} < k <= b_i, replica count sd_i) has
+ *       h(i,j,r) = ceil((T[j]-T[i]) / r)                  stage time
+ *       m(i,j,r) = (P[j]-P[i]) + ceil((A[j]-A[i]) / r)    stage memory
+ *   and fits iff m <= M (Algorithm 1 skips a candidate only when m > M).
+ *   The additive form is the paper's own stand-in for profile() in Sec. IV-D (sums over the
+ *   members of a stage); the replica divides the per-replica batch, hence time and transient
+ *   memory, and leaves the persistent part alone.
+ *
+ *   Recurrence of Sec. III-C:
+ *       V[s][j][d] = min over 0<=i<j, 0<=d'<d, V[s-1][i][d'] finite, stage (i,j,d-d') fits
+ *                    of max(V[s-1][i][d'], h(i,j,d-d'))
+ *   with V[0][0][0] = 0 and every other V[0][.][.] infinite (a plan must start at block 1
+ *   with no devices spent: b_0 = 0 in Sec. III-C).  The loops run in the order of
+ *   Algorithm 1 (s, then block count, then device total, then the split point ascending, then
+ *   the devices of the earlier stages ascending) with the strict "<" of Algorithm 1, so among
+ *   equal candidates the first one scanned is kept: the lexicographically smallest (i, d').
+ *   The device-count loop is written ascending here; cells of one level are independent, so
+ *   its direction does not change any value.  The d_min early break and the loop-range
+ *   trimming of Algorithm 1 are search-space pruning for an expensive profiler, not part of
+ *   the objective, and are not applied.
+ *
+ *   Answer: opt = min over 1 <= s <= min(S,N,D) of V[s][N][D], ties to the smallest s;
+ *   INFEASIBLE (opt = INT64_MAX, 0 stages) if no level is finite.  The plan is recovered by
+ *   following the stored (i, d') back from (s*, N, D).
+ *
+ * Pins (tests/test_oracle_*.py): brute-force enumeration of every plan from the definition,
+ * closed forms (one stage; memory not binding; the textbook linear-partition problem),
+ * invariants, and a separately written per-cell check of the canonical argmin.
+ *
+ * Layouts (caller allocates everything):
+ *   cost, fit : packed lower triangle, entry (j,i,r), 1<=j<=N, 0<=i<j, 1<=r<=D at
+ *               ((j*(j-1)/2 + i) * D + (r-1));  cost int64, fit uint8 (1 = fits)
+ *   V         : int64 [(S_eff+1)][(N+1)][(D+1)]
+ *   arg_i, arg_d : int32, same shape; -1 where no admissible candidate exists
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORACLE_INF INT64_MAX
+#define ORACLE_OK 0
+#define ORACLE_BAD_ARG (-1)
+#define ORACLE_OVERFLOW (-4)
+
+static int64_t ceil_div(int64_t x, int64_t r) { return (x + r - 1) / r; } /* x >= 0, r >= 1 */
+
+/* Inclusive prefix sums X[0] = 0, X[k] = x_1 + .. + x_k.  Rejects negative entries and
+ * totals of 2^62 or more. */
+int rannc_oracle_prefix(int32_t N, const int64_t *x, int64_t *X) {
+  if (N < 1 || !x || !X) return ORACLE_BAD_ARG;
+  const int64_t LIM = (int64_t)1 << 62;
+  X[0] = 0;
+  for (int32_t k = 1; k <= N; ++k) {
+    int64_t v = x[k - 1];
+    if (v < 0) return ORACLE_BAD_ARG;
+    if (v >= LIM - X[k - 1]) return ORACLE_OVERFLOW;
+    X[k] = X[k - 1] + v;
+  }
+  return ORACLE_OK;
+}
+
+size_t rannc_oracle_table_entries(int32_t N, int32_t D) {
+  return (size_t)N * (size_t)(N + 1) / 2 * (size_t)D;
+}
+
+/* Stage time and fits-in-memory tables straight from the definitions above. */
+int rannc_oracle_tables(int32_t N, int32_t D, const int64_t *T, const int64_t *P,
+                        const int64_t *A, int64_t M, int64_t *cost, uint8_t *fit) {
+  if (N < 1 || D < 1 || M < 0 || !T || !P || !A || !cost || !fit) return ORACLE_BAD_ARG;
+  for (int64_t j = 1; j <= N; ++j)
+    for (int64_t i = 0; i < j; ++i)
+      for (int64_t r = 1; r <= D; ++r) {
+        size_t e = (size_t)((j * (j - 1) / 2 + i) * D + (r - 1));
+        int64_t h = ceil_div(T[j] - T[i], r);
+        int64_t m = (P[j] - P[i]) + ceil_div(A[j] - A[i], r);
+        cost[e] = h;
+        fit[e] = (uint8_t)(m <= M);
+      }
+  return ORACLE_OK;
+}
+
+/* The five nested loops, levels 1..n_levels (n_levels <= min(S,N,D)).  Level 0 is set here. */
+int rannc_oracle_dp(int32_t N, int32_t D, int32_t n_levels, const int64_t *cost,
+                    const uint8_t *fit, int64_t *V, int32_t *arg_i, int32_t *arg_d,
+                    int32_t n_threads) {
+  if (N < 1 || D < 1 || n_levels < 0 || !cost || !fit || !V || !arg_i || !arg_d)
+    return ORACLE_BAD_ARG;
+  const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
+#define CELL(s, j, d) ((size_t)(s) * ND + (size_t)(j) * (size_t)(D + 1) + (size_t)(d))
+  for (size_t e = 0; e < ((size_t)n_levels + 1) * ND; ++e) {
+    V[e] = ORACLE_INF;
+    arg_i[e] = -1;
+    arg_d[e] = -1;
+  }
+  V[CELL(0, 0, 0)] = 0;
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+#else
+  (void)n_threads;
+#endif
+  for (int32_t s = 1; s <= n_levels; ++s) {
+    /* cells (j, d) of one level depend only on level s-1 */
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int32_t j = s; j <= N; ++j) {
+      for (int32_t d = s; d <= D; ++d) {
+        int64_t best = ORACLE_INF;
+        int32_t bi = -1, bd = -1;
+        for (int32_t i = s - 1; i <= j - 1; ++i) {
+          for (int32_t dp = s - 1; dp <= d - 1; ++dp) {
+            int64_t prev = V[CELL(s - 1, i, dp)];
+            if (prev == ORACLE_INF) continue; /* earlier stages infeasible */
+            size_t e = (size_t)(((int64_t)j * (j - 1) / 2 + i) * D + (d - dp - 1));
+            if (!fit[e]) continue; /* does not fit device memory */
+            int64_t v = prev > cost[e] ? prev : cost[e];
+            if (v < best) {
+              best = v;
+              bi = i;
+              bd = dp;
+            }
+          }
+        }
+        V[CELL(s, j, d)] = best;
+        arg_i[CELL(s, j, d)] = bi;
+        arg_d[CELL(s, j, d)] = bd;
+      }
+    }
+  }
+#undef CELL
+  return ORACLE_OK;
+}
+
+/* Best level for the full chain on all D devices; smallest s among equals. */
+int rannc_oracle_select(int32_t N, int32_t D, int32_t n_levels, const int64_t *V,
+                        int64_t *opt, int32_t *n_stages) {
+  if (!V || !opt || !n_stages) return ORACLE_BAD_ARG;
+  const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
+  int64_t best = ORACLE_INF;
+  int32_t bs = 0;
+  for (int32_t s = 1; s <= n_levels; ++s) {
+    int64_t v = V[(size_t)s * ND + (size_t)N * (size_t)(D + 1) + (size_t)D];
+    if (v < best) {
+      best = v;
+      bs = s;
+    }
+  }
+  *opt = best;
+  *n_stages = bs;
+  return ORACLE_OK;
+}
+
+/* Follow the stored (i, d') from (n_stages, N, D) down to level 0.  stage_end[u-1] = b_u
+ * (1-based count of blocks covered by stages 1..u), replicas[u-1] = devices of stage u;
+ * slots from n_stages up to max_slots-1 are set to -1. */
+int rannc_oracle_traceback(int32_t N, int32_t D, int32_t n_stages, const int32_t *arg_i,
+                           const int32_t *arg_d, int32_t max_slots, int32_t *stage_end,
+                           int32_t *replicas) {
+  if (!arg_i || !arg_d || !stage_end || !replicas || n_stages > max_slots) return ORACLE_BAD_ARG;
+  const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
+  for (int32_t u = 0; u < max_slots; ++u) stage_end[u] = replicas[u] = -1;
+  int32_t j = N, d = D;
+  for (int32_t s = n_stages; s >= 1; --s) {
+    size_t c = (size_t)s * ND + (size_t)j * (size_t)(D + 1) + (size_t)d;
+    int32_t i = arg_i[c], dp = arg_d[c];
+    if (i < 0 || dp < 0) return ORACLE_BAD_ARG;
+    stage_end[s - 1] = j;
+    replicas[s - 1] = d - dp;
+    j = i;
+    d = dp;
+  }
+  if (n_stages > 0 && (j != 0 || d != 0)) return ORACLE_BAD_ARG;
+  return ORACLE_OK;
+}
+
+/* Estimated time of one synchronous-pipeline iteration with MB microbatches over n_stages
+ * stages whose slowest takes opt (fill and drain of the schedule of Fig. 1): (MB + s - 1)*opt,
+ * saturating at INT64_MAX.  Secondary output only; it does not enter the search. */
+int64_t rannc_oracle_est_iter_ns(int64_t opt, int32_t n_stages, int32_t MB) {
+  if (n_stages <= 0 || opt == ORACLE_INF) return ORACLE_INF;
+  int64_t f = (int64_t)MB + n_stages - 1;
+  if (opt != 0 && f > ORACLE_INF / opt) return ORACLE_INF;
+  return f * opt;
+}
+
+int rannc_oracle_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}

@@ -1,0 +1,145 @@
+"""Independent checkers written from the problem's definition (Sec. III-C), in pure Python
+integers.  They use no prefix sums, no tables and no recurrence, and import neither the
+oracle nor the HIP path: they are what the oracle is pinned against, and what plan validity
+is judged by at any size."""
+from itertools import combinations
+
+INF = (1 << 63) - 1
+
+
+def cdiv(x, r):
+    return -((-x) // r)
+
+
+def stage_time(t, i, j, r):
+    """Time of the stage holding blocks i+1..j (1-based) at r replicas."""
+    return cdiv(sum(int(x) for x in t[i:j]), r)
+
+
+def stage_mem(p, a, i, j, r):
+    return sum(int(x) for x in p[i:j]) + cdiv(sum(int(x) for x in a[i:j]), r)
+
+
+def plan_value(t, p, a, M, bounds, reps):
+    """(feasible, max stage time) of the plan with stage ends bounds[1:] and replicas reps."""
+    worst = 0
+    for u in range(len(reps)):
+        i, j, r = bounds[u], bounds[u + 1], reps[u]
+        if stage_mem(p, a, i, j, r) > M:
+            return False, INF
+        worst = max(worst, stage_time(t, i, j, r))
+    return True, worst
+
+
+def brute_force(t, p, a, D, S, M):
+    """Enumerate every plan: s stages, every set of s-1 cut points, every way to give the
+    stages positive replica counts that sum to D.  Returns (opt, smallest s attaining it,
+    number of feasible plans); opt = INF and s = 0 when nothing is feasible."""
+    N = len(t)
+    best, best_s, n_feasible = INF, 0, 0
+    for s in range(1, min(S, N, D) + 1):
+        for cuts in combinations(range(1, N), s - 1):
+            bounds = (0,) + cuts + (N,)
+            for dc in combinations(range(1, D), s - 1):
+                dd = (0,) + dc + (D,)
+                reps = [dd[u + 1] - dd[u] for u in range(s)]
+                ok, v = plan_value(t, p, a, M, bounds, reps)
+                if ok:
+                    n_feasible += 1
+                    if v < best:
+                        best, best_s = v, s
+    return best, best_s, n_feasible
+
+
+def brute_force_prefix(t, p, a, s, j, d, M):
+    """Best value over plans of exactly s stages covering blocks 1..j with exactly d devices."""
+    best = INF
+    if s > j or s > d:
+        return best
+    for cuts in combinations(range(1, j), s - 1):
+        bounds = (0,) + cuts + (j,)
+        for dc in combinations(range(1, d), s - 1):
+            dd = (0,) + dc + (d,)
+            reps = [dd[u + 1] - dd[u] for u in range(s)]
+            ok, v = plan_value(t, p, a, M, bounds, reps)
+            if ok and v < best:
+                best = v
+    return best
+
+
+def check_plan(t, p, a, D, S, M, opt, n_stages, stage_end, replicas):
+    """Validity of a reported plan, from the definition: contiguous cover of 1..N, replicas
+    positive and summing to D, every stage fits, and the slowest stage equals opt."""
+    N = len(t)
+    if opt == INF:
+        assert n_stages == 0
+        assert all(int(x) == -1 for x in stage_end) and all(int(x) == -1 for x in replicas)
+        return
+    assert 1 <= n_stages <= min(S, N, D)
+    se = [int(x) for x in stage_end[:n_stages]]
+    rp = [int(x) for x in replicas[:n_stages]]
+    assert all(int(x) == -1 for x in stage_end[n_stages:])
+    assert all(int(x) == -1 for x in replicas[n_stages:])
+    bounds = [0] + se
+    assert all(bounds[u] < bounds[u + 1] for u in range(n_stages)) and bounds[-1] == N
+    assert all(r >= 1 for r in rp) and sum(rp) == D
+    ok, v = plan_value(t, p, a, M, bounds, rp)
+    assert ok, "a stage of the plan does not fit memory"
+    assert v == opt, (v, opt)
+
+
+def check_cells(t, p, a, D, M, V, arg_i, arg_d):
+    """Per-cell check of the value table and of the canonical argmin.
+
+    For every cell (s, j, d), s >= 1: list the admissible candidates (i, d') in
+    lexicographic order, each valued max(V[s-1][i][d'], stage time); the cell must hold their
+    minimum and the FIRST candidate attaining it, or INF / (-1,-1) if there is none.
+    Level 0 must be 0 at (0,0) and INF elsewhere."""
+    n_levels, N = V.shape[0] - 1, V.shape[1] - 1
+    for j in range(N + 1):
+        for d in range(D + 1):
+            assert int(V[0, j, d]) == (0 if (j == 0 and d == 0) else INF)
+    for s in range(1, n_levels + 1):
+        for j in range(N + 1):
+            for d in range(D + 1):
+                best, arg = INF, (-1, -1)
+                for i in range(0, j):
+                    for dp in range(0, d):
+                        prev = int(V[s - 1, i, dp])
+                        if prev == INF:
+                            continue
+                        r = d - dp
+                        if stage_mem(p, a, i, j, r) > M:
+                            continue
+                        v = max(prev, stage_time(t, i, j, r))
+                        if v < best:
+                            best, arg = v, (i, dp)
+                assert int(V[s, j, d]) == best, (s, j, d)
+                assert (int(arg_i[s, j, d]), int(arg_d[s, j, d])) == arg, (s, j, d)
+
+
+def linear_partition(t, s):
+    """Textbook problem: split the sequence into s non-empty contiguous parts so that the
+    largest part sum is minimal; solved by bisection on the answer with a greedy count."""
+    t = [int(x) for x in t]
+    assert 1 <= s <= len(t)
+
+    def parts_needed(limit):
+        cnt, cur = 1, 0
+        for x in t:
+            if x > limit:
+                return len(t) + 1
+            if cur + x > limit:
+                cnt, cur = cnt + 1, x
+            else:
+                cur += x
+        return cnt
+
+    lo, hi = max(t), sum(t)
+    while lo < hi:
+        mid = (lo + hi) // 2
+        if parts_needed(mid) <= s:
+            hi = mid
+        else:
+            lo = mid + 1
+    return lo

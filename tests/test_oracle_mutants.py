@@ -1,0 +1,90 @@
+"""Do the pins bite?  Plant one plausible mistake at a time in a COPY of the oracle's source
+(on the CPU, never in the HIP path), build it, point the oracle wrapper at the mutant and
+require that the pin battery fails.  A mutant that survives means a pin is missing."""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+from tests import test_oracle_pins as pins
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "rannc_dp_oracle.c")
+
+MUTANTS = {
+    "floor_instead_of_ceil": ("return (x + r - 1) / r;", "return x / r;"),
+    "sum_instead_of_max": ("prev > cost[e] ? prev : cost[e]", "prev + cost[e]"),
+    "min_instead_of_max": ("prev > cost[e] ? prev : cost[e]", "prev < cost[e] ? prev : cost[e]"),
+    "fit_exclusive": ("(uint8_t)(m <= M)", "(uint8_t)(m < M)"),
+    "keeps_last_minimiser": ("if (v < best) {\n              best = v;\n              bi = i;",
+                             "if (v <= best) {\n              best = v;\n              bi = i;"),
+    "level0_all_zero": ("V[CELL(0, 0, 0)] = 0;",
+                        "for (size_t e0 = 0; e0 < ND; ++e0) V[e0] = 0;"),
+    "memory_drops_persistent": ("(P[j] - P[i]) + ceil_div(A[j] - A[i], r)",
+                                "ceil_div(A[j] - A[i], r)"),
+    "memory_divides_persistent": ("(P[j] - P[i]) + ceil_div(A[j] - A[i], r)",
+                                  "ceil_div((P[j] - P[i]) + (A[j] - A[i]), r)"),
+    "memory_ignores_replicas": ("(P[j] - P[i]) + ceil_div(A[j] - A[i], r)",
+                                "(P[j] - P[i]) + (A[j] - A[i])"),
+    "wrong_replica_index": ("* D + (d - dp - 1));", "* D + (dp));"),
+    "stage_skips_first_block": ("int64_t h = ceil_div(T[j] - T[i], r);",
+                                "int64_t h = ceil_div(T[j] - T[i + 1], r);"),
+    "time_ignores_replicas": ("int64_t h = ceil_div(T[j] - T[i], r);",
+                              "int64_t h = T[j] - T[i];"),
+    "select_prefers_more_stages": ("if (v < best) {\n      best = v;\n      bs = s;",
+                                   "if (v <= best) {\n      best = v;\n      bs = s;"),
+    "traceback_wrong_replicas": ("replicas[s - 1] = d - dp;", "replicas[s - 1] = dp;"),
+    "traceback_wrong_end": ("stage_end[s - 1] = j;", "stage_end[s - 1] = i;"),
+    "est_iter_off_by_one": ("(int64_t)MB + n_stages - 1;", "(int64_t)MB + n_stages;"),
+    "skips_split_at_s_minus_1": ("for (int32_t i = s - 1; i <= j - 1; ++i)",
+                                 "for (int32_t i = s; i <= j - 1; ++i)"),
+    "device_loop_stops_early": ("for (int32_t dp = s - 1; dp <= d - 1; ++dp)",
+                                "for (int32_t dp = s - 1; dp < d - 1; ++dp)"),
+}
+
+
+def battery():
+    for row in pins.SMALL[:16]:
+        pins.test_brute_force_small(*row)
+    for seed in range(4):
+        pins.test_ties_everywhere(seed)
+    pins.test_prefix_cells_against_enumeration()
+    pins.test_tables_against_definition()
+    pins.test_fit_boundary_is_inclusive()
+    for seed in range(3):
+        pins.test_single_stage_closed_form(seed)
+        pins.test_memory_not_binding_closed_form(seed)
+        pins.test_linear_partition_special_case(seed)
+        pins.test_invariants(seed)
+    pins.test_zero_activation_fit_independent_of_replicas()
+    pins.test_oversized_block_is_infeasible()
+
+
+def test_battery_passes_on_the_real_oracle():
+    battery()
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_mutant_is_caught(name, tmp_path):
+    old, new = MUTANTS[name]
+    src = open(SRC).read()
+    assert src.count(old) == 1, f"mutation site for {name} not unique/present"
+    cfile = tmp_path / "mutant.c"
+    cfile.write_text(src.replace(old, new))
+    so = tmp_path / "mutant.so"
+    subprocess.run(["gcc", "-O1", "-std=c11", "-fPIC", "-shared", "-o", str(so), str(cfile)],
+                   check=True)
+    real = oracle.lib()
+    mutant = ctypes.CDLL(str(so))
+    for fn in ("rannc_oracle_prefix", "rannc_oracle_table_entries", "rannc_oracle_tables",
+               "rannc_oracle_dp", "rannc_oracle_select", "rannc_oracle_traceback",
+               "rannc_oracle_est_iter_ns", "rannc_oracle_max_threads"):
+        getattr(mutant, fn).argtypes = getattr(real, fn).argtypes
+        getattr(mutant, fn).restype = getattr(real, fn).restype
+    oracle._lib = mutant
+    try:
+        with pytest.raises((AssertionError, oracle.OracleError)):
+            battery()
+    finally:
+        oracle._lib = real
