@@ -1,0 +1,173 @@
+/*
+ * rannc_dp.h -- C ABI of the MI355X stage-level partition search.
+ *
+ * The search is the dynamic program of RaNNC's stage-level partitioning (Sec. III-C,
+ * Algorithm 1 "form_stage_dp"): split a chain of N coarsened blocks into at most S
+ * contiguous pipeline stages, give every stage a replica (data-parallel) device count so
+ * that the counts sum to D, require every stage to fit device memory M, and minimise the
+ * time of the slowest stage.
+ *
+ * Cost model (the additive stand-in of Sec. IV-D for the paper's profile() call): with
+ * prefix sums T, P, A of the per-block inputs, the stage of blocks i+1..j at r replicas has
+ *     time  h(i,j,r) = ceil((T[j]-T[i]) / r)
+ *     memory m(i,j,r) = (P[j]-P[i]) + ceil((A[j]-A[i]) / r),       fits iff m <= M.
+ * Recurrence (Sec. III-C):  V[s][j][d] = min over i<j, d'<d with V[s-1][i][d'] finite and
+ * (i,j,d-d') fitting of max(V[s-1][i][d'], h(i,j,d-d')),  V[0][0][0] = 0, other V[0] infinite.
+ * Result: opt = min over 1 <= s <= min(S,N,D) of V[s][N][D] (ties: fewest stages); the plan
+ * follows, from (s*,N,D), the lexicographically smallest (i,d') attaining each cell -- the
+ * candidate Algorithm 1's scan order with its strict "<" keeps.
+ *
+ * All times are int64 nanoseconds, all sizes int64 bytes; results are exact integers.
+ *
+ * Conventions
+ *  - Every function returns RANNC_DP_OK (0) or a negative rannc_dp_status_t; nothing throws.
+ *  - Pointers are marked HOST or DEVICE.  DEVICE pointers must be valid on the device that is
+ *    current when the call is made.  The library never allocates or frees device memory: the
+ *    caller passes a workspace at create time; the handle sub-allocates inside it.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).  solve and
+ *    traceback only enqueue work on that stream and return; they never synchronise the device.
+ *    Inputs may be released once the stream has passed the end of solve.
+ *  - A handle serves one solve at a time: a later solve reuses the workspace, so calls on one
+ *    handle must be issued in stream order from one host thread.
+ *  - Infeasible is a result, not an error (Algorithm 1 returns INFEASIBLE as a value):
+ *    opt = INT64_MAX, n_stages = 0, plan slots -1.
+ */
+#ifndef RANNC_DP_H_
+#define RANNC_DP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported symbols of the shared library (everything else in it is hidden). */
+#define RANNC_DP_API __attribute__((visibility("default")))
+
+typedef enum {
+  RANNC_DP_OK = 0,
+  RANNC_DP_INVALID_ARG = -1,         /* null pointer, count < 1, negative capacity, bad offsets */
+  RANNC_DP_LIMIT_EXCEEDED = -2,      /* a problem exceeds the limits the handle was created with */
+  RANNC_DP_WORKSPACE_TOO_SMALL = -3, /* workspace cannot hold the tables of this batch */
+  RANNC_DP_OVERFLOW = -4,            /* size computation overflowed */
+  RANNC_DP_HIP_ERROR = -5,           /* a HIP runtime call failed (launch, copy, event) */
+  RANNC_DP_BAD_STATE = -6,           /* traceback / read_table before a successful solve */
+  RANNC_DP_NO_HOST_MEMORY = -7
+} rannc_dp_status_t;
+
+/* Per-problem status word written to d_status by solve (device-side input validation). */
+#define RANNC_DP_PROBLEM_OK 0
+#define RANNC_DP_PROBLEM_NEGATIVE_INPUT 1   /* a block time or size is negative */
+#define RANNC_DP_PROBLEM_SUM_OVERFLOW 2     /* a prefix sum reaches 2^62 */
+#define RANNC_DP_PROBLEM_TIME_TOO_LARGE 3   /* total time exceeds limits.max_total_time_ns */
+/* A problem with a non-zero status is reported as infeasible. */
+
+#define RANNC_DP_MAX_DEVICES 64   /* largest D the kernels are built for */
+
+/* Level kernels (Sec. III-C recurrence, one stage count s per launch). */
+#define RANNC_DP_ALGO_AUTO 0
+#define RANNC_DP_ALGO_MERGE 1 /* sorted-merge form of the (min,max) convolution over d' */
+#define RANNC_DP_ALGO_SCAN 2  /* literal scan of every (i, d') candidate per cell */
+
+typedef struct rannc_dp rannc_dp_t; /* opaque; owns host memory only */
+
+/* Capacity of a handle. */
+typedef struct {
+  int32_t max_problems;      /* Q of the largest batch, >= 1 */
+  int32_t max_blocks;        /* largest N of any problem, >= 1 */
+  int32_t max_devices;       /* largest D, 1..RANNC_DP_MAX_DEVICES */
+  int32_t max_stages;        /* largest S of any problem (values above it are clamped by N, D) */
+  int64_t max_total_time_ns; /* bound on the sum of a problem's block times.  Up to
+                                4294967294 the tables hold 32-bit values (half the memory
+                                traffic); above it 64-bit.  Results are the same int64. */
+  int32_t algo;              /* RANNC_DP_ALGO_* */
+  int32_t reserved;          /* must be 0 */
+} rannc_dp_limits_t;
+
+/* A batch of Q independent searches (Algorithm 2 of Sec. III-C issues many form_stage_dp
+ * calls with different D, S and MB; one batch is one such set).  Structure of arrays. */
+typedef struct {
+  int32_t n_problems;            /* Q >= 1 */
+  const int32_t *n_blocks;       /* HOST [Q]  N_q >= 1 */
+  const int32_t *n_devices;      /* HOST [Q]  D_q >= 1 */
+  const int32_t *max_stages;     /* HOST [Q]  S_q >= 1; effective bound is min(S_q,N_q,D_q) */
+  const int32_t *n_microbatches; /* HOST [Q]  MB_q >= 1; only enters est_iter_ns */
+  const int64_t *mem_capacity;   /* HOST [Q]  M_q >= 0 bytes */
+  const int64_t *block_offset;   /* HOST [Q+1] problem q owns entries block_offset[q] ..
+                                    block_offset[q+1]-1 of the arrays below;
+                                    block_offset[q+1]-block_offset[q] == N_q, block_offset[0] >= 0 */
+  const int64_t *time_ns;        /* DEVICE  fwd+bwd time of a block, one microbatch, one replica */
+  const int64_t *param_bytes;    /* DEVICE  persistent per-replica bytes (weights, grads, optimizer) */
+  const int64_t *act_bytes;      /* DEVICE  transient bytes of one microbatch at one replica */
+} rannc_dp_batch_t;
+
+/* Bytes of device workspace that any batch within `limits` fits in (worst case).
+ * Returns 0 if limits is NULL or invalid. */
+RANNC_DP_API size_t rannc_dp_workspace_bytes(const rannc_dp_limits_t *limits);
+
+/* Exact bytes a given batch needs with these limits (only HOST members of batch are read).
+ * Returns 0 on invalid input. */
+RANNC_DP_API size_t rannc_dp_workspace_bytes_for(const rannc_dp_limits_t *limits, const rannc_dp_batch_t *batch);
+
+/* Create a handle over a caller-owned DEVICE workspace (256-byte aligned).  The workspace
+ * must stay valid until destroy.  A workspace smaller than rannc_dp_workspace_bytes(limits) is
+ * accepted; solve then rejects batches that do not fit.  *out is NULL on failure. */
+RANNC_DP_API int rannc_dp_create(const rannc_dp_limits_t *limits, void *d_workspace, size_t workspace_bytes,
+                    rannc_dp_t **out);
+
+/* Enqueue the whole search for a batch: prefix sums, stage-time / fits-in-memory tables
+ * (the h and m of Sec. III-C over every (i, j, r)), one DP level per stage count
+ * (the recurrence of Sec. III-C, loops of Algorithm 1) and the final choice of the stage count.
+ *   d_opt        DEVICE int64[Q]  slowest-stage time of the best plan; INT64_MAX if infeasible
+ *   d_n_stages   DEVICE int32[Q]  s*; 0 if infeasible
+ *   d_est_iter_ns DEVICE int64[Q] or NULL: (MB + s* - 1) * opt, the fill-and-drain time of one
+ *                synchronous pipeline iteration (Fig. 1), saturating at INT64_MAX
+ *   d_status     DEVICE int32[Q] or NULL: RANNC_DP_PROBLEM_* per problem
+ * Host-side argument errors are returned before anything is enqueued. */
+RANNC_DP_API int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *batch, void *hip_stream,
+                   int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est_iter_ns,
+                   int32_t *d_status);
+
+/* Enqueue plan recovery for the batch of the last solve ("b_i and d_i that produce
+ * V[S][|B|][D]", Algorithm 1's return): per problem, stage u (1-based) ends after block
+ * d_stage_end[q*plan_stride + u-1] (so the last used slot holds N_q) and runs on
+ * d_replicas[q*plan_stride + u-1] devices (they sum to D_q).  Slots from s* on are -1.
+ * plan_stride must be >= min(S_q,N_q,D_q) for every problem of the batch. */
+RANNC_DP_API int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride,
+                       int32_t *d_stage_end, int32_t *d_replicas);
+
+/* Export one table of one problem of the last solve in a layout-independent form, for parity
+ * checks and inspection (not part of the timed path).  d_dst is DEVICE memory of `bytes`
+ * bytes; with D = D_q, N = N_q, L = min(S_q,N_q,D_q):
+ *   COST  int64[N(N+1)/2 * D]  entry (j,i,r), 1<=j<=N, 0<=i<j, 1<=r<=D at
+ *                              ((j(j-1)/2 + i) * D + (r-1)); INT64_MAX where the stage does not fit
+ *   FIT   uint8, same indexing; 1 = fits
+ *   V     int64[(L+1)][(N+1)][(D+1)]; INT64_MAX = no plan
+ *   ARG_I, ARG_D  int32, shape of V: the (i, d') chosen for the cell, -1 where V is infinite or s = 0
+ * Returns RANNC_DP_INVALID_ARG if bytes is not exactly the table's size. */
+#define RANNC_DP_TABLE_COST 0
+#define RANNC_DP_TABLE_FIT 1
+#define RANNC_DP_TABLE_V 2
+#define RANNC_DP_TABLE_ARG_I 3
+#define RANNC_DP_TABLE_ARG_D 4
+RANNC_DP_API int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, size_t bytes,
+                        void *hip_stream);
+
+/* Frees host state only; the workspace remains the caller's.  NULL is allowed. */
+RANNC_DP_API void rannc_dp_destroy(rannc_dp_t *h);
+
+/* Static description of a status code; never NULL. */
+RANNC_DP_API const char *rannc_dp_strerror(int status);
+
+/* Kernel timing of the last solve, in milliseconds, measured with HIP events recorded on the
+ * solve's stream around (0) the prefix-sum and table-build kernels, (1) all DP level kernels,
+ * (2) the final selection.  Events are recorded only when enabled (non-zero) before solve;
+ * get blocks until the last recorded event has completed.  out_ms has 3 entries. */
+RANNC_DP_API int rannc_dp_set_timing(rannc_dp_t *h, int enabled);
+RANNC_DP_API int rannc_dp_get_timing(rannc_dp_t *h, float *out_ms, int32_t *out_level_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RANNC_DP_H_ */

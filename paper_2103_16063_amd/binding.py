@@ -1,0 +1,270 @@
+"""ctypes binding of the C ABI in include/rannc_dp.h: the same entry points under the same
+names, with torch tensors / numpy arrays marshalled to raw pointers.  No step of the search
+runs here -- every value comes out of the HIP kernels behind the library.  PyTorch is used
+only to own device memory and to provide the stream.
+
+The library must have been built (python -m paper_2103_16063_amd.build); loading fails loudly
+otherwise.  There is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librannc_dp.so")
+
+INT64_MAX = (1 << 63) - 1
+
+OK, INVALID_ARG, LIMIT_EXCEEDED, WORKSPACE_TOO_SMALL, OVERFLOW, HIP_ERROR, BAD_STATE, NO_HOST_MEMORY = \
+    0, -1, -2, -3, -4, -5, -6, -7
+PROBLEM_OK, PROBLEM_NEGATIVE_INPUT, PROBLEM_SUM_OVERFLOW, PROBLEM_TIME_TOO_LARGE = 0, 1, 2, 3
+ALGO_AUTO, ALGO_MERGE, ALGO_SCAN = 0, 1, 2
+TABLE_COST, TABLE_FIT, TABLE_V, TABLE_ARG_I, TABLE_ARG_D = 0, 1, 2, 3, 4
+MAX_DEVICES = 64
+NARROW_MAX_TOTAL_TIME = 4294967294
+
+EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp_create",
+           "rannc_dp_solve", "rannc_dp_traceback", "rannc_dp_read_table", "rannc_dp_destroy",
+           "rannc_dp_strerror", "rannc_dp_set_timing", "rannc_dp_get_timing"]
+
+
+class Limits(C.Structure):
+    _fields_ = [("max_problems", C.c_int32), ("max_blocks", C.c_int32),
+                ("max_devices", C.c_int32), ("max_stages", C.c_int32),
+                ("max_total_time_ns", C.c_int64), ("algo", C.c_int32), ("reserved", C.c_int32)]
+
+
+class Batch(C.Structure):
+    _fields_ = [("n_problems", C.c_int32),
+                ("n_blocks", C.c_void_p), ("n_devices", C.c_void_p), ("max_stages", C.c_void_p),
+                ("n_microbatches", C.c_void_p), ("mem_capacity", C.c_void_p),
+                ("block_offset", C.c_void_p),
+                ("time_ns", C.c_void_p), ("param_bytes", C.c_void_p), ("act_bytes", C.c_void_p)]
+
+
+class RanncDpError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """Load librannc_dp.so (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with "
+                              "`python -m paper_2103_16063_amd.build` (there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz = C.c_void_p, C.c_size_t
+        L.rannc_dp_workspace_bytes.argtypes = [C.POINTER(Limits)]
+        L.rannc_dp_workspace_bytes.restype = sz
+        L.rannc_dp_workspace_bytes_for.argtypes = [C.POINTER(Limits), C.POINTER(Batch)]
+        L.rannc_dp_workspace_bytes_for.restype = sz
+        L.rannc_dp_create.argtypes = [C.POINTER(Limits), vp, sz, C.POINTER(vp)]
+        L.rannc_dp_create.restype = C.c_int
+        L.rannc_dp_solve.argtypes = [vp, C.POINTER(Batch), vp, vp, vp, vp, vp]
+        L.rannc_dp_solve.restype = C.c_int
+        L.rannc_dp_traceback.argtypes = [vp, vp, C.c_int32, vp, vp]
+        L.rannc_dp_traceback.restype = C.c_int
+        L.rannc_dp_read_table.argtypes = [vp, C.c_int, C.c_int32, vp, sz, vp]
+        L.rannc_dp_read_table.restype = C.c_int
+        L.rannc_dp_destroy.argtypes = [vp]
+        L.rannc_dp_destroy.restype = None
+        L.rannc_dp_strerror.argtypes = [C.c_int]
+        L.rannc_dp_strerror.restype = C.c_char_p
+        L.rannc_dp_set_timing.argtypes = [vp, C.c_int]
+        L.rannc_dp_set_timing.restype = C.c_int
+        L.rannc_dp_get_timing.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
+        L.rannc_dp_get_timing.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().rannc_dp_strerror(int(status)).decode()
+
+
+def _ptr(x):
+    """Raw address of a torch tensor (device or host), a numpy array, an int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    return x.data_ptr()  # torch.Tensor
+
+
+def make_limits(max_problems, max_blocks, max_devices, max_stages,
+                max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO) -> Limits:
+    return Limits(int(max_problems), int(max_blocks), int(max_devices), int(max_stages),
+                  int(max_total_time_ns), int(algo), 0)
+
+
+class HostBatch:
+    """Keeps the numpy arrays of a batch's HOST members alive next to the C struct."""
+
+    def __init__(self, n_blocks, n_devices, max_stages, n_microbatches, mem_capacity, block_offset,
+                 time_ns, param_bytes, act_bytes):
+        self.keep = [np.ascontiguousarray(n_blocks, dtype=np.int32),
+                     np.ascontiguousarray(n_devices, dtype=np.int32),
+                     np.ascontiguousarray(max_stages, dtype=np.int32),
+                     np.ascontiguousarray(n_microbatches, dtype=np.int32),
+                     np.ascontiguousarray(mem_capacity, dtype=np.int64),
+                     np.ascontiguousarray(block_offset, dtype=np.int64)]
+        self.device = (time_ns, param_bytes, act_bytes)  # DEVICE tensors (kept alive)
+        self.n_problems = int(self.keep[0].shape[0])
+        self.struct = Batch(self.n_problems, *[_ptr(a) for a in self.keep],
+                            _ptr(time_ns), _ptr(param_bytes), _ptr(act_bytes))
+
+
+def rannc_dp_workspace_bytes(limits: Limits) -> int:
+    return int(lib().rannc_dp_workspace_bytes(C.byref(limits)))
+
+
+def rannc_dp_workspace_bytes_for(limits: Limits, batch: HostBatch) -> int:
+    return int(lib().rannc_dp_workspace_bytes_for(C.byref(limits), C.byref(batch.struct)))
+
+
+def rannc_dp_create(limits: Limits, d_workspace, workspace_bytes: int):
+    """Returns (status, handle).  d_workspace: torch uint8 tensor on the device, or an address."""
+    h = C.c_void_p()
+    rc = lib().rannc_dp_create(C.byref(limits), _ptr(d_workspace), int(workspace_bytes), C.byref(h))
+    return rc, (h.value if rc == OK else None)
+
+
+def rannc_dp_solve(handle, batch: HostBatch, stream, d_opt, d_n_stages, d_est_iter_ns=None,
+                   d_status=None) -> int:
+    return lib().rannc_dp_solve(handle, C.byref(batch.struct) if batch is not None else None,
+                                _ptr(stream), _ptr(d_opt), _ptr(d_n_stages), _ptr(d_est_iter_ns),
+                                _ptr(d_status))
+
+
+def rannc_dp_traceback(handle, stream, plan_stride: int, d_stage_end, d_replicas) -> int:
+    return lib().rannc_dp_traceback(handle, _ptr(stream), int(plan_stride), _ptr(d_stage_end),
+                                    _ptr(d_replicas))
+
+
+def rannc_dp_read_table(handle, which: int, problem: int, d_dst, nbytes: int, stream) -> int:
+    return lib().rannc_dp_read_table(handle, int(which), int(problem), _ptr(d_dst), int(nbytes),
+                                     _ptr(stream))
+
+
+def rannc_dp_destroy(handle) -> None:
+    lib().rannc_dp_destroy(handle)
+
+
+def rannc_dp_set_timing(handle, enabled: bool) -> int:
+    return lib().rannc_dp_set_timing(handle, 1 if enabled else 0)
+
+
+def rannc_dp_get_timing(handle):
+    """Returns (status, [build_ms, levels_ms, select_ms], level_launches)."""
+    ms = (C.c_float * 3)()
+    n = C.c_int32()
+    rc = lib().rannc_dp_get_timing(handle, ms, C.byref(n))
+    return rc, [float(ms[0]), float(ms[1]), float(ms[2])], int(n.value)
+
+
+# ---------------------------------------------------------------------------------------------
+# Convenience for tests, the smoke check and the benchmark: owns the torch buffers around one
+# handle.  Still marshalling only.
+# ---------------------------------------------------------------------------------------------
+class Session:
+    def __init__(self, batch_np: dict, *, algo=ALGO_AUTO, max_total_time_ns=NARROW_MAX_TOTAL_TIME,
+                 device="cuda:0", exact_workspace=True):
+        import torch
+        self.torch = torch
+        self.dev = torch.device(device)
+        b = batch_np
+        self.Q = int(b["n_problems"])
+        self.batch_np = b
+        self.S_eff = np.minimum(b["max_stages"], np.minimum(b["n_blocks"], b["n_devices"]))
+        self.limits = make_limits(self.Q, int(b["n_blocks"].max()), int(b["n_devices"].max()),
+                                  int(self.S_eff.max()), max_total_time_ns, algo)
+        self.d_in = [torch.from_numpy(np.ascontiguousarray(b[k], dtype=np.int64)).to(self.dev)
+                     for k in ("time_ns", "param_bytes", "act_bytes")]
+        self.hb = HostBatch(b["n_blocks"], b["n_devices"], b["max_stages"], b["n_microbatches"],
+                            b["mem_capacity"], b["block_offset"], *self.d_in)
+        nbytes = (rannc_dp_workspace_bytes_for(self.limits, self.hb) if exact_workspace
+                  else rannc_dp_workspace_bytes(self.limits))
+        if nbytes == 0:
+            raise RanncDpError(INVALID_ARG, "workspace size query")
+        self.ws_bytes = nbytes
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=self.dev)
+        rc, self.h = rannc_dp_create(self.limits, self.ws, nbytes)
+        if rc != OK:
+            raise RanncDpError(rc, "rannc_dp_create")
+        self.plan_stride = int(self.S_eff.max())
+        self.d_opt = torch.empty(self.Q, dtype=torch.int64, device=self.dev)
+        self.d_ns = torch.empty(self.Q, dtype=torch.int32, device=self.dev)
+        self.d_est = torch.empty(self.Q, dtype=torch.int64, device=self.dev)
+        self.d_status = torch.empty(self.Q, dtype=torch.int32, device=self.dev)
+        self.d_se = torch.empty((self.Q, self.plan_stride), dtype=torch.int32, device=self.dev)
+        self.d_rp = torch.empty((self.Q, self.plan_stride), dtype=torch.int32, device=self.dev)
+
+    def stream(self):
+        return self.torch.cuda.current_stream(self.dev).cuda_stream
+
+    def solve(self):
+        rc = rannc_dp_solve(self.h, self.hb, self.stream(), self.d_opt, self.d_ns, self.d_est,
+                            self.d_status)
+        if rc != OK:
+            raise RanncDpError(rc, "rannc_dp_solve")
+
+    def traceback(self):
+        rc = rannc_dp_traceback(self.h, self.stream(), self.plan_stride, self.d_se, self.d_rp)
+        if rc != OK:
+            raise RanncDpError(rc, "rannc_dp_traceback")
+
+    def run(self):
+        """solve + traceback + copy the results to the host."""
+        self.solve()
+        self.traceback()
+        self.torch.cuda.synchronize(self.dev)
+        return {"opt": self.d_opt.cpu().numpy(), "n_stages": self.d_ns.cpu().numpy(),
+                "est_iter_ns": self.d_est.cpu().numpy(), "status": self.d_status.cpu().numpy(),
+                "stage_end": self.d_se.cpu().numpy(), "replicas": self.d_rp.cpu().numpy()}
+
+    def table(self, which: int, q: int) -> np.ndarray:
+        torch = self.torch
+        N, D, L = (int(self.batch_np["n_blocks"][q]), int(self.batch_np["n_devices"][q]),
+                   int(self.S_eff[q]))
+        tri = N * (N + 1) // 2 * D
+        cells = (L + 1) * (N + 1) * (D + 1)
+        if which == TABLE_COST:
+            dst = torch.empty(tri, dtype=torch.int64, device=self.dev)
+        elif which == TABLE_FIT:
+            dst = torch.empty(tri, dtype=torch.uint8, device=self.dev)
+        elif which == TABLE_V:
+            dst = torch.empty(cells, dtype=torch.int64, device=self.dev)
+        else:
+            dst = torch.empty(cells, dtype=torch.int32, device=self.dev)
+        rc = rannc_dp_read_table(self.h, which, q, dst, dst.numel() * dst.element_size(),
+                                 self.stream())
+        if rc != OK:
+            raise RanncDpError(rc, "rannc_dp_read_table")
+        torch.cuda.synchronize(self.dev)
+        out = dst.cpu().numpy()
+        if which in (TABLE_V, TABLE_ARG_I, TABLE_ARG_D):
+            out = out.reshape(L + 1, N + 1, D + 1)
+        return out
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.torch.cuda.synchronize(self.dev)
+            rannc_dp_destroy(self.h)
+            self.h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()

@@ -1,0 +1,418 @@
+// Host orchestration behind the C ABI of include/rannc_dp.h: argument checks, workspace
+// layout, and the sequence of kernel launches of one search (prefix sums and tables, one
+// launch per DP level, final selection, plan recovery).  Nothing here computes any part of the
+// recurrence; that is all in rannc_dp_kernels.hip.
+#include "../../include/rannc_dp.h"
+#include "rannc_dp_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using rannc::LaunchShape;
+using rannc::ProblemDev;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int64_t kNarrowMax = 4294967294LL;  // largest total time a 32-bit table can hold
+constexpr int kStagingSlots = 2;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Sizes {  // bytes of one problem's regions inside the workspace
+  size_t prefix, ilo, misc, rmin, cost, V;
+  size_t total() const { return prefix * 3 + ilo + misc + rmin + cost + V; }
+};
+
+// false on arithmetic overflow
+bool problem_sizes(int N, int D, int S_eff, int bits, Sizes *o) {
+  const int nch = (N + 63) / 64;
+  const int DP = rannc::dp_class(D);
+  const size_t esz = bits / 8;
+  const unsigned __int128 rows = (unsigned __int128)rannc::rows_before(nch, N);
+  const unsigned __int128 cost = rows * (unsigned)D * esz;
+  const unsigned __int128 V = (unsigned __int128)S_eff * (unsigned)(N + 1) * (unsigned)DP * esz;
+  if (cost > ((unsigned __int128)1 << 46) || V > ((unsigned __int128)1 << 46)) return false;
+  o->prefix = align_up((size_t)(N + 1) * 8);
+  o->ilo = align_up((size_t)(N + 1) * 4);
+  o->misc = align_up(64);  // status word, result pair
+  o->rmin = align_up((size_t)rows);
+  o->cost = align_up((size_t)cost);
+  o->V = align_up((size_t)V);
+  return true;
+}
+
+bool limits_ok(const rannc_dp_limits_t *l) {
+  return l && l->max_problems >= 1 && l->max_blocks >= 1 && l->max_blocks <= 65535 &&
+         l->max_devices >= 1 && l->max_devices <= RANNC_DP_MAX_DEVICES && l->max_stages >= 1 &&
+         l->max_total_time_ns >= 0 && l->reserved == 0 && l->algo >= RANNC_DP_ALGO_AUTO &&
+         l->algo <= RANNC_DP_ALGO_SCAN;
+}
+
+int bits_of(const rannc_dp_limits_t *l) { return l->max_total_time_ns <= kNarrowMax ? 32 : 64; }
+
+size_t header_bytes(int Q) {
+  return align_up((size_t)Q * sizeof(ProblemDev)) + align_up((size_t)Q * 2 * sizeof(int32_t));
+}
+
+// Host-side validation of the batch descriptors against the limits.
+int check_batch(const rannc_dp_limits_t *l, const rannc_dp_batch_t *b) {
+  if (!b || b->n_problems < 1) return RANNC_DP_INVALID_ARG;
+  if (!b->n_blocks || !b->n_devices || !b->max_stages || !b->n_microbatches || !b->mem_capacity ||
+      !b->block_offset)
+    return RANNC_DP_INVALID_ARG;
+  if (b->n_problems > l->max_problems) return RANNC_DP_LIMIT_EXCEEDED;
+  if (b->block_offset[0] < 0) return RANNC_DP_INVALID_ARG;
+  for (int q = 0; q < b->n_problems; ++q) {
+    if (b->n_blocks[q] < 1 || b->n_devices[q] < 1 || b->max_stages[q] < 1 ||
+        b->n_microbatches[q] < 1 || b->mem_capacity[q] < 0)
+      return RANNC_DP_INVALID_ARG;
+    if (b->block_offset[q + 1] - b->block_offset[q] != (int64_t)b->n_blocks[q])
+      return RANNC_DP_INVALID_ARG;
+    if (b->n_blocks[q] > l->max_blocks || b->n_devices[q] > l->max_devices ||
+        std::min(b->max_stages[q], std::min(b->n_blocks[q], b->n_devices[q])) > l->max_stages)
+      return RANNC_DP_LIMIT_EXCEEDED;
+  }
+  return RANNC_DP_OK;
+}
+
+}  // namespace
+
+struct rannc_dp {
+  rannc_dp_limits_t lim;
+  int bits;
+  char *ws;
+  size_t ws_bytes;
+  // pinned staging for the per-problem descriptors and problem lists, reused round-robin
+  char *staging[kStagingSlots];
+  hipEvent_t staging_free[kStagingSlots];
+  bool staging_used[kStagingSlots];
+  size_t staging_bytes;
+  int next_slot;
+  // state of the last successful solve
+  bool solved;
+  int Q;
+  std::vector<ProblemDev> host_probs;
+  ProblemDev *d_probs;
+  int32_t *d_lists;  // [0,Q): identity, [Q,2Q): problems grouped by DP class
+  // timing
+  bool timing;
+  hipEvent_t ev[4];
+  bool ev_valid;
+  int level_launches;
+};
+
+extern "C" {
+
+const char *rannc_dp_strerror(int status) {
+  switch (status) {
+    case RANNC_DP_OK: return "ok";
+    case RANNC_DP_INVALID_ARG: return "invalid argument";
+    case RANNC_DP_LIMIT_EXCEEDED: return "problem exceeds the limits of the handle";
+    case RANNC_DP_WORKSPACE_TOO_SMALL: return "workspace too small for this batch";
+    case RANNC_DP_OVERFLOW: return "size computation overflow";
+    case RANNC_DP_HIP_ERROR: return "HIP runtime error";
+    case RANNC_DP_BAD_STATE: return "no solved batch on this handle";
+    case RANNC_DP_NO_HOST_MEMORY: return "out of host memory";
+    default: return "unknown status";
+  }
+}
+
+size_t rannc_dp_workspace_bytes(const rannc_dp_limits_t *l) {
+  if (!limits_ok(l)) return 0;
+  Sizes sz;
+  const int S_eff = std::min(l->max_stages, std::min(l->max_blocks, l->max_devices));
+  if (!problem_sizes(l->max_blocks, l->max_devices, S_eff, bits_of(l), &sz)) return 0;
+  const unsigned __int128 tot =
+      (unsigned __int128)sz.total() * (unsigned)l->max_problems + header_bytes(l->max_problems);
+  if (tot > ((unsigned __int128)1 << 47)) return 0;
+  return (size_t)tot;
+}
+
+size_t rannc_dp_workspace_bytes_for(const rannc_dp_limits_t *l, const rannc_dp_batch_t *b) {
+  if (!limits_ok(l) || check_batch(l, b) != RANNC_DP_OK) return 0;
+  size_t tot = header_bytes(l->max_problems);
+  for (int q = 0; q < b->n_problems; ++q) {
+    Sizes sz;
+    const int S_eff = std::min(b->max_stages[q], std::min(b->n_blocks[q], b->n_devices[q]));
+    if (!problem_sizes(b->n_blocks[q], b->n_devices[q], S_eff, bits_of(l), &sz)) return 0;
+    tot += sz.total();
+    if (tot > ((size_t)1 << 47)) return 0;
+  }
+  return tot;
+}
+
+int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t workspace_bytes,
+                    rannc_dp_t **out) {
+  if (out) *out = nullptr;
+  if (!out || !limits_ok(l) || !d_workspace || ((uintptr_t)d_workspace % kAlign) != 0)
+    return RANNC_DP_INVALID_ARG;
+  if (workspace_bytes < header_bytes(l->max_problems)) return RANNC_DP_WORKSPACE_TOO_SMALL;
+  rannc_dp *h = new (std::nothrow) rannc_dp();
+  if (!h) return RANNC_DP_NO_HOST_MEMORY;
+  h->lim = *l;
+  h->bits = bits_of(l);
+  h->ws = (char *)d_workspace;
+  h->ws_bytes = workspace_bytes;
+  h->staging_bytes = header_bytes(l->max_problems);
+  h->next_slot = 0;
+  h->solved = false;
+  h->Q = 0;
+  h->timing = false;
+  h->ev_valid = false;
+  h->level_launches = 0;
+  h->d_probs = (ProblemDev *)h->ws;
+  h->d_lists = (int32_t *)(h->ws + align_up((size_t)l->max_problems * sizeof(ProblemDev)));
+  int made_staging = 0, made_ev_s = 0, made_ev = 0;
+  bool ok = true;
+  for (int k = 0; k < kStagingSlots && ok; ++k) {
+    h->staging_used[k] = false;
+    ok = hipHostMalloc((void **)&h->staging[k], h->staging_bytes, hipHostMallocDefault) == hipSuccess;
+    if (ok) ++made_staging;
+  }
+  for (int k = 0; k < kStagingSlots && ok; ++k) {
+    ok = hipEventCreateWithFlags(&h->staging_free[k], hipEventDisableTiming) == hipSuccess;
+    if (ok) ++made_ev_s;
+  }
+  for (int k = 0; k < 4 && ok; ++k) {
+    ok = hipEventCreate(&h->ev[k]) == hipSuccess;
+    if (ok) ++made_ev;
+  }
+  if (!ok) {
+    for (int k = 0; k < made_staging; ++k) (void)hipHostFree(h->staging[k]);
+    for (int k = 0; k < made_ev_s; ++k) (void)hipEventDestroy(h->staging_free[k]);
+    for (int k = 0; k < made_ev; ++k) (void)hipEventDestroy(h->ev[k]);
+    delete h;
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  *out = h;
+  return RANNC_DP_OK;
+}
+
+void rannc_dp_destroy(rannc_dp_t *h) {
+  if (!h) return;
+  for (int k = 0; k < kStagingSlots; ++k) {
+    if (h->staging_used[k]) (void)hipEventSynchronize(h->staging_free[k]);
+    (void)hipHostFree(h->staging[k]);
+    (void)hipEventDestroy(h->staging_free[k]);
+  }
+  for (int k = 0; k < 4; ++k) (void)hipEventDestroy(h->ev[k]);
+  delete h;
+}
+
+int rannc_dp_set_timing(rannc_dp_t *h, int enabled) {
+  if (!h) return RANNC_DP_INVALID_ARG;
+  h->timing = enabled != 0;
+  return RANNC_DP_OK;
+}
+
+int rannc_dp_get_timing(rannc_dp_t *h, float *out_ms, int32_t *out_level_launches) {
+  if (!h || !out_ms) return RANNC_DP_INVALID_ARG;
+  if (!h->ev_valid) return RANNC_DP_BAD_STATE;
+  if (hipEventSynchronize(h->ev[3]) != hipSuccess) return RANNC_DP_HIP_ERROR;
+  for (int k = 0; k < 3; ++k)
+    if (hipEventElapsedTime(&out_ms[k], h->ev[k], h->ev[k + 1]) != hipSuccess) return RANNC_DP_HIP_ERROR;
+  if (out_level_launches) *out_level_launches = h->level_launches;
+  return RANNC_DP_OK;
+}
+
+int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, int64_t *d_opt,
+                   int32_t *d_n_stages, int64_t *d_est_iter_ns, int32_t *d_status) {
+  if (!h || !d_opt || !d_n_stages) return RANNC_DP_INVALID_ARG;
+  int rc = check_batch(&h->lim, b);
+  if (rc != RANNC_DP_OK) return rc;
+  if (!b->time_ns || !b->param_bytes || !b->act_bytes) return RANNC_DP_INVALID_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int Q = b->n_problems;
+
+  // ---- workspace layout -------------------------------------------------------------
+  std::vector<ProblemDev> probs;
+  try {
+    probs.resize(Q);
+  } catch (...) {
+    return RANNC_DP_NO_HOST_MEMORY;
+  }
+  size_t off = header_bytes(h->lim.max_problems);
+  for (int q = 0; q < Q; ++q) {
+    const int N = b->n_blocks[q], D = b->n_devices[q];
+    const int S_eff = std::min(b->max_stages[q], std::min(N, D));
+    Sizes sz;
+    if (!problem_sizes(N, D, S_eff, h->bits, &sz)) return RANNC_DP_OVERFLOW;
+    if (off + sz.total() > h->ws_bytes) return RANNC_DP_WORKSPACE_TOO_SMALL;
+    ProblemDev &p = probs[q];
+    std::memset(&p, 0, sizeof(p));
+    p.N = N; p.D = D; p.S_eff = S_eff; p.MB = b->n_microbatches[q];
+    p.DP = rannc::dp_class(D);
+    p.nch = (N + 63) / 64;
+    p.bits = h->bits;
+    p.M = b->mem_capacity[q];
+    p.time_limit = h->lim.max_total_time_ns;
+    p.t = b->time_ns + b->block_offset[q];
+    p.p = b->param_bytes + b->block_offset[q];
+    p.a = b->act_bytes + b->block_offset[q];
+    char *base = h->ws + off;
+    p.T = (int64_t *)base; base += sz.prefix;
+    p.P = (int64_t *)base; base += sz.prefix;
+    p.A = (int64_t *)base; base += sz.prefix;
+    p.ilo = (int32_t *)base; base += sz.ilo;
+    p.status = (int32_t *)base;
+    p.res = (int64_t *)(base + 16); base += sz.misc;
+    p.rmin = (uint8_t *)base; base += sz.rmin;
+    p.cost = base; base += sz.cost;
+    p.V = base; base += sz.V;
+    off += sz.total();
+  }
+
+  // problems grouped by the padded device dimension their kernels are specialised for
+  static const int kClasses[4] = {8, 16, 32, 64};
+  int cls_start[5] = {0, 0, 0, 0, 0};
+  LaunchShape shape[4];
+  std::memset(shape, 0, sizeof(shape));
+  std::vector<int32_t> lists(2 * (size_t)Q);
+  for (int q = 0; q < Q; ++q) {
+    lists[q] = q;
+    for (int k = 0; k < 4; ++k)
+      if (probs[q].DP == kClasses[k]) ++cls_start[k + 1];
+  }
+  for (int k = 0; k < 4; ++k) cls_start[k + 1] += cls_start[k];
+  {
+    int fill[4] = {cls_start[0], cls_start[1], cls_start[2], cls_start[3]};
+    for (int q = 0; q < Q; ++q)
+      for (int k = 0; k < 4; ++k)
+        if (probs[q].DP == kClasses[k]) {
+          lists[Q + fill[k]++] = q;
+          LaunchShape &sh = shape[k];
+          sh.nprob++;
+          sh.max_N = std::max(sh.max_N, probs[q].N);
+          sh.max_nch = std::max(sh.max_nch, probs[q].nch);
+          sh.max_D = std::max(sh.max_D, probs[q].D);
+          sh.max_S_eff = std::max(sh.max_S_eff, probs[q].S_eff);
+        }
+  }
+
+  // ---- descriptors to the device ---------------------------------------------------
+  const int slot = h->next_slot;
+  h->next_slot = (slot + 1) % kStagingSlots;
+  if (h->staging_used[slot] && hipEventSynchronize(h->staging_free[slot]) != hipSuccess)
+    return RANNC_DP_HIP_ERROR;
+  const size_t probs_bytes = (size_t)Q * sizeof(ProblemDev);
+  const size_t lists_off = align_up((size_t)h->lim.max_problems * sizeof(ProblemDev));
+  std::memcpy(h->staging[slot], probs.data(), probs_bytes);
+  std::memcpy(h->staging[slot] + lists_off, lists.data(), lists.size() * sizeof(int32_t));
+  h->solved = false;
+  if (hipMemcpyAsync(h->ws, h->staging[slot], probs_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
+      hipMemcpyAsync(h->ws + lists_off, h->staging[slot] + lists_off, lists.size() * sizeof(int32_t),
+                     hipMemcpyHostToDevice, st) != hipSuccess ||
+      hipEventRecord(h->staging_free[slot], st) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  h->staging_used[slot] = true;
+
+  // ---- kernels ---------------------------------------------------------------------------
+  const ProblemDev *dp = h->d_probs;
+  const int32_t *dl = h->d_lists + Q;  // [0,Q) is the identity list, [Q,2Q) the class-grouped one
+  bool ok = true;
+  const bool timing = h->timing;
+  h->ev_valid = false;
+  h->level_launches = 0;
+  if (timing) ok = ok && hipEventRecord(h->ev[0], st) == hipSuccess;
+  ok = ok && rannc::launch_prefix(dp, Q, st) == hipSuccess;
+  ok = ok && rannc::launch_fill(dp, Q, st) == hipSuccess;
+  for (int k = 0; k < 4 && ok; ++k)
+    if (shape[k].nprob)
+      ok = rannc::launch_build(dp, dl + cls_start[k], shape[k], h->bits, kClasses[k], st) == hipSuccess;
+  if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
+  const bool scan = h->lim.algo == RANNC_DP_ALGO_SCAN;
+  int max_levels = 0;
+  for (int k = 0; k < 4; ++k) max_levels = std::max(max_levels, shape[k].max_S_eff);
+  for (int s = 2; s <= max_levels && ok; ++s) {
+    for (int k = 0; k < 4 && ok; ++k) {
+      const LaunchShape &sh = shape[k];
+      if (!sh.nprob || sh.max_S_eff < s) continue;
+      if (scan) {
+        ok = rannc::launch_level_scan(dp, dl + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
+             hipSuccess;
+      } else {
+        // rows of predecessors per work item: as long as possible while the launch still has
+        // several waves per SIMD (1024 SIMDs on the device)
+        int steps = 32;
+        while (steps > 4) {
+          const int64_t items = (int64_t)sh.nprob * sh.max_nch * ((sh.max_N + steps - 1) / steps) / 2;
+          if (items >= 4096) break;
+          steps >>= 1;
+        }
+        ok = rannc::launch_level_merge(dp, dl + cls_start[k], sh, h->bits, kClasses[k], s, steps, st) ==
+             hipSuccess;
+      }
+      h->level_launches++;
+    }
+  }
+  if (timing) ok = ok && hipEventRecord(h->ev[2], st) == hipSuccess;
+  ok = ok && rannc::launch_select(dp, Q, d_opt, d_n_stages, d_est_iter_ns, d_status, st) == hipSuccess;
+  if (timing) ok = ok && hipEventRecord(h->ev[3], st) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  h->ev_valid = timing;
+  h->host_probs.swap(probs);
+  h->Q = Q;
+  h->solved = true;
+  return RANNC_DP_OK;
+}
+
+int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride, int32_t *d_stage_end,
+                       int32_t *d_replicas) {
+  if (!h || !d_stage_end || !d_replicas || plan_stride < 1) return RANNC_DP_INVALID_ARG;
+  if (!h->solved) return RANNC_DP_BAD_STATE;
+  for (int q = 0; q < h->Q; ++q)
+    if (h->host_probs[q].S_eff > plan_stride) return RANNC_DP_INVALID_ARG;
+  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas,
+                              (hipStream_t)hip_stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  return RANNC_DP_OK;
+}
+
+int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, size_t bytes,
+                        void *hip_stream) {
+  if (!h || !d_dst) return RANNC_DP_INVALID_ARG;
+  if (!h->solved) return RANNC_DP_BAD_STATE;
+  if (problem < 0 || problem >= h->Q) return RANNC_DP_INVALID_ARG;
+  const ProblemDev &p = h->host_probs[problem];
+  const size_t tri = (size_t)p.N * (size_t)(p.N + 1) / 2 * (size_t)p.D;
+  const size_t cells = (size_t)(p.S_eff + 1) * (size_t)(p.N + 1) * (size_t)(p.D + 1);
+  size_t want = 0;
+  switch (which) {
+    case RANNC_DP_TABLE_COST: want = tri * 8; break;
+    case RANNC_DP_TABLE_FIT: want = tri; break;
+    case RANNC_DP_TABLE_V: want = cells * 8; break;
+    case RANNC_DP_TABLE_ARG_I:
+    case RANNC_DP_TABLE_ARG_D: want = cells * 4; break;
+    default: return RANNC_DP_INVALID_ARG;
+  }
+  if (bytes != want) return RANNC_DP_INVALID_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  bool ok = rannc::launch_export(h->d_probs, problem, which, p, d_dst, st) == hipSuccess;
+  if (which == RANNC_DP_TABLE_ARG_I || which == RANNC_DP_TABLE_ARG_D) {
+    LaunchShape sh;
+    sh.nprob = 1; sh.max_N = p.N; sh.max_nch = p.nch; sh.max_D = p.D; sh.max_S_eff = p.S_eff;
+    int32_t *ai = which == RANNC_DP_TABLE_ARG_I ? (int32_t *)d_dst : nullptr;
+    int32_t *ad = which == RANNC_DP_TABLE_ARG_D ? (int32_t *)d_dst : nullptr;
+    for (int s = 2; s <= p.S_eff && ok; ++s)
+      ok = rannc::launch_level_scan(h->d_probs, h->d_lists + problem, sh, p.bits, s, 0, ai, ad, st) ==
+           hipSuccess;
+  }
+  if (!ok) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  return RANNC_DP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,613 @@
+// gfx950 kernels of the stage-level partition search (RaNNC Sec. III-C, Algorithm 1).
+//
+// One wavefront is 64 lanes; in every kernel that touches the stage-time table a lane owns one
+// output column j (blocks 1..j covered), so table rows are read with coalesced requests and no
+// value ever has to cross lanes.  All arithmetic is exact unsigned integer arithmetic.
+#include "rannc_dp_internal.h"
+
+#include "../../include/rannc_dp.h"
+
+namespace rannc {
+
+template <typename VT> struct Lim;
+template <> struct Lim<uint32_t> { static constexpr uint32_t inf = 0xFFFFFFFFu; };
+template <> struct Lim<uint64_t> { static constexpr uint64_t inf = 0x7FFFFFFFFFFFFFFFull; };
+
+template <typename VT> __device__ __forceinline__ VT vmax(VT a, VT b) { return a > b ? a : b; }
+template <typename VT> __device__ __forceinline__ VT vmin(VT a, VT b) { return a < b ? a : b; }
+
+static constexpr uint64_t kSumLimit = 1ull << 62;
+
+// ---------------------------------------------------------------------------------------
+// Prefix sums T, P, A of the block inputs (the sums over a stage's members that stand in
+// for profile(), Sec. IV-D) and input validation.  One workgroup per problem.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restrict__ probs) {
+  const ProblemDev pr = probs[blockIdx.x];
+  __shared__ uint64_t part[3][256];
+  __shared__ int flags;
+  const int N = pr.N, tid = threadIdx.x;
+  const int seg = (N + 255) / 256;
+  const int lo = min(tid * seg, N), hi = min(lo + seg, N);
+  if (tid == 0) flags = 0;
+  __syncthreads();
+  const int64_t *in[3] = {pr.t, pr.p, pr.a};
+  int64_t *out[3] = {pr.T, pr.P, pr.A};
+  int myflags = 0;
+  for (int w = 0; w < 3; ++w) {
+    uint64_t s = 0;
+    for (int k = lo; k < hi; ++k) {
+      int64_t v = in[w][k];
+      if (v < 0) { myflags |= 1; v = 0; }
+      uint64_t u = (uint64_t)v;
+      if (u >= kSumLimit) { myflags |= 2; u = kSumLimit; }
+      s = s + u; if (s > kSumLimit) s = kSumLimit;
+    }
+    part[w][tid] = s;
+  }
+  __syncthreads();
+  if (tid < 3) {  // exclusive scan of the 256 segment sums, saturating
+    uint64_t run = 0;
+    for (int k = 0; k < 256; ++k) {
+      uint64_t v = part[tid][k];
+      part[tid][k] = run;
+      run += v; if (run > kSumLimit) run = kSumLimit;
+    }
+  }
+  __syncthreads();
+  for (int w = 0; w < 3; ++w) {
+    uint64_t run = part[w][tid];
+    if (tid == 0) out[w][0] = 0;
+    for (int k = lo; k < hi; ++k) {
+      int64_t v = in[w][k];
+      uint64_t u = v < 0 ? 0 : (uint64_t)v;
+      if (u > kSumLimit) u = kSumLimit;
+      run += u; if (run > kSumLimit) run = kSumLimit;
+      if (run >= kSumLimit) myflags |= 2;
+      out[w][k + 1] = (int64_t)run;
+    }
+  }
+  if (myflags) atomicOr(&flags, myflags);
+  __syncthreads();
+  if (tid == 0) {
+    int st = RANNC_DP_PROBLEM_OK;
+    if (flags & 1) st = RANNC_DP_PROBLEM_NEGATIVE_INPUT;
+    else if (flags & 2) st = RANNC_DP_PROBLEM_SUM_OVERFLOW;
+    else if (pr.T[N] > pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
+    *pr.status = st;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Initial state: every V entry "no plan" (padding columns d > D hold 0 so that padded rows stay
+// sorted), ilo[j] = j ("no predecessor fits").
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict__ probs) {
+  const ProblemDev pr = probs[blockIdx.y];
+  const int64_t total = (int64_t)pr.S_eff * (pr.N + 1) * pr.DP;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (pr.bits == 32) {
+    uint32_t *V = (uint32_t *)pr.V;
+    for (int64_t e = t0; e < total; e += stride)
+      V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint32_t>::inf : 0u;
+  } else {
+    uint64_t *V = (uint64_t *)pr.V;
+    for (int64_t e = t0; e < total; e += stride)
+      V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint64_t>::inf : 0ull;
+  }
+  for (int64_t j = t0; j <= pr.N; j += stride) pr.ilo[j] = (int32_t)j;
+}
+
+// ---------------------------------------------------------------------------------------
+// Stage-time and fits-in-memory tables: h(i,j,r) and the m(i,j,r) <= M rule of Sec. III-C for
+// every stage (i,j) and replica count r.  Block = (row i, 64-column chunk c); a lane owns one j
+// and writes its D entries, each store instruction covering 64 consecutive columns.
+// Memory is non-increasing in r, so the fit rule is stored as the smallest fitting r and folded
+// into the time table as INF below it.  Row i = 0 is also level 1 of the DP (one stage on d
+// devices), written here.
+// ---------------------------------------------------------------------------------------
+template <typename VT, int DP>
+__global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict__ probs,
+                                                   const int32_t *__restrict__ list) {
+  const ProblemDev &pr = probs[list[blockIdx.z]];
+  if (*pr.status != 0) return;
+  const int N = pr.N, D = pr.D, nch = pr.nch;
+  const int i = blockIdx.y, c = blockIdx.x;
+  if (i >= N || c >= nch || c < (i >> 6)) return;
+  const int jj = 64 * c + (int)threadIdx.x;
+  if (jj < i || jj >= N) return;
+  const int j = jj + 1;
+  const int64_t Tij = pr.T[j] - pr.T[i];
+  const int64_t Pij = pr.P[j] - pr.P[i];
+  const int64_t Aij = pr.A[j] - pr.A[i];
+  // smallest r with Pij + ceil(Aij / r) <= M, using ceil(a/r) <= k  <=>  a <= k*r
+  int rmin = 255;
+  if (Pij <= pr.M) {
+    const int64_t slack = pr.M - Pij;
+    if (Aij <= slack) rmin = 1;
+    else if (slack > 0) {
+      const uint64_t need = ((uint64_t)Aij + (uint64_t)slack - 1) / (uint64_t)slack;
+      if (need <= (uint64_t)D) rmin = (int)need;
+    }
+  }
+  const int64_t rb = rows_before(nch, i);
+  const int col = jj - 64 * (i >> 6);
+  pr.rmin[rb + col] = (uint8_t)rmin;
+  if (rmin <= D) atomicMin(&pr.ilo[j], i);
+  const int64_t L = row_len(nch, i);
+  VT *crow = (VT *)pr.cost + rb * D + col;
+  VT *v1 = (VT *)pr.V + (int64_t)j * DP;
+  const VT tij = (VT)Tij;
+#pragma unroll
+  for (int r = 1; r <= DP; ++r) {
+    if (r > D) break;
+    const VT q = tij / (VT)r;                   // r is a compile-time constant after unrolling
+    const VT h = q + (VT)(q * (VT)r != tij);    // ceil
+    const VT v = (r >= rmin) ? h : Lim<VT>::inf;
+    crow[(int64_t)(r - 1) * L] = v;
+    if (i == 0) v1[r - 1] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// DP level s >= 2, sorted-merge form.
+//
+// For a fixed stage (i,j) the recurrence of Sec. III-C needs, for every device total d,
+//     W[d] = min over d' + r = d of max(a[d'], c[r]),   a[d'] = V[s-1][i][d'], c[r] = h(i,j,r)
+// (INF where r does not fit).  Both sequences are non-increasing: giving one more device to
+// the last stage of a plan can only lower its time and its memory, and h, m are non-increasing
+// in r.  For such sequences, W[d] <= x  <=>  (number of a's > x) + (number of c's > x) <= d-2,
+// i.e. W[d] is the (d-1)-th largest element of the merged multiset {a[1..]} U {c[1..]}.  A wave
+// therefore merges the two sorted D-vectors with a bitonic network held in registers
+// (DP*(log2 DP + 1) max/min operations instead of D^2/2 max-min pairs) and folds the result into
+// a per-lane running minimum over i.  V[s][j][d] = min over i of W[d] is then the value the
+// five nested loops of Algorithm 1 produce; which (i,d') attains it is recovered where it is
+// needed (traceback, table export) by the first-match scan, not carried here.
+//
+// Work item = (64-column chunk c, run of `i_steps` predecessor rows); a lane owns column
+// jj = 64c + lane.  a[] is wave-uniform (one row of V[s-1]), c[] comes from DP coalesced row
+// reads.  Partial minima of different i-runs are combined with atomicMin into V[s] (pre-filled
+// with INF): min is order-independent, so the result is deterministic.
+// ---------------------------------------------------------------------------------------
+template <typename VT, int DP>
+__global__ __launch_bounds__(64) void level_merge_kernel(const ProblemDev *__restrict__ probs,
+                                                         const int32_t *__restrict__ list,
+                                                         const int s, const int i_steps) {
+  const ProblemDev &pr = probs[list[blockIdx.z]];
+  const int N = pr.N, D = pr.D, nch = pr.nch;
+  if (s > pr.S_eff || *pr.status != 0) return;
+  const int c = blockIdx.y;
+  if (c >= nch || 64 * c + 64 < s) return;  // no column j >= s in this chunk
+  const int lane = threadIdx.x;
+  const int jj = 64 * c + lane;
+  int i_lo = blockIdx.x * i_steps;
+  int i_hi = min(min(i_lo + i_steps - 1, 64 * c + 63), N - 1);
+  i_lo = max(i_lo, s - 1);
+  if (i_lo > i_hi) return;
+  {  // rows below every column's first fitting predecessor hold INF only
+    int my = (jj < N) ? pr.ilo[jj + 1] : 0x7fffffff;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) my = min(my, __shfl_xor(my, o));
+    i_lo = max(i_lo, my);
+    if (i_lo > i_hi) return;
+  }
+  constexpr VT INF = Lim<VT>::inf;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT *__restrict__ Vprev = (const VT *)pr.V + (int64_t)(s - 2) * lvl;
+  VT *Vcur = (VT *)pr.V + (int64_t)(s - 1) * lvl;
+  const VT *__restrict__ cost = (const VT *)pr.cost;
+  const int rmax = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
+
+  VT acc[DP];
+#pragma unroll
+  for (int t = 0; t < DP; ++t) acc[t] = INF;
+  bool any = false;
+
+  for (int i = i_lo; i <= i_hi; ++i) {
+    const VT *__restrict__ arow = Vprev + (int64_t)i * DP;
+    if (arow[D - 1] == INF) continue;  // no (s-1)-stage plan covers blocks 1..i
+    const int g = i >> 6;
+    const int64_t rb = rows_before(nch, i);
+    const int col = jj - 64 * g;
+    bool act = (jj >= i) && (jj < N);
+    if (act) act = (int)pr.rmin[rb + col] <= rmax;
+    if (__ballot(act) == 0ull) continue;
+    any = true;
+    const int64_t L = row_len(nch, i);
+    const VT *__restrict__ crow = cost + rb * D + (act ? col : 0);
+    VT x[DP];
+    // x[k] = c[DP-k] (reversed), so that x becomes max(a[k+1], c[DP-k]): a bitonic sequence that
+    // holds the DP largest elements of the merge.
+#pragma unroll
+    for (int m = 0; m < DP; ++m) {
+      const int mr = (m < D) ? m : (D - 1);  // clamp keeps the address inside the row block
+      VT cv = INF;
+      if (act) cv = crow[(int64_t)mr * L];
+      x[DP - 1 - m] = (m < D) ? cv : (VT)0;  // padding sits below the smallest real element
+    }
+#pragma unroll
+    for (int k = 0; k < DP; ++k) x[k] = vmax(arow[k], x[k]);
+#pragma unroll
+    for (int h = DP / 2; h >= 1; h >>= 1) {
+#pragma unroll
+      for (int k = 0; k < DP; ++k) {
+        if ((k & h) == 0) {
+          const VT hi = vmax(x[k], x[k + h]);
+          const VT lo = vmin(x[k], x[k + h]);
+          x[k] = hi;
+          x[k + h] = lo;
+        }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+  }
+  if (!any) return;
+
+  // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Transpose through LDS so that one
+  // atomic instruction covers consecutive d of one column.
+  __shared__ VT tile[64 * (DP + 1)];
+#pragma unroll
+  for (int t = 0; t < DP; ++t) tile[lane * (DP + 1) + t] = acc[t];
+  __syncthreads();
+  constexpr int RPP = 64 / DP;  // rows per pass
+  const int t = lane & (DP - 1);
+#pragma unroll 4
+  for (int pass = 0; pass < DP; ++pass) {
+    const int row = pass * RPP + lane / DP;
+    const VT v = tile[row * (DP + 1) + t];
+    const int j = 64 * c + row + 1;
+    if (t + 1 <= D - 1 && j <= N && j >= s && v != INF) atomicMin(&Vcur[(int64_t)j * DP + t + 1], v);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// DP level s >= 2, literal form: one thread per cell (j, d) scans every split point i
+// (ascending) and every device count d' of the earlier stages (ascending), skipping infeasible
+// predecessors and stages that do not fit, and keeps the first strict minimum -- the loops of
+// Algorithm 1 as written.  Used as the reference level kernel (RANNC_DP_ALGO_SCAN) and to
+// produce the (i, d') tables for export.  With write_v = 0 the value table is left alone and
+// only the argmin arrays (canonical [(L+1)][N+1][D+1] layout of one problem) are written.
+// ---------------------------------------------------------------------------------------
+template <typename VT>
+__global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__restrict__ probs,
+                                                        const int32_t *__restrict__ list, const int s,
+                                                        const int write_v, int32_t *__restrict__ arg_i,
+                                                        int32_t *__restrict__ arg_d) {
+  const ProblemDev &pr = probs[list[blockIdx.z]];
+  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  if (s > pr.S_eff || *pr.status != 0) return;
+  const int c = blockIdx.x, d = blockIdx.y + 1;
+  if (c >= nch || d > D || d < s) return;
+  const int jj = 64 * c + (int)threadIdx.x;
+  const int j = jj + 1;
+  constexpr VT INF = Lim<VT>::inf;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT *__restrict__ Vprev = (const VT *)pr.V + (int64_t)(s - 2) * lvl;
+  const VT *__restrict__ cost = (const VT *)pr.cost;
+  VT best = INF;
+  int bi = -1, bd = -1;
+  const int i_end = min(64 * c + 63, N - 1);
+  for (int i = s - 1; i <= i_end; ++i) {
+    const bool act = (jj >= i) && (jj < N);
+    const int64_t rb = rows_before(nch, i);
+    const int64_t L = row_len(nch, i);
+    const VT *__restrict__ crow = cost + rb * D + (act ? jj - 64 * (i >> 6) : 0);
+    for (int dp = s - 1; dp <= d - 1; ++dp) {
+      const VT a = Vprev[(int64_t)i * DP + dp - 1];
+      if (a == INF) continue;
+      if (!act) continue;
+      const VT h = crow[(int64_t)(d - dp - 1) * L];
+      if (h == INF) continue;
+      const VT v = vmax(a, h);
+      if (v < best) { best = v; bi = i; bd = dp; }
+    }
+  }
+  if (jj >= N || j < s) return;
+  if (write_v) ((VT *)pr.V)[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1] = best;
+  const int64_t e = ((int64_t)s * (N + 1) + j) * (D + 1) + d;
+  if (arg_i) arg_i[e] = bi;
+  if (arg_d) arg_d[e] = bd;
+}
+
+// ---------------------------------------------------------------------------------------
+// Final choice of the stage count: opt = min over s of V[s][N][D], smallest s among equals.
+// ---------------------------------------------------------------------------------------
+__global__ void select_kernel(const ProblemDev *__restrict__ probs, int Q, int64_t *d_opt,
+                              int32_t *d_n_stages, int64_t *d_est, int32_t *d_status) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= Q) return;
+  const ProblemDev pr = probs[q];
+  const int st = *pr.status;
+  int64_t best = INT64_MAX;
+  int bs = 0;
+  if (st == 0) {
+    const int64_t lvl = (int64_t)(pr.N + 1) * pr.DP;
+    const int64_t cell = (int64_t)pr.N * pr.DP + pr.D - 1;
+    for (int s = 1; s <= pr.S_eff; ++s) {
+      int64_t v;
+      if (pr.bits == 32) {
+        const uint32_t u = ((const uint32_t *)pr.V)[(s - 1) * lvl + cell];
+        v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
+      } else {
+        v = (int64_t)((const uint64_t *)pr.V)[(s - 1) * lvl + cell];
+      }
+      if (v < best) { best = v; bs = s; }
+    }
+  }
+  pr.res[0] = best;
+  pr.res[1] = bs;
+  d_opt[q] = best;
+  d_n_stages[q] = bs;
+  if (d_est) {
+    int64_t e = INT64_MAX;
+    if (bs > 0) {
+      const int64_t f = (int64_t)pr.MB + bs - 1;
+      e = (best != 0 && f > INT64_MAX / best) ? INT64_MAX : f * best;
+    }
+    d_est[q] = e;
+  }
+  if (d_status) d_status[q] = st;
+}
+
+// ---------------------------------------------------------------------------------------
+// Plan recovery (Algorithm 1's return value: the b_i and d_i that produce V[S][|B|][D]).
+// One workgroup per problem walks from (s*, N, D) down to level 1.  At each cell it finds the
+// lexicographically smallest (i, d') with max(V[s-1][i][d'], h(i,j,d-d')) equal to the cell's
+// value: the candidate that the ascending scan with strict "<" of Algorithm 1 would have kept.
+// Threads cover 16 split points x 64 device counts per pass, passes ascend in i and stop at the
+// first pass with a match.
+// ---------------------------------------------------------------------------------------
+template <typename VT>
+__device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
+                               unsigned int *best_key) {
+  constexpr VT INF = Lim<VT>::inf;
+  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  const int tid = threadIdx.x;
+  const int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
+  for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
+  if (ns == 0) return;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT *V = (const VT *)pr.V;
+  const VT *cost = (const VT *)pr.cost;
+  int j = N, d = D;
+  const int dp_t = (tid & 63) + 1;  // candidate d' of this thread
+  const int di_t = tid >> 6;        // row offset of this thread within a pass
+  const int rows_per_pass = blockDim.x >> 6;
+  for (int s = ns; s >= 2; --s) {
+    const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
+    const VT *Vp = V + (int64_t)(s - 2) * lvl;
+    const int jj = j - 1;
+    bool found = false;
+    for (int ib = max(s - 1, pr.ilo[j]); ib < j; ib += rows_per_pass) {
+      if (tid == 0) *best_key = 0xFFFFFFFFu;
+      __syncthreads();
+      const int i = ib + di_t;
+      if (i < j && dp_t >= s - 1 && dp_t <= d - 1) {
+        const VT a = Vp[(int64_t)i * DP + dp_t - 1];
+        if (a <= v && v != INF) {
+          const VT h = cost[rows_before(nch, i) * D + (int64_t)(d - dp_t - 1) * row_len(nch, i) +
+                            (jj - 64 * (i >> 6))];
+          if (vmax(a, h) == v) atomicMin(best_key, ((unsigned)i << 8) | (unsigned)dp_t);
+        }
+      }
+      __syncthreads();
+      const unsigned key = *best_key;
+      __syncthreads();
+      if (key != 0xFFFFFFFFu) {
+        const int i_sel = (int)(key >> 8), d_sel = (int)(key & 255u);
+        if (tid == 0) { se[s - 1] = j; rp[s - 1] = d - d_sel; }
+        j = i_sel;
+        d = d_sel;
+        found = true;
+        break;
+      }
+    }
+    if (!found) {  // tables inconsistent: report no plan rather than walk on
+      for (int u = tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
+      return;
+    }
+  }
+  if (tid == 0) { se[0] = j; rp[0] = d; }
+}
+
+__global__ __launch_bounds__(1024) void traceback_kernel(const ProblemDev *__restrict__ probs,
+                                                         int plan_stride, int32_t *d_stage_end,
+                                                         int32_t *d_replicas) {
+  __shared__ unsigned int best_key;
+  const ProblemDev &pr = probs[blockIdx.x];
+  int32_t *se = d_stage_end + (int64_t)blockIdx.x * plan_stride;
+  int32_t *rp = d_replicas + (int64_t)blockIdx.x * plan_stride;
+  if (pr.bits == 32) traceback_body<uint32_t>(pr, plan_stride, se, rp, &best_key);
+  else traceback_body<uint64_t>(pr, plan_stride, se, rp, &best_key);
+}
+
+// ---------------------------------------------------------------------------------------
+// Table export in the layout-independent form of the public header (parity and inspection).
+// ---------------------------------------------------------------------------------------
+template <typename VT>
+__global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restrict__ probs, int q,
+                                                     int which, void *__restrict__ dst) {
+  const ProblemDev &pr = probs[q];
+  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  constexpr VT INF = Lim<VT>::inf;
+  const bool bad = *pr.status != 0;
+  if (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_FIT) {
+    const int64_t total = (int64_t)N * (N + 1) / 2 * D;
+    for (int64_t e = t0; e < total; e += stride) {
+      const int r = (int)(e % D) + 1;
+      const int64_t pair = e / D;  // j(j-1)/2 + i
+      int j = (int)((1.0 + sqrt(1.0 + 8.0 * (double)pair)) * 0.5);
+      while ((int64_t)j * (j - 1) / 2 > pair) --j;
+      while ((int64_t)(j + 1) * j / 2 <= pair) ++j;
+      const int i = (int)(pair - (int64_t)j * (j - 1) / 2);
+      const int jj = j - 1;
+      const int64_t rb = rows_before(nch, i);
+      const int col = jj - 64 * (i >> 6);
+      if (which == RANNC_DP_TABLE_FIT) {
+        ((uint8_t *)dst)[e] = bad ? 0 : (uint8_t)(r >= (int)pr.rmin[rb + col]);
+      } else {
+        const VT v = bad ? INF : ((const VT *)pr.cost)[rb * D + (int64_t)(r - 1) * row_len(nch, i) + col];
+        ((int64_t *)dst)[e] = (v == INF) ? INT64_MAX : (int64_t)v;
+      }
+    }
+  } else if (which == RANNC_DP_TABLE_V) {
+    const int64_t per = (int64_t)(N + 1) * (D + 1);
+    const int64_t total = (int64_t)(pr.S_eff + 1) * per;
+    const int64_t lvl = (int64_t)(N + 1) * DP;
+    for (int64_t e = t0; e < total; e += stride) {
+      const int s = (int)(e / per);
+      const int j = (int)((e % per) / (D + 1));
+      const int d = (int)(e % (D + 1));
+      int64_t v = INT64_MAX;
+      if (s == 0) v = (j == 0 && d == 0) ? 0 : INT64_MAX;
+      else if (d >= 1 && !bad) {
+        const VT u = ((const VT *)pr.V)[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
+        v = (u == INF) ? INT64_MAX : (int64_t)u;
+      }
+      ((int64_t *)dst)[e] = v;
+    }
+  }
+}
+
+// argmin export helpers: whole table to -1, then level 1 (the single stage 1..j on d devices
+// has predecessor (0,0)); levels >= 2 come from level_scan_kernel.
+template <typename VT>
+__global__ __launch_bounds__(256) void arg_init_kernel(const ProblemDev *__restrict__ probs, int q,
+                                                       int32_t *__restrict__ arg_i,
+                                                       int32_t *__restrict__ arg_d) {
+  const ProblemDev &pr = probs[q];
+  const int N = pr.N, D = pr.D, DP = pr.DP;
+  const int64_t per = (int64_t)(N + 1) * (D + 1);
+  const int64_t total = (int64_t)(pr.S_eff + 1) * per;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const bool bad = *pr.status != 0;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += stride) {
+    const int s = (int)(e / per);
+    const int j = (int)((e % per) / (D + 1));
+    const int d = (int)(e % (D + 1));
+    int32_t v = -1;
+    if (s == 1 && j >= 1 && d >= 1 && !bad) {
+      if (((const VT *)pr.V)[(int64_t)j * DP + d - 1] != Lim<VT>::inf) v = 0;
+    }
+    if (arg_i) arg_i[e] = v;
+    if (arg_d) arg_d[e] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------------------
+hipError_t launch_prefix(const ProblemDev *d_probs, int Q, hipStream_t st) {
+  hipLaunchKernelGGL(prefix_kernel, dim3(Q), dim3(256), 0, st, d_probs);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill(const ProblemDev *d_probs, int Q, hipStream_t st) {
+  const int per = Q >= 256 ? 4 : Q >= 16 ? 32 : 256;
+  for (int q0 = 0; q0 < Q; q0 += 65535) {
+    const int nq = min(65535, Q - q0);
+    hipLaunchKernelGGL(fill_kernel, dim3(per, nq), dim3(256), 0, st, d_probs + q0);
+  }
+  return hipGetLastError();
+}
+
+template <typename VT, int DP>
+static void build_go(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, hipStream_t st) {
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    hipLaunchKernelGGL((build_kernel<VT, DP>), dim3(sh.max_nch, sh.max_N, nq), dim3(64), 0, st, p,
+                       l + q0);
+  }
+}
+
+hipError_t launch_build(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int bits,
+                        int DP, hipStream_t st) {
+  if (sh.max_N > 65535) return hipErrorInvalidValue;
+#define GO(B, T)                                                  \
+  if (bits == B) {                                                \
+    if (DP == 8) build_go<T, 8>(p, l, sh, st);                    \
+    else if (DP == 16) build_go<T, 16>(p, l, sh, st);             \
+    else if (DP == 32) build_go<T, 32>(p, l, sh, st);             \
+    else build_go<T, 64>(p, l, sh, st);                           \
+  }
+  GO(32, uint32_t)
+  GO(64, uint64_t)
+#undef GO
+  return hipGetLastError();
+}
+
+template <typename VT, int DP>
+static void merge_go(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int s, int i_steps,
+                     hipStream_t st) {
+  const int nsub = (sh.max_N + i_steps - 1) / i_steps;
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    hipLaunchKernelGGL((level_merge_kernel<VT, DP>), dim3(nsub, sh.max_nch, nq), dim3(64), 0, st, p,
+                       l + q0, s, i_steps);
+  }
+}
+
+hipError_t launch_level_merge(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int bits,
+                              int DP, int s, int i_steps, hipStream_t st) {
+#define GO(B, T)                                                  \
+  if (bits == B) {                                                \
+    if (DP == 8) merge_go<T, 8>(p, l, sh, s, i_steps, st);        \
+    else if (DP == 16) merge_go<T, 16>(p, l, sh, s, i_steps, st); \
+    else if (DP == 32) merge_go<T, 32>(p, l, sh, s, i_steps, st); \
+    else merge_go<T, 64>(p, l, sh, s, i_steps, st);               \
+  }
+  GO(32, uint32_t)
+  GO(64, uint64_t)
+#undef GO
+  return hipGetLastError();
+}
+
+hipError_t launch_level_scan(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int bits,
+                             int s, int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st) {
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    const dim3 grid(sh.max_nch, sh.max_D, nq);
+    if (bits == 32)
+      hipLaunchKernelGGL((level_scan_kernel<uint32_t>), grid, dim3(64), 0, st, p, l + q0, s, write_v,
+                         arg_i, arg_d);
+    else
+      hipLaunchKernelGGL((level_scan_kernel<uint64_t>), grid, dim3(64), 0, st, p, l + q0, s, write_v,
+                         arg_i, arg_d);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const ProblemDev *p, int Q, int64_t *d_opt, int32_t *d_n_stages,
+                         int64_t *d_est, int32_t *d_status, hipStream_t st) {
+  hipLaunchKernelGGL(select_kernel, dim3((Q + 127) / 128), dim3(128), 0, st, p, Q, d_opt, d_n_stages,
+                     d_est, d_status);
+  return hipGetLastError();
+}
+
+hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t *d_stage_end,
+                            int32_t *d_replicas, hipStream_t st) {
+  hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(1024), 0, st, p, plan_stride, d_stage_end,
+                     d_replicas);
+  return hipGetLastError();
+}
+
+hipError_t launch_export(const ProblemDev *p, int q, int which, const ProblemDev &hc, void *d_dst,
+                         hipStream_t st) {
+  const dim3 grid(1024), block(256);
+  if (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_FIT || which == RANNC_DP_TABLE_V) {
+    if (hc.bits == 32) hipLaunchKernelGGL((export_kernel<uint32_t>), grid, block, 0, st, p, q, which, d_dst);
+    else hipLaunchKernelGGL((export_kernel<uint64_t>), grid, block, 0, st, p, q, which, d_dst);
+  } else {
+    int32_t *ai = which == RANNC_DP_TABLE_ARG_I ? (int32_t *)d_dst : nullptr;
+    int32_t *ad = which == RANNC_DP_TABLE_ARG_D ? (int32_t *)d_dst : nullptr;
+    if (hc.bits == 32) hipLaunchKernelGGL((arg_init_kernel<uint32_t>), grid, block, 0, st, p, q, ai, ad);
+    else hipLaunchKernelGGL((arg_init_kernel<uint64_t>), grid, block, 0, st, p, q, ai, ad);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace rannc

@@ -1,0 +1,167 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Everything is integer, so every comparison is bit-exact."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2103_16063_amd import binding as B
+from paper_2103_16063_amd import synth
+from tests import defcheck
+from tests.gpu_util import INF, assert_results_match, assert_tables_match, gpu_run
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = [B.ALGO_MERGE, B.ALGO_SCAN]
+WIDTHS = [B.NARROW_MAX_TOTAL_TIME, 1 << 50]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("width", WIDTHS)
+@pytest.mark.parametrize("k", [1, 2, 3])
+def test_configs_1_to_3_tables_and_plan(k, algo, width):
+    pr = synth.named_config(k)
+    res, sess = gpu_run([pr], algo=algo, max_total_time_ns=width)
+    with sess:
+        assert_results_match([pr], res)
+        assert_tables_match(pr, sess, 0)
+
+
+def test_config4_full_size():
+    """N=1024, D=64, S<=32 in the launch configuration the benchmark times: optimum, plan and
+    the whole value table against the oracle (a few seconds of CPU with all cores)."""
+    pr = synth.named_config(4)
+    res, sess = gpu_run([pr])
+    with sess:
+        assert_results_match([pr], res)
+        o = assert_tables_match(pr, sess, 0, args=False)
+        t, p, a = pr["time_ns"], pr["param_bytes"], pr["act_bytes"]
+        defcheck.check_plan(t, p, a, 64, 32, pr["mem_capacity"], int(res["opt"][0]),
+                            int(res["n_stages"][0]), res["stage_end"][0], res["replicas"][0])
+        assert o["opt"] == 5541252 and o["n_stages"] == 12
+
+
+SHAPES = [  # (N, D, S): edge shapes, ragged tails, several 64-column chunks, non-power-of-two D
+    (1, 1, 1), (1, 7, 3), (9, 1, 4), (3, 3, 9), (2, 64, 2), (5, 2, 5),
+    (16, 4, 4), (33, 5, 5), (63, 8, 8), (64, 9, 6), (65, 12, 7), (100, 17, 9),
+    (129, 24, 6), (130, 33, 5), (200, 40, 4), (70, 63, 10), (96, 64, 12),
+]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("width", WIDTHS)
+def test_shape_sweep_single(algo, width):
+    for n, (N, D, S) in enumerate(SHAPES):
+        for tight in (1.05, 1.6, 40.0):
+            pr = synth.random_small(900 + n, N, D, S, tight=tight, tmax=5000)
+            if width > B.NARROW_MAX_TOTAL_TIME:
+                pr["time_ns"] = pr["time_ns"] * (1 << 24)  # totals beyond 32 bits
+            res, sess = gpu_run([pr], algo=algo, max_total_time_ns=width)
+            with sess:
+                assert_results_match([pr], res)
+                assert_tables_match(pr, sess, 0, args=(N <= 100))
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_ties_and_zero_times(algo):
+    """Constant and zero block times: many equal candidates per cell, so the smallest-(i,d')
+    rule and the smallest-s rule decide the plan."""
+    for seed in range(6):
+        N, D, S = 40, 9, 6
+        pr = synth.random_small(300 + seed, N, D, S, tight=[1.2, 2.0, 50.0][seed % 3], tmax=3,
+                                zero_time_frac=0.3)
+        if seed >= 3:
+            pr["time_ns"] = np.full(N, seed - 3, dtype=np.int64)  # includes all-zero times
+        res, sess = gpu_run([pr], algo=algo)
+        with sess:
+            assert_results_match([pr], res)
+            assert_tables_match(pr, sess, 0)
+
+
+def test_infeasible_and_oversized_block():
+    pr = synth.random_small(1, 30, 6, 5, tight=5.0)
+    pr["param_bytes"] = pr["param_bytes"].copy()
+    pr["param_bytes"][11] = pr["mem_capacity"] + 1
+    pr2 = synth.random_small(2, 20, 4, 4, tight=0.3)  # capacity far too small
+    res, sess = gpu_run([pr, pr2])
+    with sess:
+        assert (res["opt"] == INF).all() and (res["n_stages"] == 0).all()
+        assert (res["stage_end"] == -1).all() and (res["replicas"] == -1).all()
+        assert (res["est_iter_ns"] == INF).all()
+        assert_results_match([pr, pr2], res)
+        assert_tables_match(pr, sess, 0)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_batched_mixed_shapes(algo):
+    """One launch sequence over problems of different N, D, S, MB and capacity: each equals
+    its oracle solve and its own single-problem GPU solve, byte for byte."""
+    g = np.random.default_rng(7)
+    probs = []
+    for q in range(40):
+        N = int(g.integers(1, 150))
+        D = int(g.choice([1, 2, 3, 5, 8, 9, 16, 17, 31, 32, 33, 48, 64]))
+        S = int(g.integers(1, 12))
+        probs.append(synth.random_small(2000 + q, N, D, S, tight=float(g.choice([0.9, 1.3, 2.0, 30.0])),
+                                        tmax=int(g.choice([3, 100, 100000]))))
+    res, sess = gpu_run(probs, algo=algo)
+    with sess:
+        assert_results_match(probs, res)
+        for q in (0, 7, 19, 39):
+            assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
+    for q in (3, 11, 25):
+        r1, s1 = gpu_run([probs[q]], algo=algo)
+        with s1:
+            for key in ("opt", "n_stages", "est_iter_ns"):
+                assert r1[key][0] == res[key][q]
+            k = r1["stage_end"].shape[1]
+            assert np.array_equal(r1["stage_end"][0], res["stage_end"][q][:k])
+            assert np.array_equal(r1["replicas"][0], res["replicas"][q][:k])
+
+
+def test_config5_batched_sweep_full_size():
+    """All 2048 searches in one batch.  The oracle checks a sample one by one; every plan is
+    checked from the definition (fits, covers the chain, replicas sum to D, attains opt), and
+    opt respects the lower bound ceil(T_total / D)."""
+    probs = synth.named_config(5)
+    res, sess = gpu_run(probs)
+    with sess:
+        assert (res["status"] == 0).all()
+        sample = list(range(0, 2048, 43)) + [1, 2, 3, 2047]
+        assert_results_match([probs[q] for q in sample],
+                             {k: v[sample] for k, v in res.items()})
+        for q in (0, 1000):
+            assert_tables_match(probs[q], sess, q, args=False)
+        for q, pr in enumerate(probs):
+            D = pr["n_devices"]
+            opt, ns = int(res["opt"][q]), int(res["n_stages"][q])
+            defcheck.check_plan(pr["time_ns"], pr["param_bytes"], pr["act_bytes"], D, 16,
+                                pr["mem_capacity"], opt, ns, res["stage_end"][q], res["replicas"][q])
+            if opt != INF:
+                assert opt >= defcheck.cdiv(int(pr["time_ns"].sum()), D)
+                assert int(res["est_iter_ns"][q]) == (pr["n_microbatches"] + ns - 1) * opt
+        assert (res["opt"] != INF).sum() > 1500
+
+
+def test_deterministic_across_runs():
+    probs = synth.batched_sweep(Q=64)
+    res1, s1 = gpu_run(probs)
+    with s1:
+        V1 = s1.table(B.TABLE_V, 5)
+        s1.solve()
+        s1.traceback()
+        res2 = s1.run()
+        V2 = s1.table(B.TABLE_V, 5)
+    for k in res1:
+        assert np.array_equal(res1[k], res2[k]), k
+    assert np.array_equal(V1, V2)
+
+
+def test_merge_and_scan_levels_agree_at_medium_size():
+    pr = synth.enlarged_transformer_chain(seed=11, N=300, D=48, S=20, M=24 * synth.GiB)
+    rm, sm = gpu_run([pr], algo=B.ALGO_MERGE)
+    rs, ss = gpu_run([pr], algo=B.ALGO_SCAN)
+    with sm, ss:
+        assert np.array_equal(sm.table(B.TABLE_V, 0), ss.table(B.TABLE_V, 0))
+        for k in rm:
+            assert np.array_equal(rm[k], rs[k]), k
+        assert_results_match([pr], rm)
