@@ -6,6 +6,7 @@
 #include "rannc_dp_internal.h"
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -22,8 +23,8 @@ constexpr int kStagingSlots = 2;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Sizes {  // bytes of one problem's regions inside the workspace
-  size_t prefix, ilo, misc, rmin, cost, V;
-  size_t total() const { return prefix * 3 + ilo + misc + rmin + cost + V; }
+  size_t prefix, wlo, runs, misc, rmin, cost, V;
+  size_t total() const { return prefix * 3 + wlo + runs + misc + rmin + cost + V; }
 };
 
 // false on arithmetic overflow
@@ -31,12 +32,13 @@ bool problem_sizes(int N, int D, int S_eff, int bits, Sizes *o) {
   const int nch = (N + 63) / 64;
   const int DP = rannc::dp_class(D);
   const size_t esz = bits / 8;
-  const unsigned __int128 rows = (unsigned __int128)rannc::rows_before(nch, N);
+  const unsigned __int128 rows = (unsigned __int128)rannc::units_before(nch, N) * 64;
   const unsigned __int128 cost = rows * (unsigned)D * esz;
   const unsigned __int128 V = (unsigned __int128)S_eff * (unsigned)(N + 1) * (unsigned)DP * esz;
   if (cost > ((unsigned __int128)1 << 46) || V > ((unsigned __int128)1 << 46)) return false;
   o->prefix = align_up((size_t)(N + 1) * 8);
-  o->ilo = align_up((size_t)(N + 1) * 4);
+  o->wlo = align_up((size_t)nch * 4);
+  o->runs = align_up((size_t)(rannc::max_runs(nch) + 1) * 4);
   o->misc = align_up(64);  // status word, result pair
   o->rmin = align_up((size_t)rows);
   o->cost = align_up((size_t)cost);
@@ -53,9 +55,7 @@ bool limits_ok(const rannc_dp_limits_t *l) {
 
 int bits_of(const rannc_dp_limits_t *l) { return l->max_total_time_ns <= kNarrowMax ? 32 : 64; }
 
-size_t header_bytes(int Q) {
-  return align_up((size_t)Q * sizeof(ProblemDev)) + align_up((size_t)Q * 2 * sizeof(int32_t));
-}
+size_t header_bytes(int Q) { return align_up((size_t)Q * sizeof(ProblemDev)); }
 
 // Host-side validation of the batch descriptors against the limits.
 int check_batch(const rannc_dp_limits_t *l, const rannc_dp_batch_t *b) {
@@ -94,14 +94,15 @@ struct rannc_dp {
   // state of the last successful solve
   bool solved;
   int Q;
-  std::vector<ProblemDev> host_probs;
+  std::vector<ProblemDev> host_probs;  // in device order: grouped by DP class
+  std::vector<int32_t> pos_of;         // position of the caller's problem q in that order
   ProblemDev *d_probs;
-  int32_t *d_lists;  // [0,Q): identity, [Q,2Q): problems grouped by DP class
   // timing
   bool timing;
   hipEvent_t ev[4];
   bool ev_valid;
   int level_launches;
+  int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
 };
 
 extern "C" {
@@ -163,8 +164,9 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->timing = false;
   h->ev_valid = false;
   h->level_launches = 0;
+  h->tune_spw = 0;
+  if (const char *e = std::getenv("RANNC_DP_ROWS_PER_WAVE")) h->tune_spw = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
-  h->d_lists = (int32_t *)(h->ws + align_up((size_t)l->max_problems * sizeof(ProblemDev)));
   int made_staging = 0, made_ev_s = 0, made_ev = 0;
   bool ok = true;
   for (int k = 0; k < kStagingSlots && ok; ++k) {
@@ -228,13 +230,32 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   hipStream_t st = (hipStream_t)hip_stream;
   const int Q = b->n_problems;
 
-  // ---- workspace layout -------------------------------------------------------------
+  // ---- device order: problems grouped by the padded device dimension their kernels are
+  //      specialised for, so that one launch covers a contiguous slice of descriptors --------
+  static const int kClasses[4] = {8, 16, 32, 64};
   std::vector<ProblemDev> probs;
+  std::vector<int32_t> pos_of;
   try {
     probs.resize(Q);
+    pos_of.resize(Q);
   } catch (...) {
     return RANNC_DP_NO_HOST_MEMORY;
   }
+  int cls_start[5] = {0, 0, 0, 0, 0};
+  for (int q = 0; q < Q; ++q)
+    for (int k = 0; k < 4; ++k)
+      if (rannc::dp_class(b->n_devices[q]) == kClasses[k]) ++cls_start[k + 1];
+  for (int k = 0; k < 4; ++k) cls_start[k + 1] += cls_start[k];
+  {
+    int next[4] = {cls_start[0], cls_start[1], cls_start[2], cls_start[3]};
+    for (int q = 0; q < Q; ++q)
+      for (int k = 0; k < 4; ++k)
+        if (rannc::dp_class(b->n_devices[q]) == kClasses[k]) pos_of[q] = next[k]++;
+  }
+
+  // ---- workspace layout -------------------------------------------------------------
+  LaunchShape shape[4];
+  std::memset(shape, 0, sizeof(shape));
   size_t off = header_bytes(h->lim.max_problems);
   for (int q = 0; q < Q; ++q) {
     const int N = b->n_blocks[q], D = b->n_devices[q];
@@ -242,12 +263,13 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     Sizes sz;
     if (!problem_sizes(N, D, S_eff, h->bits, &sz)) return RANNC_DP_OVERFLOW;
     if (off + sz.total() > h->ws_bytes) return RANNC_DP_WORKSPACE_TOO_SMALL;
-    ProblemDev &p = probs[q];
+    ProblemDev &p = probs[pos_of[q]];
     std::memset(&p, 0, sizeof(p));
     p.N = N; p.D = D; p.S_eff = S_eff; p.MB = b->n_microbatches[q];
     p.DP = rannc::dp_class(D);
     p.nch = (N + 63) / 64;
     p.bits = h->bits;
+    p.q = q;
     p.M = b->mem_capacity[q];
     p.time_limit = h->lim.max_total_time_ns;
     p.t = b->time_ns + b->block_offset[q];
@@ -257,40 +279,23 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     p.T = (int64_t *)base; base += sz.prefix;
     p.P = (int64_t *)base; base += sz.prefix;
     p.A = (int64_t *)base; base += sz.prefix;
-    p.ilo = (int32_t *)base; base += sz.ilo;
+    p.wlo = (int32_t *)base; base += sz.wlo;
+    p.runs = (int32_t *)base; base += sz.runs;
     p.status = (int32_t *)base;
     p.res = (int64_t *)(base + 16); base += sz.misc;
     p.rmin = (uint8_t *)base; base += sz.rmin;
     p.cost = base; base += sz.cost;
     p.V = base; base += sz.V;
     off += sz.total();
-  }
-
-  // problems grouped by the padded device dimension their kernels are specialised for
-  static const int kClasses[4] = {8, 16, 32, 64};
-  int cls_start[5] = {0, 0, 0, 0, 0};
-  LaunchShape shape[4];
-  std::memset(shape, 0, sizeof(shape));
-  std::vector<int32_t> lists(2 * (size_t)Q);
-  for (int q = 0; q < Q; ++q) {
-    lists[q] = q;
     for (int k = 0; k < 4; ++k)
-      if (probs[q].DP == kClasses[k]) ++cls_start[k + 1];
-  }
-  for (int k = 0; k < 4; ++k) cls_start[k + 1] += cls_start[k];
-  {
-    int fill[4] = {cls_start[0], cls_start[1], cls_start[2], cls_start[3]};
-    for (int q = 0; q < Q; ++q)
-      for (int k = 0; k < 4; ++k)
-        if (probs[q].DP == kClasses[k]) {
-          lists[Q + fill[k]++] = q;
-          LaunchShape &sh = shape[k];
-          sh.nprob++;
-          sh.max_N = std::max(sh.max_N, probs[q].N);
-          sh.max_nch = std::max(sh.max_nch, probs[q].nch);
-          sh.max_D = std::max(sh.max_D, probs[q].D);
-          sh.max_S_eff = std::max(sh.max_S_eff, probs[q].S_eff);
-        }
+      if (p.DP == kClasses[k]) {
+        LaunchShape &sh = shape[k];
+        sh.nprob++;
+        sh.max_N = std::max(sh.max_N, p.N);
+        sh.max_nch = std::max(sh.max_nch, p.nch);
+        sh.max_D = std::max(sh.max_D, p.D);
+        sh.max_S_eff = std::max(sh.max_S_eff, p.S_eff);
+      }
   }
 
   // ---- descriptors to the device ---------------------------------------------------
@@ -299,13 +304,9 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   if (h->staging_used[slot] && hipEventSynchronize(h->staging_free[slot]) != hipSuccess)
     return RANNC_DP_HIP_ERROR;
   const size_t probs_bytes = (size_t)Q * sizeof(ProblemDev);
-  const size_t lists_off = align_up((size_t)h->lim.max_problems * sizeof(ProblemDev));
   std::memcpy(h->staging[slot], probs.data(), probs_bytes);
-  std::memcpy(h->staging[slot] + lists_off, lists.data(), lists.size() * sizeof(int32_t));
   h->solved = false;
   if (hipMemcpyAsync(h->ws, h->staging[slot], probs_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
-      hipMemcpyAsync(h->ws + lists_off, h->staging[slot] + lists_off, lists.size() * sizeof(int32_t),
-                     hipMemcpyHostToDevice, st) != hipSuccess ||
       hipEventRecord(h->staging_free[slot], st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
@@ -314,7 +315,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
 
   // ---- kernels ---------------------------------------------------------------------------
   const ProblemDev *dp = h->d_probs;
-  const int32_t *dl = h->d_lists + Q;  // [0,Q) is the identity list, [Q,2Q) the class-grouped one
+  const bool scan = h->lim.algo == RANNC_DP_ALGO_SCAN;
   bool ok = true;
   const bool timing = h->timing;
   h->ev_valid = false;
@@ -322,32 +323,36 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   if (timing) ok = ok && hipEventRecord(h->ev[0], st) == hipSuccess;
   ok = ok && rannc::launch_prefix(dp, Q, st) == hipSuccess;
   ok = ok && rannc::launch_fill(dp, Q, st) == hipSuccess;
-  for (int k = 0; k < 4 && ok; ++k)
-    if (shape[k].nprob)
-      ok = rannc::launch_build(dp, dl + cls_start[k], shape[k], h->bits, kClasses[k], st) == hipSuccess;
+  int spw[4] = {1, 1, 1, 1};
+  for (int k = 0; k < 4 && ok; ++k) {
+    const LaunchShape &sh = shape[k];
+    if (!sh.nprob) continue;
+    ok = rannc::launch_build(dp + cls_start[k], sh, h->bits, kClasses[k], st) == hipSuccess;
+    if (scan) continue;
+    // predecessor rows per wave of a work item: few, so that a launch has enough waves in
+    // flight to hide the latency of the row reads; more for big batches, where fewer partial
+    // results then have to be combined with atomics
+    int64_t units = 0;  // (row, 64-column chunk) pairs of a dense level
+    for (int c = 0; c < sh.max_nch; ++c) units += std::min(64 * c + 64, sh.max_N);
+    units *= sh.nprob;
+    spw[k] = units <= 16384 ? 1 : units <= 65536 ? 2 : 4;
+    if (h->tune_spw > 0) spw[k] = h->tune_spw;
+    ok = ok && rannc::launch_windows(dp + cls_start[k], sh.nprob, rannc::merge_rows_per_item(spw[k]),
+                                     st) == hipSuccess;
+  }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
-  const bool scan = h->lim.algo == RANNC_DP_ALGO_SCAN;
   int max_levels = 0;
   for (int k = 0; k < 4; ++k) max_levels = std::max(max_levels, shape[k].max_S_eff);
   for (int s = 2; s <= max_levels && ok; ++s) {
     for (int k = 0; k < 4 && ok; ++k) {
       const LaunchShape &sh = shape[k];
       if (!sh.nprob || sh.max_S_eff < s) continue;
-      if (scan) {
-        ok = rannc::launch_level_scan(dp, dl + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
+      if (scan)
+        ok = rannc::launch_level_scan(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;
-      } else {
-        // rows of predecessors per work item: as long as possible while the launch still has
-        // several waves per SIMD (1024 SIMDs on the device)
-        int steps = 32;
-        while (steps > 4) {
-          const int64_t items = (int64_t)sh.nprob * sh.max_nch * ((sh.max_N + steps - 1) / steps) / 2;
-          if (items >= 4096) break;
-          steps >>= 1;
-        }
-        ok = rannc::launch_level_merge(dp, dl + cls_start[k], sh, h->bits, kClasses[k], s, steps, st) ==
+      else
+        ok = rannc::launch_level_merge(dp + cls_start[k], sh, h->bits, kClasses[k], s, spw[k], st) ==
              hipSuccess;
-      }
       h->level_launches++;
     }
   }
@@ -360,6 +365,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   }
   h->ev_valid = timing;
   h->host_probs.swap(probs);
+  h->pos_of.swap(pos_of);
   h->Q = Q;
   h->solved = true;
   return RANNC_DP_OK;
@@ -384,7 +390,8 @@ int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, 
   if (!h || !d_dst) return RANNC_DP_INVALID_ARG;
   if (!h->solved) return RANNC_DP_BAD_STATE;
   if (problem < 0 || problem >= h->Q) return RANNC_DP_INVALID_ARG;
-  const ProblemDev &p = h->host_probs[problem];
+  const int pos = h->pos_of[problem];
+  const ProblemDev &p = h->host_probs[pos];
   const size_t tri = (size_t)p.N * (size_t)(p.N + 1) / 2 * (size_t)p.D;
   const size_t cells = (size_t)(p.S_eff + 1) * (size_t)(p.N + 1) * (size_t)(p.D + 1);
   size_t want = 0;
@@ -398,15 +405,14 @@ int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, 
   }
   if (bytes != want) return RANNC_DP_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
-  bool ok = rannc::launch_export(h->d_probs, problem, which, p, d_dst, st) == hipSuccess;
+  bool ok = rannc::launch_export(h->d_probs + pos, which, p.bits, d_dst, st) == hipSuccess;
   if (which == RANNC_DP_TABLE_ARG_I || which == RANNC_DP_TABLE_ARG_D) {
     LaunchShape sh;
     sh.nprob = 1; sh.max_N = p.N; sh.max_nch = p.nch; sh.max_D = p.D; sh.max_S_eff = p.S_eff;
     int32_t *ai = which == RANNC_DP_TABLE_ARG_I ? (int32_t *)d_dst : nullptr;
     int32_t *ad = which == RANNC_DP_TABLE_ARG_D ? (int32_t *)d_dst : nullptr;
     for (int s = 2; s <= p.S_eff && ok; ++s)
-      ok = rannc::launch_level_scan(h->d_probs, h->d_lists + problem, sh, p.bits, s, 0, ai, ad, st) ==
-           hipSuccess;
+      ok = rannc::launch_level_scan(h->d_probs + pos, sh, p.bits, s, 0, ai, ad, st) == hipSuccess;
   }
   if (!ok) {
     (void)hipGetLastError();

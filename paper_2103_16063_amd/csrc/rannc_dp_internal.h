@@ -12,33 +12,34 @@ namespace rannc {
 //
 // Indices follow the recurrence of Sec. III-C: a stage holds blocks i+1..j (0 <= i < j <= N)
 // and runs on r = d - d' replicas.  The level kernel keeps one output column j per lane, so
-// every table that is indexed by j is stored with j fastest: a wavefront then reads 64
-// consecutive columns of one (i, r) row with one coalesced 256-byte (32-bit values) or
-// 512-byte (64-bit values) request.
+// the stage-time table is cut into UNITS: unit (i, c) holds predecessor row i for the 64
+// columns jj = j-1 in [64c, 64c+63], all D replica counts, as a contiguous block
 //
-// Columns are addressed by jj = j-1 and grouped in chunks of 64.  The row of predecessor i
-// covers the chunks that can hold a j > i, i.e. chunks g(i) = i/64 .. nch-1, so each row
-// starts on a chunk boundary (rows stay 256-byte aligned) and has
-//     row_len(i) = 64 * (nch - i/64)         entries (nch = ceil(N/64)).
-// Entries with jj < i or jj >= N are padding: never written, never read.
+//     cost[(unit(i,c) * D + (r-1)) * 64 + (jj - 64c)]         stage time h(i,j,r), INF if r < rmin
+//     rmin[ unit(i,c) * 64      + (jj - 64c)]                 uint8: smallest r whose stage fits
+//                                                             memory (the m <= M rule), 255 = none
 //
-//   rmin[rows_before(i) + (jj - 64*(i/64))]                uint8: smallest r whose stage fits
-//                                                          memory (the m <= M rule), 255 = none
-//   cost[rows_before(i)*D + (r-1)*row_len(i) + (jj - 64*(i/64))]
-//                                                          stage time h(i,j,r); INF if r < rmin
-//   V[(s-1)*(N+1)*DP + j*DP + (d-1)]                       level s >= 1, DP = 8/16/32/64 >= D;
-//                                                          entries with d > D hold 0
+// so that one wavefront reads a unit with D coalesced 256-byte (32-bit values) or 512-byte
+// (64-bit) requests out of one contiguous 16 KiB / 32 KiB region.  Row i has units for the
+// chunks that can hold a j > i, c = i/64 .. nch-1 (nch = ceil(N/64)); units are numbered row by
+// row.  Lanes with jj < i or jj >= N are padding: never written, never read.
+//
+//     V[(s-1)*(N+1)*DP + j*DP + (d-1)]     level s >= 1, DP = 8/16/32/64 >= D; entries d > D hold 0
 //
 // The d-fastest layout of V makes the row V[s-1][i][.] one contiguous, wave-uniform read.
 // ---------------------------------------------------------------------------------------
 
-__host__ __device__ inline int64_t row_len(int nch, int i) { return 64LL * (nch - (i >> 6)); }
-
-// sum of row_len(i') over i' < i
-__host__ __device__ inline int64_t rows_before(int nch, int i) {
+// number of units in rows i' < i
+__host__ __device__ inline int64_t units_before(int nch, int i) {
   const int64_t g = i >> 6;
-  return 4096LL * (g * nch - g * (g - 1) / 2) + (int64_t)(i - 64 * g) * 64LL * (nch - g);
+  return 64LL * (g * nch - g * (g - 1) / 2) + (int64_t)(i - 64 * g) * (nch - g);
 }
+__host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
+  return units_before(nch, i) + (c - (i >> 6));
+}
+// upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
+// groups of at least 4
+__host__ __device__ inline int64_t max_runs(int nch) { return 8LL * nch * (nch + 1); }
 
 __host__ __device__ inline int dp_class(int D) { return D <= 8 ? 8 : D <= 16 ? 16 : D <= 32 ? 32 : 64; }
 
@@ -47,7 +48,7 @@ struct ProblemDev {
   int32_t DP;   // padded device dimension of a V row
   int32_t nch;  // 64-wide column chunks
   int32_t bits; // 32 or 64: width of the values in cost and V
-  int32_t pad_;
+  int32_t q;    // index of the problem in the caller's batch (outputs go there)
   int64_t M;
   int64_t time_limit;          // limits.max_total_time_ns
   const int64_t *t, *p, *a;    // caller's inputs (DEVICE), N entries each
@@ -55,13 +56,15 @@ struct ProblemDev {
   uint8_t *rmin;
   void *cost;
   void *V;
-  int32_t *ilo;                // [N+1], by j: smallest i whose stage (i,j) fits for some r <= D; j if none
+  int32_t *wlo;                // [nch] smallest row i with a stage (i, j in chunk) that fits for some
+                               // r <= D; 0x7fffffff if none
+  int32_t *runs;               // runs[0] = count, then (c << 16 | first row) per work item
   int32_t *status;             // RANNC_DP_PROBLEM_*
   int64_t *res;                // res[0] = opt (int64, INT64_MAX if none), res[1] = n_stages
 };
 
 struct LaunchShape {
-  int nprob;     // problems in the launch (blockIdx.z runs over list[0..nprob))
+  int nprob;     // problems in the launch (blockIdx.z runs over them)
   int max_N;     // largest N among them
   int max_nch;   // largest nch among them
   int max_D;
@@ -69,21 +72,21 @@ struct LaunchShape {
 };
 
 // Kernel launchers (rannc_dp_kernels.hip).  All enqueue on `st` and return the launch status.
-hipError_t launch_prefix(const ProblemDev *d_probs, int Q, hipStream_t st);
-hipError_t launch_fill(const ProblemDev *d_probs, int Q, hipStream_t st);
-hipError_t launch_build(const ProblemDev *d_probs, const int32_t *d_list, const LaunchShape &sh,
-                        int bits, int DP, hipStream_t st);
-hipError_t launch_level_merge(const ProblemDev *d_probs, const int32_t *d_list,
-                              const LaunchShape &sh, int bits, int DP, int s, int i_steps,
-                              hipStream_t st);
-hipError_t launch_level_scan(const ProblemDev *d_probs, const int32_t *d_list,
-                             const LaunchShape &sh, int bits, int s, int write_v, int32_t *arg_i,
-                             int32_t *arg_d, hipStream_t st);
-hipError_t launch_select(const ProblemDev *d_probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
+// `probs` points at the first ProblemDev of the launch; problems of one launch are contiguous.
+hipError_t launch_prefix(const ProblemDev *probs, int Q, hipStream_t st);
+hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st);
+hipError_t launch_build(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, hipStream_t st);
+hipError_t launch_windows(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st);
+hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
+                              int rows_per_wave, hipStream_t st);
+hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int bits, int s,
+                             int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st);
+hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
-hipError_t launch_traceback(const ProblemDev *d_probs, int Q, int plan_stride, int32_t *d_stage_end,
+hipError_t launch_traceback(const ProblemDev *probs, int Q, int plan_stride, int32_t *d_stage_end,
                             int32_t *d_replicas, hipStream_t st);
-hipError_t launch_export(const ProblemDev *d_probs, int q, int which, const ProblemDev &host_copy,
-                         void *d_dst, hipStream_t st);
+hipError_t launch_export(const ProblemDev *prob, int which, int bits, void *d_dst, hipStream_t st);
+
+int merge_rows_per_item(int rows_per_wave);
 
 }  // namespace rannc

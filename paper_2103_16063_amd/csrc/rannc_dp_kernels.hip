@@ -3,6 +3,10 @@
 // One wavefront is 64 lanes; in every kernel that touches the stage-time table a lane owns one
 // output column j (blocks 1..j covered), so table rows are read with coalesced requests and no
 // value ever has to cross lanes.  All arithmetic is exact unsigned integer arithmetic.
+//
+// A problem whose inputs failed validation (status word != 0) still runs through the table and
+// level kernels: every access stays inside the problem's own regions, and its values are never
+// reported (the final selection, the plan recovery and the exports check the status word).
 #include "rannc_dp_internal.h"
 
 #include "../../include/rannc_dp.h"
@@ -17,6 +21,7 @@ template <typename VT> __device__ __forceinline__ VT vmax(VT a, VT b) { return a
 template <typename VT> __device__ __forceinline__ VT vmin(VT a, VT b) { return a < b ? a : b; }
 
 static constexpr uint64_t kSumLimit = 1ull << 62;
+static constexpr int kNoRow = 0x7fffffff;
 
 // ---------------------------------------------------------------------------------------
 // Prefix sums T, P, A of the block inputs (the sums over a stage's members that stand in
@@ -80,7 +85,7 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
 
 // ---------------------------------------------------------------------------------------
 // Initial state: every V entry "no plan" (padding columns d > D hold 0 so that padded rows stay
-// sorted), ilo[j] = j ("no predecessor fits").
+// sorted), no chunk has a fitting predecessor row yet.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict__ probs) {
   const ProblemDev pr = probs[blockIdx.y];
@@ -96,28 +101,27 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
     for (int64_t e = t0; e < total; e += stride)
       V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint64_t>::inf : 0ull;
   }
-  for (int64_t j = t0; j <= pr.N; j += stride) pr.ilo[j] = (int32_t)j;
+  for (int64_t c = t0; c < pr.nch; c += stride) pr.wlo[c] = kNoRow;
 }
 
 // ---------------------------------------------------------------------------------------
 // Stage-time and fits-in-memory tables: h(i,j,r) and the m(i,j,r) <= M rule of Sec. III-C for
-// every stage (i,j) and replica count r.  Block = (row i, 64-column chunk c); a lane owns one j
-// and writes its D entries, each store instruction covering 64 consecutive columns.
-// Memory is non-increasing in r, so the fit rule is stored as the smallest fitting r and folded
-// into the time table as INF below it.  Row i = 0 is also level 1 of the DP (one stage on d
-// devices), written here.
+// every stage (i,j) and replica count r.  One wave per unit (row i, 64-column chunk c); a lane
+// owns one j and writes its D entries, each store instruction covering 64 consecutive columns
+// of one contiguous unit.  Memory is non-increasing in r, so the fit rule is stored as the
+// smallest fitting r and folded into the time table as INF below it.  Row i = 0 is also level 1
+// of the DP (one stage on d devices), written here.
 // ---------------------------------------------------------------------------------------
 template <typename VT, int DP>
-__global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict__ probs,
-                                                   const int32_t *__restrict__ list) {
-  const ProblemDev &pr = probs[list[blockIdx.z]];
-  if (*pr.status != 0) return;
+__global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict__ probs) {
+  const ProblemDev &pr = probs[blockIdx.z];
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int i = blockIdx.y, c = blockIdx.x;
   if (i >= N || c >= nch || c < (i >> 6)) return;
-  const int jj = 64 * c + (int)threadIdx.x;
-  if (jj < i || jj >= N) return;
-  const int j = jj + 1;
+  const int lane = threadIdx.x;
+  const int jj = 64 * c + lane;
+  const bool valid = (jj >= i) && (jj < N);
+  const int j = valid ? jj + 1 : i + 1;  // padding lanes compute a harmless in-range stage
   const int64_t Tij = pr.T[j] - pr.T[i];
   const int64_t Pij = pr.P[j] - pr.P[i];
   const int64_t Aij = pr.A[j] - pr.A[i];
@@ -131,12 +135,12 @@ __global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict_
       if (need <= (uint64_t)D) rmin = (int)need;
     }
   }
-  const int64_t rb = rows_before(nch, i);
-  const int col = jj - 64 * (i >> 6);
-  pr.rmin[rb + col] = (uint8_t)rmin;
-  if (rmin <= D) atomicMin(&pr.ilo[j], i);
-  const int64_t L = row_len(nch, i);
-  VT *crow = (VT *)pr.cost + rb * D + col;
+  const bool fits = valid && rmin <= D;
+  if (__ballot(fits) != 0ull && lane == 0) atomicMin(&pr.wlo[c], i);
+  if (!valid) return;
+  const int64_t u = unit_index(nch, i, c);
+  pr.rmin[u * 64 + lane] = (uint8_t)rmin;
+  VT *crow = (VT *)pr.cost + u * 64 * D + lane;
   VT *v1 = (VT *)pr.V + (int64_t)j * DP;
   const VT tij = (VT)Tij;
 #pragma unroll
@@ -145,8 +149,34 @@ __global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict_
     const VT q = tij / (VT)r;                   // r is a compile-time constant after unrolling
     const VT h = q + (VT)(q * (VT)r != tij);    // ceil
     const VT v = (r >= rmin) ? h : Lim<VT>::inf;
-    crow[(int64_t)(r - 1) * L] = v;
+    crow[(r - 1) * 64] = v;
     if (i == 0) v1[r - 1] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Work list of the level kernels.  For chunk c only rows wlo[c] .. min(64c+63, N-1) can hold a
+// stage that fits; they are cut into items of `rows` consecutive rows, listed chunk by chunk.
+// One workgroup per problem.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restrict__ probs, int rows) {
+  const ProblemDev &pr = probs[blockIdx.x];
+  __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
+  const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
+  for (int c = tid; c < nch; c += 256) {
+    const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
+    start[c + 1] = lo <= hi ? (hi - lo + rows) / rows : 0;  // items of chunk c
+  }
+  __syncthreads();
+  if (tid == 0) {
+    start[0] = 0;
+    for (int c = 0; c < nch; ++c) start[c + 1] += start[c];
+    pr.runs[0] = start[nch];
+  }
+  __syncthreads();
+  for (int c = 0; c < nch; ++c) {
+    const int lo = pr.wlo[c], n = start[c + 1] - start[c];
+    for (int k = tid; k < n; k += 256) pr.runs[1 + start[c] + k] = (c << 16) | (lo + k * rows);
   }
 }
 
@@ -165,97 +195,137 @@ __global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict_
 // five nested loops of Algorithm 1 produce; which (i,d') attains it is recovered where it is
 // needed (traceback, table export) by the first-match scan, not carried here.
 //
-// Work item = (64-column chunk c, run of `i_steps` predecessor rows); a lane owns column
-// jj = 64c + lane.  a[] is wave-uniform (one row of V[s-1]), c[] comes from DP coalesced row
-// reads.  Partial minima of different i-runs are combined with atomicMin into V[s] (pre-filled
-// with INF): min is order-independent, so the result is deterministic.
+// Only replica counts r <= D-s+1 can occur at level s (s-1 devices are spent on the earlier
+// stages); the larger ones rank below position D-1 of the merge, so they are not read.
+//
+// Work item (one workgroup of four waves) = `4*SPW` consecutive rows of one chunk, taken from
+// the work list; wave w takes rows i0+w, i0+w+4, ...  A lane owns column jj = 64c + lane.  a[] is
+// wave-uniform (one row of V[s-1]), c[] comes from coalesced reads of one contiguous unit.  The
+// reads of the next row are issued before the current row is merged (two register buffers).
+// The four waves fold their running minima together in LDS; partial minima of different items
+// are combined with atomicMin into V[s] (pre-filled with INF): min is order-independent, so the
+// result is deterministic.
 // ---------------------------------------------------------------------------------------
+constexpr int kMergeWaves = 4;
+constexpr int kMaxRowsPerWave = 4;
+
+int merge_rows_per_item(int rows_per_wave) {
+  const int spw = rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : kMaxRowsPerWave;
+  return kMergeWaves * spw;
+}
+
 template <typename VT, int DP>
-__global__ __launch_bounds__(64) void level_merge_kernel(const ProblemDev *__restrict__ probs,
-                                                         const int32_t *__restrict__ list,
-                                                         const int s, const int i_steps) {
-  const ProblemDev &pr = probs[list[blockIdx.z]];
-  const int N = pr.N, D = pr.D, nch = pr.nch;
-  if (s > pr.S_eff || *pr.status != 0) return;
-  const int c = blockIdx.y;
-  if (c >= nch || 64 * c + 64 < s) return;  // no column j >= s in this chunk
-  const int lane = threadIdx.x;
-  const int jj = 64 * c + lane;
-  int i_lo = blockIdx.x * i_steps;
-  int i_hi = min(min(i_lo + i_steps - 1, 64 * c + 63), N - 1);
-  i_lo = max(i_lo, s - 1);
-  if (i_lo > i_hi) return;
-  {  // rows below every column's first fitting predecessor hold INF only
-    int my = (jj < N) ? pr.ilo[jj + 1] : 0x7fffffff;
+__device__ __forceinline__ void unit_load(VT (&x)[DP], const VT *__restrict__ unit, bool act, int rl) {
+  // x[DP-1-m] = c[m+1]: reversed, so that max(a, x) is a bitonic sequence
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) my = min(my, __shfl_xor(my, o));
-    i_lo = max(i_lo, my);
-    if (i_lo > i_hi) return;
+  for (int m = 0; m < DP; ++m) {
+    const int mr = (m < rl) ? m : (rl - 1);  // clamp keeps the address inside the unit
+    VT cv = Lim<VT>::inf;
+    if (act) cv = unit[mr * 64];
+    x[DP - 1 - m] = (m < rl) ? cv : (VT)0;   // unread entries rank below everything that matters
   }
+}
+
+template <typename VT, int DP>
+__device__ __forceinline__ void unit_merge(VT (&acc)[DP], VT (&x)[DP], const VT *__restrict__ arow) {
+#pragma unroll
+  for (int q = 0; q < DP; ++q) x[q] = vmax(arow[q], x[q]);
+#pragma unroll
+  for (int h = DP / 2; h >= 1; h >>= 1) {
+#pragma unroll
+    for (int q = 0; q < DP; ++q) {
+      if ((q & h) == 0) {
+        const VT hi = vmax(x[q], x[q + h]);
+        const VT lo = vmin(x[q], x[q + h]);
+        x[q] = hi;
+        x[q + h] = lo;
+      }
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+}
+
+template <typename VT, int DP, int SPW>
+__global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
+    const ProblemDev *__restrict__ probs, const int s) {
+  const ProblemDev &pr = probs[blockIdx.z];
+  if (s > pr.S_eff || (int)blockIdx.x >= pr.runs[0]) return;
+  const int N = pr.N, D = pr.D, nch = pr.nch;
+  const int desc = pr.runs[1 + blockIdx.x];
+  const int c = desc >> 16, i0 = desc & 0xffff;
+  if (64 * c + 64 < s) return;  // no column j >= s in this chunk
+  const int i_hi = min(min(i0 + kMergeWaves * SPW - 1, 64 * c + 63), N - 1);
+  if (i_hi < s - 1) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int jj = 64 * c + lane;
   constexpr VT INF = Lim<VT>::inf;
   const int64_t lvl = (int64_t)(N + 1) * DP;
   const VT *__restrict__ Vprev = (const VT *)pr.V + (int64_t)(s - 2) * lvl;
   VT *Vcur = (VT *)pr.V + (int64_t)(s - 1) * lvl;
   const VT *__restrict__ cost = (const VT *)pr.cost;
-  const int rmax = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
+  const int rl = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
+
+  // Which of this wave's rows can contribute: the row of V[s-1] must hold a finite plan and the
+  // lane's stage must fit with at most rl replicas.  All loads issued together.
+  bool act[SPW];
+  int64_t ubase[SPW];
+  {
+    VT alast[SPW];
+    int rmn[SPW];
+#pragma unroll
+    for (int k = 0; k < SPW; ++k) {
+      const int i = i0 + wave + kMergeWaves * k;
+      alast[k] = INF;
+      rmn[k] = 255;
+      ubase[k] = 0;
+      if (i >= s - 1 && i <= i_hi) {
+        ubase[k] = unit_index(nch, i, c);
+        alast[k] = Vprev[(int64_t)i * DP + D - 1];
+        if (jj >= i && jj < N) rmn[k] = pr.rmin[ubase[k] * 64 + lane];
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < SPW; ++k) act[k] = (alast[k] != INF) && (rmn[k] <= rl);
+  }
 
   VT acc[DP];
 #pragma unroll
   for (int t = 0; t < DP; ++t) acc[t] = INF;
   bool any = false;
 
-  for (int i = i_lo; i <= i_hi; ++i) {
-    const VT *__restrict__ arow = Vprev + (int64_t)i * DP;
-    if (arow[D - 1] == INF) continue;  // no (s-1)-stage plan covers blocks 1..i
-    const int g = i >> 6;
-    const int64_t rb = rows_before(nch, i);
-    const int col = jj - 64 * g;
-    bool act = (jj >= i) && (jj < N);
-    if (act) act = (int)pr.rmin[rb + col] <= rmax;
-    if (__ballot(act) == 0ull) continue;
-    any = true;
-    const int64_t L = row_len(nch, i);
-    const VT *__restrict__ crow = cost + rb * D + (act ? col : 0);
-    VT x[DP];
-    // x[k] = c[DP-k] (reversed), so that x becomes max(a[k+1], c[DP-k]): a bitonic sequence that
-    // holds the DP largest elements of the merge.
+  VT xa[DP], xb[DP];
+  unit_load<VT, DP>(xa, cost + ubase[0] * 64 * D + lane, act[0], rl);
 #pragma unroll
-    for (int m = 0; m < DP; ++m) {
-      const int mr = (m < D) ? m : (D - 1);  // clamp keeps the address inside the row block
-      VT cv = INF;
-      if (act) cv = crow[(int64_t)mr * L];
-      x[DP - 1 - m] = (m < D) ? cv : (VT)0;  // padding sits below the smallest real element
+  for (int k = 0; k < SPW; ++k) {
+    // issue the next row's reads into the idle buffer, then merge the current one
+    if (k + 1 < SPW) {
+      if ((k & 1) == 0) unit_load<VT, DP>(xb, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
+      else unit_load<VT, DP>(xa, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
     }
-#pragma unroll
-    for (int k = 0; k < DP; ++k) x[k] = vmax(arow[k], x[k]);
-#pragma unroll
-    for (int h = DP / 2; h >= 1; h >>= 1) {
-#pragma unroll
-      for (int k = 0; k < DP; ++k) {
-        if ((k & h) == 0) {
-          const VT hi = vmax(x[k], x[k + h]);
-          const VT lo = vmin(x[k], x[k + h]);
-          x[k] = hi;
-          x[k + h] = lo;
-        }
-      }
+    if (__ballot(act[k]) != 0ull) {
+      any = true;
+      const VT *__restrict__ arow = Vprev + (int64_t)(i0 + wave + kMergeWaves * k) * DP;
+      if ((k & 1) == 0) unit_merge<VT, DP>(acc, xa, arow);
+      else unit_merge<VT, DP>(acc, xb, arow);
     }
-#pragma unroll
-    for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
   }
-  if (!any) return;
 
-  // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Transpose through LDS so that one
-  // atomic instruction covers consecutive d of one column.
+  // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Fold the four waves in LDS, then
+  // write transposed so that one atomic instruction covers consecutive d of one column.
   __shared__ VT tile[64 * (DP + 1)];
+  for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
+  if (__syncthreads_or(any) == 0) return;
+  if (any) {
 #pragma unroll
-  for (int t = 0; t < DP; ++t) tile[lane * (DP + 1) + t] = acc[t];
+    for (int t = 0; t < DP; ++t)
+      if (acc[t] != INF) atomicMin(&tile[lane * (DP + 1) + t], acc[t]);
+  }
   __syncthreads();
-  constexpr int RPP = 64 / DP;  // rows per pass
-  const int t = lane & (DP - 1);
-#pragma unroll 4
-  for (int pass = 0; pass < DP; ++pass) {
-    const int row = pass * RPP + lane / DP;
+  constexpr int RPP = 64 * kMergeWaves / DP;  // rows per pass
+  const int t = threadIdx.x & (DP - 1);
+  for (int row = threadIdx.x / DP; row < 64; row += RPP) {
     const VT v = tile[row * (DP + 1) + t];
     const int j = 64 * c + row + 1;
     if (t + 1 <= D - 1 && j <= N && j >= s && v != INF) atomicMin(&Vcur[(int64_t)j * DP + t + 1], v);
@@ -271,16 +341,16 @@ __global__ __launch_bounds__(64) void level_merge_kernel(const ProblemDev *__res
 // only the argmin arrays (canonical [(L+1)][N+1][D+1] layout of one problem) are written.
 // ---------------------------------------------------------------------------------------
 template <typename VT>
-__global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__restrict__ probs,
-                                                        const int32_t *__restrict__ list, const int s,
+__global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__restrict__ probs, const int s,
                                                         const int write_v, int32_t *__restrict__ arg_i,
                                                         int32_t *__restrict__ arg_d) {
-  const ProblemDev &pr = probs[list[blockIdx.z]];
+  const ProblemDev &pr = probs[blockIdx.z];
   const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
-  if (s > pr.S_eff || *pr.status != 0) return;
+  if (s > pr.S_eff) return;
   const int c = blockIdx.x, d = blockIdx.y + 1;
   if (c >= nch || d > D || d < s) return;
-  const int jj = 64 * c + (int)threadIdx.x;
+  const int lane = threadIdx.x;
+  const int jj = 64 * c + lane;
   const int j = jj + 1;
   constexpr VT INF = Lim<VT>::inf;
   const int64_t lvl = (int64_t)(N + 1) * DP;
@@ -291,15 +361,13 @@ __global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__rest
   const int i_end = min(64 * c + 63, N - 1);
   for (int i = s - 1; i <= i_end; ++i) {
     const bool act = (jj >= i) && (jj < N);
-    const int64_t rb = rows_before(nch, i);
-    const int64_t L = row_len(nch, i);
-    const VT *__restrict__ crow = cost + rb * D + (act ? jj - 64 * (i >> 6) : 0);
+    const VT *__restrict__ unit = cost + unit_index(nch, i, c) * 64 * D + lane;
     for (int dp = s - 1; dp <= d - 1; ++dp) {
       const VT a = Vprev[(int64_t)i * DP + dp - 1];
-      if (a == INF) continue;
+      if (a == INF) continue;  // earlier stages infeasible
       if (!act) continue;
-      const VT h = crow[(int64_t)(d - dp - 1) * L];
-      if (h == INF) continue;
+      const VT h = unit[(d - dp - 1) * 64];
+      if (h == INF) continue;  // does not fit device memory
       const VT v = vmax(a, h);
       if (v < best) { best = v; bi = i; bd = dp; }
     }
@@ -313,29 +381,37 @@ __global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__rest
 
 // ---------------------------------------------------------------------------------------
 // Final choice of the stage count: opt = min over s of V[s][N][D], smallest s among equals.
+// One wave per problem, lane s-1 reads V[s][N][D] (S_eff <= D <= 64).
 // ---------------------------------------------------------------------------------------
-__global__ void select_kernel(const ProblemDev *__restrict__ probs, int Q, int64_t *d_opt,
-                              int32_t *d_n_stages, int64_t *d_est, int32_t *d_status) {
-  const int q = blockIdx.x * blockDim.x + threadIdx.x;
-  if (q >= Q) return;
-  const ProblemDev pr = probs[q];
+__global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict__ probs,
+                                                    int64_t *d_opt, int32_t *d_n_stages,
+                                                    int64_t *d_est, int32_t *d_status) {
+  const ProblemDev &pr = probs[blockIdx.x];
+  const int q = pr.q;
+  const int lane = threadIdx.x;
   const int st = *pr.status;
-  int64_t best = INT64_MAX;
-  int bs = 0;
-  if (st == 0) {
+  int64_t v = INT64_MAX;
+  if (st == 0 && lane < pr.S_eff) {
     const int64_t lvl = (int64_t)(pr.N + 1) * pr.DP;
     const int64_t cell = (int64_t)pr.N * pr.DP + pr.D - 1;
-    for (int s = 1; s <= pr.S_eff; ++s) {
-      int64_t v;
-      if (pr.bits == 32) {
-        const uint32_t u = ((const uint32_t *)pr.V)[(s - 1) * lvl + cell];
-        v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
-      } else {
-        v = (int64_t)((const uint64_t *)pr.V)[(s - 1) * lvl + cell];
-      }
-      if (v < best) { best = v; bs = s; }
+    if (pr.bits == 32) {
+      const uint32_t u = ((const uint32_t *)pr.V)[lane * lvl + cell];
+      v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
+    } else {
+      v = (int64_t)((const uint64_t *)pr.V)[lane * lvl + cell];
     }
   }
+  // lexicographic minimum of (value, s): fewest stages among equal values
+  int bs = lane + 1;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const int64_t ov = __shfl_xor(v, o);
+    const int os = __shfl_xor(bs, o);
+    if (ov < v || (ov == v && os < bs)) { v = ov; bs = os; }
+  }
+  if (lane != 0) return;
+  const int64_t best = v;
+  if (best == INT64_MAX) bs = 0;
   pr.res[0] = best;
   pr.res[1] = bs;
   d_opt[q] = best;
@@ -378,17 +454,17 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
   for (int s = ns; s >= 2; --s) {
     const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
     const VT *Vp = V + (int64_t)(s - 2) * lvl;
-    const int jj = j - 1;
+    const int jj = j - 1, c = jj >> 6;
     bool found = false;
-    for (int ib = max(s - 1, pr.ilo[j]); ib < j; ib += rows_per_pass) {
+    const int first = max(s - 1, min(pr.wlo[c], j));  // earlier rows hold no stage that fits
+    for (int ib = first; ib < j; ib += rows_per_pass) {
       if (tid == 0) *best_key = 0xFFFFFFFFu;
       __syncthreads();
       const int i = ib + di_t;
       if (i < j && dp_t >= s - 1 && dp_t <= d - 1) {
         const VT a = Vp[(int64_t)i * DP + dp_t - 1];
         if (a <= v && v != INF) {
-          const VT h = cost[rows_before(nch, i) * D + (int64_t)(d - dp_t - 1) * row_len(nch, i) +
-                            (jj - 64 * (i >> 6))];
+          const VT h = cost[(unit_index(nch, i, c) * D + (d - dp_t - 1)) * 64 + (jj & 63)];
           if (vmax(a, h) == v) atomicMin(best_key, ((unsigned)i << 8) | (unsigned)dp_t);
         }
       }
@@ -417,8 +493,8 @@ __global__ __launch_bounds__(1024) void traceback_kernel(const ProblemDev *__res
                                                          int32_t *d_replicas) {
   __shared__ unsigned int best_key;
   const ProblemDev &pr = probs[blockIdx.x];
-  int32_t *se = d_stage_end + (int64_t)blockIdx.x * plan_stride;
-  int32_t *rp = d_replicas + (int64_t)blockIdx.x * plan_stride;
+  int32_t *se = d_stage_end + (int64_t)pr.q * plan_stride;
+  int32_t *rp = d_replicas + (int64_t)pr.q * plan_stride;
   if (pr.bits == 32) traceback_body<uint32_t>(pr, plan_stride, se, rp, &best_key);
   else traceback_body<uint64_t>(pr, plan_stride, se, rp, &best_key);
 }
@@ -427,9 +503,9 @@ __global__ __launch_bounds__(1024) void traceback_kernel(const ProblemDev *__res
 // Table export in the layout-independent form of the public header (parity and inspection).
 // ---------------------------------------------------------------------------------------
 template <typename VT>
-__global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restrict__ probs, int q,
-                                                     int which, void *__restrict__ dst) {
-  const ProblemDev &pr = probs[q];
+__global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restrict__ prob, int which,
+                                                     void *__restrict__ dst) {
+  const ProblemDev &pr = *prob;
   const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -445,12 +521,11 @@ __global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restric
       while ((int64_t)(j + 1) * j / 2 <= pair) ++j;
       const int i = (int)(pair - (int64_t)j * (j - 1) / 2);
       const int jj = j - 1;
-      const int64_t rb = rows_before(nch, i);
-      const int col = jj - 64 * (i >> 6);
+      const int64_t u = unit_index(nch, i, jj >> 6);
       if (which == RANNC_DP_TABLE_FIT) {
-        ((uint8_t *)dst)[e] = bad ? 0 : (uint8_t)(r >= (int)pr.rmin[rb + col]);
+        ((uint8_t *)dst)[e] = bad ? 0 : (uint8_t)(r >= (int)pr.rmin[u * 64 + (jj & 63)]);
       } else {
-        const VT v = bad ? INF : ((const VT *)pr.cost)[rb * D + (int64_t)(r - 1) * row_len(nch, i) + col];
+        const VT v = bad ? INF : ((const VT *)pr.cost)[(u * D + (r - 1)) * 64 + (jj & 63)];
         ((int64_t *)dst)[e] = (v == INF) ? INT64_MAX : (int64_t)v;
       }
     }
@@ -476,10 +551,9 @@ __global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restric
 // argmin export helpers: whole table to -1, then level 1 (the single stage 1..j on d devices
 // has predecessor (0,0)); levels >= 2 come from level_scan_kernel.
 template <typename VT>
-__global__ __launch_bounds__(256) void arg_init_kernel(const ProblemDev *__restrict__ probs, int q,
-                                                       int32_t *__restrict__ arg_i,
-                                                       int32_t *__restrict__ arg_d) {
-  const ProblemDev &pr = probs[q];
+__global__ __launch_bounds__(256) void arg_init_kernel(const ProblemDev *__restrict__ prob,
+                                                       int32_t *__restrict__ arg) {
+  const ProblemDev &pr = *prob;
   const int N = pr.N, D = pr.D, DP = pr.DP;
   const int64_t per = (int64_t)(N + 1) * (D + 1);
   const int64_t total = (int64_t)(pr.S_eff + 1) * per;
@@ -493,72 +567,83 @@ __global__ __launch_bounds__(256) void arg_init_kernel(const ProblemDev *__restr
     if (s == 1 && j >= 1 && d >= 1 && !bad) {
       if (((const VT *)pr.V)[(int64_t)j * DP + d - 1] != Lim<VT>::inf) v = 0;
     }
-    if (arg_i) arg_i[e] = v;
-    if (arg_d) arg_d[e] = v;
+    arg[e] = v;
   }
 }
 
 // ---------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------
-hipError_t launch_prefix(const ProblemDev *d_probs, int Q, hipStream_t st) {
-  hipLaunchKernelGGL(prefix_kernel, dim3(Q), dim3(256), 0, st, d_probs);
+hipError_t launch_prefix(const ProblemDev *probs, int Q, hipStream_t st) {
+  hipLaunchKernelGGL(prefix_kernel, dim3(Q), dim3(256), 0, st, probs);
   return hipGetLastError();
 }
 
-hipError_t launch_fill(const ProblemDev *d_probs, int Q, hipStream_t st) {
+hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st) {
   const int per = Q >= 256 ? 4 : Q >= 16 ? 32 : 256;
   for (int q0 = 0; q0 < Q; q0 += 65535) {
     const int nq = min(65535, Q - q0);
-    hipLaunchKernelGGL(fill_kernel, dim3(per, nq), dim3(256), 0, st, d_probs + q0);
+    hipLaunchKernelGGL(fill_kernel, dim3(per, nq), dim3(256), 0, st, probs + q0);
   }
   return hipGetLastError();
 }
 
+hipError_t launch_windows(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st) {
+  hipLaunchKernelGGL(windows_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item);
+  return hipGetLastError();
+}
+
 template <typename VT, int DP>
-static void build_go(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, hipStream_t st) {
+static void build_go(const ProblemDev *p, const LaunchShape &sh, hipStream_t st) {
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((build_kernel<VT, DP>), dim3(sh.max_nch, sh.max_N, nq), dim3(64), 0, st, p,
-                       l + q0);
+    hipLaunchKernelGGL((build_kernel<VT, DP>), dim3(sh.max_nch, sh.max_N, nq), dim3(64), 0, st, p + q0);
   }
 }
 
-hipError_t launch_build(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int bits,
-                        int DP, hipStream_t st) {
+hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, hipStream_t st) {
   if (sh.max_N > 65535) return hipErrorInvalidValue;
-#define GO(B, T)                                                  \
-  if (bits == B) {                                                \
-    if (DP == 8) build_go<T, 8>(p, l, sh, st);                    \
-    else if (DP == 16) build_go<T, 16>(p, l, sh, st);             \
-    else if (DP == 32) build_go<T, 32>(p, l, sh, st);             \
-    else build_go<T, 64>(p, l, sh, st);                           \
+#define GO(B, T)                                            \
+  if (bits == B) {                                          \
+    if (DP == 8) build_go<T, 8>(p, sh, st);                 \
+    else if (DP == 16) build_go<T, 16>(p, sh, st);          \
+    else if (DP == 32) build_go<T, 32>(p, sh, st);          \
+    else build_go<T, 64>(p, sh, st);                        \
   }
   GO(32, uint32_t)
   GO(64, uint64_t)
 #undef GO
   return hipGetLastError();
+}
+
+template <typename VT, int DP, int SPW>
+static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, hipStream_t st) {
+  // upper bound on the items of any problem of the launch: every chunk's rows, none pruned
+  int64_t items = 0;
+  const int rows = kMergeWaves * SPW;
+  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + rows - 1) / rows;
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    hipLaunchKernelGGL((level_merge_kernel<VT, DP, SPW>), dim3((unsigned)items, 1, nq),
+                       dim3(64 * kMergeWaves), 0, st, p + q0, s);
+  }
 }
 
 template <typename VT, int DP>
-static void merge_go(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int s, int i_steps,
-                     hipStream_t st) {
-  const int nsub = (sh.max_N + i_steps - 1) / i_steps;
-  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
-    const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((level_merge_kernel<VT, DP>), dim3(nsub, sh.max_nch, nq), dim3(64), 0, st, p,
-                       l + q0, s, i_steps);
-  }
+static void merge_spw(const ProblemDev *p, const LaunchShape &sh, int s, int spw, hipStream_t st) {
+  if (spw <= 1) merge_go<VT, DP, 1>(p, sh, s, st);
+  else if (spw <= 2) merge_go<VT, DP, 2>(p, sh, s, st);
+  else merge_go<VT, DP, 4>(p, sh, s, st);
 }
 
-hipError_t launch_level_merge(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int bits,
-                              int DP, int s, int i_steps, hipStream_t st) {
+hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s,
+                              int spw, hipStream_t st) {
 #define GO(B, T)                                                  \
   if (bits == B) {                                                \
-    if (DP == 8) merge_go<T, 8>(p, l, sh, s, i_steps, st);        \
-    else if (DP == 16) merge_go<T, 16>(p, l, sh, s, i_steps, st); \
-    else if (DP == 32) merge_go<T, 32>(p, l, sh, s, i_steps, st); \
-    else merge_go<T, 64>(p, l, sh, s, i_steps, st);               \
+    if (DP == 8) merge_spw<T, 8>(p, sh, s, spw, st);              \
+    else if (DP == 16) merge_spw<T, 16>(p, sh, s, spw, st);       \
+    else if (DP == 32) merge_spw<T, 32>(p, sh, s, spw, st);       \
+    else merge_spw<T, 64>(p, sh, s, spw, st);                     \
   }
   GO(32, uint32_t)
   GO(64, uint64_t)
@@ -566,25 +651,24 @@ hipError_t launch_level_merge(const ProblemDev *p, const int32_t *l, const Launc
   return hipGetLastError();
 }
 
-hipError_t launch_level_scan(const ProblemDev *p, const int32_t *l, const LaunchShape &sh, int bits,
-                             int s, int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st) {
+hipError_t launch_level_scan(const ProblemDev *p, const LaunchShape &sh, int bits, int s, int write_v,
+                             int32_t *arg_i, int32_t *arg_d, hipStream_t st) {
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
     const dim3 grid(sh.max_nch, sh.max_D, nq);
     if (bits == 32)
-      hipLaunchKernelGGL((level_scan_kernel<uint32_t>), grid, dim3(64), 0, st, p, l + q0, s, write_v,
-                         arg_i, arg_d);
+      hipLaunchKernelGGL((level_scan_kernel<uint32_t>), grid, dim3(64), 0, st, p + q0, s, write_v, arg_i,
+                         arg_d);
     else
-      hipLaunchKernelGGL((level_scan_kernel<uint64_t>), grid, dim3(64), 0, st, p, l + q0, s, write_v,
-                         arg_i, arg_d);
+      hipLaunchKernelGGL((level_scan_kernel<uint64_t>), grid, dim3(64), 0, st, p + q0, s, write_v, arg_i,
+                         arg_d);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_select(const ProblemDev *p, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel, dim3((Q + 127) / 128), dim3(128), 0, st, p, Q, d_opt, d_n_stages,
-                     d_est, d_status);
+  hipLaunchKernelGGL(select_kernel, dim3(Q), dim3(64), 0, st, p, d_opt, d_n_stages, d_est, d_status);
   return hipGetLastError();
 }
 
@@ -595,17 +679,14 @@ hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t
   return hipGetLastError();
 }
 
-hipError_t launch_export(const ProblemDev *p, int q, int which, const ProblemDev &hc, void *d_dst,
-                         hipStream_t st) {
+hipError_t launch_export(const ProblemDev *p, int which, int bits, void *d_dst, hipStream_t st) {
   const dim3 grid(1024), block(256);
   if (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_FIT || which == RANNC_DP_TABLE_V) {
-    if (hc.bits == 32) hipLaunchKernelGGL((export_kernel<uint32_t>), grid, block, 0, st, p, q, which, d_dst);
-    else hipLaunchKernelGGL((export_kernel<uint64_t>), grid, block, 0, st, p, q, which, d_dst);
+    if (bits == 32) hipLaunchKernelGGL((export_kernel<uint32_t>), grid, block, 0, st, p, which, d_dst);
+    else hipLaunchKernelGGL((export_kernel<uint64_t>), grid, block, 0, st, p, which, d_dst);
   } else {
-    int32_t *ai = which == RANNC_DP_TABLE_ARG_I ? (int32_t *)d_dst : nullptr;
-    int32_t *ad = which == RANNC_DP_TABLE_ARG_D ? (int32_t *)d_dst : nullptr;
-    if (hc.bits == 32) hipLaunchKernelGGL((arg_init_kernel<uint32_t>), grid, block, 0, st, p, q, ai, ad);
-    else hipLaunchKernelGGL((arg_init_kernel<uint64_t>), grid, block, 0, st, p, q, ai, ad);
+    if (bits == 32) hipLaunchKernelGGL((arg_init_kernel<uint32_t>), grid, block, 0, st, p, (int32_t *)d_dst);
+    else hipLaunchKernelGGL((arg_init_kernel<uint64_t>), grid, block, 0, st, p, (int32_t *)d_dst);
   }
   return hipGetLastError();
 }
