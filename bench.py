@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy first: the dispatch of known "
+                         "size against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (D is a search parameter, not a GPU "
@@ -84,6 +87,12 @@ def main():
         sess.solve()
         sess.traceback()
 
+    if args.calibration_copy:
+        src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
