@@ -23,8 +23,8 @@ constexpr int kStagingSlots = 2;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Sizes {  // bytes of one problem's regions inside the workspace
-  size_t prefix, wlo, runs, misc, rmin, cost, V;
-  size_t total() const { return prefix * 3 + wlo + runs + misc + rmin + cost + V; }
+  size_t prefix, wlo, runs, ufit, misc, rmin, cost, V;
+  size_t total() const { return prefix * 3 + wlo + runs + ufit + misc + rmin + cost + V; }
 };
 
 // false on arithmetic overflow
@@ -39,6 +39,7 @@ bool problem_sizes(int N, int D, int S_eff, int bits, Sizes *o) {
   o->prefix = align_up((size_t)(N + 1) * 8);
   o->wlo = align_up((size_t)nch * 4);
   o->runs = align_up((size_t)(rannc::max_runs(nch) + 1) * 4);
+  o->ufit = align_up((size_t)rannc::units_before(nch, N));
   o->misc = align_up(64);  // status word, result pair
   o->rmin = align_up((size_t)rows);
   o->cost = align_up((size_t)cost);
@@ -281,6 +282,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     p.A = (int64_t *)base; base += sz.prefix;
     p.wlo = (int32_t *)base; base += sz.wlo;
     p.runs = (int32_t *)base; base += sz.runs;
+    p.ufit = (uint8_t *)base; base += sz.ufit;
     p.status = (int32_t *)base;
     p.res = (int64_t *)(base + 16); base += sz.misc;
     p.rmin = (uint8_t *)base; base += sz.rmin;
@@ -328,6 +330,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     const LaunchShape &sh = shape[k];
     if (!sh.nprob) continue;
     ok = rannc::launch_build(dp + cls_start[k], sh, h->bits, kClasses[k], st) == hipSuccess;
+    ok = ok && rannc::launch_windows(dp + cls_start[k], sh, st) == hipSuccess;  // also used by traceback
     if (scan) continue;
     // predecessor rows per wave of a work item: few, so that a launch has enough waves in
     // flight to hide the latency of the row reads; more for big batches, where fewer partial
@@ -337,8 +340,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     units *= sh.nprob;
     spw[k] = units <= 16384 ? 1 : units <= 65536 ? 2 : 4;
     if (h->tune_spw > 0) spw[k] = h->tune_spw;
-    ok = ok && rannc::launch_windows(dp + cls_start[k], sh.nprob, rannc::merge_rows_per_item(spw[k]),
-                                     st) == hipSuccess;
+    ok = ok && rannc::launch_runs(dp + cls_start[k], sh.nprob, rannc::merge_rows_per_item(spw[k]), st) ==
+                   hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;

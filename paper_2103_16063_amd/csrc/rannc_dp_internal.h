@@ -37,6 +37,7 @@ __host__ __device__ inline int64_t units_before(int nch, int i) {
 __host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
   return units_before(nch, i) + (c - (i >> 6));
 }
+
 // upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
 // groups of at least 4
 __host__ __device__ inline int64_t max_runs(int nch) { return 8LL * nch * (nch + 1); }
@@ -56,6 +57,7 @@ struct ProblemDev {
   uint8_t *rmin;
   void *cost;
   void *V;
+  uint8_t *ufit;               // per unit: 1 if any of its stages fits for some r <= D
   int32_t *wlo;                // [nch] smallest row i with a stage (i, j in chunk) that fits for some
                                // r <= D; 0x7fffffff if none
   int32_t *runs;               // runs[0] = count, then (c << 16 | first row) per work item
@@ -76,7 +78,9 @@ struct LaunchShape {
 hipError_t launch_prefix(const ProblemDev *probs, int Q, hipStream_t st);
 hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st);
 hipError_t launch_build(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, hipStream_t st);
-hipError_t launch_windows(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st);
+hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStream_t st);
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st);
+int merge_rows_per_item(int rows_per_wave);
 hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
                               int rows_per_wave, hipStream_t st);
 hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int bits, int s,
@@ -87,6 +91,5 @@ hipError_t launch_traceback(const ProblemDev *probs, int Q, int plan_stride, int
                             int32_t *d_replicas, hipStream_t st);
 hipError_t launch_export(const ProblemDev *prob, int which, int bits, void *d_dst, hipStream_t st);
 
-int merge_rows_per_item(int rows_per_wave);
 
 }  // namespace rannc

@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
 
 // ---------------------------------------------------------------------------------------
 // Initial state: every V entry "no plan" (padding columns d > D hold 0 so that padded rows stay
-// sorted), no chunk has a fitting predecessor row yet.
+// sorted).
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict__ probs) {
   const ProblemDev pr = probs[blockIdx.y];
@@ -101,24 +101,27 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
     for (int64_t e = t0; e < total; e += stride)
       V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint64_t>::inf : 0ull;
   }
-  for (int64_t c = t0; c < pr.nch; c += stride) pr.wlo[c] = kNoRow;
 }
 
 // ---------------------------------------------------------------------------------------
 // Stage-time and fits-in-memory tables: h(i,j,r) and the m(i,j,r) <= M rule of Sec. III-C for
-// every stage (i,j) and replica count r.  One wave per unit (row i, 64-column chunk c); a lane
+// every stage (i,j) and replica count r.  One wave per unit (row i, 64-column chunk c), four
+// rows per workgroup; a lane
 // owns one j and writes its D entries, each store instruction covering 64 consecutive columns
 // of one contiguous unit.  Memory is non-increasing in r, so the fit rule is stored as the
-// smallest fitting r and folded into the time table as INF below it.  Row i = 0 is also level 1
+// smallest fitting r and folded into the time table as INF below it (within units that hold at
+// least one fitting stage; the others keep only their rmin bytes).  Row i = 0 is also level 1
 // of the DP (one stage on d devices), written here.
 // ---------------------------------------------------------------------------------------
+constexpr int kBuildWaves = 4;
+
 template <typename VT, int DP>
-__global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict__ probs) {
+__global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs) {
   const ProblemDev &pr = probs[blockIdx.z];
   const int N = pr.N, D = pr.D, nch = pr.nch;
-  const int i = blockIdx.y, c = blockIdx.x;
+  const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
   if (i >= N || c >= nch || c < (i >> 6)) return;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
   const int j = valid ? jj + 1 : i + 1;  // padding lanes compute a harmless in-range stage
@@ -136,10 +139,14 @@ __global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict_
     }
   }
   const bool fits = valid && rmin <= D;
-  if (__ballot(fits) != 0ull && lane == 0) atomicMin(&pr.wlo[c], i);
-  if (!valid) return;
+  const bool unit_fits = __ballot(fits) != 0ull;
   const int64_t u = unit_index(nch, i, c);
+  if (lane == 0) pr.ufit[u] = (uint8_t)unit_fits;
+  if (!valid) return;
   pr.rmin[u * 64 + lane] = (uint8_t)rmin;
+  // A unit in which no stage fits for any r is never read (every reader consults ufit or rmin
+  // first): only those are written.  Row 0 also carries level 1 and is always written.
+  if (!unit_fits && i != 0) return;
   VT *crow = (VT *)pr.cost + u * 64 * D + lane;
   VT *v1 = (VT *)pr.V + (int64_t)j * DP;
   const VT tij = (VT)Tij;
@@ -155,11 +162,32 @@ __global__ __launch_bounds__(64) void build_kernel(const ProblemDev *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------
-// Work list of the level kernels.  For chunk c only rows wlo[c] .. min(64c+63, N-1) can hold a
-// stage that fits; they are cut into items of `rows` consecutive rows, listed chunk by chunk.
-// One workgroup per problem.
+// Window of the level kernels: wlo[c] = first row i that holds a stage into chunk c that fits for
+// some r <= D (0x7fffffff if none).  Rows below it are never visited.  One workgroup per
+// (chunk, problem); no global atomics (same-address atomics serialise badly).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restrict__ probs, int rows) {
+__global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restrict__ probs) {
+  const ProblemDev &pr = probs[blockIdx.y];
+  const int c = blockIdx.x, nch = pr.nch;
+  if (c >= nch) return;
+  __shared__ int first;
+  if (threadIdx.x == 0) first = kNoRow;
+  __syncthreads();
+  const int hi = min(64 * c + 63, pr.N - 1);
+  int mine = kNoRow;
+  for (int i = threadIdx.x; i <= hi; i += 256)
+    if (pr.ufit[unit_index(nch, i, c)]) { mine = i; break; }  // rows ascend
+  if (mine != kNoRow) atomicMin(&first, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) pr.wlo[c] = first;
+}
+
+// ---------------------------------------------------------------------------------------
+// Work list of the merge level kernel: the rows wlo[c] .. min(64c+63, N-1) of every chunk, cut into
+// items of `rows` consecutive rows, listed chunk by chunk.  A compact list keeps the workgroups
+// that have work at the front of the grid.  One workgroup per problem.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
   const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
@@ -198,8 +226,9 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // Only replica counts r <= D-s+1 can occur at level s (s-1 devices are spent on the earlier
 // stages); the larger ones rank below position D-1 of the merge, so they are not read.
 //
-// Work item (one workgroup of four waves) = `4*SPW` consecutive rows of one chunk, taken from
-// the work list; wave w takes rows i0+w, i0+w+4, ...  A lane owns column jj = 64c + lane.  a[] is
+// Work item (one workgroup of four waves) = `4*SPW` consecutive rows of one chunk's window, taken
+// from the work list;
+// wave w takes rows i0+w, i0+w+4, ...  A lane owns column jj = 64c + lane.  a[] is
 // wave-uniform (one row of V[s-1]), c[] comes from coalesced reads of one contiguous unit.  The
 // reads of the next row are issued before the current row is merged (two register buffers).
 // The four waves fold their running minima together in LDS; partial minima of different items
@@ -207,12 +236,6 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // result is deterministic.
 // ---------------------------------------------------------------------------------------
 constexpr int kMergeWaves = 4;
-constexpr int kMaxRowsPerWave = 4;
-
-int merge_rows_per_item(int rows_per_wave) {
-  const int spw = rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : kMaxRowsPerWave;
-  return kMergeWaves * spw;
-}
 
 template <typename VT, int DP>
 __device__ __forceinline__ void unit_load(VT (&x)[DP], const VT *__restrict__ unit, bool act, int rl) {
@@ -250,12 +273,14 @@ template <typename VT, int DP, int SPW>
 __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
     const ProblemDev *__restrict__ probs, const int s) {
   const ProblemDev &pr = probs[blockIdx.z];
-  if (s > pr.S_eff || (int)blockIdx.x >= pr.runs[0]) return;
+  if (s > pr.S_eff) return;
   const int N = pr.N, D = pr.D, nch = pr.nch;
+  constexpr int R = kMergeWaves * SPW;
+  if ((int)blockIdx.x >= pr.runs[0]) return;
   const int desc = pr.runs[1 + blockIdx.x];
   const int c = desc >> 16, i0 = desc & 0xffff;
   if (64 * c + 64 < s) return;  // no column j >= s in this chunk
-  const int i_hi = min(min(i0 + kMergeWaves * SPW - 1, 64 * c + 63), N - 1);
+  const int i_hi = min(min(i0 + R - 1, 64 * c + 63), N - 1);
   if (i_hi < s - 1) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -361,13 +386,14 @@ __global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__rest
   const int i_end = min(64 * c + 63, N - 1);
   for (int i = s - 1; i <= i_end; ++i) {
     const bool act = (jj >= i) && (jj < N);
-    const VT *__restrict__ unit = cost + unit_index(nch, i, c) * 64 * D + lane;
+    const int64_t u = unit_index(nch, i, c);
+    const VT *__restrict__ unit = cost + u * 64 * D + lane;
+    const int rmn = act ? (int)pr.rmin[u * 64 + lane] : 255;
     for (int dp = s - 1; dp <= d - 1; ++dp) {
       const VT a = Vprev[(int64_t)i * DP + dp - 1];
       if (a == INF) continue;  // earlier stages infeasible
-      if (!act) continue;
+      if (d - dp < rmn) continue;  // does not fit device memory
       const VT h = unit[(d - dp - 1) * 64];
-      if (h == INF) continue;  // does not fit device memory
       const VT v = vmax(a, h);
       if (v < best) { best = v; bi = i; bd = dp; }
     }
@@ -432,14 +458,16 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
 // One workgroup per problem walks from (s*, N, D) down to level 1.  At each cell it finds the
 // lexicographically smallest (i, d') with max(V[s-1][i][d'], h(i,j,d-d')) equal to the cell's
 // value: the candidate that the ascending scan with strict "<" of Algorithm 1 would have kept.
-// Threads cover 16 split points x 64 device counts per pass, passes ascend in i and stop at the
-// first pass with a match.
+// A thread owns a split point i.  Both V[s-1][i][.] and h(i,j,.) are non-increasing (the property
+// the merge kernel rests on), so in row i the only candidate is the smallest d' whose earlier-stages
+// value is <= the cell's value: one row read and one table read per split point.
 // ---------------------------------------------------------------------------------------
-template <typename VT>
+template <typename VT, int DP>
 __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
                                unsigned int *best_key) {
   constexpr VT INF = Lim<VT>::inf;
-  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  constexpr int PER = 16 / (int)sizeof(VT);  // values per 16-byte read
+  const int N = pr.N, D = pr.D, nch = pr.nch;
   const int tid = threadIdx.x;
   const int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
   for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
@@ -448,55 +476,77 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
   const VT *V = (const VT *)pr.V;
   const VT *cost = (const VT *)pr.cost;
   int j = N, d = D;
-  const int dp_t = (tid & 63) + 1;  // candidate d' of this thread
-  const int di_t = tid >> 6;        // row offset of this thread within a pass
-  const int rows_per_pass = blockDim.x >> 6;
   for (int s = ns; s >= 2; --s) {
     const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
     const VT *Vp = V + (int64_t)(s - 2) * lvl;
     const int jj = j - 1, c = jj >> 6;
-    bool found = false;
+    if (tid == 0) *best_key = 0xFFFFFFFFu;
+    __syncthreads();
     const int first = max(s - 1, min(pr.wlo[c], j));  // earlier rows hold no stage that fits
-    for (int ib = first; ib < j; ib += rows_per_pass) {
-      if (tid == 0) *best_key = 0xFFFFFFFFu;
-      __syncthreads();
-      const int i = ib + di_t;
-      if (i < j && dp_t >= s - 1 && dp_t <= d - 1) {
-        const VT a = Vp[(int64_t)i * DP + dp_t - 1];
-        if (a <= v && v != INF) {
-          const VT h = cost[(unit_index(nch, i, c) * D + (d - dp_t - 1)) * 64 + (jj & 63)];
-          if (vmax(a, h) == v) atomicMin(best_key, ((unsigned)i << 8) | (unsigned)dp_t);
+    unsigned mine = 0xFFFFFFFFu;
+    for (int i = first + tid; i < j; i += blockDim.x) {
+      // the whole row V[s-1][i][.] in registers: 16-byte reads that do not depend on v
+      VT a[DP];
+      const uint4 *row = (const uint4 *)(Vp + (int64_t)i * DP);  // rows are 16-byte aligned
+#pragma unroll
+      for (int q = 0; q < DP / PER; ++q) {
+        const uint4 w = row[q];
+        if constexpr (sizeof(VT) == 4) {
+          a[4 * q] = w.x; a[4 * q + 1] = w.y; a[4 * q + 2] = w.z; a[4 * q + 3] = w.w;
+        } else {
+          a[2 * q] = ((VT)w.y << 32) | w.x; a[2 * q + 1] = ((VT)w.w << 32) | w.z;
         }
       }
-      __syncthreads();
-      const unsigned key = *best_key;
-      __syncthreads();
-      if (key != 0xFFFFFFFFu) {
-        const int i_sel = (int)(key >> 8), d_sel = (int)(key & 255u);
-        if (tid == 0) { se[s - 1] = j; rp[s - 1] = d - d_sel; }
-        j = i_sel;
-        d = d_sel;
-        found = true;
-        break;
+      // smallest d' in [s-1, d-1] with a[d'] <= v; smaller d' cannot match (a > v), and if this
+      // one does not match no larger one does (c only grows as r = d - d' shrinks)
+      int dsel = 0;
+      VT asel = INF;
+#pragma unroll
+      for (int k = DP - 1; k >= 0; --k)
+        if (k + 1 >= s - 1 && k + 1 <= d - 1 && a[k] <= v) { dsel = k + 1; asel = a[k]; }
+      // both table reads are issued together (the time entry is garbage where r < rmin)
+      const int64_t u = unit_index(nch, i, c);
+      const int r = d - max(dsel, 1);
+      const int rmn = (int)pr.rmin[u * 64 + (jj & 63)];
+      const VT h = cost[(u * D + (r - 1)) * 64 + (jj & 63)];
+      if (dsel != 0 && v != INF && r >= rmn && vmax(asel, h) == v) {
+        mine = ((unsigned)i << 8) | (unsigned)dsel;
+        break;  // rows ascend
       }
     }
-    if (!found) {  // tables inconsistent: report no plan rather than walk on
+    if (mine != 0xFFFFFFFFu) atomicMin(best_key, mine);
+    __syncthreads();
+    const unsigned key = *best_key;
+    __syncthreads();
+    if (key == 0xFFFFFFFFu) {  // tables inconsistent: report no plan rather than walk on
       for (int u = tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
       return;
     }
+    const int i_sel = (int)(key >> 8), d_sel = (int)(key & 255u);
+    if (tid == 0) { se[s - 1] = j; rp[s - 1] = d - d_sel; }
+    j = i_sel;
+    d = d_sel;
   }
   if (tid == 0) { se[0] = j; rp[0] = d; }
 }
 
-__global__ __launch_bounds__(1024) void traceback_kernel(const ProblemDev *__restrict__ probs,
-                                                         int plan_stride, int32_t *d_stage_end,
-                                                         int32_t *d_replicas) {
+constexpr int kTracebackThreads = 512;
+
+__global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
+    const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas) {
   __shared__ unsigned int best_key;
-  const ProblemDev &pr = probs[blockIdx.x];
+  const ProblemDev pr = probs[blockIdx.x];  // by value: no reloads after the plan stores
   int32_t *se = d_stage_end + (int64_t)pr.q * plan_stride;
   int32_t *rp = d_replicas + (int64_t)pr.q * plan_stride;
-  if (pr.bits == 32) traceback_body<uint32_t>(pr, plan_stride, se, rp, &best_key);
-  else traceback_body<uint64_t>(pr, plan_stride, se, rp, &best_key);
+#define GO(T)                                                                           \
+  switch (pr.DP) {                                                                      \
+    case 8: traceback_body<T, 8>(pr, plan_stride, se, rp, &best_key); break;            \
+    case 16: traceback_body<T, 16>(pr, plan_stride, se, rp, &best_key); break;          \
+    case 32: traceback_body<T, 32>(pr, plan_stride, se, rp, &best_key); break;          \
+    default: traceback_body<T, 64>(pr, plan_stride, se, rp, &best_key); break;          \
+  }
+  if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
+#undef GO
 }
 
 // ---------------------------------------------------------------------------------------
@@ -525,7 +575,8 @@ __global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restric
       if (which == RANNC_DP_TABLE_FIT) {
         ((uint8_t *)dst)[e] = bad ? 0 : (uint8_t)(r >= (int)pr.rmin[u * 64 + (jj & 63)]);
       } else {
-        const VT v = bad ? INF : ((const VT *)pr.cost)[(u * D + (r - 1)) * 64 + (jj & 63)];
+        const bool fit = !bad && r >= (int)pr.rmin[u * 64 + (jj & 63)];
+        const VT v = fit ? ((const VT *)pr.cost)[(u * D + (r - 1)) * 64 + (jj & 63)] : INF;
         ((int64_t *)dst)[e] = (v == INF) ? INT64_MAX : (int64_t)v;
       }
     }
@@ -588,8 +639,20 @@ hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st) {
   return hipGetLastError();
 }
 
-hipError_t launch_windows(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st) {
-  hipLaunchKernelGGL(windows_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item);
+int merge_rows_per_item(int rows_per_wave) {
+  return kMergeWaves * (rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : 4);
+}
+
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st) {
+  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item);
+  return hipGetLastError();
+}
+
+hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStream_t st) {
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    hipLaunchKernelGGL(windows_kernel, dim3(sh.max_nch, nq), dim3(256), 0, st, probs + q0);
+  }
   return hipGetLastError();
 }
 
@@ -597,7 +660,9 @@ template <typename VT, int DP>
 static void build_go(const ProblemDev *p, const LaunchShape &sh, hipStream_t st) {
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((build_kernel<VT, DP>), dim3(sh.max_nch, sh.max_N, nq), dim3(64), 0, st, p + q0);
+    hipLaunchKernelGGL((build_kernel<VT, DP>),
+                       dim3(sh.max_nch, (sh.max_N + kBuildWaves - 1) / kBuildWaves, nq),
+                       dim3(64 * kBuildWaves), 0, st, p + q0);
   }
 }
 
@@ -618,6 +683,7 @@ hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, in
 
 template <typename VT, int DP, int SPW>
 static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, hipStream_t st) {
+  // upper bound on the items of any problem of the launch: every chunk's rows, none pruned
   // upper bound on the items of any problem of the launch: every chunk's rows, none pruned
   int64_t items = 0;
   const int rows = kMergeWaves * SPW;
@@ -674,7 +740,7 @@ hipError_t launch_select(const ProblemDev *p, int Q, int64_t *d_opt, int32_t *d_
 
 hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t *d_stage_end,
                             int32_t *d_replicas, hipStream_t st) {
-  hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(1024), 0, st, p, plan_stride, d_stage_end,
+  hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(kTracebackThreads), 0, st, p, plan_stride, d_stage_end,
                      d_replicas);
   return hipGetLastError();
 }
