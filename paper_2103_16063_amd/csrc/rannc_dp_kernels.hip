@@ -20,6 +20,17 @@ template <> struct Lim<uint64_t> { static constexpr uint64_t inf = 0x7FFFFFFFFFF
 template <typename VT> __device__ __forceinline__ VT vmax(VT a, VT b) { return a > b ? a : b; }
 template <typename VT> __device__ __forceinline__ VT vmin(VT a, VT b) { return a < b ? a : b; }
 
+// Pointers that are read out of a descriptor in memory are generic to the compiler, and generic
+// (FLAT) loads count against the 4-bit LDS/scalar counter: at most 15 of them can be in flight per
+// wave.  Everything the library addresses is device memory, so the hot kernels say so and get
+// GLOBAL loads, which have 63 in flight.
+#define RANNC_GLOBAL __attribute__((address_space(1)))
+template <typename T> __device__ __forceinline__ T RANNC_GLOBAL *gptr(T *p) { return (T RANNC_GLOBAL *)p; }
+
+template <typename VT> __device__ __forceinline__ void global_min(VT RANNC_GLOBAL *p, VT v) {
+  (void)__hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 static constexpr uint64_t kSumLimit = 1ull << 62;
 static constexpr int kNoRow = 0x7fffffff;
 
@@ -238,7 +249,8 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
 constexpr int kMergeWaves = 4;
 
 template <typename VT, int DP>
-__device__ __forceinline__ void unit_load(VT (&x)[DP], const VT *__restrict__ unit, bool act, int rl) {
+__device__ __forceinline__ void unit_load(VT (&x)[DP], const VT RANNC_GLOBAL *__restrict__ unit, bool act,
+                                          int rl) {
   // x[DP-1-m] = c[m+1]: reversed, so that max(a, x) is a bitonic sequence
 #pragma unroll
   for (int m = 0; m < DP; ++m) {
@@ -249,8 +261,9 @@ __device__ __forceinline__ void unit_load(VT (&x)[DP], const VT *__restrict__ un
   }
 }
 
+// x := the DP largest elements of merge(a, c), sorted descending (x holds c reversed on entry)
 template <typename VT, int DP>
-__device__ __forceinline__ void unit_merge(VT (&acc)[DP], VT (&x)[DP], const VT *__restrict__ arow) {
+__device__ __forceinline__ void unit_sort(VT (&x)[DP], const VT RANNC_GLOBAL *__restrict__ arow) {
 #pragma unroll
   for (int q = 0; q < DP; ++q) x[q] = vmax(arow[q], x[q]);
 #pragma unroll
@@ -265,6 +278,12 @@ __device__ __forceinline__ void unit_merge(VT (&acc)[DP], VT (&x)[DP], const VT 
       }
     }
   }
+}
+
+template <typename VT, int DP>
+__device__ __forceinline__ void unit_merge(VT (&acc)[DP], VT (&x)[DP],
+                                           const VT RANNC_GLOBAL *__restrict__ arow) {
+  unit_sort<VT, DP>(x, arow);
 #pragma unroll
   for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
 }
@@ -276,8 +295,9 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
   if (s > pr.S_eff) return;
   const int N = pr.N, D = pr.D, nch = pr.nch;
   constexpr int R = kMergeWaves * SPW;
-  if ((int)blockIdx.x >= pr.runs[0]) return;
-  const int desc = pr.runs[1 + blockIdx.x];
+  const int32_t RANNC_GLOBAL *__restrict__ runs = gptr((const int32_t *)pr.runs);
+  if ((int)blockIdx.x >= runs[0]) return;
+  const int desc = runs[1 + blockIdx.x];
   const int c = desc >> 16, i0 = desc & 0xffff;
   if (64 * c + 64 < s) return;  // no column j >= s in this chunk
   const int i_hi = min(min(i0 + R - 1, 64 * c + 63), N - 1);
@@ -287,9 +307,10 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
   const int jj = 64 * c + lane;
   constexpr VT INF = Lim<VT>::inf;
   const int64_t lvl = (int64_t)(N + 1) * DP;
-  const VT *__restrict__ Vprev = (const VT *)pr.V + (int64_t)(s - 2) * lvl;
-  VT *Vcur = (VT *)pr.V + (int64_t)(s - 1) * lvl;
-  const VT *__restrict__ cost = (const VT *)pr.cost;
+  const VT RANNC_GLOBAL *__restrict__ Vprev = gptr((const VT *)pr.V) + (int64_t)(s - 2) * lvl;
+  VT RANNC_GLOBAL *Vcur = gptr((VT *)pr.V) + (int64_t)(s - 1) * lvl;
+  const VT RANNC_GLOBAL *__restrict__ cost = gptr((const VT *)pr.cost);
+  const uint8_t RANNC_GLOBAL *__restrict__ rmin = gptr((const uint8_t *)pr.rmin);
   const int rl = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
 
   // Which of this wave's rows can contribute: the row of V[s-1] must hold a finite plan and the
@@ -308,32 +329,40 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
       if (i >= s - 1 && i <= i_hi) {
         ubase[k] = unit_index(nch, i, c);
         alast[k] = Vprev[(int64_t)i * DP + D - 1];
-        if (jj >= i && jj < N) rmn[k] = pr.rmin[ubase[k] * 64 + lane];
+        if (jj >= i && jj < N) rmn[k] = rmin[ubase[k] * 64 + lane];
       }
     }
 #pragma unroll
     for (int k = 0; k < SPW; ++k) act[k] = (alast[k] != INF) && (rmn[k] <= rl);
   }
 
+  // acc[t] = running minimum over this wave's rows of the sorted merge
   VT acc[DP];
-#pragma unroll
-  for (int t = 0; t < DP; ++t) acc[t] = INF;
   bool any = false;
-
-  VT xa[DP], xb[DP];
-  unit_load<VT, DP>(xa, cost + ubase[0] * 64 * D + lane, act[0], rl);
-#pragma unroll
-  for (int k = 0; k < SPW; ++k) {
-    // issue the next row's reads into the idle buffer, then merge the current one
-    if (k + 1 < SPW) {
-      if ((k & 1) == 0) unit_load<VT, DP>(xb, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
-      else unit_load<VT, DP>(xa, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
-    }
-    if (__ballot(act[k]) != 0ull) {
+  if constexpr (SPW == 1) {  // one row: its sorted merge is the result, no second array
+    unit_load<VT, DP>(acc, cost + ubase[0] * 64 * D + lane, act[0], rl);
+    if (__ballot(act[0]) != 0ull) {
       any = true;
-      const VT *__restrict__ arow = Vprev + (int64_t)(i0 + wave + kMergeWaves * k) * DP;
-      if ((k & 1) == 0) unit_merge<VT, DP>(acc, xa, arow);
-      else unit_merge<VT, DP>(acc, xb, arow);
+      unit_sort<VT, DP>(acc, Vprev + (int64_t)(i0 + wave) * DP);
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < DP; ++t) acc[t] = INF;
+    VT xa[DP], xb[DP];
+    unit_load<VT, DP>(xa, cost + ubase[0] * 64 * D + lane, act[0], rl);
+#pragma unroll
+    for (int k = 0; k < SPW; ++k) {
+      // issue the next row's reads into the idle buffer, then merge the current one
+      if (k + 1 < SPW) {
+        if ((k & 1) == 0) unit_load<VT, DP>(xb, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
+        else unit_load<VT, DP>(xa, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
+      }
+      if (__ballot(act[k]) != 0ull) {
+        any = true;
+        const VT RANNC_GLOBAL *__restrict__ arow = Vprev + (int64_t)(i0 + wave + kMergeWaves * k) * DP;
+        if ((k & 1) == 0) unit_merge<VT, DP>(acc, xa, arow);
+        else unit_merge<VT, DP>(acc, xb, arow);
+      }
     }
   }
 
@@ -353,7 +382,7 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
   for (int row = threadIdx.x / DP; row < 64; row += RPP) {
     const VT v = tile[row * (DP + 1) + t];
     const int j = 64 * c + row + 1;
-    if (t + 1 <= D - 1 && j <= N && j >= s && v != INF) atomicMin(&Vcur[(int64_t)j * DP + t + 1], v);
+    if (t + 1 <= D - 1 && j <= N && j >= s && v != INF) global_min(&Vcur[(int64_t)j * DP + t + 1], v);
   }
 }
 
