@@ -332,13 +332,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     ok = rannc::launch_build(dp + cls_start[k], sh, h->bits, kClasses[k], st) == hipSuccess;
     ok = ok && rannc::launch_windows(dp + cls_start[k], sh, st) == hipSuccess;  // also used by traceback
     if (scan) continue;
-    // predecessor rows per wave of a work item: few, so that a launch has enough waves in
-    // flight to hide the latency of the row reads; more for big batches, where fewer partial
-    // results then have to be combined with atomics
-    int64_t units = 0;  // (row, 64-column chunk) pairs of a dense level
-    for (int c = 0; c < sh.max_nch; ++c) units += std::min(64 * c + 64, sh.max_N);
-    units *= sh.nprob;
-    spw[k] = units <= 16384 ? 1 : units <= 65536 ? 2 : 4;
+    // One predecessor row per wave: measured best on every configuration (most waves in flight
+    // to hide the latency of the row reads).  RANNC_DP_ROWS_PER_WAVE = 2 or 4 selects the variants
+    // that keep several rows per wave with double-buffered reads.
+    spw[k] = 1;
     if (h->tune_spw > 0) spw[k] = h->tune_spw;
     ok = ok && rannc::launch_runs(dp + cls_start[k], sh.nprob, rannc::merge_rows_per_item(spw[k]), st) ==
                    hipSuccess;

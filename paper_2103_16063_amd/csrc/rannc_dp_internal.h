@@ -39,8 +39,8 @@ __host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
 }
 
 // upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
-// groups of at least 4
-__host__ __device__ inline int64_t max_runs(int nch) { return 8LL * nch * (nch + 1); }
+// groups of at least 8
+__host__ __device__ inline int64_t max_runs(int nch) { return 4LL * nch * (nch + 1); }
 
 __host__ __device__ inline int dp_class(int D) { return D <= 8 ? 8 : D <= 16 ? 16 : D <= 32 ? 32 : 64; }
 

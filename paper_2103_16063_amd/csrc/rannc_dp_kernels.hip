@@ -237,16 +237,16 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
 // Only replica counts r <= D-s+1 can occur at level s (s-1 devices are spent on the earlier
 // stages); the larger ones rank below position D-1 of the merge, so they are not read.
 //
-// Work item (one workgroup of four waves) = `4*SPW` consecutive rows of one chunk's window, taken
+// Work item (one workgroup of eight waves) = `8*SPW` consecutive rows of one chunk's window, taken
 // from the work list;
-// wave w takes rows i0+w, i0+w+4, ...  A lane owns column jj = 64c + lane.  a[] is
+// wave w takes rows i0+w, i0+w+8, ...  A lane owns column jj = 64c + lane.  a[] is
 // wave-uniform (one row of V[s-1]), c[] comes from coalesced reads of one contiguous unit.  The
 // reads of the next row are issued before the current row is merged (two register buffers).
-// The four waves fold their running minima together in LDS; partial minima of different items
+// The eight waves fold their running minima together in LDS; partial minima of different items
 // are combined with atomicMin into V[s] (pre-filled with INF): min is order-independent, so the
 // result is deterministic.
 // ---------------------------------------------------------------------------------------
-constexpr int kMergeWaves = 4;
+constexpr int kMergeWaves = 8;
 
 template <typename VT, int DP>
 __device__ __forceinline__ void unit_load(VT (&x)[DP], const VT RANNC_GLOBAL *__restrict__ unit, bool act,
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
     }
   }
 
-  // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Fold the four waves in LDS, then
+  // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Fold the waves in LDS, then
   // write transposed so that one atomic instruction covers consecutive d of one column.
   __shared__ VT tile[64 * (DP + 1)];
   for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
