@@ -31,6 +31,15 @@ template <typename VT> __device__ __forceinline__ void global_min(VT RANNC_GLOBA
   (void)__hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ uint32_t lane_bcast(uint32_t v, int q) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, q);
+}
+__device__ __forceinline__ uint64_t lane_bcast(uint64_t v, int q) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, q);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), q);
+  return ((uint64_t)hi << 32) | lo;
+}
+
 static constexpr uint64_t kSumLimit = 1ull << 62;
 static constexpr int kNoRow = 0x7fffffff;
 
@@ -487,61 +496,69 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
 // One workgroup per problem walks from (s*, N, D) down to level 1.  At each cell it finds the
 // lexicographically smallest (i, d') with max(V[s-1][i][d'], h(i,j,d-d')) equal to the cell's
 // value: the candidate that the ascending scan with strict "<" of Algorithm 1 would have kept.
-// A thread owns a split point i.  Both V[s-1][i][.] and h(i,j,.) are non-increasing (the property
-// the merge kernel rests on), so in row i the only candidate is the smallest d' whose earlier-stages
-// value is <= the cell's value: one row read and one table read per split point.
+// A wave owns a split point i and reads the row V[s-1][i][.] with one coalesced request (lane =
+// d'-1).  Both that row and h(i,j,.) are non-increasing (the property the merge kernel rests on),
+// so in row i the only candidate is the smallest d' whose earlier-stages value is <= the cell's
+// value: one row read and one table read per split point, and the reads of one pass (192 rows)
+// do not depend on each other.
 // ---------------------------------------------------------------------------------------
 template <typename VT, int DP>
 __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
                                unsigned int *best_key) {
   constexpr VT INF = Lim<VT>::inf;
-  constexpr int PER = 16 / (int)sizeof(VT);  // values per 16-byte read
+  constexpr int KB = 12;  // rows per wave and pass; their reads are independent
   const int N = pr.N, D = pr.D, nch = pr.nch;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
   const int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
   for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
   if (ns == 0) return;
   const int64_t lvl = (int64_t)(N + 1) * DP;
-  const VT *V = (const VT *)pr.V;
-  const VT *cost = (const VT *)pr.cost;
+  const VT RANNC_GLOBAL *V = gptr((const VT *)pr.V);
+  const VT RANNC_GLOBAL *cost = gptr((const VT *)pr.cost);
+  const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
+  const int32_t RANNC_GLOBAL *wlo = gptr((const int32_t *)pr.wlo);
   int j = N, d = D;
   for (int s = ns; s >= 2; --s) {
-    const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
-    const VT *Vp = V + (int64_t)(s - 2) * lvl;
+    const VT RANNC_GLOBAL *Vp = V + (int64_t)(s - 2) * lvl;
     const int jj = j - 1, c = jj >> 6;
     if (tid == 0) *best_key = 0xFFFFFFFFu;
     __syncthreads();
-    const int first = max(s - 1, min(pr.wlo[c], j));  // earlier rows hold no stage that fits
+    // the cell's value, the window bound and the first pass of rows are read together
+    const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
+    const int first = max(s - 1, min(wlo[c], j));  // earlier rows hold no stage that fits
     unsigned mine = 0xFFFFFFFFu;
-    for (int i = first + tid; i < j; i += blockDim.x) {
-      // the whole row V[s-1][i][.] in registers: 16-byte reads that do not depend on v
-      VT a[DP];
-      const uint4 *row = (const uint4 *)(Vp + (int64_t)i * DP);  // rows are 16-byte aligned
+    for (int top = j - 1; top >= s - 1; top -= nw * KB) {  // rows top, top-1, ... downwards
+      VT a[KB];
 #pragma unroll
-      for (int q = 0; q < DP / PER; ++q) {
-        const uint4 w = row[q];
-        if constexpr (sizeof(VT) == 4) {
-          a[4 * q] = w.x; a[4 * q + 1] = w.y; a[4 * q + 2] = w.z; a[4 * q + 3] = w.w;
-        } else {
-          a[2 * q] = ((VT)w.y << 32) | w.x; a[2 * q + 1] = ((VT)w.w << 32) | w.z;
+      for (int k = 0; k < KB; ++k) {
+        const int i = top - (wave + nw * k);
+        a[k] = (i >= s - 1 && lane < DP) ? Vp[(int64_t)i * DP + lane] : INF;  // lane = d'-1
+      }
+      // per row: smallest d' in [s-1, d-1] with a[d'] <= v (smaller d' cannot match, and if this
+      // one does not match no larger one does: c only grows as r = d - d' shrinks); lane k then
+      // checks row k against the table
+      int my_d = 0;
+      VT my_a = INF;
+#pragma unroll
+      for (int k = 0; k < KB; ++k) {
+        const bool ok = lane + 1 >= s - 1 && lane + 1 <= d - 1 && a[k] <= v;
+        const unsigned long long m = __ballot(ok);
+        if (m != 0ull) {
+          const int q = __ffsll((long long)m) - 1;
+          const VT aq = lane_bcast(a[k], q);
+          if (lane == k) { my_d = q + 1; my_a = aq; }
         }
       }
-      // smallest d' in [s-1, d-1] with a[d'] <= v; smaller d' cannot match (a > v), and if this
-      // one does not match no larger one does (c only grows as r = d - d' shrinks)
-      int dsel = 0;
-      VT asel = INF;
-#pragma unroll
-      for (int k = DP - 1; k >= 0; --k)
-        if (k + 1 >= s - 1 && k + 1 <= d - 1 && a[k] <= v) { dsel = k + 1; asel = a[k]; }
-      // both table reads are issued together (the time entry is garbage where r < rmin)
-      const int64_t u = unit_index(nch, i, c);
-      const int r = d - max(dsel, 1);
-      const int rmn = (int)pr.rmin[u * 64 + (jj & 63)];
-      const VT h = cost[(u * D + (r - 1)) * 64 + (jj & 63)];
-      if (dsel != 0 && v != INF && r >= rmn && vmax(asel, h) == v) {
-        mine = ((unsigned)i << 8) | (unsigned)dsel;
-        break;  // rows ascend
+      const int i = top - (wave + nw * lane);  // the row lane < KB is responsible for
+      if (lane < KB && my_d != 0 && i >= first && v != INF) {
+        const int64_t u = unit_index(nch, i, c);
+        const int r = d - my_d;
+        const int rmn = (int)rmin[u * 64 + (jj & 63)];
+        const VT h = cost[(u * D + (r - 1)) * 64 + (jj & 63)];  // garbage where r < rmin
+        if (r >= rmn && vmax(my_a, h) == v) mine = min(mine, ((unsigned)i << 8) | (unsigned)my_d);
       }
+      if (top - nw * KB < first) break;  // the remaining rows lie below the window
     }
     if (mine != 0xFFFFFFFFu) atomicMin(best_key, mine);
     __syncthreads();
@@ -559,7 +576,7 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
   if (tid == 0) { se[0] = j; rp[0] = d; }
 }
 
-constexpr int kTracebackThreads = 512;
+constexpr int kTracebackThreads = 1024;
 
 __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
     const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas) {

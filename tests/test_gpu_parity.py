@@ -165,3 +165,20 @@ def test_merge_and_scan_levels_agree_at_medium_size():
         for k in rm:
             assert np.array_equal(rm[k], rs[k]), k
         assert_results_match([pr], rm)
+
+
+@pytest.mark.parametrize("rows", ["1", "2", "4"])
+def test_rows_per_wave_variants(rows, monkeypatch):
+    """The merge level kernel exists in three shapes (1, 2 or 4 predecessor rows per wave, the
+    latter two with double-buffered reads); the library reads the choice when a handle is created.
+    All must give the oracle's tables."""
+    monkeypatch.setenv("RANNC_DP_ROWS_PER_WAVE", rows)
+    probs = [synth.enlarged_transformer_chain(seed=21, N=333, D=64, S=12, M=24 * synth.GiB),
+             synth.random_small(77, 150, 40, 9, tight=1.3, tmax=5000),
+             synth.random_small(78, 65, 7, 7, tight=1.1, tmax=50)]
+    for width in WIDTHS:
+        res, sess = gpu_run(probs, max_total_time_ns=width)
+        with sess:
+            assert_results_match(probs, res)
+            for q in range(3):
+                assert_tables_match(probs[q], sess, q, args=False)
