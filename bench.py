@@ -1,7 +1,7 @@
 """Benchmark of the stage-level partition search on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c5|c3|c2|c1|c4dense]
-                    [--no-cpu-baseline]
+                    [--no-cpu-baseline] [--no-dense] [--calibration-copy]
 
 A step is one pass of the whole path over one batch of synthetic input that is already resident
 in HBM: prefix sums, stage-time / fit tables, every DP level, the choice of the stage count and
@@ -22,6 +22,15 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configurations run in
+
+# HBM bytes per level-kernel launch from the committed rocprofv3 --pmc runs (profiles/*.md):
+# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB (factors from the 256 MiB copy of the same runs).
+PMC_TRAFFIC_BYTES = {
+    "c4": 26.97e6,        # profiles/level_merge_config4.md: 24.41 MB fetched + 2.56 MB written
+    "c4dense": 115.86e6,  # profiles/level_merge_config4_dense.md: 102.51 MB + 13.35 MB
+    "c5": 503.1e6,        # profiles/level_merge_config5_batched.md: mean over the 52 launches of a step
+}
 
 
 def updates(N, D, S):
@@ -31,9 +40,9 @@ def updates(N, D, S):
                for s in range(1, L + 1))
 
 
-def level_bytes(N, D, esize):
-    """Algorithmic bytes of one DP level: the stage-time table read once (entries of `esize`
-    bytes), V[s-1] read, V[s] written."""
+def level_bytes(N, D, esize=ESIZE):
+    """Algorithmic bytes of one DP level: every stage-time entry (i,j,r) read once (entries of
+    `esize` bytes), V[s-1] read, V[s] written."""
     return esize * D * N * (N + 1) // 2 + 2 * esize * (N + 1) * D
 
 
@@ -41,7 +50,7 @@ def make_workload(name):
     from paper_2103_16063_amd import synth
     if name == "c5":
         probs = synth.named_config(5)
-        label = "config5 batched sweep: 2048 searches, N=128, D in {8,16,32,64}, S<=16"
+        label = "config5 batched sweep: 2048 searches, N=128, D in {8,16,32,64}, S<=16, M=16GiB"
     elif name == "c4dense":
         pr = synth.named_config(4)
         pr["mem_capacity"] = 1 << 50
@@ -56,6 +65,55 @@ def make_workload(name):
     return probs, label
 
 
+def run_workload(name, steps, warmup):
+    """Times `steps` solve+traceback passes of one workload; returns the measurements."""
+    import torch
+    from paper_2103_16063_amd import binding as B
+    from paper_2103_16063_amd import synth
+
+    probs, label = make_workload(name)
+    U = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"]) for p in probs)
+    sess = B.Session(synth.concat_batch(probs))
+    B.rannc_dp_set_timing(sess.h, True)
+
+    def step():
+        sess.solve()
+        sess.traceback()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    phase = np.zeros(3)
+    launches = 0
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+        # per-phase device times of this step (HIP events recorded by the library on the solve's
+        # stream); waiting for them keeps one step in flight at a time: wall time = step latency
+        rc, ms, launches = B.rannc_dp_get_timing(sess.h)
+        assert rc == B.OK
+        phase += ms
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    res = sess.run()
+    sess.close()
+    phase /= steps
+    # algorithmic bytes of all level launches of one step
+    lvl_bytes = 0
+    for p in probs:
+        N, D = p["time_ns"].shape[0], p["n_devices"]
+        lvl_bytes += (min(p["max_stages"], N, D) - 1) * level_bytes(N, D)
+    per_launch_ms = phase[1] / max(launches, 1)
+    achieved = lvl_bytes / max(launches, 1) / (per_launch_ms * 1e-3) / 1e9
+    traffic = PMC_TRAFFIC_BYTES.get(name)
+    roof = {"bound": "hbm", "kernel": "level_merge_kernel (32-bit values)", "achieved": achieved,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": traffic, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
+            "algorithmic_bytes_per_launch": lvl_bytes / max(launches, 1)}
+    return {"probs": probs, "label": label, "U": U, "ms_per_step": wall / steps * 1e3,
+            "phase": phase, "launches": launches, "res": res, "roofline": roof}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +121,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true",
+                    help="skip the extra roofline_dense measurement (c4 workload only)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy first: the dispatch of known "
                          "size against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -73,90 +133,47 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2103_16063_amd import binding as B
-    from paper_2103_16063_amd import synth
-
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    probs, label = make_workload(args.workload)
-    U = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"]) for p in probs)
-    sess = B.Session(synth.concat_batch(probs))
-    esize = 4
-    B.rannc_dp_set_timing(sess.h, True)
-
-    def step():
-        sess.solve()
-        sess.traceback()
-
     if args.calibration_copy:
         src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda:0")
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    phase = np.zeros(3)
-    launches = 0
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-        # per-phase device times of this step (HIP events on the solve's stream); waiting for
-        # them also keeps one step in flight at a time, so wall time is per-step latency
-        rc, ms, launches = B.rannc_dp_get_timing(sess.h)
-        assert rc == B.OK
-        phase += ms
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall / args.steps * 1e3
-    res = sess.run()
-    phase /= args.steps
+        del src, dst
 
-    # roofline of the dominant kernel (the DP level kernel): algorithmic bytes of one level of
-    # every problem in the launch over the average duration of one level launch
-    if len(probs) == 1:
-        N, D = probs[0]["time_ns"].shape[0], probs[0]["n_devices"]
-        lb = level_bytes(N, D, esize)
-        per_launch_ms = phase[1] / max(launches, 1)
-        achieved = lb / (per_launch_ms * 1e-3) / 1e9
-    else:
-        # batched: launches are per (level, device-count class); use whole-phase totals
-        tot = 0
-        for p in probs:
-            N, D = p["time_ns"].shape[0], p["n_devices"]
-            L = min(p["max_stages"], N, D)
-            tot += (L - 1) * level_bytes(N, D, esize)
-        per_launch_ms = phase[1] / max(launches, 1)
-        achieved = tot / (phase[1] * 1e-3) / 1e9
+    m = run_workload(args.workload, args.steps, args.warmup)
+    probs, res, phase = m["probs"], m["res"], m["phase"]
     out = {
         "metric": "DP cell-updates/sec (definitional count, whole solve incl. table build and traceback)",
-        "value": U / (ms_per_step * 1e-3) / 1e9,
+        "value": m["U"] / (m["ms_per_step"] * 1e-3) / 1e9,
         "unit": "G cell-updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32" if esize == 4 else "u64", "data": "synthetic",
-        "config": {"workload": label, "n_problems": len(probs), "cell_updates": U},
+        "dtype": "u32", "data": "synthetic",
+        "config": {"workload": m["label"], "n_problems": len(probs), "cell_updates": m["U"]},
         "result": {"opt": int(res["opt"][0]), "n_stages": int(res["n_stages"][0])},
         "phases_ms": {"prefix_and_tables": float(phase[0]), "dp_levels": float(phase[1]),
-                      "select": float(phase[2]), "level_launches": int(launches)},
-        "level_updates_per_s_G": U / (phase[1] * 1e-3) / 1e9 if phase[1] > 0 else None,
-        "roofline": {"bound": "hbm", "kernel": "level_merge_kernel<u32,64>",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "avg_launch_ms": per_launch_ms},
+                      "select": float(phase[2]), "level_launches": int(m["launches"])},
+        "level_updates_per_s_G": m["U"] / (phase[1] * 1e-3) / 1e9 if phase[1] > 0 else None,
+        "roofline": m["roofline"],
     }
-    sess.close()
+    if args.workload == "c4" and not args.no_dense:
+        # the same kernel where nothing can be pruned: achieved ~ real traffic
+        dm = run_workload("c4dense", max(5, args.steps // 5), 2)
+        out["roofline_dense"] = dict(dm["roofline"], workload=dm["label"],
+                                     ms_per_step=dm["ms_per_step"])
 
     if not args.no_cpu_baseline:
         import oracle
-        pr = probs[0] if len(probs) == 1 else None
         threads = min(oracle.max_threads(), 16)
-        if pr is not None:
+        if len(probs) == 1:
+            pr = probs[0]
             t0 = time.perf_counter()
             o = oracle.solve(pr, n_threads=threads)
             dt = time.perf_counter() - t0
-            Ucpu = updates(pr["time_ns"].shape[0], pr["n_devices"], pr["max_stages"])
+            Ucpu = m["U"]
             sample = "the whole workload once (tables, all levels, traceback)"
             assert o["opt"] == int(res["opt"][0]) and o["n_stages"] == int(res["n_stages"][0])
         else:

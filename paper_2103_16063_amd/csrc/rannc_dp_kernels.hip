@@ -71,17 +71,19 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
     part[w][tid] = s;
   }
   __syncthreads();
-  if (tid < 3) {  // exclusive scan of the 256 segment sums, saturating
-    uint64_t run = 0;
-    for (int k = 0; k < 256; ++k) {
-      uint64_t v = part[tid][k];
-      part[tid][k] = run;
-      run += v; if (run > kSumLimit) run = kSumLimit;
+  // inclusive scan of the 256 segment sums (saturating add is associative on [0, limit])
+  for (int off = 1; off < 256; off <<= 1) {
+    uint64_t add[3];
+    for (int w = 0; w < 3; ++w) add[w] = tid >= off ? part[w][tid - off] : 0;
+    __syncthreads();
+    for (int w = 0; w < 3; ++w) {
+      uint64_t v = part[w][tid] + add[w];
+      part[w][tid] = v > kSumLimit ? kSumLimit : v;
     }
+    __syncthreads();
   }
-  __syncthreads();
   for (int w = 0; w < 3; ++w) {
-    uint64_t run = part[w][tid];
+    uint64_t run = tid ? part[w][tid - 1] : 0;  // sum of the segments before this thread's
     if (tid == 0) out[w][0] = 0;
     for (int k = lo; k < hi; ++k) {
       int64_t v = in[w][k];
