@@ -182,3 +182,28 @@ def test_rows_per_wave_variants(rows, monkeypatch):
             assert_results_match(probs, res)
             for q in range(3):
                 assert_tables_match(probs[q], sess, q, args=False)
+
+
+@pytest.mark.parametrize("width", WIDTHS)
+def test_random_batches_against_oracle(width):
+    """Several hundred random searches (chains of 1..200 blocks, every device count 1..64, tight
+    and loose memory, small value ranges that force ties) in batches of 64."""
+    g = np.random.default_rng(12345)
+    for batch in range(4):
+        probs = []
+        for q in range(64):
+            N = int(g.integers(1, 200))
+            D = int(g.integers(1, 65))
+            S = int(g.integers(1, 20))
+            pr = synth.random_small(7000 + 64 * batch + q, N, D, S,
+                                    tight=float(g.choice([0.8, 1.0, 1.2, 1.6, 3.0, 100.0])),
+                                    tmax=int(g.choice([1, 4, 1000, 10 ** 6])),
+                                    zero_time_frac=float(g.choice([0.0, 0.0, 0.3])))
+            if width > B.NARROW_MAX_TOTAL_TIME and q % 2:
+                pr["time_ns"] = pr["time_ns"] * (1 << 22)
+            probs.append(pr)
+        res, sess = gpu_run(probs, max_total_time_ns=width)
+        with sess:
+            assert_results_match(probs, res)
+            for q in (0, 13, 37, 63):
+                assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 80))
