@@ -65,7 +65,7 @@ def make_workload(name):
     return probs, label
 
 
-def run_workload(name, steps, warmup):
+def run_workload(name, steps, warmup, wide=False):
     """Times `steps` solve+traceback passes of one workload; returns the measurements."""
     import torch
     from paper_2103_16063_amd import binding as B
@@ -73,7 +73,8 @@ def run_workload(name, steps, warmup):
 
     probs, label = make_workload(name)
     U = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"]) for p in probs)
-    sess = B.Session(synth.concat_batch(probs))
+    sess = B.Session(synth.concat_batch(probs), max_total_time_ns=(1 << 60) if wide else B.NARROW_MAX_TOTAL_TIME)
+    esize = 8 if wide else ESIZE
     B.rannc_dp_set_timing(sess.h, True)
 
     def step():
@@ -102,11 +103,11 @@ def run_workload(name, steps, warmup):
     lvl_bytes = 0
     for p in probs:
         N, D = p["time_ns"].shape[0], p["n_devices"]
-        lvl_bytes += (min(p["max_stages"], N, D) - 1) * level_bytes(N, D)
+        lvl_bytes += (min(p["max_stages"], N, D) - 1) * level_bytes(N, D, esize)
     per_launch_ms = phase[1] / max(launches, 1)
     achieved = lvl_bytes / max(launches, 1) / (per_launch_ms * 1e-3) / 1e9
-    traffic = PMC_TRAFFIC_BYTES.get(name)
-    roof = {"bound": "hbm", "kernel": "level_merge_kernel (32-bit values)", "achieved": achieved,
+    traffic = None if wide else PMC_TRAFFIC_BYTES.get(name)
+    roof = {"bound": "hbm", "kernel": "level_merge_kernel (%d-bit values)" % (8 * esize), "achieved": achieved,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
             "algorithmic_bytes_per_launch": lvl_bytes / max(launches, 1)}
@@ -123,6 +124,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the extra roofline_dense measurement (c4 workload only)")
+    ap.add_argument("--wide", action="store_true",
+                    help="use a 64-bit handle (tables of 8-byte values) for the same inputs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy first: the dispatch of known "
                          "size against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -142,7 +145,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    m = run_workload(args.workload, args.steps, args.warmup)
+    m = run_workload(args.workload, args.steps, args.warmup, args.wide)
     probs, res, phase = m["probs"], m["res"], m["phase"]
     out = {
         "metric": "DP cell-updates/sec (definitional count, whole solve incl. table build and traceback)",
@@ -151,7 +154,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": m["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32", "data": "synthetic",
+        "dtype": "u64" if args.wide else "u32", "data": "synthetic",
         "config": {"workload": m["label"], "n_problems": len(probs), "cell_updates": m["U"]},
         "result": {"opt": int(res["opt"][0]), "n_stages": int(res["n_stages"][0])},
         "phases_ms": {"prefix_and_tables": float(phase[0]), "dp_levels": float(phase[1]),
@@ -159,7 +162,7 @@ def main():
         "level_updates_per_s_G": m["U"] / (phase[1] * 1e-3) / 1e9 if phase[1] > 0 else None,
         "roofline": m["roofline"],
     }
-    if args.workload == "c4" and not args.no_dense:
+    if args.workload == "c4" and not args.no_dense and not args.wide:
         # the same kernel where nothing can be pruned: achieved ~ real traffic
         dm = run_workload("c4dense", max(5, args.steps // 5), 2)
         out["roofline_dense"] = dict(dm["roofline"], workload=dm["label"],

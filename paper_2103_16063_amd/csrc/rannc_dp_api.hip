@@ -104,6 +104,8 @@ struct rannc_dp {
   bool ev_valid;
   int level_launches;
   int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
+  int fused_small;  // one-launch kernel for classes of small searches: 1 = where it pays (default),
+                    // 0 = never, 2 = whenever N <= 128 (RANNC_DP_FUSED_SMALL)
 };
 
 extern "C" {
@@ -167,6 +169,8 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->level_launches = 0;
   h->tune_spw = 0;
   if (const char *e = std::getenv("RANNC_DP_ROWS_PER_WAVE")) h->tune_spw = std::atoi(e);
+  h->fused_small = 1;
+  if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
   int made_staging = 0, made_ev_s = 0, made_ev = 0;
   bool ok = true;
@@ -323,30 +327,51 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   h->ev_valid = false;
   h->level_launches = 0;
   if (timing) ok = ok && hipEventRecord(h->ev[0], st) == hipSuccess;
-  ok = ok && rannc::launch_prefix(dp, Q, st) == hipSuccess;
-  ok = ok && rannc::launch_fill(dp, Q, st) == hipSuccess;
   int spw[4] = {1, 1, 1, 1};
+  bool fused[4] = {false, false, false, false};
   for (int k = 0; k < 4 && ok; ++k) {
     const LaunchShape &sh = shape[k];
     if (!sh.nprob) continue;
-    ok = rannc::launch_build(dp + cls_start[k], sh, h->bits, kClasses[k], st) == hipSuccess;
-    ok = ok && rannc::launch_windows(dp + cls_start[k], sh, st) == hipSuccess;  // also used by traceback
+    const ProblemDev *cp = dp + cls_start[k];
+    // Small searches: everything in one launch, one workgroup per search.  Measured on MI355X:
+    // it wins for batches at D <= 16 (no launch per level, levels folded in LDS) and for a lone
+    // tiny search; at D >= 32 a workgroup's waves work through too many table rows one after the
+    // other and the launch per level, which spreads the rows over the whole device, is faster.
+    {
+      const int64_t rows = std::min(sh.max_N, 64) + (sh.max_nch > 1 ? sh.max_N : 0);
+      const bool batch = sh.nprob >= 32 && kClasses[k] <= 16;
+      const bool tiny = rows * (sh.max_S_eff - 1) <= 256;
+      fused[k] = !scan && sh.max_N <= rannc::small_max_blocks() &&
+                 (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);
+    }
+    if (fused[k]) continue;
+    ok = rannc::launch_prefix(cp, sh.nprob, st) == hipSuccess;
+    ok = ok && rannc::launch_fill(cp, sh.nprob, st) == hipSuccess;
+    ok = ok && rannc::launch_build(cp, sh, h->bits, kClasses[k], st) == hipSuccess;
+    ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
     if (scan) continue;
     // One predecessor row per wave: measured best on every configuration (most waves in flight
     // to hide the latency of the row reads).  RANNC_DP_ROWS_PER_WAVE = 2 or 4 selects the variants
     // that keep several rows per wave with double-buffered reads.
     spw[k] = 1;
     if (h->tune_spw > 0) spw[k] = h->tune_spw;
-    ok = ok && rannc::launch_runs(dp + cls_start[k], sh.nprob, rannc::merge_rows_per_item(spw[k]), st) ==
-                   hipSuccess;
+    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(spw[k]), st) == hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;
-  for (int k = 0; k < 4; ++k) max_levels = std::max(max_levels, shape[k].max_S_eff);
+  for (int k = 0; k < 4; ++k) {
+    if (fused[k]) {
+      ok = ok && rannc::launch_solve_small(dp + cls_start[k], shape[k].nprob, h->bits, kClasses[k], d_opt,
+                                           d_n_stages, d_est_iter_ns, d_status, st) == hipSuccess;
+      h->level_launches++;
+    } else {
+      max_levels = std::max(max_levels, shape[k].max_S_eff);
+    }
+  }
   for (int s = 2; s <= max_levels && ok; ++s) {
     for (int k = 0; k < 4 && ok; ++k) {
       const LaunchShape &sh = shape[k];
-      if (!sh.nprob || sh.max_S_eff < s) continue;
+      if (!sh.nprob || sh.max_S_eff < s || fused[k]) continue;
       if (scan)
         ok = rannc::launch_level_scan(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;
@@ -357,7 +382,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     }
   }
   if (timing) ok = ok && hipEventRecord(h->ev[2], st) == hipSuccess;
-  ok = ok && rannc::launch_select(dp, Q, d_opt, d_n_stages, d_est_iter_ns, d_status, st) == hipSuccess;
+  for (int k = 0; k < 4 && ok; ++k)
+    if (shape[k].nprob && !fused[k])
+      ok = rannc::launch_select(dp + cls_start[k], shape[k].nprob, d_opt, d_n_stages, d_est_iter_ns,
+                                d_status, st) == hipSuccess;
   if (timing) ok = ok && hipEventRecord(h->ev[3], st) == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();

@@ -83,6 +83,10 @@ hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStr
 int merge_rows_per_item(int rows_per_wave);
 hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
                               int rows_per_wave, hipStream_t st);
+// whole search of problems with N <= small_max_blocks() in one launch, one workgroup each
+int small_max_blocks();
+hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, int64_t *d_opt,
+                              int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st);
 hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int bits, int s,
                              int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st);
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,

@@ -137,19 +137,20 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
 // ---------------------------------------------------------------------------------------
 constexpr int kBuildWaves = 4;
 
+// One unit (row i, chunk c) of the tables, by one wave.  T, P, A may live in global memory or in
+// LDS.  Returns whether any stage of the unit fits.  If lds_level1 is given, row 0's entries
+// (= level 1 of V) are also written there with row stride ls.
 template <typename VT, int DP>
-__global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs) {
-  const ProblemDev &pr = probs[blockIdx.z];
+__device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *T, const int64_t *P,
+                                           const int64_t *A, int i, int c, int lane, VT *lds_level1,
+                                           int ls) {
   const int N = pr.N, D = pr.D, nch = pr.nch;
-  const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
-  if (i >= N || c >= nch || c < (i >> 6)) return;
-  const int lane = threadIdx.x & 63;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
   const int j = valid ? jj + 1 : i + 1;  // padding lanes compute a harmless in-range stage
-  const int64_t Tij = pr.T[j] - pr.T[i];
-  const int64_t Pij = pr.P[j] - pr.P[i];
-  const int64_t Aij = pr.A[j] - pr.A[i];
+  const int64_t Tij = T[j] - T[i];
+  const int64_t Pij = P[j] - P[i];
+  const int64_t Aij = A[j] - A[i];
   // smallest r with Pij + ceil(Aij / r) <= M, using ceil(a/r) <= k  <=>  a <= k*r
   int rmin = 255;
   if (Pij <= pr.M) {
@@ -164,13 +165,13 @@ __global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDe
   const bool unit_fits = __ballot(fits) != 0ull;
   const int64_t u = unit_index(nch, i, c);
   if (lane == 0) pr.ufit[u] = (uint8_t)unit_fits;
-  if (!valid) return;
+  if (!valid) return unit_fits;
   pr.rmin[u * 64 + lane] = (uint8_t)rmin;
   // A unit in which no stage fits for any r is never read (every reader consults ufit or rmin
   // first): only those are written.  Row 0 also carries level 1 and is always written.
-  if (!unit_fits && i != 0) return;
-  VT *crow = (VT *)pr.cost + u * 64 * D + lane;
-  VT *v1 = (VT *)pr.V + (int64_t)j * DP;
+  if (!unit_fits && i != 0) return unit_fits;
+  VT RANNC_GLOBAL *crow = gptr((VT *)pr.cost) + u * 64 * D + lane;
+  VT RANNC_GLOBAL *v1 = gptr((VT *)pr.V) + (int64_t)j * DP;
   const VT tij = (VT)Tij;
 #pragma unroll
   for (int r = 1; r <= DP; ++r) {
@@ -179,8 +180,20 @@ __global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDe
     const VT h = q + (VT)(q * (VT)r != tij);    // ceil
     const VT v = (r >= rmin) ? h : Lim<VT>::inf;
     crow[(r - 1) * 64] = v;
-    if (i == 0) v1[r - 1] = v;
+    if (i == 0) {
+      v1[r - 1] = v;
+      if (lds_level1) lds_level1[j * ls + r - 1] = v;
+    }
   }
+  return unit_fits;
+}
+
+template <typename VT, int DP>
+__global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs) {
+  const ProblemDev &pr = probs[blockIdx.z];
+  const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
+  if (i >= pr.N || c >= pr.nch || c < (i >> 6)) return;
+  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, i, c, threadIdx.x & 63, nullptr, 0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -273,8 +286,8 @@ __device__ __forceinline__ void unit_load(VT (&x)[DP], const VT RANNC_GLOBAL *__
 }
 
 // x := the DP largest elements of merge(a, c), sorted descending (x holds c reversed on entry)
-template <typename VT, int DP>
-__device__ __forceinline__ void unit_sort(VT (&x)[DP], const VT RANNC_GLOBAL *__restrict__ arow) {
+template <typename VT, int DP, typename AP>
+__device__ __forceinline__ void unit_sort(VT (&x)[DP], AP arow) {
 #pragma unroll
   for (int q = 0; q < DP; ++q) x[q] = vmax(arow[q], x[q]);
 #pragma unroll
@@ -294,7 +307,7 @@ __device__ __forceinline__ void unit_sort(VT (&x)[DP], const VT RANNC_GLOBAL *__
 template <typename VT, int DP>
 __device__ __forceinline__ void unit_merge(VT (&acc)[DP], VT (&x)[DP],
                                            const VT RANNC_GLOBAL *__restrict__ arow) {
-  unit_sort<VT, DP>(x, arow);
+  unit_sort<VT, DP, const VT RANNC_GLOBAL *>(x, arow);
 #pragma unroll
   for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
 }
@@ -354,7 +367,7 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
     unit_load<VT, DP>(acc, cost + ubase[0] * 64 * D + lane, act[0], rl);
     if (__ballot(act[0]) != 0ull) {
       any = true;
-      unit_sort<VT, DP>(acc, Vprev + (int64_t)(i0 + wave) * DP);
+      unit_sort<VT, DP, const VT RANNC_GLOBAL *>(acc, Vprev + (int64_t)(i0 + wave) * DP);
     }
   } else {
 #pragma unroll
@@ -394,6 +407,145 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
     const VT v = tile[row * (DP + 1) + t];
     const int j = 64 * c + row + 1;
     if (t + 1 <= D - 1 && j <= N && j >= s && v != INF) global_min(&Vcur[(int64_t)j * DP + t + 1], v);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Whole search of a SMALL problem (N <= 128, i.e. at most two column chunks) in one workgroup and
+// one launch: prefix sums, tables, every level, choice of the stage count.  Same arithmetic as the
+// kernels above (the same build_unit / unit_load / unit_sort), but two consecutive levels of V
+// live in LDS, so the waves of the workgroup fold their merges with LDS atomics and meet at
+// workgroup barriers: no launch per level, no global atomics.  Every level is also copied to the
+// V table in memory (plan recovery and export read it there).  Meant for searches at the
+// paper's own scale (k = 32 blocks, D <= 32, Sec. IV-A) and for batches of them (the many
+// form_stage_dp calls of Algorithm 2): one workgroup per search.
+// ---------------------------------------------------------------------------------------
+constexpr int kSmallMaxN = 128;
+constexpr int kSmallWaves = 8;
+
+__device__ __forceinline__ void select_finish(const ProblemDev &pr, int64_t v, int st, int64_t *d_opt,
+                                              int32_t *d_n_stages, int64_t *d_est, int32_t *d_status);
+
+template <typename VT, int DP>
+__global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
+    const ProblemDev *__restrict__ probs, int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est,
+    int32_t *d_status) {
+  const ProblemDev pr = probs[blockIdx.x];
+  constexpr VT INF = Lim<VT>::inf;
+  constexpr int LS = DP + 1;  // row stride of a level in LDS: lanes (= columns) hit different banks
+  constexpr int NT = 64 * kSmallWaves;
+  __shared__ int64_t sT[kSmallMaxN + 1], sP[kSmallMaxN + 1], sA[kSmallMaxN + 1];
+  __shared__ uint64_t scan[3][kSmallMaxN];
+  __shared__ VT lv[2][(kSmallMaxN + 1) * LS];
+  __shared__ VT s_top[64];
+  __shared__ int s_flags, s_wlo[2];
+  const int N = pr.N, D = pr.D, nch = pr.nch, S_eff = pr.S_eff;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // ---- prefix sums and validation (as prefix_kernel) ----
+  if (tid == 0) { s_flags = 0; s_wlo[0] = kNoRow; s_wlo[1] = kNoRow; }
+  int myflags = 0;
+  if (tid < N) {
+    const int64_t *in[3] = {pr.t, pr.p, pr.a};
+    for (int w = 0; w < 3; ++w) {
+      int64_t v = in[w][tid];
+      if (v < 0) { myflags |= 1; v = 0; }
+      uint64_t u = (uint64_t)v;
+      if (u >= kSumLimit) { myflags |= 2; u = kSumLimit; }
+      scan[w][tid] = u;
+    }
+  }
+  __syncthreads();
+  for (int off = 1; off < kSmallMaxN; off <<= 1) {
+    uint64_t add[3] = {0, 0, 0};
+    if (tid < N && tid >= off)
+      for (int w = 0; w < 3; ++w) add[w] = scan[w][tid - off];
+    __syncthreads();
+    if (tid < N)
+      for (int w = 0; w < 3; ++w) {
+        const uint64_t v = scan[w][tid] + add[w];
+        scan[w][tid] = v > kSumLimit ? kSumLimit : v;
+      }
+    __syncthreads();
+  }
+  if (tid < N) {
+    if (scan[0][tid] >= kSumLimit || scan[1][tid] >= kSumLimit || scan[2][tid] >= kSumLimit) myflags |= 2;
+    sT[tid + 1] = (int64_t)scan[0][tid]; sP[tid + 1] = (int64_t)scan[1][tid]; sA[tid + 1] = (int64_t)scan[2][tid];
+    pr.T[tid + 1] = sT[tid + 1]; pr.P[tid + 1] = sP[tid + 1]; pr.A[tid + 1] = sA[tid + 1];
+  }
+  if (tid == 0) { sT[0] = sP[0] = sA[0] = 0; pr.T[0] = pr.P[0] = pr.A[0] = 0; }
+  if (myflags) atomicOr(&s_flags, myflags);
+  // level 1 buffer: "no plan" everywhere, padding columns 0
+  for (int e = tid; e < (N + 1) * LS; e += NT) lv[0][e] = ((e % LS) < D) ? INF : (VT)0;
+  __syncthreads();
+  int st = RANNC_DP_PROBLEM_OK;
+  if (s_flags & 1) st = RANNC_DP_PROBLEM_NEGATIVE_INPUT;
+  else if (s_flags & 2) st = RANNC_DP_PROBLEM_SUM_OVERFLOW;
+  else if (sT[N] > pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
+  if (tid == 0) *pr.status = st;
+
+  // ---- tables (as build_kernel): rows 0..min(63,N-1) of chunk 0, then rows 0..N-1 of chunk 1 ----
+  const int R0 = min(64, N), RT = R0 + (nch > 1 ? N : 0);
+  for (int f = wave; f < RT; f += kSmallWaves) {
+    const int c = f >= R0, i = c ? f - R0 : f;
+    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, i, c, lane, lv[0], LS);
+    if (fits && lane == 0) atomicMin(&s_wlo[c], i);
+  }
+  __syncthreads();
+  if (tid < nch) pr.wlo[tid] = s_wlo[tid];
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  VT RANNC_GLOBAL *Vg = gptr((VT *)pr.V);
+  const VT RANNC_GLOBAL *cost = gptr((const VT *)pr.cost);
+  const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
+  // level 1, rows that build_unit did not touch (j = 0) and the padding columns, to memory
+  for (int e = tid; e < (N + 1) * DP; e += NT) {
+    const int j = e / DP, k = e % DP;
+    if (j == 0 || k >= D) Vg[e] = lv[0][j * LS + k];
+  }
+  if (tid == 0) s_top[0] = lv[0][N * LS + D - 1];
+
+  // ---- levels 2..S_eff ----
+  for (int s = 2; s <= S_eff; ++s) {
+    const VT *prev = lv[s & 1];        // level s-1
+    VT *cur = lv[(s - 1) & 1];         // level s
+    const int rl = D - s + 1;
+    for (int e = tid; e < (N + 1) * LS; e += NT) cur[e] = ((e % LS) < D) ? INF : (VT)0;
+    __syncthreads();
+    for (int f = wave; f < RT; f += kSmallWaves) {
+      const int c = f >= R0, i = c ? f - R0 : f;
+      if (i < s - 1 || i < s_wlo[c] || 64 * c + 64 < s) continue;
+      if (prev[i * LS + D - 1] == INF) continue;  // no (s-1)-stage plan covers blocks 1..i
+      const int jj = 64 * c + lane;
+      const int64_t u = unit_index(nch, i, c);
+      int rmn = 255;
+      if (jj >= i && jj < N) rmn = rmin[u * 64 + lane];
+      const bool act = rmn <= rl;
+      if (__ballot(act) == 0ull) continue;
+      VT x[DP];
+      unit_load<VT, DP>(x, cost + u * 64 * D + lane, act, rl);
+      unit_sort<VT, DP, const VT *>(x, prev + i * LS);
+      if (act && jj + 1 >= s) {
+#pragma unroll
+        for (int t = 0; t < DP - 1; ++t)
+          if (t + 1 <= D - 1 && x[t] != INF) atomicMin(&cur[(jj + 1) * LS + t + 1], x[t]);
+      }
+    }
+    __syncthreads();
+    VT RANNC_GLOBAL *Vs = Vg + (int64_t)(s - 1) * lvl;
+    for (int e = tid; e < (N + 1) * DP; e += NT) Vs[e] = cur[(e / DP) * LS + (e % DP)];
+    if (tid == 0) s_top[s - 1] = cur[N * LS + D - 1];
+  }
+  __syncthreads();
+
+  // ---- choice of the stage count (as select_kernel) ----
+  if (wave == 0) {
+    int64_t v = INT64_MAX;
+    if (st == 0 && lane < S_eff) {
+      const VT u = s_top[lane];
+      v = (u == INF) ? INT64_MAX : (int64_t)u;
+    }
+    select_finish(pr, v, st, d_opt, d_n_stages, d_est, d_status);
   }
 }
 
@@ -449,24 +601,11 @@ __global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__rest
 // Final choice of the stage count: opt = min over s of V[s][N][D], smallest s among equals.
 // One wave per problem, lane s-1 reads V[s][N][D] (S_eff <= D <= 64).
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict__ probs,
-                                                    int64_t *d_opt, int32_t *d_n_stages,
-                                                    int64_t *d_est, int32_t *d_status) {
-  const ProblemDev &pr = probs[blockIdx.x];
+// one wave: lane s-1 brings V[s][N][D] (INT64_MAX beyond S_eff or if the status is bad)
+__device__ __forceinline__ void select_finish(const ProblemDev &pr, int64_t v, int st, int64_t *d_opt,
+                                              int32_t *d_n_stages, int64_t *d_est, int32_t *d_status) {
+  const int lane = threadIdx.x & 63;
   const int q = pr.q;
-  const int lane = threadIdx.x;
-  const int st = *pr.status;
-  int64_t v = INT64_MAX;
-  if (st == 0 && lane < pr.S_eff) {
-    const int64_t lvl = (int64_t)(pr.N + 1) * pr.DP;
-    const int64_t cell = (int64_t)pr.N * pr.DP + pr.D - 1;
-    if (pr.bits == 32) {
-      const uint32_t u = ((const uint32_t *)pr.V)[lane * lvl + cell];
-      v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
-    } else {
-      v = (int64_t)((const uint64_t *)pr.V)[lane * lvl + cell];
-    }
-  }
   // lexicographic minimum of (value, s): fewest stages among equal values
   int bs = lane + 1;
 #pragma unroll
@@ -491,6 +630,26 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
     d_est[q] = e;
   }
   if (d_status) d_status[q] = st;
+}
+
+__global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict__ probs,
+                                                    int64_t *d_opt, int32_t *d_n_stages,
+                                                    int64_t *d_est, int32_t *d_status) {
+  const ProblemDev &pr = probs[blockIdx.x];
+  const int lane = threadIdx.x;
+  const int st = *pr.status;
+  int64_t v = INT64_MAX;
+  if (st == 0 && lane < pr.S_eff) {
+    const int64_t lvl = (int64_t)(pr.N + 1) * pr.DP;
+    const int64_t cell = (int64_t)pr.N * pr.DP + pr.D - 1;
+    if (pr.bits == 32) {
+      const uint32_t u = ((const uint32_t *)pr.V)[lane * lvl + cell];
+      v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
+    } else {
+      v = (int64_t)((const uint64_t *)pr.V)[lane * lvl + cell];
+    }
+  }
+  select_finish(pr, v, st, d_opt, d_n_stages, d_est, d_status);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -761,6 +920,20 @@ hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bi
   }
   GO(32, uint32_t)
   GO(64, uint64_t)
+#undef GO
+  return hipGetLastError();
+}
+
+int small_max_blocks() { return kSmallMaxN; }
+
+hipError_t launch_solve_small(const ProblemDev *p, int Q, int bits, int DP, int64_t *d_opt,
+                              int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st) {
+#define GO(B, T, W)                                                                              \
+  if (bits == B && DP == W)                                                                      \
+    hipLaunchKernelGGL((solve_small_kernel<T, W>), dim3(Q), dim3(64 * kSmallWaves), 0, st, p, d_opt, \
+                       d_n_stages, d_est, d_status);
+  GO(32, uint32_t, 8) GO(32, uint32_t, 16) GO(32, uint32_t, 32) GO(32, uint32_t, 64)
+  GO(64, uint64_t, 8) GO(64, uint64_t, 16) GO(64, uint64_t, 32) GO(64, uint64_t, 64)
 #undef GO
   return hipGetLastError();
 }

@@ -207,3 +207,26 @@ def test_random_batches_against_oracle(width):
             assert_results_match(probs, res)
             for q in (0, 13, 37, 63):
                 assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 80))
+
+
+@pytest.mark.parametrize("mode", ["0", "2"])
+@pytest.mark.parametrize("width", WIDTHS)
+def test_small_search_kernel_on_and_off(mode, width, monkeypatch):
+    """Searches of at most 128 blocks can run as one launch with one workgroup per search (levels
+    folded in LDS) or through the per-level launches; the library chooses by batch shape.  Both
+    are forced here (0 = never, 2 = always) on the same inputs: identical tables, optimum, plan."""
+    monkeypatch.setenv("RANNC_DP_FUSED_SMALL", mode)
+    g = np.random.default_rng(99)
+    probs = [synth.named_config(1), synth.named_config(2)]
+    for q in range(30):
+        N = int(g.integers(1, 129))
+        D = int(g.choice([1, 2, 4, 7, 8, 9, 16, 17, 32, 33, 64]))
+        probs.append(synth.random_small(4000 + q, N, D, int(g.integers(1, 18)),
+                                        tight=float(g.choice([0.9, 1.2, 2.0, 50.0])),
+                                        tmax=int(g.choice([2, 1000, 10 ** 6])),
+                                        zero_time_frac=float(g.choice([0.0, 0.25]))))
+    res, sess = gpu_run(probs, max_total_time_ns=width)
+    with sess:
+        assert_results_match(probs, res)
+        for q in range(0, len(probs), 3):
+            assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
