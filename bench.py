@@ -29,7 +29,8 @@ ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configuratio
 PMC_TRAFFIC_BYTES = {
     "c4": 26.97e6,        # profiles/level_merge_config4.md: 24.41 MB fetched + 2.56 MB written
     "c4dense": 115.86e6,  # profiles/level_merge_config4_dense.md: 102.51 MB + 13.35 MB
-    "c5": 503.1e6,        # profiles/level_merge_config5_batched.md: mean over the 52 launches of a step
+    "c5": 811.8e6,        # profiles/level_merge_config5_batched.md: 25 978 MB per step over its 32 launches
+                          # (30 level launches at D = 32, 64 and the two one-launch kernels at D = 8, 16)
 }
 
 
