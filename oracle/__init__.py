@@ -154,3 +154,64 @@ def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=Non
     if keep_tables:
         out.update(T=T, P=P, A=A, cost=cost, fit=fit, V=V, arg_i=ai, arg_d=ad)
     return out
+
+
+def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: int,
+               devices_per_node: int, batch_size: int, mem_capacity: int, n_threads: int = 1):
+    """Outer driver of the search (Algorithm 2 "form_stage" of Sec. III-C), loops in the paper's
+    order: node count n = 1, 2, 4, ... <= n_nodes; D = devices_per_node * n devices, replica factor
+    R = n_nodes / n; stage count S ascending over (devices_per_node*(n-1), devices_per_node*n]; for
+    each S every microbatch count MB = 1, 2, 4, ... <= floor(batch_size / R) is tried with
+    form_stage_dp for EXACTLY S stages (Algorithm 1's answer V[S][|B|][D]); the first S with a
+    feasible MB returns the best of its solutions.
+
+    Readings (the paper leaves them open): a block's time and transient bytes grow linearly with
+    the samples of a microbatch on one pipeline replica, b = floor(batch_size / R / MB), its
+    persistent bytes do not; "best" = smallest (MB + S - 1) * V, the time of one synchronous
+    pipeline iteration (Fig. 1), the first found among equals (smallest MB); R is the integer
+    quotient.  The DP for one (n, MB) yields every exact-S value at once, so it is memoised.
+
+    Returns None if infeasible, else a dict with n, devices (D), replica_factor (R), n_stages (S),
+    n_microbatches (MB), stage_time_ns (V), est_iter_ns, stage_end[S], replicas[S] (d_i, before
+    the factor R)."""
+    ts = np.ascontiguousarray(time_per_sample_ns, dtype=np.int64)
+    as_ = np.ascontiguousarray(act_bytes_per_sample, dtype=np.int64)
+    pp = np.ascontiguousarray(param_bytes, dtype=np.int64)
+    N = int(ts.shape[0])
+    if n_nodes < 1 or devices_per_node < 1 or batch_size < 1 or mem_capacity < 0:
+        raise OracleError("bad scalar argument")
+    memo = {}
+
+    def dp_tables(n, MB):
+        if (n, MB) not in memo:
+            D = devices_per_node * n
+            R = n_nodes // n
+            b = batch_size // R // MB
+            T, P, A = prefix(ts * b), prefix(pp), prefix(as_ * b)
+            cost, fit = tables(T, P, A, D, mem_capacity)
+            memo[(n, MB)] = dp(N, D, min(D, N), cost, fit, n_threads)
+        return memo[(n, MB)]
+
+    n = 1
+    while n <= n_nodes:
+        D = devices_per_node * n
+        R = n_nodes // n
+        for S in range(devices_per_node * (n - 1) + 1, devices_per_node * n + 1):
+            best = None
+            MB = 1
+            while MB <= batch_size // R:
+                if S <= min(N, D):
+                    V, ai, ad = dp_tables(n, MB)
+                    v = int(V[S, N, D])
+                    if v != INF:
+                        est = (MB + S - 1) * v
+                        if best is None or est < best["est_iter_ns"]:
+                            se, rp = traceback(ai, ad, S, S)
+                            best = {"n": n, "devices": D, "replica_factor": R, "n_stages": S,
+                                    "n_microbatches": MB, "stage_time_ns": v, "est_iter_ns": est,
+                                    "stage_end": se, "replicas": rp}
+                MB *= 2
+            if best is not None:
+                return best
+        n *= 2
+    return None
