@@ -137,6 +137,68 @@ RANNC_DP_API int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *batch, vo
 RANNC_DP_API int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride,
                        int32_t *d_stage_end, int32_t *d_replicas);
 
+/* As rannc_dp_traceback, but for problem q the plan of EXACTLY d_levels[q] stages is recovered
+ * (Algorithm 1's own answer, "b_i and d_i that produce V[S][|B|][D]", for a given S) when
+ * d_levels[q] > 0; all slots are -1 if no plan of that many stages exists.  d_levels[q] == 0 or
+ * d_levels == NULL: the best stage count chosen by solve.  d_levels: DEVICE int32[Q]. */
+RANNC_DP_API int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels,
+                                       int32_t plan_stride, int32_t *d_stage_end, int32_t *d_replicas);
+
+/* V[s][N][D] of the last solve for every exact stage count: d_values[q*stride + s-1], s = 1..stride
+ * (DEVICE int64), INT64_MAX where no plan of exactly s stages exists or s > min(S_q,N_q,D_q).
+ * stride must be >= min(S_q,N_q,D_q) for every problem. */
+RANNC_DP_API int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t stride, int64_t *d_values);
+
+/* Outer driver of the search: Algorithm 2 "form_stage(N, D_node, BS)" of Sec. III-C.  For node
+ * counts n = 1, 2, 4, ... <= n_nodes (D = devices_per_node * n devices, replica factor
+ * R = n_nodes / n), stage counts S ascending over (devices_per_node*(n-1), devices_per_node*n] and
+ * microbatch counts MB = 1, 2, 4, ... <= floor(batch_size / R), form_stage_dp is asked for a plan
+ * of exactly S stages; the first S with any feasible MB returns the best of its solutions.
+ * All these searches run as ONE batch through rannc_dp_solve on the given handle; the loops then
+ * run over the per-level values on the host.  Readings where the paper is silent: a block's time
+ * and transient bytes are linear in the b = floor(batch_size / R / MB) samples of a microbatch on
+ * one pipeline replica (inputs are per sample), persistent bytes are not scaled; "best" is the
+ * smallest (MB + S - 1) * V (one synchronous pipeline iteration, Fig. 1), the smallest MB among
+ * equals.  This call is synchronous: it waits for the stream twice.
+ *   h            handle whose limits cover rannc_dp_form_stage_problems(in) problems of n_blocks
+ *                blocks, devices_per_node * n_max devices and as many stages
+ *   d_scratch    DEVICE memory, 256-byte aligned, rannc_dp_form_stage_scratch_bytes(in) bytes
+ *   out          HOST result; out->feasible == 0 means INFEASIBLE (not an error)
+ *   stage_end, replicas  HOST int32[plan_stride]: the plan as in rannc_dp_traceback (replicas
+ *                before the factor R: stage u runs on replicas[u] * R devices in total)
+ * Errors: INVALID_ARG (bad sizes, negative inputs, devices_per_node * n_max > 64,
+ * plan_stride < min(devices_per_node * n_max, n_blocks)), OVERFLOW (scaled inputs or their sums
+ * exceed the handle's value width or 2^62), LIMIT_EXCEEDED / WORKSPACE_TOO_SMALL from solve. */
+typedef struct {
+  int32_t n_blocks;                   /* N >= 1 */
+  int32_t n_nodes;                    /* >= 1; only n = 1, 2, 4, ... <= n_nodes are visited */
+  int32_t devices_per_node;           /* D_node >= 1 */
+  int32_t reserved;                   /* must be 0 */
+  int64_t batch_size;                 /* BS >= 1 samples per iteration */
+  int64_t mem_capacity;               /* M bytes */
+  const int64_t *time_per_sample_ns;  /* HOST [N] fwd+bwd time of a block for one sample */
+  const int64_t *act_bytes_per_sample;/* HOST [N] transient bytes of a block for one sample */
+  const int64_t *param_bytes;         /* HOST [N] persistent per-replica bytes */
+} rannc_dp_form_stage_in_t;
+
+typedef struct {
+  int32_t feasible;        /* 0: INFEASIBLE, every other field 0 and the plan -1 */
+  int32_t n;               /* nodes per pipeline replica */
+  int32_t devices;         /* D = devices_per_node * n */
+  int32_t replica_factor;  /* R = n_nodes / n */
+  int32_t n_stages;        /* S */
+  int32_t n_microbatches;  /* MB */
+  int64_t stage_time_ns;   /* V[S][N][D]: slowest stage, one microbatch */
+  int64_t est_iter_ns;     /* (MB + S - 1) * stage_time_ns, saturating */
+} rannc_dp_form_stage_out_t;
+
+RANNC_DP_API int32_t rannc_dp_form_stage_problems(const rannc_dp_form_stage_in_t *in); /* 0 if invalid */
+RANNC_DP_API size_t rannc_dp_form_stage_scratch_bytes(const rannc_dp_form_stage_in_t *in);
+RANNC_DP_API int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void *hip_stream,
+                                     void *d_scratch, size_t scratch_bytes,
+                                     rannc_dp_form_stage_out_t *out, int32_t *stage_end,
+                                     int32_t *replicas, int32_t plan_stride);
+
 /* Export one table of one problem of the last solve in a layout-independent form, for parity
  * checks and inspection (not part of the timed path).  d_dst is DEVICE memory of `bytes`
  * bytes; with D = D_q, N = N_q, L = min(S_q,N_q,D_q):

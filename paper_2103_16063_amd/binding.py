@@ -28,7 +28,9 @@ NARROW_MAX_TOTAL_TIME = 4294967294
 
 EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp_create",
            "rannc_dp_solve", "rannc_dp_traceback", "rannc_dp_read_table", "rannc_dp_destroy",
-           "rannc_dp_strerror", "rannc_dp_set_timing", "rannc_dp_get_timing"]
+           "rannc_dp_strerror", "rannc_dp_set_timing", "rannc_dp_get_timing",
+           "rannc_dp_traceback_at", "rannc_dp_level_values", "rannc_dp_form_stage_problems",
+           "rannc_dp_form_stage_scratch_bytes", "rannc_dp_form_stage"]
 
 
 class Limits(C.Structure):
@@ -43,6 +45,19 @@ class Batch(C.Structure):
                 ("n_microbatches", C.c_void_p), ("mem_capacity", C.c_void_p),
                 ("block_offset", C.c_void_p),
                 ("time_ns", C.c_void_p), ("param_bytes", C.c_void_p), ("act_bytes", C.c_void_p)]
+
+
+class FormStageIn(C.Structure):
+    _fields_ = [("n_blocks", C.c_int32), ("n_nodes", C.c_int32), ("devices_per_node", C.c_int32),
+                ("reserved", C.c_int32), ("batch_size", C.c_int64), ("mem_capacity", C.c_int64),
+                ("time_per_sample_ns", C.c_void_p), ("act_bytes_per_sample", C.c_void_p),
+                ("param_bytes", C.c_void_p)]
+
+
+class FormStageOut(C.Structure):
+    _fields_ = [("feasible", C.c_int32), ("n", C.c_int32), ("devices", C.c_int32),
+                ("replica_factor", C.c_int32), ("n_stages", C.c_int32), ("n_microbatches", C.c_int32),
+                ("stage_time_ns", C.c_int64), ("est_iter_ns", C.c_int64)]
 
 
 class RanncDpError(RuntimeError):
@@ -83,6 +98,17 @@ def lib():
         L.rannc_dp_set_timing.restype = C.c_int
         L.rannc_dp_get_timing.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
         L.rannc_dp_get_timing.restype = C.c_int
+        L.rannc_dp_traceback_at.argtypes = [vp, vp, vp, C.c_int32, vp, vp]
+        L.rannc_dp_traceback_at.restype = C.c_int
+        L.rannc_dp_level_values.argtypes = [vp, vp, C.c_int32, vp]
+        L.rannc_dp_level_values.restype = C.c_int
+        L.rannc_dp_form_stage_problems.argtypes = [C.POINTER(FormStageIn)]
+        L.rannc_dp_form_stage_problems.restype = C.c_int32
+        L.rannc_dp_form_stage_scratch_bytes.argtypes = [C.POINTER(FormStageIn)]
+        L.rannc_dp_form_stage_scratch_bytes.restype = sz
+        L.rannc_dp_form_stage.argtypes = [vp, C.POINTER(FormStageIn), vp, vp, sz,
+                                          C.POINTER(FormStageOut), vp, vp, C.c_int32]
+        L.rannc_dp_form_stage.restype = C.c_int
         _lib = L
     return _lib
 
@@ -150,6 +176,47 @@ def rannc_dp_solve(handle, batch: HostBatch, stream, d_opt, d_n_stages, d_est_it
 def rannc_dp_traceback(handle, stream, plan_stride: int, d_stage_end, d_replicas) -> int:
     return lib().rannc_dp_traceback(handle, _ptr(stream), int(plan_stride), _ptr(d_stage_end),
                                     _ptr(d_replicas))
+
+
+def rannc_dp_traceback_at(handle, stream, d_levels, plan_stride: int, d_stage_end, d_replicas) -> int:
+    return lib().rannc_dp_traceback_at(handle, _ptr(stream), _ptr(d_levels), int(plan_stride),
+                                       _ptr(d_stage_end), _ptr(d_replicas))
+
+
+def rannc_dp_level_values(handle, stream, stride: int, d_values) -> int:
+    return lib().rannc_dp_level_values(handle, _ptr(stream), int(stride), _ptr(d_values))
+
+
+class HostFormStageIn:
+    """Keeps the HOST arrays of a form_stage input alive next to the C struct."""
+
+    def __init__(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes,
+                 devices_per_node, batch_size, mem_capacity):
+        self.keep = [np.ascontiguousarray(time_per_sample_ns, dtype=np.int64),
+                     np.ascontiguousarray(act_bytes_per_sample, dtype=np.int64),
+                     np.ascontiguousarray(param_bytes, dtype=np.int64)]
+        self.struct = FormStageIn(int(self.keep[0].shape[0]), int(n_nodes), int(devices_per_node), 0,
+                                  int(batch_size), int(mem_capacity), *[_ptr(a) for a in self.keep])
+
+
+def rannc_dp_form_stage_problems(fin: HostFormStageIn) -> int:
+    return int(lib().rannc_dp_form_stage_problems(C.byref(fin.struct)))
+
+
+def rannc_dp_form_stage_scratch_bytes(fin: HostFormStageIn) -> int:
+    return int(lib().rannc_dp_form_stage_scratch_bytes(C.byref(fin.struct)))
+
+
+def rannc_dp_form_stage(handle, fin: HostFormStageIn, stream, d_scratch, scratch_bytes: int,
+                        plan_stride: int):
+    """Returns (status, FormStageOut, stage_end[plan_stride], replicas[plan_stride]) (HOST arrays)."""
+    out = FormStageOut()
+    se = np.full(plan_stride, -2, dtype=np.int32)
+    rp = np.full(plan_stride, -2, dtype=np.int32)
+    rc = lib().rannc_dp_form_stage(handle, C.byref(fin.struct), _ptr(stream), _ptr(d_scratch),
+                                   int(scratch_bytes), C.byref(out), _ptr(se), _ptr(rp),
+                                   int(plan_stride))
+    return rc, out, se, rp
 
 
 def rannc_dp_read_table(handle, which: int, problem: int, d_dst, nbytes: int, stream) -> int:
@@ -268,3 +335,50 @@ class Session:
 
     def __exit__(self, *a):
         self.close()
+
+
+class FormStageSession:
+    """Owns handle, workspace and scratch for rannc_dp_form_stage calls on inputs of one shape."""
+
+    def __init__(self, n_blocks, n_nodes, devices_per_node, batch_size, *,
+                 max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.dev = torch.device(device)
+        self.shape = (int(n_blocks), int(n_nodes), int(devices_per_node), int(batch_size))
+        probe = HostFormStageIn(np.zeros(n_blocks), np.zeros(n_blocks), np.zeros(n_blocks), n_nodes,
+                                devices_per_node, batch_size, 0)
+        self.Q = rannc_dp_form_stage_problems(probe)
+        if self.Q == 0:
+            raise RanncDpError(INVALID_ARG, "rannc_dp_form_stage_problems")
+        n_max = 1
+        while 2 * n_max <= n_nodes:
+            n_max *= 2
+        self.max_D = devices_per_node * n_max
+        self.plan_stride = self.max_D
+        self.limits = make_limits(self.Q, n_blocks, self.max_D, min(self.max_D, n_blocks),
+                                  max_total_time_ns, algo)
+        self.ws_bytes = rannc_dp_workspace_bytes(self.limits)
+        if self.ws_bytes == 0:
+            raise RanncDpError(INVALID_ARG, "workspace size query")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.dev)
+        rc, self.h = rannc_dp_create(self.limits, self.ws, self.ws_bytes)
+        if rc != OK:
+            raise RanncDpError(rc, "rannc_dp_create")
+        self.scratch_bytes = rannc_dp_form_stage_scratch_bytes(probe)
+        self.scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.dev)
+
+    def run(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, mem_capacity):
+        n_blocks, n_nodes, dn, bs = self.shape
+        fin = HostFormStageIn(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes, dn, bs,
+                              mem_capacity)
+        assert fin.struct.n_blocks == n_blocks
+        stream = self.torch.cuda.current_stream(self.dev).cuda_stream
+        return rannc_dp_form_stage(self.h, fin, stream, self.scratch, self.scratch_bytes,
+                                   self.plan_stride)
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.torch.cuda.synchronize(self.dev)
+            rannc_dp_destroy(self.h)
+            self.h = None

@@ -399,17 +399,224 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   return RANNC_DP_OK;
 }
 
-int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride, int32_t *d_stage_end,
-                       int32_t *d_replicas) {
+int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels, int32_t plan_stride,
+                          int32_t *d_stage_end, int32_t *d_replicas) {
   if (!h || !d_stage_end || !d_replicas || plan_stride < 1) return RANNC_DP_INVALID_ARG;
   if (!h->solved) return RANNC_DP_BAD_STATE;
   for (int q = 0; q < h->Q; ++q)
     if (h->host_probs[q].S_eff > plan_stride) return RANNC_DP_INVALID_ARG;
-  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas,
+  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas, d_levels,
                               (hipStream_t)hip_stream) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
   }
+  return RANNC_DP_OK;
+}
+
+int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride, int32_t *d_stage_end,
+                       int32_t *d_replicas) {
+  return rannc_dp_traceback_at(h, hip_stream, nullptr, plan_stride, d_stage_end, d_replicas);
+}
+
+int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t stride, int64_t *d_values) {
+  if (!h || !d_values || stride < 1) return RANNC_DP_INVALID_ARG;
+  if (!h->solved) return RANNC_DP_BAD_STATE;
+  for (int q = 0; q < h->Q; ++q)
+    if (h->host_probs[q].S_eff > stride) return RANNC_DP_INVALID_ARG;
+  if (rannc::launch_level_values(h->d_probs, h->Q, stride, d_values, (hipStream_t)hip_stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  return RANNC_DP_OK;
+}
+
+// ---- Algorithm 2 ("form_stage"): host-level driver over one batched solve ---------------------
+namespace {
+
+struct FsPair { int n, MB; int64_t b; };
+
+// the (n, MB) pairs Algorithm 2 can visit, in its order; false if the input is invalid
+bool fs_pairs(const rannc_dp_form_stage_in_t *in, std::vector<FsPair> *out, int *max_D) {
+  if (!in || in->n_blocks < 1 || in->n_nodes < 1 || in->devices_per_node < 1 || in->batch_size < 1 ||
+      in->mem_capacity < 0 || in->reserved != 0)
+    return false;
+  *max_D = 0;
+  for (int64_t n = 1; n <= in->n_nodes; n *= 2) {
+    const int64_t D = (int64_t)in->devices_per_node * n;
+    if (D > RANNC_DP_MAX_DEVICES) return false;
+    *max_D = (int)D;
+    const int64_t R = in->n_nodes / n;
+    for (int64_t MB = 1; MB <= in->batch_size / R; MB *= 2) {
+      if (out) out->push_back({(int)n, (int)MB, in->batch_size / R / MB});
+      if (MB > (1 << 29)) break;
+    }
+  }
+  return true;
+}
+
+size_t fs_scratch(int Q, int N, int stride) {
+  size_t b = 0;
+  b += 3 * align_up((size_t)Q * N * 8);       // scaled time, param, act
+  b += 2 * align_up((size_t)Q * 8);           // opt, (n_stages + status as int32 pairs)
+  b += align_up((size_t)Q * stride * 8);      // per-level values
+  b += align_up((size_t)Q * 4);               // forced levels
+  b += 2 * align_up((size_t)Q * stride * 4);  // plan
+  return b;
+}
+
+}  // namespace
+
+int32_t rannc_dp_form_stage_problems(const rannc_dp_form_stage_in_t *in) {
+  std::vector<FsPair> pairs;
+  int max_D = 0;
+  try {
+    if (!fs_pairs(in, &pairs, &max_D)) return 0;
+  } catch (...) {
+    return 0;
+  }
+  return (int32_t)pairs.size();
+}
+
+size_t rannc_dp_form_stage_scratch_bytes(const rannc_dp_form_stage_in_t *in) {
+  const int Q = rannc_dp_form_stage_problems(in);
+  int max_D = 0;
+  if (Q == 0 || !fs_pairs(in, nullptr, &max_D)) return 0;
+  return fs_scratch(Q, in->n_blocks, max_D);
+}
+
+int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void *hip_stream,
+                        void *d_scratch, size_t scratch_bytes, rannc_dp_form_stage_out_t *out,
+                        int32_t *stage_end, int32_t *replicas, int32_t plan_stride) {
+  if (!h || !in || !out || !stage_end || !replicas || !d_scratch) return RANNC_DP_INVALID_ARG;
+  if (!in->time_per_sample_ns || !in->act_bytes_per_sample || !in->param_bytes) return RANNC_DP_INVALID_ARG;
+  std::vector<FsPair> pairs;
+  int max_D = 0;
+  std::vector<int64_t> ht, hp, ha, hvals, hM, hoff;
+  std::vector<int32_t> hN, hD, hS, hMB, hlev, hns, hse, hrp;
+  const int N = in->n_blocks;
+  try {
+    if (!fs_pairs(in, &pairs, &max_D)) return RANNC_DP_INVALID_ARG;
+  } catch (...) {
+    return RANNC_DP_NO_HOST_MEMORY;
+  }
+  const int Q = (int)pairs.size();
+  if (Q == 0) return RANNC_DP_INVALID_ARG;
+  const int stride = max_D;
+  if (plan_stride < std::min(stride, N)) return RANNC_DP_INVALID_ARG;
+  if (scratch_bytes < fs_scratch(Q, N, stride)) return RANNC_DP_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)d_scratch % kAlign) != 0) return RANNC_DP_INVALID_ARG;
+  try {
+    ht.resize((size_t)Q * N); hp.resize((size_t)Q * N); ha.resize((size_t)Q * N);
+    hvals.resize((size_t)Q * stride); hM.assign(Q, in->mem_capacity); hoff.resize(Q + 1);
+    hN.assign(Q, N); hD.resize(Q); hS.resize(Q); hMB.resize(Q); hlev.assign(Q, 0); hns.resize(2 * (size_t)Q);
+    hse.resize(stride); hrp.resize(stride);
+  } catch (...) {
+    return RANNC_DP_NO_HOST_MEMORY;
+  }
+  // per-microbatch inputs of every (n, MB): b samples on one pipeline replica
+  const __int128 lim = (__int128)1 << 62;
+  for (int q = 0; q < Q; ++q) {
+    hD[q] = in->devices_per_node * pairs[q].n;
+    hS[q] = hD[q];
+    hMB[q] = pairs[q].MB;
+    hoff[q] = (int64_t)q * N;
+    for (int k = 0; k < N; ++k) {
+      const int64_t ts = in->time_per_sample_ns[k], as = in->act_bytes_per_sample[k];
+      if (ts < 0 || as < 0 || in->param_bytes[k] < 0) return RANNC_DP_INVALID_ARG;
+      if ((__int128)ts * pairs[q].b >= lim || (__int128)as * pairs[q].b >= lim) return RANNC_DP_OVERFLOW;
+      ht[(size_t)q * N + k] = ts * pairs[q].b;
+      ha[(size_t)q * N + k] = as * pairs[q].b;
+      hp[(size_t)q * N + k] = in->param_bytes[k];
+    }
+  }
+  hoff[Q] = (int64_t)Q * N;
+  // scratch layout
+  char *base = (char *)d_scratch;
+  int64_t *d_t = (int64_t *)base; base += align_up((size_t)Q * N * 8);
+  int64_t *d_p = (int64_t *)base; base += align_up((size_t)Q * N * 8);
+  int64_t *d_a = (int64_t *)base; base += align_up((size_t)Q * N * 8);
+  int64_t *d_opt = (int64_t *)base; base += align_up((size_t)Q * 8);
+  int32_t *d_ns = (int32_t *)base;
+  int32_t *d_st = d_ns + Q; base += align_up((size_t)Q * 8);
+  int64_t *d_vals = (int64_t *)base; base += align_up((size_t)Q * stride * 8);
+  int32_t *d_lev = (int32_t *)base; base += align_up((size_t)Q * 4);
+  int32_t *d_se = (int32_t *)base; base += align_up((size_t)Q * stride * 4);
+  int32_t *d_rp = (int32_t *)base;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const size_t nb = (size_t)Q * N * 8;
+  if (hipMemcpyAsync(d_t, ht.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
+      hipMemcpyAsync(d_p, hp.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
+      hipMemcpyAsync(d_a, ha.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  rannc_dp_batch_t b;
+  b.n_problems = Q;
+  b.n_blocks = hN.data(); b.n_devices = hD.data(); b.max_stages = hS.data();
+  b.n_microbatches = hMB.data(); b.mem_capacity = hM.data(); b.block_offset = hoff.data();
+  b.time_ns = d_t; b.param_bytes = d_p; b.act_bytes = d_a;
+  int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
+  if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
+  if (rc != RANNC_DP_OK) {
+    (void)hipStreamSynchronize(st);  // the host copies above must not outlive their buffers
+    return rc;
+  }
+  if (hipMemcpyAsync(hvals.data(), d_vals, (size_t)Q * stride * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipMemcpyAsync(hns.data(), d_ns, (size_t)Q * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  for (int q = 0; q < Q; ++q) {
+    const int stq = hns[Q + q];
+    if (stq == RANNC_DP_PROBLEM_NEGATIVE_INPUT) return RANNC_DP_INVALID_ARG;
+    if (stq != RANNC_DP_PROBLEM_OK) return RANNC_DP_OVERFLOW;  // sums or times beyond the handle's width
+  }
+  // Algorithm 2's loops over the values of the solved batch: first n, then first S with a
+  // feasible MB; among those the smallest (MB + S - 1) * V, first found among equals
+  std::memset(out, 0, sizeof(*out));
+  for (int u = 0; u < plan_stride; ++u) stage_end[u] = replicas[u] = -1;
+  int q_sel = -1, S_sel = 0;
+  int64_t est_sel = 0;
+  for (int64_t n = 1; n <= in->n_nodes && q_sel < 0; n *= 2) {
+    const int dn = in->devices_per_node;
+    for (int S = dn * ((int)n - 1) + 1; S <= dn * (int)n && q_sel < 0; ++S) {
+      for (int q = 0; q < Q; ++q) {
+        if (pairs[q].n != n || S > std::min(N, hD[q])) continue;
+        const int64_t v = hvals[(size_t)q * stride + S - 1];
+        if (v == INT64_MAX) continue;
+        const __int128 e128 = (__int128)(pairs[q].MB + S - 1) * v;
+        const int64_t est = e128 > (__int128)INT64_MAX ? INT64_MAX : (int64_t)e128;
+        if (q_sel < 0 || est < est_sel) { q_sel = q; S_sel = S; est_sel = est; }
+      }
+    }
+  }
+  if (q_sel < 0) return RANNC_DP_OK;  // infeasible: out->feasible = 0
+  hlev[q_sel] = S_sel;
+  if (hipMemcpyAsync(d_lev, hlev.data(), (size_t)Q * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  rc = rannc_dp_traceback_at(h, hip_stream, d_lev, stride, d_se, d_rp);
+  if (rc != RANNC_DP_OK) {
+    (void)hipStreamSynchronize(st);
+    return rc;
+  }
+  if (hipMemcpyAsync(hse.data(), d_se + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipMemcpyAsync(hrp.data(), d_rp + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  out->feasible = 1;
+  out->n = pairs[q_sel].n;
+  out->devices = hD[q_sel];
+  out->replica_factor = in->n_nodes / pairs[q_sel].n;
+  out->n_stages = S_sel;
+  out->n_microbatches = pairs[q_sel].MB;
+  out->stage_time_ns = hvals[(size_t)q_sel * stride + S_sel - 1];
+  out->est_iter_ns = est_sel;
+  for (int u = 0; u < std::min(stride, (int)plan_stride); ++u) { stage_end[u] = hse[u]; replicas[u] = hrp[u]; }
   return RANNC_DP_OK;
 }
 

@@ -91,8 +91,10 @@ hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int
                              int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st);
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
+// d_levels: per problem (caller's order) the exact stage count to recover, 0 = the best one; or null
 hipError_t launch_traceback(const ProblemDev *probs, int Q, int plan_stride, int32_t *d_stage_end,
-                            int32_t *d_replicas, hipStream_t st);
+                            int32_t *d_replicas, const int32_t *d_levels, hipStream_t st);
+hipError_t launch_level_values(const ProblemDev *probs, int Q, int stride, int64_t *d_out, hipStream_t st);
 hipError_t launch_export(const ProblemDev *prob, int which, int bits, void *d_dst, hipStream_t st);
 
 

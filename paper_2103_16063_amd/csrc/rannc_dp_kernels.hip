@@ -665,17 +665,21 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
 // ---------------------------------------------------------------------------------------
 template <typename VT, int DP>
 __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
-                               unsigned int *best_key) {
+                               unsigned int *best_key, int forced) {
   constexpr VT INF = Lim<VT>::inf;
   constexpr int KB = 12;  // rows per wave and pass; their reads are independent
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
-  const int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
-  for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
-  if (ns == 0) return;
   const int64_t lvl = (int64_t)(N + 1) * DP;
   const VT RANNC_GLOBAL *V = gptr((const VT *)pr.V);
+  // forced > 0: the plan of exactly `forced` stages (Algorithm 1's own answer V[S][|B|][D]), if
+  // that level holds one; otherwise the best level chosen by the solve
+  int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
+  if (forced > 0 && *pr.status == 0)
+    ns = (forced <= pr.S_eff && V[(int64_t)(forced - 1) * lvl + (int64_t)N * DP + D - 1] != INF) ? forced : 0;
+  for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
+  if (ns == 0) return;
   const VT RANNC_GLOBAL *cost = gptr((const VT *)pr.cost);
   const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
   const int32_t RANNC_GLOBAL *wlo = gptr((const int32_t *)pr.wlo);
@@ -740,17 +744,19 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
 constexpr int kTracebackThreads = 1024;
 
 __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
-    const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas) {
+    const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas,
+    const int32_t *__restrict__ d_levels) {
   __shared__ unsigned int best_key;
   const ProblemDev pr = probs[blockIdx.x];  // by value: no reloads after the plan stores
+  const int forced = d_levels ? d_levels[pr.q] : 0;
   int32_t *se = d_stage_end + (int64_t)pr.q * plan_stride;
   int32_t *rp = d_replicas + (int64_t)pr.q * plan_stride;
 #define GO(T)                                                                           \
   switch (pr.DP) {                                                                      \
-    case 8: traceback_body<T, 8>(pr, plan_stride, se, rp, &best_key); break;            \
-    case 16: traceback_body<T, 16>(pr, plan_stride, se, rp, &best_key); break;          \
-    case 32: traceback_body<T, 32>(pr, plan_stride, se, rp, &best_key); break;          \
-    default: traceback_body<T, 64>(pr, plan_stride, se, rp, &best_key); break;          \
+    case 8: traceback_body<T, 8>(pr, plan_stride, se, rp, &best_key, forced); break;            \
+    case 16: traceback_body<T, 16>(pr, plan_stride, se, rp, &best_key, forced); break;          \
+    case 32: traceback_body<T, 32>(pr, plan_stride, se, rp, &best_key, forced); break;          \
+    default: traceback_body<T, 64>(pr, plan_stride, se, rp, &best_key, forced); break;          \
   }
   if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
@@ -960,9 +966,36 @@ hipError_t launch_select(const ProblemDev *p, int Q, int64_t *d_opt, int32_t *d_
 }
 
 hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t *d_stage_end,
-                            int32_t *d_replicas, hipStream_t st) {
+                            int32_t *d_replicas, const int32_t *d_levels, hipStream_t st) {
   hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(kTracebackThreads), 0, st, p, plan_stride, d_stage_end,
-                     d_replicas);
+                     d_replicas, d_levels);
+  return hipGetLastError();
+}
+
+// V[s][N][D] for s = 1..S_eff of every problem (INT64_MAX: no plan of exactly s stages, or s
+// beyond S_eff, or bad inputs): Algorithm 1's answer for each exact stage count.
+__global__ __launch_bounds__(64) void level_values_kernel(const ProblemDev *__restrict__ probs, int stride,
+                                                          int64_t *__restrict__ out) {
+  const ProblemDev &pr = probs[blockIdx.x];
+  const bool bad = *pr.status != 0;
+  const int64_t lvl = (int64_t)(pr.N + 1) * pr.DP;
+  const int64_t cell = (int64_t)pr.N * pr.DP + pr.D - 1;
+  for (int k = threadIdx.x; k < stride; k += 64) {
+    int64_t v = INT64_MAX;
+    if (!bad && k < pr.S_eff) {
+      if (pr.bits == 32) {
+        const uint32_t u = ((const uint32_t *)pr.V)[k * lvl + cell];
+        v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
+      } else {
+        v = (int64_t)((const uint64_t *)pr.V)[k * lvl + cell];
+      }
+    }
+    out[(int64_t)pr.q * stride + k] = v;
+  }
+}
+
+hipError_t launch_level_values(const ProblemDev *p, int Q, int stride, int64_t *d_out, hipStream_t st) {
+  hipLaunchKernelGGL(level_values_kernel, dim3(Q), dim3(64), 0, st, p, stride, d_out);
   return hipGetLastError();
 }
 

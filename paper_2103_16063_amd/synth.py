@@ -125,6 +125,37 @@ def random_small(seed: int, N: int, D: int, S: int, *, tight: float = 1.0,
     return _problem(t, p, a, D, S, MB, M, f"rand_N{N}_D{D}_S{S}_seed{seed}")
 
 
+def form_stage_case(seed: int, N: int, n_nodes: int, devices_per_node: int, batch_size: int, *,
+                    tight: float = 1.0, tmax: int = 2000, layered: bool = False):
+    """Inputs of the outer driver of the search (node counts, stage counts and microbatch counts
+    tried around the dynamic program): per-SAMPLE block times and transient bytes, persistent
+    bytes, the cluster shape and the batch size.  `tight` scales the capacity relative to an even
+    share of all bytes of one whole batch over all devices.  `layered` repeats a four-block
+    transformer-layer pattern (attention, projection, two MLP halves) instead of i.i.d. blocks."""
+    g = np.random.default_rng(seed)
+    if layered:
+        base_t = np.array([3, 1, 4, 4]) * max(1, tmax // 8)
+        base_a = np.array([6, 2, 8, 2])
+        base_p = np.array([3, 1, 4, 4])
+        k = np.arange(N) % 4
+        t = base_t[k] + g.integers(0, max(1, tmax // 16), N, endpoint=True)
+        a = (base_a[k] * 64 + g.integers(0, 32, N, endpoint=True)) * 1024
+        p = (base_p[k] * 16 + g.integers(0, 8, N, endpoint=True)) * MiB
+    else:
+        t = g.integers(1, tmax, N, endpoint=True)
+        a = g.integers(1, 64, N, endpoint=True) * 64 * 1024
+        p = g.integers(1, 64, N, endpoint=True) * MiB
+    M = int(tight * (int(p.sum()) + int(a.sum()) * batch_size) / (devices_per_node * n_nodes)) + 1
+    return {
+        "name": f"form_stage_N{N}_nodes{n_nodes}x{devices_per_node}_BS{batch_size}_seed{seed}",
+        "time_per_sample_ns": np.ascontiguousarray(t, dtype=np.int64),
+        "act_bytes_per_sample": np.ascontiguousarray(a, dtype=np.int64),
+        "param_bytes": np.ascontiguousarray(p, dtype=np.int64),
+        "n_nodes": int(n_nodes), "devices_per_node": int(devices_per_node),
+        "batch_size": int(batch_size), "mem_capacity": M,
+    }
+
+
 def concat_batch(problems):
     """Concatenate problems into the structure-of-arrays form of the batched call:
     per-problem scalars, block_offset[Q+1], and the three concatenated block arrays."""

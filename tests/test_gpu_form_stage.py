@@ -1,0 +1,184 @@
+"""GPU parity of the outer driver (Algorithm 2 of Sec. III-C) and of the two calls it is built
+from -- the value of every exact stage count, and the plan of a given stage count -- against the
+CPU oracle on the same seeded inputs.  Integers: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2103_16063_amd import binding as B
+from paper_2103_16063_amd import synth
+from tests.gpu_util import gpu_run
+
+pytestmark = pytest.mark.gpu
+INF = B.INT64_MAX
+
+
+def _oracle_form_stage(c, threads=0):
+    return oracle.form_stage(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"],
+                             c["n_nodes"], c["devices_per_node"], c["batch_size"], c["mem_capacity"],
+                             n_threads=threads)
+
+
+def _gpu_form_stage(c, **kw):
+    N = c["time_per_sample_ns"].shape[0]
+    fs = B.FormStageSession(N, c["n_nodes"], c["devices_per_node"], c["batch_size"], **kw)
+    try:
+        return fs.run(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"],
+                      c["mem_capacity"]), fs.plan_stride
+    finally:
+        fs.close()
+
+
+def _assert_same(c, got, want, stride):
+    rc, out, se, rp = got
+    assert rc == B.OK, (c["name"], B.strerror(rc))
+    if want is None:
+        assert out.feasible == 0, c["name"]
+        assert (se == -1).all() and (rp == -1).all()
+        assert (out.n, out.devices, out.n_stages, out.n_microbatches, out.stage_time_ns,
+                out.est_iter_ns) == (0, 0, 0, 0, 0, 0)
+        return
+    assert out.feasible == 1, c["name"]
+    have = {"n": out.n, "devices": out.devices, "replica_factor": out.replica_factor,
+            "n_stages": out.n_stages, "n_microbatches": out.n_microbatches,
+            "stage_time_ns": out.stage_time_ns, "est_iter_ns": out.est_iter_ns}
+    for k, v in have.items():
+        assert v == want[k], (c["name"], k, v, want[k])
+    S = want["n_stages"]
+    assert np.array_equal(se[:S], want["stage_end"]), (c["name"], se, want["stage_end"])
+    assert np.array_equal(rp[:S], want["replicas"]), (c["name"], rp, want["replicas"])
+    assert (se[S:] == -1).all() and (rp[S:] == -1).all()
+    assert len(se) == stride
+
+
+SMALL = []
+for seed in range(40):
+    g = np.random.default_rng(52_000 + seed)
+    SMALL.append((seed, int(g.integers(1, 40)), int(g.choice([1, 2, 3, 4, 8])), int(g.integers(1, 5)),
+                  int(g.choice([1, 3, 4, 8, 16, 64])), float(g.choice([0.3, 0.6, 1.0, 2.0, 20.0]))))
+
+
+@pytest.mark.parametrize("seed,N,n_nodes,d_node,BS,tight", SMALL)
+def test_form_stage_small_random(seed, N, n_nodes, d_node, BS, tight):
+    c = synth.form_stage_case(seed, N, n_nodes, d_node, BS, tight=tight, tmax=60)
+    got, stride = _gpu_form_stage(c)
+    _assert_same(c, got, _oracle_form_stage(c), stride)
+
+
+def test_form_stage_outcomes_are_mixed():
+    kinds = {"none": 0, "n1": 0, "n>1": 0, "mb>1": 0, "s>1": 0}
+    for seed, N, n_nodes, d_node, BS, tight in SMALL:
+        c = synth.form_stage_case(seed, N, n_nodes, d_node, BS, tight=tight, tmax=60)
+        r = _oracle_form_stage(c)
+        if r is None:
+            kinds["none"] += 1
+            continue
+        kinds["n1" if r["n"] == 1 else "n>1"] += 1
+        kinds["mb>1"] += r["n_microbatches"] > 1
+        kinds["s>1"] += r["n_stages"] > 1
+    assert all(v >= 2 for v in kinds.values()), kinds
+
+
+# the paper's cluster shape (Sec. IV-A: 4 nodes of 8 devices, batch size 256) on a layered chain
+# of transformer-like blocks, and twice that cluster; the times need 64-bit tables
+@pytest.mark.parametrize("N,n_nodes,d_node,BS,tight,wide",
+                         [(96, 4, 8, 256, 0.9, False), (96, 4, 8, 256, 2.5, True), (200, 4, 8, 256, 1.3, True),
+                          (128, 8, 8, 512, 1.5, True), (128, 4, 8, 256, 0.2, False)])
+def test_form_stage_cluster_shapes(N, n_nodes, d_node, BS, tight, wide):
+    c = synth.form_stage_case(7, N, n_nodes, d_node, BS, tight=tight, tmax=200_000, layered=True)
+    got, stride = _gpu_form_stage(c, **({"max_total_time_ns": 1 << 60} if wide else {}))
+    _assert_same(c, got, _oracle_form_stage(c), stride)
+
+
+def test_form_stage_narrow_handle_reports_overflow():
+    c = synth.form_stage_case(7, 96, 4, 8, 256, tight=2.0, tmax=20_000_000, layered=True)
+    (rc, out, se, rp), _ = _gpu_form_stage(c)  # 32-bit tables cannot hold these totals
+    assert rc == B.OVERFLOW
+
+
+def test_form_stage_rejects_bad_arguments():
+    c = synth.form_stage_case(1, 8, 2, 2, 8)
+    fs = B.FormStageSession(8, 2, 2, 8)
+    try:
+        t, a, p, M = c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], c["mem_capacity"]
+        stream = torch.cuda.current_stream().cuda_stream
+        fin = B.HostFormStageIn(t, a, p, 2, 2, 8, M)
+        rc, *_ = B.rannc_dp_form_stage(fs.h, fin, stream, fs.scratch, fs.scratch_bytes - 256, fs.plan_stride)
+        assert rc == B.WORKSPACE_TOO_SMALL
+        rc, *_ = B.rannc_dp_form_stage(fs.h, fin, stream, fs.scratch, fs.scratch_bytes, 1)
+        assert rc == B.INVALID_ARG
+        neg = t.copy(); neg[3] = -1
+        rc, *_ = B.rannc_dp_form_stage(fs.h, B.HostFormStageIn(neg, a, p, 2, 2, 8, M), stream, fs.scratch,
+                                       fs.scratch_bytes, fs.plan_stride)
+        assert rc == B.INVALID_ARG
+        big = B.HostFormStageIn(t, a, p, 4, 2, 8, M)  # more searches than the handle was made for
+        rc, *_ = B.rannc_dp_form_stage(fs.h, big, stream, fs.scratch, 1 << 30, 8)
+        assert rc in (B.LIMIT_EXCEEDED, B.WORKSPACE_TOO_SMALL)
+        assert B.rannc_dp_form_stage_problems(B.HostFormStageIn(t, a, p, 64, 2, 8, M)) == 0  # D > 64
+        # the handle still works afterwards
+        rc, out, se, rp = fs.run(t, a, p, M)
+        assert rc == B.OK
+    finally:
+        fs.close()
+
+
+# ---- the two calls the driver is built from ------------------------------------------------------
+def _exact_level_plans(pr):
+    """Oracle: V[s][N][D] for every s, and the canonical plan of exactly s stages."""
+    o = oracle.solve(pr, n_threads=0, keep_tables=True)
+    N, D, L = pr["time_ns"].shape[0], pr["n_devices"], o["n_levels"]
+    vals = [int(o["V"][s, N, D]) for s in range(1, L + 1)]
+    plans = [oracle.traceback(o["arg_i"], o["arg_d"], s, s) if vals[s - 1] != INF else None
+             for s in range(1, L + 1)]
+    return vals, plans
+
+
+@pytest.mark.parametrize("fused", ["0", "2"])
+def test_level_values_and_traceback_at(monkeypatch, fused):
+    monkeypatch.setenv("RANNC_DP_FUSED_SMALL", fused)
+    probs = []
+    for seed in range(24):
+        g = np.random.default_rng(77_000 + seed)
+        N, D = int(g.integers(1, 100)), int(g.integers(1, 33))
+        probs.append(synth.random_small(seed, N, D, int(g.integers(1, 20)),
+                                        tight=float(g.choice([0.7, 1.2, 3.0])), tmax=int(g.choice([5, 1000]))))
+    res, sess = gpu_run(probs)
+    try:
+        stride = sess.plan_stride
+        Q = len(probs)
+        d_vals = torch.empty((Q, stride), dtype=torch.int64, device="cuda:0")
+        assert B.rannc_dp_level_values(sess.h, sess.stream(), stride, d_vals) == B.OK
+        torch.cuda.synchronize()
+        vals = d_vals.cpu().numpy()
+        want = [_exact_level_plans(pr) for pr in probs]
+        for q in range(Q):
+            wv = want[q][0]
+            assert vals[q, :len(wv)].tolist() == wv, (q, probs[q]["name"])
+            assert (vals[q, len(wv):] == INF).all()
+        # every exact stage count in turn (0 = the best one, as rannc_dp_traceback)
+        seen_forced_differs = 0
+        for s in range(0, stride + 2):
+            lev = torch.full((Q,), s, dtype=torch.int32, device="cuda:0")
+            d_se = torch.full((Q, stride), -7, dtype=torch.int32, device="cuda:0")
+            d_rp = torch.full((Q, stride), -7, dtype=torch.int32, device="cuda:0")
+            assert B.rannc_dp_traceback_at(sess.h, sess.stream(), lev, stride, d_se, d_rp) == B.OK
+            torch.cuda.synchronize()
+            se, rp = d_se.cpu().numpy(), d_rp.cpu().numpy()
+            for q in range(Q):
+                wv, wp = want[q]
+                if s == 0:
+                    assert np.array_equal(se[q], res["stage_end"][q]) and np.array_equal(rp[q], res["replicas"][q])
+                    continue
+                plan = wp[s - 1] if s <= len(wv) else None
+                if plan is None:
+                    assert (se[q] == -1).all() and (rp[q] == -1).all(), (q, s)
+                else:
+                    assert np.array_equal(se[q, :s], plan[0]) and np.array_equal(rp[q, :s], plan[1]), (q, s)
+                    assert (se[q, s:] == -1).all() and (rp[q, s:] == -1).all()
+                    seen_forced_differs += s != int(res["n_stages"][q])
+        assert seen_forced_differs >= 10
+        bad = B.rannc_dp_level_values(sess.h, sess.stream(), stride - 1, d_vals) if stride > 1 else B.INVALID_ARG
+        assert bad == B.INVALID_ARG
+    finally:
+        sess.close()
