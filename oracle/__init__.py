@@ -44,7 +44,7 @@ def lib():
         L.rannc_oracle_prefix.restype = C.c_int
         L.rannc_oracle_table_entries.argtypes = [i32, i32]
         L.rannc_oracle_table_entries.restype = C.c_size_t
-        L.rannc_oracle_tables.argtypes = [i32, i32, pi64, pi64, pi64, i64, pi64, pu8]
+        L.rannc_oracle_tables.argtypes = [i32, i32, pi64, pi64, pi64, i64, pi64, i64, pi64, pu8]
         L.rannc_oracle_tables.restype = C.c_int
         L.rannc_oracle_dp.argtypes = [i32, i32, i32, pi64, pu8, pi64, pi32, pi32, i32]
         L.rannc_oracle_dp.restype = C.c_int
@@ -80,14 +80,22 @@ def prefix(x) -> np.ndarray:
     return X
 
 
-def tables(T, P, A, D: int, M: int):
-    """cost (int64) and fit (uint8), packed as ((j*(j-1)/2 + i)*D + (r-1))."""
+def tables(T, P, A, D: int, M: int, cut_bytes=None, bandwidth_bytes_per_us: int = 0):
+    """cost (int64) and fit (uint8), packed as ((j*(j-1)/2 + i)*D + (r-1)).  cut_bytes[k-1] =
+    bytes crossing the cut after block k (None: no communication term)."""
     N = T.shape[0] - 1
     n = lib().rannc_oracle_table_entries(N, D)
     cost = np.empty(n, dtype=np.int64)
     fit = np.empty(n, dtype=np.uint8)
+    o = None
+    if cut_bytes is not None:
+        o = np.ascontiguousarray(cut_bytes, dtype=np.int64)
+        if o.shape[0] != N:
+            raise OracleError("cut_bytes must have one entry per block")
     _chk(lib().rannc_oracle_tables(N, D, _p(T, C.c_int64), _p(P, C.c_int64), _p(A, C.c_int64),
-                                   int(M), _p(cost, C.c_int64), _p(fit, C.c_uint8)), "tables")
+                                   int(M), _p(o, C.c_int64) if o is not None else None,
+                                   int(bandwidth_bytes_per_us), _p(cost, C.c_int64),
+                                   _p(fit, C.c_uint8)), "tables")
     return cost, fit
 
 
@@ -142,7 +150,8 @@ def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=Non
     if D < 1 or S < 1 or MB < 1 or M < 0:
         raise OracleError("bad scalar argument")
     T, P, A = prefix(t), prefix(p), prefix(a)
-    cost, fit = tables(T, P, A, D, M)
+    cost, fit = tables(T, P, A, D, M, problem.get("cut_bytes"),
+                       int(problem.get("bandwidth_bytes_per_us", 0)))
     n_levels = min(S, N, D)
     if max_levels is not None:
         n_levels = min(n_levels, int(max_levels))
@@ -157,7 +166,8 @@ def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=Non
 
 
 def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: int,
-               devices_per_node: int, batch_size: int, mem_capacity: int, n_threads: int = 1):
+               devices_per_node: int, batch_size: int, mem_capacity: int, n_threads: int = 1,
+               cut_bytes_per_sample=None, bandwidth_bytes_per_us: int = 0):
     """Outer driver of the search (Algorithm 2 "form_stage" of Sec. III-C), loops in the paper's
     order: node count n = 1, 2, 4, ... <= n_nodes; D = devices_per_node * n devices, replica factor
     R = n_nodes / n; stage count S ascending over (devices_per_node*(n-1), devices_per_node*n]; for
@@ -167,7 +177,7 @@ def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: i
 
     Readings (the paper leaves them open): a block's time and transient bytes grow linearly with
     the samples of a microbatch on one pipeline replica, b = floor(batch_size / R / MB), its
-    persistent bytes do not; "best" = smallest (MB + S - 1) * V, the time of one synchronous
+    persistent bytes do not (the bytes crossing a cut, if given, grow the same way); "best" = smallest (MB + S - 1) * V, the time of one synchronous
     pipeline iteration (Fig. 1), the first found among equals (smallest MB); R is the integer
     quotient.  The DP for one (n, MB) yields every exact-S value at once, so it is memoised.
 
@@ -177,6 +187,8 @@ def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: i
     ts = np.ascontiguousarray(time_per_sample_ns, dtype=np.int64)
     as_ = np.ascontiguousarray(act_bytes_per_sample, dtype=np.int64)
     pp = np.ascontiguousarray(param_bytes, dtype=np.int64)
+    os_ = (None if cut_bytes_per_sample is None
+           else np.ascontiguousarray(cut_bytes_per_sample, dtype=np.int64))
     N = int(ts.shape[0])
     if n_nodes < 1 or devices_per_node < 1 or batch_size < 1 or mem_capacity < 0:
         raise OracleError("bad scalar argument")
@@ -188,7 +200,8 @@ def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: i
             R = n_nodes // n
             b = batch_size // R // MB
             T, P, A = prefix(ts * b), prefix(pp), prefix(as_ * b)
-            cost, fit = tables(T, P, A, D, mem_capacity)
+            cost, fit = tables(T, P, A, D, mem_capacity, None if os_ is None else os_ * b,
+                               bandwidth_bytes_per_us)
             memo[(n, MB)] = dp(N, D, min(D, N), cost, fit, n_threads)
         return memo[(n, MB)]
 

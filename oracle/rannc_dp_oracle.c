@@ -14,6 +14,13 @@
  *       h(i,j,r) = ceil((T[j]-T[i]) / r)                  stage time
  *       m(i,j,r) = (P[j]-P[i]) + ceil((A[j]-A[i]) / r)    stage memory
  *   and fits iff m <= M (Algorithm 1 skips a candidate only when m > M).
+ *   Optional communication term (Sec. III-C counts the time to send a stage's outputs to the
+ *   following stage into its execution time; Sec. III-B estimates it from the sizes of the
+ *   values and the bandwidth): with o_k = bytes that cross the cut after block k for one
+ *   microbatch and bandwidth w in bytes per microsecond, every stage that ends at j < N has
+ *       h(i,j,r) = ceil((T[j]-T[i]) / r) + ceil(1000 * o_j / (r * w))   [ns]
+ *   (each replica sends 1/r of the microbatch); the stage that ends at j = N has no follower
+ *   and sends nothing.
  *   The additive form is the paper's own stand-in for profile() in Sec. IV-D (sums over the
  *   members of a stage); the replica divides the per-replica batch, hence time and transient
  *   memory, and leaves the persistent part alone.
@@ -80,13 +87,25 @@ size_t rannc_oracle_table_entries(int32_t N, int32_t D) {
 
 /* Stage time and fits-in-memory tables straight from the definitions above. */
 int rannc_oracle_tables(int32_t N, int32_t D, const int64_t *T, const int64_t *P,
-                        const int64_t *A, int64_t M, int64_t *cost, uint8_t *fit) {
+                        const int64_t *A, int64_t M, const int64_t *o, int64_t w, int64_t *cost,
+                        uint8_t *fit) {
   if (N < 1 || D < 1 || M < 0 || !T || !P || !A || !cost || !fit) return ORACLE_BAD_ARG;
+  if (o) { /* o[k-1] = bytes crossing the cut after block k; w = bytes per microsecond */
+    if (w < 1) return ORACLE_BAD_ARG;
+    for (int32_t k = 0; k < N; ++k) {
+      if (o[k] < 0) return ORACLE_BAD_ARG;
+      if (o[k] > (((int64_t)1 << 62) - 1) / 1000) return ORACLE_OVERFLOW;
+    }
+  }
   for (int64_t j = 1; j <= N; ++j)
     for (int64_t i = 0; i < j; ++i)
       for (int64_t r = 1; r <= D; ++r) {
         size_t e = (size_t)((j * (j - 1) / 2 + i) * D + (r - 1));
         int64_t h = ceil_div(T[j] - T[i], r);
+        if (o && j < N) { /* time to send this replica's share of the cut's bytes */
+          __int128 den = (__int128)r * w, num = (__int128)1000 * o[j - 1];
+          h += (int64_t)((num + den - 1) / den);
+        }
         int64_t m = (P[j] - P[i]) + ceil_div(A[j] - A[i], r);
         cost[e] = h;
         fit[e] = (uint8_t)(m <= M);

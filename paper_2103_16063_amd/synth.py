@@ -125,6 +125,23 @@ def random_small(seed: int, N: int, D: int, S: int, *, tight: float = 1.0,
     return _problem(t, p, a, D, S, MB, M, f"rand_N{N}_D{D}_S{S}_seed{seed}")
 
 
+def with_cut_bytes(problem, seed: int, bandwidth_bytes_per_us: int, lo: int = 1 << 16,
+                   hi: int = 16 << 20, zero_frac: float = 0.0):
+    """Copy of a problem with the inputs of the communication term added: cut_bytes[k] = bytes of
+    the values that cross the cut after block k+1 for one microbatch (uniform in [lo, hi], a
+    fraction of them zero), and the bandwidth in bytes per microsecond."""
+    g = np.random.default_rng(seed)
+    N = problem["time_ns"].shape[0]
+    o = g.integers(lo, hi, N, endpoint=True)
+    if zero_frac > 0:
+        o = np.where(g.random(N) < zero_frac, 0, o)
+    out = dict(problem)
+    out["cut_bytes"] = np.ascontiguousarray(o, dtype=np.int64)
+    out["bandwidth_bytes_per_us"] = int(bandwidth_bytes_per_us)
+    out["name"] = problem["name"] + "_comm"
+    return out
+
+
 def form_stage_case(seed: int, N: int, n_nodes: int, devices_per_node: int, batch_size: int, *,
                     tight: float = 1.0, tmax: int = 2000, layered: bool = False):
     """Inputs of the outer driver of the search (node counts, stage counts and microbatch counts
@@ -165,7 +182,15 @@ def concat_batch(problems):
         off[q + 1] = off[q] + pr["time_ns"].shape[0]
     cat = lambda k: (np.concatenate([pr[k] for pr in problems]).astype(np.int64)
                      if Q else np.zeros(0, np.int64))
+    extra = {}
+    if any("cut_bytes" in pr for pr in problems):
+        # problems without a communication term get zero bytes on every cut
+        extra["cut_bytes"] = np.concatenate(
+            [pr.get("cut_bytes", np.zeros(pr["time_ns"].shape[0], np.int64)) for pr in problems]).astype(np.int64)
+        extra["bandwidth_bytes_per_us"] = np.array(
+            [pr.get("bandwidth_bytes_per_us", 1) for pr in problems], dtype=np.int64)
     return {
+        **extra,
         "n_problems": Q,
         "n_blocks": np.array([pr["time_ns"].shape[0] for pr in problems], dtype=np.int32),
         "n_devices": np.array([pr["n_devices"] for pr in problems], dtype=np.int32),

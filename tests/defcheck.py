@@ -11,27 +11,33 @@ def cdiv(x, r):
     return -((-x) // r)
 
 
-def stage_time(t, i, j, r):
-    """Time of the stage holding blocks i+1..j (1-based) at r replicas."""
-    return cdiv(sum(int(x) for x in t[i:j]), r)
+def stage_time(t, i, j, r, comm=None):
+    """Time of the stage holding blocks i+1..j (1-based) at r replicas.  comm = (o, w): a stage
+    that is followed by another one (j < N) also sends its replica's share of the o[j-1] bytes
+    that cross the cut after block j, at w bytes per microsecond; times are nanoseconds."""
+    h = cdiv(sum(int(x) for x in t[i:j]), r)
+    if comm is not None and j < len(t):
+        o, w = comm
+        h += cdiv(1000 * int(o[j - 1]), r * int(w))
+    return h
 
 
 def stage_mem(p, a, i, j, r):
     return sum(int(x) for x in p[i:j]) + cdiv(sum(int(x) for x in a[i:j]), r)
 
 
-def plan_value(t, p, a, M, bounds, reps):
+def plan_value(t, p, a, M, bounds, reps, comm=None):
     """(feasible, max stage time) of the plan with stage ends bounds[1:] and replicas reps."""
     worst = 0
     for u in range(len(reps)):
         i, j, r = bounds[u], bounds[u + 1], reps[u]
         if stage_mem(p, a, i, j, r) > M:
             return False, INF
-        worst = max(worst, stage_time(t, i, j, r))
+        worst = max(worst, stage_time(t, i, j, r, comm))
     return True, worst
 
 
-def brute_force(t, p, a, D, S, M):
+def brute_force(t, p, a, D, S, M, comm=None):
     """Enumerate every plan: s stages, every set of s-1 cut points, every way to give the
     stages positive replica counts that sum to D.  Returns (opt, smallest s attaining it,
     number of feasible plans); opt = INF and s = 0 when nothing is feasible."""
@@ -43,7 +49,7 @@ def brute_force(t, p, a, D, S, M):
             for dc in combinations(range(1, D), s - 1):
                 dd = (0,) + dc + (D,)
                 reps = [dd[u + 1] - dd[u] for u in range(s)]
-                ok, v = plan_value(t, p, a, M, bounds, reps)
+                ok, v = plan_value(t, p, a, M, bounds, reps, comm)
                 if ok:
                     n_feasible += 1
                     if v < best:
@@ -51,7 +57,7 @@ def brute_force(t, p, a, D, S, M):
     return best, best_s, n_feasible
 
 
-def brute_force_prefix(t, p, a, s, j, d, M):
+def brute_force_prefix(t, p, a, s, j, d, M, comm=None):
     """Best value over plans of exactly s stages covering blocks 1..j with exactly d devices."""
     best = INF
     if s > j or s > d:
@@ -61,13 +67,13 @@ def brute_force_prefix(t, p, a, s, j, d, M):
         for dc in combinations(range(1, d), s - 1):
             dd = (0,) + dc + (d,)
             reps = [dd[u + 1] - dd[u] for u in range(s)]
-            ok, v = plan_value(t, p, a, M, bounds, reps)
+            ok, v = plan_value(t, p, a, M, bounds, reps, comm)
             if ok and v < best:
                 best = v
     return best
 
 
-def check_plan(t, p, a, D, S, M, opt, n_stages, stage_end, replicas):
+def check_plan(t, p, a, D, S, M, opt, n_stages, stage_end, replicas, comm=None):
     """Validity of a reported plan, from the definition: contiguous cover of 1..N, replicas
     positive and summing to D, every stage fits, and the slowest stage equals opt."""
     N = len(t)
@@ -83,12 +89,12 @@ def check_plan(t, p, a, D, S, M, opt, n_stages, stage_end, replicas):
     bounds = [0] + se
     assert all(bounds[u] < bounds[u + 1] for u in range(n_stages)) and bounds[-1] == N
     assert all(r >= 1 for r in rp) and sum(rp) == D
-    ok, v = plan_value(t, p, a, M, bounds, rp)
+    ok, v = plan_value(t, p, a, M, bounds, rp, comm)
     assert ok, "a stage of the plan does not fit memory"
     assert v == opt, (v, opt)
 
 
-def check_cells(t, p, a, D, M, V, arg_i, arg_d):
+def check_cells(t, p, a, D, M, V, arg_i, arg_d, comm=None):
     """Per-cell check of the value table and of the canonical argmin.
 
     For every cell (s, j, d), s >= 1: list the admissible candidates (i, d') in
@@ -111,7 +117,7 @@ def check_cells(t, p, a, D, M, V, arg_i, arg_d):
                         r = d - dp
                         if stage_mem(p, a, i, j, r) > M:
                             continue
-                        v = max(prev, stage_time(t, i, j, r))
+                        v = max(prev, stage_time(t, i, j, r, comm))
                         if v < best:
                             best, arg = v, (i, dp)
                 assert int(V[s, j, d]) == best, (s, j, d)

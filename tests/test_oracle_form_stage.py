@@ -10,7 +10,7 @@ from tests import defcheck
 INF = defcheck.INF
 
 
-def enumerate_form_stage(ts, as_, pp, n_nodes, d_node, BS, M):
+def enumerate_form_stage(ts, as_, pp, n_nodes, d_node, BS, M, os_=None, w=0):
     N = len(ts)
     n = 1
     while n <= n_nodes:
@@ -22,7 +22,8 @@ def enumerate_form_stage(ts, as_, pp, n_nodes, d_node, BS, M):
                 b = BS // R // MB
                 t = [int(x) * b for x in ts]
                 a = [int(x) * b for x in as_]
-                v = defcheck.brute_force_prefix(t, pp, a, S, N, D, M)  # exactly S stages, D devices
+                comm = None if os_ is None else ([int(x) * b for x in os_], w)
+                v = defcheck.brute_force_prefix(t, pp, a, S, N, D, M, comm)  # exactly S stages, D devices
                 if v != INF:
                     cands.append(((MB + S - 1) * v, MB, v))
                 MB *= 2
@@ -89,3 +90,27 @@ def test_single_node_single_block_closed_form():
     r = oracle.form_stage([10], [5], [1], 1, 2, 4, 6)
     assert (r["n_microbatches"], r["stage_time_ns"]) == (2, 10)  # b = 2, ceil(2*5/2) = 5 fits
     assert oracle.form_stage([10], [5], [7], 1, 2, 4, 6) is None
+
+
+@pytest.mark.parametrize("seed,N,n_nodes,d_node,BS,tight", CASES[:16])
+def test_form_stage_with_comm_against_enumeration(seed, N, n_nodes, d_node, BS, tight):
+    """The bytes crossing a cut grow with the samples of a microbatch like the times do."""
+    g = np.random.default_rng(seed)
+    ts, as_, pp = g.integers(1, 50, N), g.integers(1, 40, N), g.integers(1, 100, N)
+    os_ = g.integers(0, 30, N)
+    w = int(g.choice([700, 1000, 2500]))
+    M = int(tight * (int(pp.sum()) + int(as_.sum()) * BS) / (d_node * n_nodes)) + 1
+    want = enumerate_form_stage(ts, as_, pp, n_nodes, d_node, BS, M, os_, w)
+    got = oracle.form_stage(ts, as_, pp, n_nodes, d_node, BS, M, cut_bytes_per_sample=os_,
+                            bandwidth_bytes_per_us=w)
+    if want is None:
+        assert got is None
+        return
+    assert got is not None
+    for k in want:
+        assert got[k] == want[k], (k, got[k], want[k])
+    R, MB, S, D = got["replica_factor"], got["n_microbatches"], got["n_stages"], got["devices"]
+    b = BS // R // MB
+    defcheck.check_plan([int(x) * b for x in ts], pp, [int(x) * b for x in as_], D, S, M,
+                        got["stage_time_ns"], S, got["stage_end"], got["replicas"],
+                        ([int(x) * b for x in os_], w))

@@ -8,6 +8,7 @@ import subprocess
 import pytest
 
 import oracle
+from tests import test_oracle_comm as comm_pins
 from tests import test_oracle_pins as pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "rannc_dp_oracle.c")
@@ -39,6 +40,12 @@ MUTANTS = {
     "est_iter_off_by_one": ("(int64_t)MB + n_stages - 1;", "(int64_t)MB + n_stages;"),
     "skips_split_at_s_minus_1": ("for (int32_t i = s - 1; i <= j - 1; ++i)",
                                  "for (int32_t i = s; i <= j - 1; ++i)"),
+    "comm_on_last_stage_too": ("if (o && j < N) {", "if (o) {"),
+    "comm_ignores_replicas": ("__int128 den = (__int128)r * w,", "__int128 den = (__int128)w,"),
+    "comm_takes_cut_before_stage": ("num = (__int128)1000 * o[j - 1];", "num = (__int128)1000 * o[i];"),
+    "comm_floor_instead_of_ceil": ("h += (int64_t)((num + den - 1) / den);", "h += (int64_t)(num / den);"),
+    "comm_wrong_time_unit": ("num = (__int128)1000 * o[j - 1];", "num = (__int128)1024 * o[j - 1];"),
+    "comm_replaces_compute": ("h += (int64_t)((num + den - 1) / den);", "h = (int64_t)((num + den - 1) / den);"),
     "device_loop_stops_early": ("for (int32_t dp = s - 1; dp <= d - 1; ++dp)",
                                 "for (int32_t dp = s - 1; dp < d - 1; ++dp)"),
 }
@@ -59,6 +66,11 @@ def battery():
         pins.test_invariants(seed)
     pins.test_zero_activation_fit_independent_of_replicas()
     pins.test_oversized_block_is_infeasible()
+    for row in comm_pins.SMALL[:16]:
+        comm_pins.test_brute_force_small_with_comm(*row)
+    comm_pins.test_worked_example()
+    comm_pins.test_tables_against_definition_with_comm()
+    comm_pins.test_comm_invariants(0)
 
 
 def test_battery_passes_on_the_real_oracle():
