@@ -59,8 +59,9 @@ typedef enum {
 /* Per-problem status word written to d_status by solve (device-side input validation). */
 #define RANNC_DP_PROBLEM_OK 0
 #define RANNC_DP_PROBLEM_NEGATIVE_INPUT 1   /* a block time or size is negative */
-#define RANNC_DP_PROBLEM_SUM_OVERFLOW 2     /* a prefix sum reaches 2^62 */
-#define RANNC_DP_PROBLEM_TIME_TOO_LARGE 3   /* total time exceeds limits.max_total_time_ns */
+#define RANNC_DP_PROBLEM_SUM_OVERFLOW 2     /* a prefix sum reaches 2^62, or a cut's bytes exceed (2^62-1)/1000 */
+#define RANNC_DP_PROBLEM_TIME_TOO_LARGE 3   /* total time (plus the longest send time of a cut at one
+                                               replica) exceeds limits.max_total_time_ns */
 /* A problem with a non-zero status is reported as infeasible. */
 
 #define RANNC_DP_MAX_DEVICES 64   /* largest D the kernels are built for */
@@ -100,6 +101,14 @@ typedef struct {
   const int64_t *time_ns;        /* DEVICE  fwd+bwd time of a block, one microbatch, one replica */
   const int64_t *param_bytes;    /* DEVICE  persistent per-replica bytes (weights, grads, optimizer) */
   const int64_t *act_bytes;      /* DEVICE  transient bytes of one microbatch at one replica */
+  /* Optional communication term (Sec. III-C: a stage's execution time includes sending its
+   * outputs to the following stage; Sec. III-B: estimated from the sizes of the values and the
+   * bandwidth).  Both NULL: no term.  Otherwise a stage that ends after block j < N_q on r
+   * replicas takes ceil(1000 * cut_bytes[j] / (r * bandwidth)) ns longer (each replica sends its
+   * 1/r of the microbatch); the stage that ends at block N_q sends nothing. */
+  const int64_t *bandwidth_bytes_per_us; /* HOST [Q]  >= 1, bytes per microsecond */
+  const int64_t *cut_bytes;      /* DEVICE  indexed like time_ns: bytes of the values that cross the cut
+                                    after the block, one microbatch; 0 .. (2^62-1)/1000 */
 } rannc_dp_batch_t;
 
 /* Bytes of device workspace that any batch within `limits` fits in (worst case).
@@ -179,6 +188,10 @@ typedef struct {
   const int64_t *time_per_sample_ns;  /* HOST [N] fwd+bwd time of a block for one sample */
   const int64_t *act_bytes_per_sample;/* HOST [N] transient bytes of a block for one sample */
   const int64_t *param_bytes;         /* HOST [N] persistent per-replica bytes */
+  const int64_t *cut_bytes_per_sample;/* HOST [N] or NULL: bytes crossing the cut after a block for one
+                                         sample (communication term of rannc_dp_batch_t; grows
+                                         with the samples of a microbatch like the times) */
+  int64_t bandwidth_bytes_per_us;     /* >= 1 if cut_bytes_per_sample is given, else ignored */
 } rannc_dp_form_stage_in_t;
 
 typedef struct {

@@ -44,14 +44,16 @@ class Batch(C.Structure):
                 ("n_blocks", C.c_void_p), ("n_devices", C.c_void_p), ("max_stages", C.c_void_p),
                 ("n_microbatches", C.c_void_p), ("mem_capacity", C.c_void_p),
                 ("block_offset", C.c_void_p),
-                ("time_ns", C.c_void_p), ("param_bytes", C.c_void_p), ("act_bytes", C.c_void_p)]
+                ("time_ns", C.c_void_p), ("param_bytes", C.c_void_p), ("act_bytes", C.c_void_p),
+                ("bandwidth_bytes_per_us", C.c_void_p), ("cut_bytes", C.c_void_p)]
 
 
 class FormStageIn(C.Structure):
     _fields_ = [("n_blocks", C.c_int32), ("n_nodes", C.c_int32), ("devices_per_node", C.c_int32),
                 ("reserved", C.c_int32), ("batch_size", C.c_int64), ("mem_capacity", C.c_int64),
                 ("time_per_sample_ns", C.c_void_p), ("act_bytes_per_sample", C.c_void_p),
-                ("param_bytes", C.c_void_p)]
+                ("param_bytes", C.c_void_p), ("cut_bytes_per_sample", C.c_void_p),
+                ("bandwidth_bytes_per_us", C.c_int64)]
 
 
 class FormStageOut(C.Structure):
@@ -138,17 +140,20 @@ class HostBatch:
     """Keeps the numpy arrays of a batch's HOST members alive next to the C struct."""
 
     def __init__(self, n_blocks, n_devices, max_stages, n_microbatches, mem_capacity, block_offset,
-                 time_ns, param_bytes, act_bytes):
+                 time_ns, param_bytes, act_bytes, bandwidth_bytes_per_us=None, cut_bytes=None):
         self.keep = [np.ascontiguousarray(n_blocks, dtype=np.int32),
                      np.ascontiguousarray(n_devices, dtype=np.int32),
                      np.ascontiguousarray(max_stages, dtype=np.int32),
                      np.ascontiguousarray(n_microbatches, dtype=np.int32),
                      np.ascontiguousarray(mem_capacity, dtype=np.int64),
                      np.ascontiguousarray(block_offset, dtype=np.int64)]
-        self.device = (time_ns, param_bytes, act_bytes)  # DEVICE tensors (kept alive)
+        self.device = (time_ns, param_bytes, act_bytes, cut_bytes)  # DEVICE tensors (kept alive)
         self.n_problems = int(self.keep[0].shape[0])
+        self.bw = (None if bandwidth_bytes_per_us is None
+                   else np.ascontiguousarray(bandwidth_bytes_per_us, dtype=np.int64))
         self.struct = Batch(self.n_problems, *[_ptr(a) for a in self.keep],
-                            _ptr(time_ns), _ptr(param_bytes), _ptr(act_bytes))
+                            _ptr(time_ns), _ptr(param_bytes), _ptr(act_bytes), _ptr(self.bw),
+                            _ptr(cut_bytes))
 
 
 def rannc_dp_workspace_bytes(limits: Limits) -> int:
@@ -191,12 +196,16 @@ class HostFormStageIn:
     """Keeps the HOST arrays of a form_stage input alive next to the C struct."""
 
     def __init__(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes,
-                 devices_per_node, batch_size, mem_capacity):
+                 devices_per_node, batch_size, mem_capacity, cut_bytes_per_sample=None,
+                 bandwidth_bytes_per_us=0):
         self.keep = [np.ascontiguousarray(time_per_sample_ns, dtype=np.int64),
                      np.ascontiguousarray(act_bytes_per_sample, dtype=np.int64),
                      np.ascontiguousarray(param_bytes, dtype=np.int64)]
+        self.cut = (None if cut_bytes_per_sample is None
+                    else np.ascontiguousarray(cut_bytes_per_sample, dtype=np.int64))
         self.struct = FormStageIn(int(self.keep[0].shape[0]), int(n_nodes), int(devices_per_node), 0,
-                                  int(batch_size), int(mem_capacity), *[_ptr(a) for a in self.keep])
+                                  int(batch_size), int(mem_capacity), *[_ptr(a) for a in self.keep],
+                                  _ptr(self.cut), int(bandwidth_bytes_per_us))
 
 
 def rannc_dp_form_stage_problems(fin: HostFormStageIn) -> int:
@@ -258,8 +267,12 @@ class Session:
                                   int(self.S_eff.max()), max_total_time_ns, algo)
         self.d_in = [torch.from_numpy(np.ascontiguousarray(b[k], dtype=np.int64)).to(self.dev)
                      for k in ("time_ns", "param_bytes", "act_bytes")]
+        self.d_cut = None
+        if "cut_bytes" in b:
+            self.d_cut = torch.from_numpy(np.ascontiguousarray(b["cut_bytes"], dtype=np.int64)).to(self.dev)
         self.hb = HostBatch(b["n_blocks"], b["n_devices"], b["max_stages"], b["n_microbatches"],
-                            b["mem_capacity"], b["block_offset"], *self.d_in)
+                            b["mem_capacity"], b["block_offset"], *self.d_in,
+                            b.get("bandwidth_bytes_per_us"), self.d_cut)
         nbytes = (rannc_dp_workspace_bytes_for(self.limits, self.hb) if exact_workspace
                   else rannc_dp_workspace_bytes(self.limits))
         if nbytes == 0:
@@ -368,10 +381,11 @@ class FormStageSession:
         self.scratch_bytes = rannc_dp_form_stage_scratch_bytes(probe)
         self.scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.dev)
 
-    def run(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, mem_capacity):
+    def run(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, mem_capacity,
+            cut_bytes_per_sample=None, bandwidth_bytes_per_us=0):
         n_blocks, n_nodes, dn, bs = self.shape
         fin = HostFormStageIn(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes, dn, bs,
-                              mem_capacity)
+                              mem_capacity, cut_bytes_per_sample, bandwidth_bytes_per_us)
         assert fin.struct.n_blocks == n_blocks
         stream = self.torch.cuda.current_stream(self.dev).cuda_stream
         return rannc_dp_form_stage(self.h, fin, stream, self.scratch, self.scratch_bytes,

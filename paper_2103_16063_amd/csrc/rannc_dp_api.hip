@@ -24,7 +24,7 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Sizes {  // bytes of one problem's regions inside the workspace
   size_t prefix, wlo, runs, ufit, misc, rmin, cost, V;
-  size_t total() const { return prefix * 3 + wlo + runs + ufit + misc + rmin + cost + V; }
+  size_t total() const { return prefix * 4 + wlo + runs + ufit + misc + rmin + cost + V; }
 };
 
 // false on arithmetic overflow
@@ -66,10 +66,12 @@ int check_batch(const rannc_dp_limits_t *l, const rannc_dp_batch_t *b) {
     return RANNC_DP_INVALID_ARG;
   if (b->n_problems > l->max_problems) return RANNC_DP_LIMIT_EXCEEDED;
   if (b->block_offset[0] < 0) return RANNC_DP_INVALID_ARG;
+  if ((b->bandwidth_bytes_per_us == nullptr) != (b->cut_bytes == nullptr)) return RANNC_DP_INVALID_ARG;
   for (int q = 0; q < b->n_problems; ++q) {
     if (b->n_blocks[q] < 1 || b->n_devices[q] < 1 || b->max_stages[q] < 1 ||
         b->n_microbatches[q] < 1 || b->mem_capacity[q] < 0)
       return RANNC_DP_INVALID_ARG;
+    if (b->bandwidth_bytes_per_us && b->bandwidth_bytes_per_us[q] < 1) return RANNC_DP_INVALID_ARG;
     if (b->block_offset[q + 1] - b->block_offset[q] != (int64_t)b->n_blocks[q])
       return RANNC_DP_INVALID_ARG;
     if (b->n_blocks[q] > l->max_blocks || b->n_devices[q] > l->max_devices ||
@@ -280,10 +282,13 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     p.t = b->time_ns + b->block_offset[q];
     p.p = b->param_bytes + b->block_offset[q];
     p.a = b->act_bytes + b->block_offset[q];
+    p.o = b->cut_bytes ? b->cut_bytes + b->block_offset[q] : nullptr;
+    p.bw = b->cut_bytes ? b->bandwidth_bytes_per_us[q] : 0;
     char *base = h->ws + off;
     p.T = (int64_t *)base; base += sz.prefix;
     p.P = (int64_t *)base; base += sz.prefix;
     p.A = (int64_t *)base; base += sz.prefix;
+    p.C = b->cut_bytes ? (int64_t *)base : nullptr; base += sz.prefix;
     p.wlo = (int32_t *)base; base += sz.wlo;
     p.runs = (int32_t *)base; base += sz.runs;
     p.ufit = (uint8_t *)base; base += sz.ufit;
@@ -440,6 +445,7 @@ bool fs_pairs(const rannc_dp_form_stage_in_t *in, std::vector<FsPair> *out, int 
   if (!in || in->n_blocks < 1 || in->n_nodes < 1 || in->devices_per_node < 1 || in->batch_size < 1 ||
       in->mem_capacity < 0 || in->reserved != 0)
     return false;
+  if (in->cut_bytes_per_sample && in->bandwidth_bytes_per_us < 1) return false;
   *max_D = 0;
   for (int64_t n = 1; n <= in->n_nodes; n *= 2) {
     const int64_t D = (int64_t)in->devices_per_node * n;
@@ -456,7 +462,7 @@ bool fs_pairs(const rannc_dp_form_stage_in_t *in, std::vector<FsPair> *out, int 
 
 size_t fs_scratch(int Q, int N, int stride) {
   size_t b = 0;
-  b += 3 * align_up((size_t)Q * N * 8);       // scaled time, param, act
+  b += 4 * align_up((size_t)Q * N * 8);       // scaled time, param, act, cut bytes
   b += 2 * align_up((size_t)Q * 8);           // opt, (n_stages + status as int32 pairs)
   b += align_up((size_t)Q * stride * 8);      // per-level values
   b += align_up((size_t)Q * 4);               // forced levels
@@ -491,7 +497,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (!in->time_per_sample_ns || !in->act_bytes_per_sample || !in->param_bytes) return RANNC_DP_INVALID_ARG;
   std::vector<FsPair> pairs;
   int max_D = 0;
-  std::vector<int64_t> ht, hp, ha, hvals, hM, hoff;
+  std::vector<int64_t> ht, hp, ha, ho, hbw, hvals, hM, hoff;
+  const bool comm = in->cut_bytes_per_sample != nullptr;
   std::vector<int32_t> hN, hD, hS, hMB, hlev, hns, hse, hrp;
   const int N = in->n_blocks;
   try {
@@ -507,6 +514,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (((uintptr_t)d_scratch % kAlign) != 0) return RANNC_DP_INVALID_ARG;
   try {
     ht.resize((size_t)Q * N); hp.resize((size_t)Q * N); ha.resize((size_t)Q * N);
+    if (comm) { ho.resize((size_t)Q * N); hbw.assign(Q, in->bandwidth_bytes_per_us); }
     hvals.resize((size_t)Q * stride); hM.assign(Q, in->mem_capacity); hoff.resize(Q + 1);
     hN.assign(Q, N); hD.resize(Q); hS.resize(Q); hMB.resize(Q); hlev.assign(Q, 0); hns.resize(2 * (size_t)Q);
     hse.resize(stride); hrp.resize(stride);
@@ -527,6 +535,12 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
       ht[(size_t)q * N + k] = ts * pairs[q].b;
       ha[(size_t)q * N + k] = as * pairs[q].b;
       hp[(size_t)q * N + k] = in->param_bytes[k];
+      if (comm) {
+        const int64_t os = in->cut_bytes_per_sample[k];
+        if (os < 0) return RANNC_DP_INVALID_ARG;
+        if ((__int128)os * pairs[q].b > (lim - 1) / 1000) return RANNC_DP_OVERFLOW;
+        ho[(size_t)q * N + k] = os * pairs[q].b;
+      }
     }
   }
   hoff[Q] = (int64_t)Q * N;
@@ -535,6 +549,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   int64_t *d_t = (int64_t *)base; base += align_up((size_t)Q * N * 8);
   int64_t *d_p = (int64_t *)base; base += align_up((size_t)Q * N * 8);
   int64_t *d_a = (int64_t *)base; base += align_up((size_t)Q * N * 8);
+  int64_t *d_o = (int64_t *)base; base += align_up((size_t)Q * N * 8);
   int64_t *d_opt = (int64_t *)base; base += align_up((size_t)Q * 8);
   int32_t *d_ns = (int32_t *)base;
   int32_t *d_st = d_ns + Q; base += align_up((size_t)Q * 8);
@@ -546,8 +561,10 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   const size_t nb = (size_t)Q * N * 8;
   if (hipMemcpyAsync(d_t, ht.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
       hipMemcpyAsync(d_p, hp.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
-      hipMemcpyAsync(d_a, ha.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess) {
+      hipMemcpyAsync(d_a, ha.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
+      (comm && hipMemcpyAsync(d_o, ho.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess)) {
     (void)hipGetLastError();
+    (void)hipStreamSynchronize(st);  // copies already enqueued must not outlive their host buffers
     return RANNC_DP_HIP_ERROR;
   }
   rannc_dp_batch_t b;
@@ -555,6 +572,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   b.n_blocks = hN.data(); b.n_devices = hD.data(); b.max_stages = hS.data();
   b.n_microbatches = hMB.data(); b.mem_capacity = hM.data(); b.block_offset = hoff.data();
   b.time_ns = d_t; b.param_bytes = d_p; b.act_bytes = d_a;
+  b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
+  b.cut_bytes = comm ? d_o : nullptr;
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
   if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
   if (rc != RANNC_DP_OK) {

@@ -53,7 +53,11 @@ struct ProblemDev {
   int64_t M;
   int64_t time_limit;          // limits.max_total_time_ns
   const int64_t *t, *p, *a;    // caller's inputs (DEVICE), N entries each
+  const int64_t *o;            // caller's bytes per cut (DEVICE), N entries, or null: no communication term
+  int64_t bw;                  // bandwidth in bytes per microsecond (>= 1 when o is given)
   int64_t *T, *P, *A;          // prefix sums, N+1 entries each
+  int64_t *C;                  // C[j] = ns to send the bytes of the cut after block j at one replica
+                               // (C[0] = C[N] = 0), N+1 entries; null when o is null
   uint8_t *rmin;
   void *cost;
   void *V;

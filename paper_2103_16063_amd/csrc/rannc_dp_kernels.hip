@@ -41,6 +41,18 @@ __device__ __forceinline__ uint64_t lane_bcast(uint64_t v, int q) {
 }
 
 static constexpr uint64_t kSumLimit = 1ull << 62;
+static constexpr uint64_t kCutLimit = (kSumLimit - 1) / 1000;  // largest bytes of a cut: 1000 * bytes < 2^62
+
+// Time in ns to send `bytes` at `bw` bytes per microsecond from one replica (the communication term
+// of a stage's execution time, Sec. III-C); flags as in the prefix sums.  With r replicas each
+// sends 1/r of it: ceil(1000*bytes / (r*bw)) = ceil(ceil(1000*bytes / bw) / r), so the per-cut
+// value is all the table builder needs.
+__device__ __forceinline__ uint64_t cut_time(int64_t bytes, int64_t bw, int &flags) {
+  if (bytes < 0) { flags |= 1; bytes = 0; }
+  uint64_t u = (uint64_t)bytes;
+  if (u > kCutLimit) { flags |= 2; u = kCutLimit; }
+  return (u * 1000ull + (uint64_t)bw - 1) / (uint64_t)bw;
+}
 static constexpr int kNoRow = 0x7fffffff;
 
 // ---------------------------------------------------------------------------------------
@@ -51,10 +63,11 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
   const ProblemDev pr = probs[blockIdx.x];
   __shared__ uint64_t part[3][256];
   __shared__ int flags;
+  __shared__ unsigned long long max_cut;
   const int N = pr.N, tid = threadIdx.x;
   const int seg = (N + 255) / 256;
   const int lo = min(tid * seg, N), hi = min(lo + seg, N);
-  if (tid == 0) flags = 0;
+  if (tid == 0) { flags = 0; max_cut = 0ull; }
   __syncthreads();
   const int64_t *in[3] = {pr.t, pr.p, pr.a};
   int64_t *out[3] = {pr.T, pr.P, pr.A};
@@ -94,13 +107,23 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
       out[w][k + 1] = (int64_t)run;
     }
   }
+  if (pr.o) {  // per-cut send time; the last block has no follower
+    unsigned long long mc = 0ull;
+    if (tid == 0) pr.C[0] = 0;
+    for (int k = lo; k < hi; ++k) {
+      const uint64_t c = cut_time(pr.o[k], pr.bw, myflags);
+      pr.C[k + 1] = (k + 1 < N) ? (int64_t)c : 0;
+      if (k + 1 < N && c > mc) mc = c;
+    }
+    if (mc) atomicMax(&max_cut, mc);
+  }
   if (myflags) atomicOr(&flags, myflags);
   __syncthreads();
   if (tid == 0) {
     int st = RANNC_DP_PROBLEM_OK;
     if (flags & 1) st = RANNC_DP_PROBLEM_NEGATIVE_INPUT;
     else if (flags & 2) st = RANNC_DP_PROBLEM_SUM_OVERFLOW;
-    else if (pr.T[N] > pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
+    else if ((uint64_t)pr.T[N] + max_cut > (uint64_t)pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
     *pr.status = st;
   }
 }
@@ -137,13 +160,35 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
 // ---------------------------------------------------------------------------------------
 constexpr int kBuildWaves = 4;
 
-// One unit (row i, chunk c) of the tables, by one wave.  T, P, A may live in global memory or in
-// LDS.  Returns whether any stage of the unit fits.  If lds_level1 is given, row 0's entries
+// The D entries of one stage (i,j): ceil(tij / r) (+ ceil(cj / r) with the communication term), INF
+// below rmin.  r is a compile-time constant after unrolling, so the divisions are multiplications.
+template <typename VT, int DP, bool COMM>
+__device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RANNC_GLOBAL *crow,
+                                           VT RANNC_GLOBAL *v1, VT *lds1) {
+#pragma unroll
+  for (int r = 1; r <= DP; ++r) {
+    if (r > D) break;
+    const VT q = tij / (VT)r;
+    VT h = q + (VT)(q * (VT)r != tij);  // ceil
+    if (COMM) {
+      const VT qc = cj / (VT)r;
+      h += qc + (VT)(qc * (VT)r != cj);
+    }
+    const VT v = (r >= rmin) ? h : Lim<VT>::inf;
+    crow[(r - 1) * 64] = v;
+    if (v1) v1[r - 1] = v;
+    if (lds1) lds1[r - 1] = v;
+  }
+}
+
+// One unit (row i, chunk c) of the tables, by one wave.  T, P, A, Cc may live in global memory or in
+// LDS; Cc (per-cut send time at one replica, Cc[N] = 0) is null when there is no communication
+// term.  Returns whether any stage of the unit fits.  If lds_level1 is given, row 0's entries
 // (= level 1 of V) are also written there with row stride ls.
 template <typename VT, int DP>
 __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *T, const int64_t *P,
-                                           const int64_t *A, int i, int c, int lane, VT *lds_level1,
-                                           int ls) {
+                                           const int64_t *A, const int64_t *Cc, int i, int c, int lane,
+                                           VT *lds_level1, int ls) {
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
@@ -173,18 +218,12 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
   VT RANNC_GLOBAL *crow = gptr((VT *)pr.cost) + u * 64 * D + lane;
   VT RANNC_GLOBAL *v1 = gptr((VT *)pr.V) + (int64_t)j * DP;
   const VT tij = (VT)Tij;
-#pragma unroll
-  for (int r = 1; r <= DP; ++r) {
-    if (r > D) break;
-    const VT q = tij / (VT)r;                   // r is a compile-time constant after unrolling
-    const VT h = q + (VT)(q * (VT)r != tij);    // ceil
-    const VT v = (r >= rmin) ? h : Lim<VT>::inf;
-    crow[(r - 1) * 64] = v;
-    if (i == 0) {
-      v1[r - 1] = v;
-      if (lds_level1) lds_level1[j * ls + r - 1] = v;
-    }
-  }
+  if (Cc)  // wave-uniform: with the stage's own send time at one replica (0 for j = N)
+    build_rows<VT, DP, true>(tij, (VT)Cc[j], rmin, D, crow, i == 0 ? v1 : nullptr,
+                             (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
+  else
+    build_rows<VT, DP, false>(tij, (VT)0, rmin, D, crow, i == 0 ? v1 : nullptr,
+                              (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
   return unit_fits;
 }
 
@@ -193,7 +232,7 @@ __global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDe
   const ProblemDev &pr = probs[blockIdx.z];
   const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
   if (i >= pr.N || c >= pr.nch || c < (i >> 6)) return;
-  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, i, c, threadIdx.x & 63, nullptr, 0);
+  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, pr.C, i, c, threadIdx.x & 63, nullptr, 0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -434,7 +473,8 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   constexpr VT INF = Lim<VT>::inf;
   constexpr int LS = DP + 1;  // row stride of a level in LDS: lanes (= columns) hit different banks
   constexpr int NT = 64 * kSmallWaves;
-  __shared__ int64_t sT[kSmallMaxN + 1], sP[kSmallMaxN + 1], sA[kSmallMaxN + 1];
+  __shared__ int64_t sT[kSmallMaxN + 1], sP[kSmallMaxN + 1], sA[kSmallMaxN + 1], sC[kSmallMaxN + 1];
+  __shared__ unsigned long long s_max_cut;
   __shared__ uint64_t scan[3][kSmallMaxN];
   __shared__ VT lv[2][(kSmallMaxN + 1) * LS];
   __shared__ VT s_top[64];
@@ -444,8 +484,14 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- prefix sums and validation (as prefix_kernel) ----
-  if (tid == 0) { s_flags = 0; s_wlo[0] = kNoRow; s_wlo[1] = kNoRow; }
+  if (tid == 0) { s_flags = 0; s_wlo[0] = kNoRow; s_wlo[1] = kNoRow; s_max_cut = 0ull; sC[0] = 0; }
   int myflags = 0;
+  __syncthreads();
+  if (tid < N && pr.o) {  // per-cut send time (as prefix_kernel)
+    const uint64_t c = cut_time(pr.o[tid], pr.bw, myflags);
+    sC[tid + 1] = (tid + 1 < N) ? (int64_t)c : 0;
+    if (tid + 1 < N && c) atomicMax(&s_max_cut, (unsigned long long)c);
+  }
   if (tid < N) {
     const int64_t *in[3] = {pr.t, pr.p, pr.a};
     for (int w = 0; w < 3; ++w) {
@@ -482,14 +528,14 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   int st = RANNC_DP_PROBLEM_OK;
   if (s_flags & 1) st = RANNC_DP_PROBLEM_NEGATIVE_INPUT;
   else if (s_flags & 2) st = RANNC_DP_PROBLEM_SUM_OVERFLOW;
-  else if (sT[N] > pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
+  else if ((uint64_t)sT[N] + s_max_cut > (uint64_t)pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
   if (tid == 0) *pr.status = st;
 
   // ---- tables (as build_kernel): rows 0..min(63,N-1) of chunk 0, then rows 0..N-1 of chunk 1 ----
   const int R0 = min(64, N), RT = R0 + (nch > 1 ? N : 0);
   for (int f = wave; f < RT; f += kSmallWaves) {
     const int c = f >= R0, i = c ? f - R0 : f;
-    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, i, c, lane, lv[0], LS);
+    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, pr.o ? sC : nullptr, i, c, lane, lv[0], LS);
     if (fits && lane == 0) atomicMin(&s_wlo[c], i);
   }
   __syncthreads();
