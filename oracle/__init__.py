@@ -48,6 +48,8 @@ def lib():
         L.rannc_oracle_tables.restype = C.c_int
         L.rannc_oracle_dp.argtypes = [i32, i32, i32, pi64, pu8, pi64, pi32, pi32, i32]
         L.rannc_oracle_dp.restype = C.c_int
+        L.rannc_oracle_dp_split.argtypes = [i32, i32, i32, pi64, pi64, pu8, pi64, pi64, pi64, pi32, pi32, i32]
+        L.rannc_oracle_dp_split.restype = C.c_int
         L.rannc_oracle_select.argtypes = [i32, i32, i32, pi64, pi64, pi32]
         L.rannc_oracle_select.restype = C.c_int
         L.rannc_oracle_traceback.argtypes = [i32, i32, i32, pi32, pi32, i32, pi32, pi32]
@@ -114,6 +116,19 @@ def dp(N: int, D: int, n_levels: int, cost, fit, n_threads: int = 1):
     return V, ai, ad
 
 
+def dp_split(N: int, D: int, n_levels: int, costf, costb, fit, n_threads: int = 1):
+    """Algorithm 1 with separate forward / backward maxima: V, TF, TB, arg_i, arg_d."""
+    shape = (n_levels + 1, N + 1, D + 1)
+    V, TF, TB = (np.empty(shape, dtype=np.int64) for _ in range(3))
+    ai = np.empty(shape, dtype=np.int32)
+    ad = np.empty(shape, dtype=np.int32)
+    _chk(lib().rannc_oracle_dp_split(N, D, n_levels, _p(costf, C.c_int64), _p(costb, C.c_int64),
+                                     _p(fit, C.c_uint8), _p(V, C.c_int64), _p(TF, C.c_int64),
+                                     _p(TB, C.c_int64), _p(ai, C.c_int32), _p(ad, C.c_int32),
+                                     int(n_threads)), "dp_split")
+    return V, TF, TB, ai, ad
+
+
 def select(V):
     n_levels, N, D = V.shape[0] - 1, V.shape[1] - 1, V.shape[2] - 1
     opt = C.c_int64()
@@ -142,7 +157,11 @@ def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=Non
 
     Returns a dict with opt, n_stages, est_iter_ns, stage_end[S], replicas[S] and, with
     keep_tables, T/P/A, cost, fit, V, arg_i, arg_d.  max_levels bounds the number of levels
-    computed (used only to time a bounded sample of a large search)."""
+    computed (used only to time a bounded sample of a large search).  A problem that carries
+    "time_bwd_ns" is searched with the split objective of Algorithm 1 ("time_ns" is then the
+    forward time; the communication term, if any, belongs to the forward pass): opt is the
+    sum of the largest forward and the largest backward stage time, also returned as max_fwd,
+    max_bwd, and keep_tables adds cost_bwd, TF, TB."""
     t, p, a = problem["time_ns"], problem["param_bytes"], problem["act_bytes"]
     N = int(t.shape[0])
     D, S = int(problem["n_devices"]), int(problem["max_stages"])
@@ -155,13 +174,22 @@ def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=Non
     n_levels = min(S, N, D)
     if max_levels is not None:
         n_levels = min(n_levels, int(max_levels))
-    V, ai, ad = dp(N, D, n_levels, cost, fit, n_threads)
+    split = "time_bwd_ns" in problem
+    if split:
+        costb, _ = tables(prefix(problem["time_bwd_ns"]), P, A, D, M)
+        V, TF, TB, ai, ad = dp_split(N, D, n_levels, cost, costb, fit, n_threads)
+    else:
+        V, ai, ad = dp(N, D, n_levels, cost, fit, n_threads)
     opt, ns = select(V)
     se, rp = traceback(ai, ad, ns, S)
     out = {"opt": opt, "n_stages": ns, "est_iter_ns": est_iter_ns(opt, ns, MB),
            "stage_end": se, "replicas": rp, "n_levels": n_levels}
+    if split:
+        out.update(max_fwd=int(TF[ns, N, D]) if ns else INF, max_bwd=int(TB[ns, N, D]) if ns else INF)
     if keep_tables:
         out.update(T=T, P=P, A=A, cost=cost, fit=fit, V=V, arg_i=ai, arg_d=ad)
+        if split:
+            out.update(cost_bwd=costb, TF=TF, TB=TB)
     return out
 
 

@@ -42,6 +42,18 @@
  *   INFEASIBLE (opt = INT64_MAX, 0 stages) if no level is finite.  The plan is recovered by
  *   following the stored (i, d') back from (s*, N, D).
  *
+ *   Split objective (Algorithm 1 as printed): with separate forward and backward block times
+ *   (two stage-time tables hf, hb), every cell also carries the largest forward and the largest
+ *   backward stage time of its chosen plan, tf and tb.  A candidate (i, d') is valued
+ *       v = max(tf[s-1][i][d'], hf(i,j,d-d')) + max(tb[s-1][i][d'], hb(i,j,d-d'))
+ *   and replaces the cell's (V, tf, tb) when v is strictly smaller, candidates scanned in the
+ *   same order as above.  Only ONE (tf, tb) pair survives per cell, so from the third level on
+ *   this is a heuristic for min over plans of (max forward + max backward), not its exact
+ *   minimum; rannc_oracle_dp_split therefore follows the algorithm's steps in its own order.
+ *   What the mathematics still fixes (and the tests pin): levels 1 and 2 are exact; equal or
+ *   all-zero backward times reduce to the min-max search above; every value is the value of the
+ *   plan it comes with and never below the exact minimum.
+ *
  * Pins (tests/test_oracle_*.py): brute-force enumeration of every plan from the definition,
  * closed forms (one stage; memory not binding; the textbook linear-partition problem),
  * invariants, and a separately written per-cell check of the canonical argmin.
@@ -158,6 +170,62 @@ int rannc_oracle_dp(int32_t N, int32_t D, int32_t n_levels, const int64_t *cost,
         V[CELL(s, j, d)] = best;
         arg_i[CELL(s, j, d)] = bi;
         arg_d[CELL(s, j, d)] = bd;
+      }
+    }
+  }
+#undef CELL
+  return ORACLE_OK;
+}
+
+/* Algorithm 1 with the forward and backward maxima carried separately (see the header): costf and
+ * costb are two stage-time tables in the layout of `cost`, TF and TB have the shape of V and hold
+ * the largest forward / backward stage time of the plan behind each cell (0 at level 0's origin,
+ * INF where V is). */
+int rannc_oracle_dp_split(int32_t N, int32_t D, int32_t n_levels, const int64_t *costf,
+                          const int64_t *costb, const uint8_t *fit, int64_t *V, int64_t *TF,
+                          int64_t *TB, int32_t *arg_i, int32_t *arg_d, int32_t n_threads) {
+  if (N < 1 || D < 1 || n_levels < 0 || !costf || !costb || !fit || !V || !TF || !TB || !arg_i ||
+      !arg_d)
+    return ORACLE_BAD_ARG;
+  const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
+#define CELL(s, j, d) ((size_t)(s) * ND + (size_t)(j) * (size_t)(D + 1) + (size_t)(d))
+  for (size_t e = 0; e < ((size_t)n_levels + 1) * ND; ++e) {
+    V[e] = TF[e] = TB[e] = ORACLE_INF;
+    arg_i[e] = -1;
+    arg_d[e] = -1;
+  }
+  V[CELL(0, 0, 0)] = TF[CELL(0, 0, 0)] = TB[CELL(0, 0, 0)] = 0;
+#ifdef _OPENMP
+  if (n_threads > 0) omp_set_num_threads(n_threads);
+#else
+  (void)n_threads;
+#endif
+  for (int32_t s = 1; s <= n_levels; ++s) {
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (int32_t j = s; j <= N; ++j) {
+      for (int32_t d = s; d <= D; ++d) {
+        const size_t c = CELL(s, j, d);
+        for (int32_t i = s - 1; i < j; ++i) {       /* split point b', ascending */
+          for (int32_t dp = s - 1; dp < d; ++dp) {  /* devices of the earlier stages d', ascending */
+            const size_t pc = CELL(s - 1, i, dp);
+            if (V[pc] == ORACLE_INF) continue; /* earlier stages infeasible */
+            const int32_t r = d - dp; /* replicas of the stage being formed */
+            size_t e = (size_t)(((int64_t)j * (j - 1) / 2 + i) * D) + (size_t)(r - 1);
+            if (!fit[e]) continue; /* does not fit device memory */
+            int64_t f = TF[pc] > costf[e] ? TF[pc] : costf[e]; /* longest forward pass so far */
+            int64_t b = TB[pc] > costb[e] ? TB[pc] : costb[e]; /* longest backward pass so far */
+            int64_t v = f + b;
+            if (v < V[c]) {
+              V[c] = v;
+              TF[c] = f;
+              TB[c] = b;
+              arg_i[c] = i;
+              arg_d[c] = dp;
+            }
+          }
+        }
       }
     }
   }

@@ -142,6 +142,24 @@ def with_cut_bytes(problem, seed: int, bandwidth_bytes_per_us: int, lo: int = 1 
     return out
 
 
+def with_backward_times(problem, seed: int, tmax: int = 0, ratio: float = 2.0):
+    """Copy of a problem with separate backward block times (the split objective of the search:
+    "time_ns" then holds the forward times).  tmax > 0: uniform in [0, tmax], independent of the
+    forward times; tmax = 0: about `ratio` times the forward time with +-25 % jitter, the usual
+    shape of a backward pass."""
+    g = np.random.default_rng(seed)
+    t = problem["time_ns"]
+    N = t.shape[0]
+    if tmax > 0:
+        tb = g.integers(0, tmax, N, endpoint=True)
+    else:
+        tb = (t * ratio * (0.75 + 0.5 * g.random(N))).astype(np.int64)
+    out = dict(problem)
+    out["time_bwd_ns"] = np.ascontiguousarray(tb, dtype=np.int64)
+    out["name"] = problem["name"] + "_split"
+    return out
+
+
 def form_stage_case(seed: int, N: int, n_nodes: int, devices_per_node: int, batch_size: int, *,
                     tight: float = 1.0, tmax: int = 2000, layered: bool = False):
     """Inputs of the outer driver of the search (node counts, stage counts and microbatch counts

@@ -149,3 +149,73 @@ def linear_partition(t, s):
         else:
             lo = mid + 1
     return lo
+
+
+# ---- split objective of Algorithm 1: largest forward time + largest backward time -------------
+def plan_value_split(tf, tb, p, a, M, bounds, reps, comm=None):
+    """(feasible, max forward stage time, max backward stage time) of a plan; the communication
+    term, if any, belongs to the forward pass."""
+    mf = mb = 0
+    for u in range(len(reps)):
+        i, j, r = bounds[u], bounds[u + 1], reps[u]
+        if stage_mem(p, a, i, j, r) > M:
+            return False, INF, INF
+        mf = max(mf, stage_time(tf, i, j, r, comm))
+        mb = max(mb, stage_time(tb, i, j, r))
+    return True, mf, mb
+
+
+def brute_force_prefix_split(tf, tb, p, a, s, j, d, M, comm=None):
+    """Exact minimum of (max forward + max backward) over the plans of exactly s stages covering
+    blocks 1..j with exactly d devices."""
+    best = INF
+    if s > j or s > d:
+        return best
+    for cuts in combinations(range(1, j), s - 1):
+        bounds = (0,) + cuts + (j,)
+        for dc in combinations(range(1, d), s - 1):
+            dd = (0,) + dc + (d,)
+            reps = [dd[u + 1] - dd[u] for u in range(s)]
+            ok, mf, mb = plan_value_split(tf, tb, p, a, M, bounds, reps, comm)
+            if ok and mf + mb < best:
+                best = mf + mb
+    return best
+
+
+def walk_back(arg_i, arg_d, s, j, d):
+    """Stage bounds and replica counts of the plan stored behind cell (s, j, d)."""
+    ends, reps = [], []
+    while s >= 1:
+        i, dp = int(arg_i[s, j, d]), int(arg_d[s, j, d])
+        assert 0 <= i < j and 0 <= dp < d
+        ends.append(j)
+        reps.append(d - dp)
+        s, j, d = s - 1, i, dp
+    assert (j, d) == (0, 0)
+    return [0] + ends[::-1], reps[::-1]
+
+
+def split_steps(tf, tb, p, a, D, M, n_levels, comm=None):
+    """Algorithm 1's steps with the separate maxima, written out cell by cell in plain Python
+    (a second, separately written run of the same steps: a cross-check against slips, not a pin)."""
+    N = len(tf)
+    cells = {(0, 0, 0): (0, 0, 0, -1, -1)}
+    for s in range(1, n_levels + 1):
+        for j in range(s, N + 1):
+            for d in range(s, D + 1):
+                best = None
+                for i in range(s - 1, j):
+                    for dp in range(s - 1, d):
+                        prev = cells.get((s - 1, i, dp))
+                        if prev is None:
+                            continue
+                        r = d - dp
+                        if stage_mem(p, a, i, j, r) > M:
+                            continue
+                        f = max(prev[1], stage_time(tf, i, j, r, comm))
+                        b = max(prev[2], stage_time(tb, i, j, r))
+                        if best is None or f + b < best[0]:
+                            best = (f + b, f, b, i, dp)
+                if best is not None:
+                    cells[(s, j, d)] = best
+    return cells

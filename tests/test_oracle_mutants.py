@@ -10,6 +10,7 @@ import pytest
 import oracle
 from tests import test_oracle_comm as comm_pins
 from tests import test_oracle_pins as pins
+from tests import test_oracle_split as split_pins
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "rannc_dp_oracle.c")
 
@@ -46,6 +47,18 @@ MUTANTS = {
     "comm_floor_instead_of_ceil": ("h += (int64_t)((num + den - 1) / den);", "h += (int64_t)(num / den);"),
     "comm_wrong_time_unit": ("num = (__int128)1000 * o[j - 1];", "num = (__int128)1024 * o[j - 1];"),
     "comm_replaces_compute": ("h += (int64_t)((num + den - 1) / den);", "h = (int64_t)((num + den - 1) / den);"),
+    "split_max_instead_of_sum": ("int64_t v = f + b;", "int64_t v = f > b ? f : b;"),
+    "split_keeps_last_minimiser": ("if (v < V[c]) {", "if (v <= V[c]) {"),
+    "split_backward_takes_forward_table": ("int64_t b = TB[pc] > costb[e] ? TB[pc] : costb[e];",
+                                           "int64_t b = TB[pc] > costf[e] ? TB[pc] : costf[e];"),
+    "split_forward_ignores_history": ("int64_t f = TF[pc] > costf[e] ? TF[pc] : costf[e];",
+                                      "int64_t f = costf[e];"),
+    "split_stores_wrong_half": ("TB[c] = b;", "TB[c] = f;"),
+    "split_history_from_value": ("int64_t b = TB[pc] > costb[e] ? TB[pc] : costb[e];",
+                                 "int64_t b = V[pc] > costb[e] ? V[pc] : costb[e];"),
+    "split_skips_split_at_s_minus_1": ("for (int32_t i = s - 1; i < j; ++i) {", "for (int32_t i = s; i < j; ++i) {"),
+    "split_device_loop_stops_early": ("for (int32_t dp = s - 1; dp < d; ++dp) {", "for (int32_t dp = s - 1; dp < d - 1; ++dp) {"),
+    "split_wrong_replica_index": ("const int32_t r = d - dp;", "const int32_t r = dp + 1;"),
     "device_loop_stops_early": ("for (int32_t dp = s - 1; dp <= d - 1; ++dp)",
                                 "for (int32_t dp = s - 1; dp < d - 1; ++dp)"),
 }
@@ -71,6 +84,11 @@ def battery():
     comm_pins.test_worked_example()
     comm_pins.test_tables_against_definition_with_comm()
     comm_pins.test_comm_invariants(0)
+    for row in split_pins.SMALL[:12]:
+        split_pins.test_values_are_plan_values_bounded_by_the_exact_minimum(*row)
+    split_pins.test_worked_example_where_one_pair_per_cell_loses()
+    for seed in range(3):
+        split_pins.test_equal_halves_reduce_to_the_min_max_search(seed)
 
 
 def test_battery_passes_on_the_real_oracle():
@@ -90,7 +108,7 @@ def test_mutant_is_caught(name, tmp_path):
     real = oracle.lib()
     mutant = ctypes.CDLL(str(so))
     for fn in ("rannc_oracle_prefix", "rannc_oracle_table_entries", "rannc_oracle_tables",
-               "rannc_oracle_dp", "rannc_oracle_select", "rannc_oracle_traceback",
+               "rannc_oracle_dp", "rannc_oracle_dp_split", "rannc_oracle_select", "rannc_oracle_traceback",
                "rannc_oracle_est_iter_ns", "rannc_oracle_max_threads"):
         getattr(mutant, fn).argtypes = getattr(real, fn).argtypes
         getattr(mutant, fn).restype = getattr(real, fn).restype
