@@ -60,8 +60,8 @@ typedef enum {
 #define RANNC_DP_PROBLEM_OK 0
 #define RANNC_DP_PROBLEM_NEGATIVE_INPUT 1   /* a block time or size is negative */
 #define RANNC_DP_PROBLEM_SUM_OVERFLOW 2     /* a prefix sum reaches 2^62, or a cut's bytes exceed (2^62-1)/1000 */
-#define RANNC_DP_PROBLEM_TIME_TOO_LARGE 3   /* total time (plus the longest send time of a cut at one
-                                               replica) exceeds limits.max_total_time_ns */
+#define RANNC_DP_PROBLEM_TIME_TOO_LARGE 3   /* total time (forward plus backward, plus the longest send time
+                                               of a cut at one replica) exceeds limits.max_total_time_ns */
 /* A problem with a non-zero status is reported as infeasible. */
 
 #define RANNC_DP_MAX_DEVICES 64   /* largest D the kernels are built for */
@@ -70,6 +70,18 @@ typedef enum {
 #define RANNC_DP_ALGO_AUTO 0
 #define RANNC_DP_ALGO_MERGE 1 /* sorted-merge form of the (min,max) convolution over d' */
 #define RANNC_DP_ALGO_SCAN 2  /* literal scan of every (i, d') candidate per cell */
+
+/* Handle flag: run Algorithm 1 as printed, with separate forward and backward block times.  A
+ * cell of the search then keeps, besides its value, the largest forward and the largest backward
+ * stage time of the plan behind it; a candidate is worth
+ *   max(fwd so far, fwd time of the new stage) + max(bwd so far, bwd time of the new stage),
+ * and the first candidate in scan order (split point ascending, then devices of the earlier
+ * stages ascending) with the smallest sum is kept.  Only that one pair is seen by the next level:
+ * from three stages on this is the paper's heuristic, not the exact minimum of
+ * (largest forward + largest backward).  Batches on such a handle must carry time_bwd_ns
+ * (time_ns is then the forward time); opt is the sum.  The workspace holds two more value tables
+ * and a second stage-time table. */
+#define RANNC_DP_FLAG_SPLIT_OBJECTIVE 1
 
 typedef struct rannc_dp rannc_dp_t; /* opaque; owns host memory only */
 
@@ -83,7 +95,7 @@ typedef struct {
                                 4294967294 the tables hold 32-bit values (half the memory
                                 traffic); above it 64-bit.  Results are the same int64. */
   int32_t algo;              /* RANNC_DP_ALGO_* */
-  int32_t reserved;          /* must be 0 */
+  int32_t flags;             /* RANNC_DP_FLAG_* or 0 */
 } rannc_dp_limits_t;
 
 /* A batch of Q independent searches (Algorithm 2 of Sec. III-C issues many form_stage_dp
@@ -109,6 +121,9 @@ typedef struct {
   const int64_t *bandwidth_bytes_per_us; /* HOST [Q]  >= 1, bytes per microsecond */
   const int64_t *cut_bytes;      /* DEVICE  indexed like time_ns: bytes of the values that cross the cut
                                     after the block, one microbatch; 0 .. (2^62-1)/1000 */
+  const int64_t *time_bwd_ns;    /* DEVICE  backward time of a block; required on a handle with
+                                    RANNC_DP_FLAG_SPLIT_OBJECTIVE (time_ns is then the forward time and
+                                    the send time of a cut belongs to the forward pass), NULL otherwise */
 } rannc_dp_batch_t;
 
 /* Bytes of device workspace that any batch within `limits` fits in (worst case).
@@ -175,7 +190,8 @@ RANNC_DP_API int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t 
  *   out          HOST result; out->feasible == 0 means INFEASIBLE (not an error)
  *   stage_end, replicas  HOST int32[plan_stride]: the plan as in rannc_dp_traceback (replicas
  *                before the factor R: stage u runs on replicas[u] * R devices in total)
- * Errors: INVALID_ARG (bad sizes, negative inputs, devices_per_node * n_max > 64,
+ * Errors: INVALID_ARG (bad sizes, negative inputs, a handle with RANNC_DP_FLAG_SPLIT_OBJECTIVE,
+ * devices_per_node * n_max > 64,
  * plan_stride < min(devices_per_node * n_max, n_blocks)), OVERFLOW (scaled inputs or their sums
  * exceed the handle's value width or 2^62), LIMIT_EXCEEDED / WORKSPACE_TOO_SMALL from solve. */
 typedef struct {
@@ -226,6 +242,11 @@ RANNC_DP_API int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in
 #define RANNC_DP_TABLE_V 2
 #define RANNC_DP_TABLE_ARG_I 3
 #define RANNC_DP_TABLE_ARG_D 4
+/* split objective only: backward stage times (as COST), and per cell the largest forward /
+ * backward stage time of the plan behind it (as V) */
+#define RANNC_DP_TABLE_COST_BWD 5
+#define RANNC_DP_TABLE_MAX_FWD 6
+#define RANNC_DP_TABLE_MAX_BWD 7
 RANNC_DP_API int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, size_t bytes,
                         void *hip_stream);
 

@@ -23,6 +23,8 @@ OK, INVALID_ARG, LIMIT_EXCEEDED, WORKSPACE_TOO_SMALL, OVERFLOW, HIP_ERROR, BAD_S
 PROBLEM_OK, PROBLEM_NEGATIVE_INPUT, PROBLEM_SUM_OVERFLOW, PROBLEM_TIME_TOO_LARGE = 0, 1, 2, 3
 ALGO_AUTO, ALGO_MERGE, ALGO_SCAN = 0, 1, 2
 TABLE_COST, TABLE_FIT, TABLE_V, TABLE_ARG_I, TABLE_ARG_D = 0, 1, 2, 3, 4
+TABLE_COST_BWD, TABLE_MAX_FWD, TABLE_MAX_BWD = 5, 6, 7
+FLAG_SPLIT_OBJECTIVE = 1
 MAX_DEVICES = 64
 NARROW_MAX_TOTAL_TIME = 4294967294
 
@@ -36,7 +38,7 @@ EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp
 class Limits(C.Structure):
     _fields_ = [("max_problems", C.c_int32), ("max_blocks", C.c_int32),
                 ("max_devices", C.c_int32), ("max_stages", C.c_int32),
-                ("max_total_time_ns", C.c_int64), ("algo", C.c_int32), ("reserved", C.c_int32)]
+                ("max_total_time_ns", C.c_int64), ("algo", C.c_int32), ("flags", C.c_int32)]
 
 
 class Batch(C.Structure):
@@ -45,7 +47,8 @@ class Batch(C.Structure):
                 ("n_microbatches", C.c_void_p), ("mem_capacity", C.c_void_p),
                 ("block_offset", C.c_void_p),
                 ("time_ns", C.c_void_p), ("param_bytes", C.c_void_p), ("act_bytes", C.c_void_p),
-                ("bandwidth_bytes_per_us", C.c_void_p), ("cut_bytes", C.c_void_p)]
+                ("bandwidth_bytes_per_us", C.c_void_p), ("cut_bytes", C.c_void_p),
+                ("time_bwd_ns", C.c_void_p)]
 
 
 class FormStageIn(C.Structure):
@@ -131,29 +134,30 @@ def _ptr(x):
 
 
 def make_limits(max_problems, max_blocks, max_devices, max_stages,
-                max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO) -> Limits:
+                max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO, flags=0) -> Limits:
     return Limits(int(max_problems), int(max_blocks), int(max_devices), int(max_stages),
-                  int(max_total_time_ns), int(algo), 0)
+                  int(max_total_time_ns), int(algo), int(flags))
 
 
 class HostBatch:
     """Keeps the numpy arrays of a batch's HOST members alive next to the C struct."""
 
     def __init__(self, n_blocks, n_devices, max_stages, n_microbatches, mem_capacity, block_offset,
-                 time_ns, param_bytes, act_bytes, bandwidth_bytes_per_us=None, cut_bytes=None):
+                 time_ns, param_bytes, act_bytes, bandwidth_bytes_per_us=None, cut_bytes=None,
+                 time_bwd_ns=None):
         self.keep = [np.ascontiguousarray(n_blocks, dtype=np.int32),
                      np.ascontiguousarray(n_devices, dtype=np.int32),
                      np.ascontiguousarray(max_stages, dtype=np.int32),
                      np.ascontiguousarray(n_microbatches, dtype=np.int32),
                      np.ascontiguousarray(mem_capacity, dtype=np.int64),
                      np.ascontiguousarray(block_offset, dtype=np.int64)]
-        self.device = (time_ns, param_bytes, act_bytes, cut_bytes)  # DEVICE tensors (kept alive)
+        self.device = (time_ns, param_bytes, act_bytes, cut_bytes, time_bwd_ns)  # DEVICE tensors (kept alive)
         self.n_problems = int(self.keep[0].shape[0])
         self.bw = (None if bandwidth_bytes_per_us is None
                    else np.ascontiguousarray(bandwidth_bytes_per_us, dtype=np.int64))
         self.struct = Batch(self.n_problems, *[_ptr(a) for a in self.keep],
                             _ptr(time_ns), _ptr(param_bytes), _ptr(act_bytes), _ptr(self.bw),
-                            _ptr(cut_bytes))
+                            _ptr(cut_bytes), _ptr(time_bwd_ns))
 
 
 def rannc_dp_workspace_bytes(limits: Limits) -> int:
@@ -263,16 +267,21 @@ class Session:
         self.Q = int(b["n_problems"])
         self.batch_np = b
         self.S_eff = np.minimum(b["max_stages"], np.minimum(b["n_blocks"], b["n_devices"]))
+        self.split = "time_bwd_ns" in b
         self.limits = make_limits(self.Q, int(b["n_blocks"].max()), int(b["n_devices"].max()),
-                                  int(self.S_eff.max()), max_total_time_ns, algo)
+                                  int(self.S_eff.max()), max_total_time_ns, algo,
+                                  FLAG_SPLIT_OBJECTIVE if self.split else 0)
         self.d_in = [torch.from_numpy(np.ascontiguousarray(b[k], dtype=np.int64)).to(self.dev)
                      for k in ("time_ns", "param_bytes", "act_bytes")]
+        self.d_bwd = None
+        if self.split:
+            self.d_bwd = torch.from_numpy(np.ascontiguousarray(b["time_bwd_ns"], dtype=np.int64)).to(self.dev)
         self.d_cut = None
         if "cut_bytes" in b:
             self.d_cut = torch.from_numpy(np.ascontiguousarray(b["cut_bytes"], dtype=np.int64)).to(self.dev)
         self.hb = HostBatch(b["n_blocks"], b["n_devices"], b["max_stages"], b["n_microbatches"],
                             b["mem_capacity"], b["block_offset"], *self.d_in,
-                            b.get("bandwidth_bytes_per_us"), self.d_cut)
+                            b.get("bandwidth_bytes_per_us"), self.d_cut, self.d_bwd)
         nbytes = (rannc_dp_workspace_bytes_for(self.limits, self.hb) if exact_workspace
                   else rannc_dp_workspace_bytes(self.limits))
         if nbytes == 0:
@@ -319,11 +328,11 @@ class Session:
                    int(self.S_eff[q]))
         tri = N * (N + 1) // 2 * D
         cells = (L + 1) * (N + 1) * (D + 1)
-        if which == TABLE_COST:
+        if which in (TABLE_COST, TABLE_COST_BWD):
             dst = torch.empty(tri, dtype=torch.int64, device=self.dev)
         elif which == TABLE_FIT:
             dst = torch.empty(tri, dtype=torch.uint8, device=self.dev)
-        elif which == TABLE_V:
+        elif which in (TABLE_V, TABLE_MAX_FWD, TABLE_MAX_BWD):
             dst = torch.empty(cells, dtype=torch.int64, device=self.dev)
         else:
             dst = torch.empty(cells, dtype=torch.int32, device=self.dev)
@@ -333,7 +342,7 @@ class Session:
             raise RanncDpError(rc, "rannc_dp_read_table")
         torch.cuda.synchronize(self.dev)
         out = dst.cpu().numpy()
-        if which in (TABLE_V, TABLE_ARG_I, TABLE_ARG_D):
+        if which in (TABLE_V, TABLE_ARG_I, TABLE_ARG_D, TABLE_MAX_FWD, TABLE_MAX_BWD):
             out = out.reshape(L + 1, N + 1, D + 1)
         return out
 

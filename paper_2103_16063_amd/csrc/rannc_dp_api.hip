@@ -24,11 +24,15 @@ inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Sizes {  // bytes of one problem's regions inside the workspace
   size_t prefix, wlo, runs, ufit, misc, rmin, cost, V;
-  size_t total() const { return prefix * 4 + wlo + runs + ufit + misc + rmin + cost + V; }
+  bool split;  // split objective: a fifth prefix array, a second stage-time table, two more value tables
+  size_t total() const {
+    return prefix * (split ? 5 : 4) + wlo + runs + ufit + misc + rmin + cost * (split ? 2 : 1) +
+           V * (split ? 3 : 1);
+  }
 };
 
 // false on arithmetic overflow
-bool problem_sizes(int N, int D, int S_eff, int bits, Sizes *o) {
+bool problem_sizes(int N, int D, int S_eff, int bits, bool split, Sizes *o) {
   const int nch = (N + 63) / 64;
   const int DP = rannc::dp_class(D);
   const size_t esz = bits / 8;
@@ -44,16 +48,18 @@ bool problem_sizes(int N, int D, int S_eff, int bits, Sizes *o) {
   o->rmin = align_up((size_t)rows);
   o->cost = align_up((size_t)cost);
   o->V = align_up((size_t)V);
+  o->split = split;
   return true;
 }
 
 bool limits_ok(const rannc_dp_limits_t *l) {
   return l && l->max_problems >= 1 && l->max_blocks >= 1 && l->max_blocks <= 65535 &&
          l->max_devices >= 1 && l->max_devices <= RANNC_DP_MAX_DEVICES && l->max_stages >= 1 &&
-         l->max_total_time_ns >= 0 && l->reserved == 0 && l->algo >= RANNC_DP_ALGO_AUTO &&
+         l->max_total_time_ns >= 0 && (l->flags & ~RANNC_DP_FLAG_SPLIT_OBJECTIVE) == 0 && l->algo >= RANNC_DP_ALGO_AUTO &&
          l->algo <= RANNC_DP_ALGO_SCAN;
 }
 
+bool split_of(const rannc_dp_limits_t *l) { return (l->flags & RANNC_DP_FLAG_SPLIT_OBJECTIVE) != 0; }
 int bits_of(const rannc_dp_limits_t *l) { return l->max_total_time_ns <= kNarrowMax ? 32 : 64; }
 
 size_t header_bytes(int Q) { return align_up((size_t)Q * sizeof(ProblemDev)); }
@@ -130,7 +136,7 @@ size_t rannc_dp_workspace_bytes(const rannc_dp_limits_t *l) {
   if (!limits_ok(l)) return 0;
   Sizes sz;
   const int S_eff = std::min(l->max_stages, std::min(l->max_blocks, l->max_devices));
-  if (!problem_sizes(l->max_blocks, l->max_devices, S_eff, bits_of(l), &sz)) return 0;
+  if (!problem_sizes(l->max_blocks, l->max_devices, S_eff, bits_of(l), split_of(l), &sz)) return 0;
   const unsigned __int128 tot =
       (unsigned __int128)sz.total() * (unsigned)l->max_problems + header_bytes(l->max_problems);
   if (tot > ((unsigned __int128)1 << 47)) return 0;
@@ -143,7 +149,7 @@ size_t rannc_dp_workspace_bytes_for(const rannc_dp_limits_t *l, const rannc_dp_b
   for (int q = 0; q < b->n_problems; ++q) {
     Sizes sz;
     const int S_eff = std::min(b->max_stages[q], std::min(b->n_blocks[q], b->n_devices[q]));
-    if (!problem_sizes(b->n_blocks[q], b->n_devices[q], S_eff, bits_of(l), &sz)) return 0;
+    if (!problem_sizes(b->n_blocks[q], b->n_devices[q], S_eff, bits_of(l), split_of(l), &sz)) return 0;
     tot += sz.total();
     if (tot > ((size_t)1 << 47)) return 0;
   }
@@ -234,6 +240,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   int rc = check_batch(&h->lim, b);
   if (rc != RANNC_DP_OK) return rc;
   if (!b->time_ns || !b->param_bytes || !b->act_bytes) return RANNC_DP_INVALID_ARG;
+  const bool split = split_of(&h->lim);
+  if (split != (b->time_bwd_ns != nullptr)) return RANNC_DP_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
   const int Q = b->n_problems;
 
@@ -268,7 +276,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     const int N = b->n_blocks[q], D = b->n_devices[q];
     const int S_eff = std::min(b->max_stages[q], std::min(N, D));
     Sizes sz;
-    if (!problem_sizes(N, D, S_eff, h->bits, &sz)) return RANNC_DP_OVERFLOW;
+    if (!problem_sizes(N, D, S_eff, h->bits, split, &sz)) return RANNC_DP_OVERFLOW;
     if (off + sz.total() > h->ws_bytes) return RANNC_DP_WORKSPACE_TOO_SMALL;
     ProblemDev &p = probs[pos_of[q]];
     std::memset(&p, 0, sizeof(p));
@@ -289,6 +297,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     p.P = (int64_t *)base; base += sz.prefix;
     p.A = (int64_t *)base; base += sz.prefix;
     p.C = b->cut_bytes ? (int64_t *)base : nullptr; base += sz.prefix;
+    if (split) {
+      p.tb = b->time_bwd_ns + b->block_offset[q];
+      p.TB = (int64_t *)base; base += sz.prefix;
+    }
     p.wlo = (int32_t *)base; base += sz.wlo;
     p.runs = (int32_t *)base; base += sz.runs;
     p.ufit = (uint8_t *)base; base += sz.ufit;
@@ -297,6 +309,11 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     p.rmin = (uint8_t *)base; base += sz.rmin;
     p.cost = base; base += sz.cost;
     p.V = base; base += sz.V;
+    if (split) {
+      p.costb = base; base += sz.cost;
+      p.VF = base; base += sz.V;
+      p.VB = base; base += sz.V;
+    }
     off += sz.total();
     for (int k = 0; k < 4; ++k)
       if (p.DP == kClasses[k]) {
@@ -346,7 +363,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       const int64_t rows = std::min(sh.max_N, 64) + (sh.max_nch > 1 ? sh.max_N : 0);
       const bool batch = sh.nprob >= 32 && kClasses[k] <= 16;
       const bool tiny = rows * (sh.max_S_eff - 1) <= 256;
-      fused[k] = !scan && sh.max_N <= rannc::small_max_blocks() &&
+      fused[k] = !scan && !split && sh.max_N <= rannc::small_max_blocks() &&
                  (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);
     }
     if (fused[k]) continue;
@@ -354,7 +371,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     ok = ok && rannc::launch_fill(cp, sh.nprob, st) == hipSuccess;
     ok = ok && rannc::launch_build(cp, sh, h->bits, kClasses[k], st) == hipSuccess;
     ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
-    if (scan) continue;
+    if (split) ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
+    if (scan || split) continue;
     // One predecessor row per wave: measured best on every configuration (most waves in flight
     // to hide the latency of the row reads).  RANNC_DP_ROWS_PER_WAVE = 2 or 4 selects the variants
     // that keep several rows per wave with double-buffered reads.
@@ -377,7 +395,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     for (int k = 0; k < 4 && ok; ++k) {
       const LaunchShape &sh = shape[k];
       if (!sh.nprob || sh.max_S_eff < s || fused[k]) continue;
-      if (scan)
+      if (split)
+        ok = rannc::launch_level_split(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
+             hipSuccess;
+      else if (scan)
         ok = rannc::launch_level_scan(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;
       else
@@ -508,6 +529,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   }
   const int Q = (int)pairs.size();
   if (Q == 0) return RANNC_DP_INVALID_ARG;
+  if (split_of(&h->lim)) return RANNC_DP_INVALID_ARG;  // the driver's inputs carry one time per block
   const int stride = max_D;
   if (plan_stride < std::min(stride, N)) return RANNC_DP_INVALID_ARG;
   if (scratch_bytes < fs_scratch(Q, N, stride)) return RANNC_DP_WORKSPACE_TOO_SMALL;
@@ -574,6 +596,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   b.time_ns = d_t; b.param_bytes = d_p; b.act_bytes = d_a;
   b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
   b.cut_bytes = comm ? d_o : nullptr;
+  b.time_bwd_ns = nullptr;
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
   if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
   if (rc != RANNC_DP_OK) {
@@ -650,6 +673,15 @@ int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, 
   const size_t cells = (size_t)(p.S_eff + 1) * (size_t)(p.N + 1) * (size_t)(p.D + 1);
   size_t want = 0;
   switch (which) {
+    case RANNC_DP_TABLE_COST_BWD:
+      if (!p.costb) return RANNC_DP_INVALID_ARG;
+      want = tri * 8;
+      break;
+    case RANNC_DP_TABLE_MAX_FWD:
+    case RANNC_DP_TABLE_MAX_BWD:
+      if (!p.VF) return RANNC_DP_INVALID_ARG;
+      want = cells * 8;
+      break;
     case RANNC_DP_TABLE_COST: want = tri * 8; break;
     case RANNC_DP_TABLE_FIT: want = tri; break;
     case RANNC_DP_TABLE_V: want = cells * 8; break;
@@ -666,7 +698,8 @@ int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, 
     int32_t *ai = which == RANNC_DP_TABLE_ARG_I ? (int32_t *)d_dst : nullptr;
     int32_t *ad = which == RANNC_DP_TABLE_ARG_D ? (int32_t *)d_dst : nullptr;
     for (int s = 2; s <= p.S_eff && ok; ++s)
-      ok = rannc::launch_level_scan(h->d_probs + pos, sh, p.bits, s, 0, ai, ad, st) == hipSuccess;
+      ok = (p.VF ? rannc::launch_level_split(h->d_probs + pos, sh, p.bits, s, 0, ai, ad, st)
+                 : rannc::launch_level_scan(h->d_probs + pos, sh, p.bits, s, 0, ai, ad, st)) == hipSuccess;
   }
   if (!ok) {
     (void)hipGetLastError();

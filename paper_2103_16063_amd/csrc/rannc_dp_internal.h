@@ -53,6 +53,11 @@ struct ProblemDev {
   int64_t M;
   int64_t time_limit;          // limits.max_total_time_ns
   const int64_t *t, *p, *a;    // caller's inputs (DEVICE), N entries each
+  const int64_t *tb;           // caller's backward block times (DEVICE), or null: one time per block (min-max search)
+  int64_t *TB;                 // prefix sums of tb, N+1 entries; null when tb is null
+  void *costb;                 // backward stage-time table, layout of cost; null when tb is null
+  void *VF, *VB;               // largest forward / backward stage time of the plan behind each V entry
+                               // (layout of V); null when tb is null
   const int64_t *o;            // caller's bytes per cut (DEVICE), N entries, or null: no communication term
   int64_t bw;                  // bandwidth in bytes per microsecond (>= 1 when o is given)
   int64_t *T, *P, *A;          // prefix sums, N+1 entries each
@@ -93,6 +98,12 @@ hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, 
                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st);
 hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int bits, int s,
                              int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st);
+// Algorithm 1 with forward and backward maxima carried separately (problems with tb != null):
+// level 1 from the two tables, then one launch per level s >= 2.  write_v = 0: only the argmin
+// arrays (canonical layout of ONE problem) are written.
+hipError_t launch_split_level1(const ProblemDev *probs, const LaunchShape &sh, int bits, hipStream_t st);
+hipError_t launch_level_split(const ProblemDev *probs, const LaunchShape &sh, int bits, int s, int write_v,
+                              int32_t *arg_i, int32_t *arg_d, hipStream_t st);
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
 // d_levels: per problem (caller's order) the exact stage count to recover, 0 = the best one; or null

@@ -61,7 +61,7 @@ static constexpr int kNoRow = 0x7fffffff;
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restrict__ probs) {
   const ProblemDev pr = probs[blockIdx.x];
-  __shared__ uint64_t part[3][256];
+  __shared__ uint64_t part[4][256];
   __shared__ int flags;
   __shared__ unsigned long long max_cut;
   const int N = pr.N, tid = threadIdx.x;
@@ -69,10 +69,11 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
   const int lo = min(tid * seg, N), hi = min(lo + seg, N);
   if (tid == 0) { flags = 0; max_cut = 0ull; }
   __syncthreads();
-  const int64_t *in[3] = {pr.t, pr.p, pr.a};
-  int64_t *out[3] = {pr.T, pr.P, pr.A};
+  const int64_t *in[4] = {pr.t, pr.p, pr.a, pr.tb};
+  int64_t *out[4] = {pr.T, pr.P, pr.A, pr.TB};
+  const int nw = pr.tb ? 4 : 3;  // backward times only with the split objective
   int myflags = 0;
-  for (int w = 0; w < 3; ++w) {
+  for (int w = 0; w < nw; ++w) {
     uint64_t s = 0;
     for (int k = lo; k < hi; ++k) {
       int64_t v = in[w][k];
@@ -86,16 +87,16 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
   __syncthreads();
   // inclusive scan of the 256 segment sums (saturating add is associative on [0, limit])
   for (int off = 1; off < 256; off <<= 1) {
-    uint64_t add[3];
-    for (int w = 0; w < 3; ++w) add[w] = tid >= off ? part[w][tid - off] : 0;
+    uint64_t add[4];
+    for (int w = 0; w < nw; ++w) add[w] = tid >= off ? part[w][tid - off] : 0;
     __syncthreads();
-    for (int w = 0; w < 3; ++w) {
+    for (int w = 0; w < nw; ++w) {
       uint64_t v = part[w][tid] + add[w];
       part[w][tid] = v > kSumLimit ? kSumLimit : v;
     }
     __syncthreads();
   }
-  for (int w = 0; w < 3; ++w) {
+  for (int w = 0; w < nw; ++w) {
     uint64_t run = tid ? part[w][tid - 1] : 0;  // sum of the segments before this thread's
     if (tid == 0) out[w][0] = 0;
     for (int k = lo; k < hi; ++k) {
@@ -123,7 +124,8 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
     int st = RANNC_DP_PROBLEM_OK;
     if (flags & 1) st = RANNC_DP_PROBLEM_NEGATIVE_INPUT;
     else if (flags & 2) st = RANNC_DP_PROBLEM_SUM_OVERFLOW;
-    else if ((uint64_t)pr.T[N] + max_cut > (uint64_t)pr.time_limit) st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;
+    else if ((uint64_t)pr.T[N] + (pr.tb ? (uint64_t)pr.TB[N] : 0ull) + max_cut > (uint64_t)pr.time_limit)
+      st = RANNC_DP_PROBLEM_TIME_TOO_LARGE;  // a value is at most forward + send + backward time of all blocks
     *pr.status = st;
   }
 }
@@ -137,14 +139,17 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
   const int64_t total = (int64_t)pr.S_eff * (pr.N + 1) * pr.DP;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (pr.bits == 32) {
-    uint32_t *V = (uint32_t *)pr.V;
-    for (int64_t e = t0; e < total; e += stride)
-      V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint32_t>::inf : 0u;
-  } else {
-    uint64_t *V = (uint64_t *)pr.V;
-    for (int64_t e = t0; e < total; e += stride)
-      V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint64_t>::inf : 0ull;
+  void *tabs[3] = {pr.V, pr.VF, pr.VB};
+  for (int w = 0; w < (pr.VF ? 3 : 1); ++w) {
+    if (pr.bits == 32) {
+      uint32_t *V = (uint32_t *)tabs[w];
+      for (int64_t e = t0; e < total; e += stride)
+        V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint32_t>::inf : 0u;
+    } else {
+      uint64_t *V = (uint64_t *)tabs[w];
+      for (int64_t e = t0; e < total; e += stride)
+        V[e] = ((int)(e & (pr.DP - 1)) < pr.D) ? Lim<uint64_t>::inf : 0ull;
+    }
   }
 }
 
@@ -188,7 +193,7 @@ __device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RA
 template <typename VT, int DP>
 __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *T, const int64_t *P,
                                            const int64_t *A, const int64_t *Cc, int i, int c, int lane,
-                                           VT *lds_level1, int ls) {
+                                           VT *lds_level1, int ls, const int64_t *TBp = nullptr) {
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
@@ -224,6 +229,9 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
   else
     build_rows<VT, DP, false>(tij, (VT)0, rmin, D, crow, i == 0 ? v1 : nullptr,
                               (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
+  if (TBp)  // split objective: the backward times get a table of their own (never a send time)
+    build_rows<VT, DP, false>((VT)(TBp[j] - TBp[i]), (VT)0, rmin, D,
+                              gptr((VT *)pr.costb) + u * 64 * D + lane, nullptr, nullptr);
   return unit_fits;
 }
 
@@ -232,7 +240,7 @@ __global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDe
   const ProblemDev &pr = probs[blockIdx.z];
   const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
   if (i >= pr.N || c >= pr.nch || c < (i >> 6)) return;
-  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, pr.C, i, c, threadIdx.x & 63, nullptr, 0);
+  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, pr.C, i, c, threadIdx.x & 63, nullptr, 0, pr.TB);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -644,6 +652,141 @@ __global__ __launch_bounds__(64) void level_scan_kernel(const ProblemDev *__rest
 }
 
 // ---------------------------------------------------------------------------------------
+// Algorithm 1 as printed: forward and backward maxima carried separately (problems with backward
+// times).  A cell keeps V = f + b together with the pair (f, b) of the first candidate, in the
+// scan order (i ascending, then d' ascending), that attains the smallest sum; only that pair is
+// seen by the next level.  The sum of two maxima does not separate over the two sequences, so the
+// sorted-merge form does not apply: every candidate is evaluated, one wave per (64 columns, d),
+// a lane per column j, as in the literal scan kernel.
+// ---------------------------------------------------------------------------------------
+// Level 1: the single stage 1..j on d replicas.
+template <typename VT>
+__global__ __launch_bounds__(64) void split_level1_kernel(const ProblemDev *__restrict__ probs) {
+  const ProblemDev &pr = probs[blockIdx.z];
+  const int c = blockIdx.x, d = blockIdx.y + 1;
+  if (c >= pr.nch || d > pr.D) return;
+  const int lane = threadIdx.x, jj = 64 * c + lane;
+  if (jj >= pr.N) return;
+  const int D = pr.D, DP = pr.DP;
+  const int64_t u = unit_index(pr.nch, 0, c);
+  const int64_t e = (int64_t)(jj + 1) * DP + d - 1;
+  if (d < (int)pr.rmin[u * 64 + lane]) return;  // stays "no plan"
+  const VT f = ((const VT *)pr.cost)[(u * D + (d - 1)) * 64 + lane];
+  const VT b = ((const VT *)pr.costb)[(u * D + (d - 1)) * 64 + lane];
+  ((VT *)pr.V)[e] = f + b;
+  ((VT *)pr.VF)[e] = f;
+  ((VT *)pr.VB)[e] = b;
+}
+
+template <typename VT>
+__global__ __launch_bounds__(64) void level_split_kernel(const ProblemDev *__restrict__ probs, const int s,
+                                                         const int write_v, int32_t *__restrict__ arg_i,
+                                                         int32_t *__restrict__ arg_d) {
+  const ProblemDev &pr = probs[blockIdx.z];
+  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  if (s > pr.S_eff) return;
+  const int c = blockIdx.x, d = blockIdx.y + 1;
+  if (c >= nch || d > D || d < s) return;
+  const int lane = threadIdx.x;
+  const int jj = 64 * c + lane;
+  const int j = jj + 1;
+  constexpr VT INF = Lim<VT>::inf;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT RANNC_GLOBAL *Vprev = gptr((const VT *)pr.V) + (int64_t)(s - 2) * lvl;
+  const VT RANNC_GLOBAL *Fprev = gptr((const VT *)pr.VF) + (int64_t)(s - 2) * lvl;
+  const VT RANNC_GLOBAL *Bprev = gptr((const VT *)pr.VB) + (int64_t)(s - 2) * lvl;
+  const VT RANNC_GLOBAL *costf = gptr((const VT *)pr.cost);
+  const VT RANNC_GLOBAL *costb = gptr((const VT *)pr.costb);
+  const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
+  const uint8_t RANNC_GLOBAL *ufit = gptr((const uint8_t *)pr.ufit);
+  VT best = INF, bf = INF, bb = INF;
+  int bi = -1, bd = -1;
+  const int i_end = min(64 * c + 63, N - 1);
+  for (int i = s - 1; i <= i_end; ++i) {
+    // a plan of s-1 stages over blocks 1..i exists on d-1 devices iff it exists on any fewer
+    if (Vprev[(int64_t)i * DP + d - 2] == INF) continue;
+    const int64_t u = unit_index(nch, i, c);
+    if (!ufit[u]) continue;  // no stage of this unit fits: its table rows were never written
+    const bool act = (jj >= i) && (jj < N);
+    const VT RANNC_GLOBAL *uf = costf + u * 64 * D + lane;
+    const VT RANNC_GLOBAL *ub = costb + u * 64 * D + lane;
+    const int rmn = act ? (int)rmin[u * 64 + lane] : 255;
+    for (int dp = s - 1; dp <= d - 1; ++dp) {
+      const VT a = Vprev[(int64_t)i * DP + dp - 1];
+      if (a == INF) continue;      // earlier stages infeasible
+      if (d - dp < rmn) continue;  // does not fit device memory
+      const VT f = vmax(Fprev[(int64_t)i * DP + dp - 1], uf[(d - dp - 1) * 64]);
+      const VT b = vmax(Bprev[(int64_t)i * DP + dp - 1], ub[(d - dp - 1) * 64]);
+      const VT v = f + b;
+      if (v < best) { best = v; bf = f; bb = b; bi = i; bd = dp; }
+    }
+  }
+  if (jj >= N || j < s) return;
+  if (write_v) {
+    const int64_t e = (int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1;
+    ((VT *)pr.V)[e] = best;
+    ((VT *)pr.VF)[e] = bf;
+    ((VT *)pr.VB)[e] = bb;
+  }
+  const int64_t e = ((int64_t)s * (N + 1) + j) * (D + 1) + d;
+  if (arg_i) arg_i[e] = bi;
+  if (arg_d) arg_d[e] = bd;
+}
+
+// Plan recovery for the split objective: the candidate kept by a cell is the first one, in scan
+// order, whose sum equals the cell's value.  All threads of the workgroup evaluate the candidates
+// of one cell, numbered in scan order, and the smallest matching number wins.
+template <typename VT>
+__device__ void traceback_split_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
+                                     unsigned int *best_key, int forced) {
+  constexpr VT INF = Lim<VT>::inf;
+  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  const int tid = threadIdx.x;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT *V = (const VT *)pr.V, *VF = (const VT *)pr.VF, *VB = (const VT *)pr.VB;
+  const VT *costf = (const VT *)pr.cost, *costb = (const VT *)pr.costb;
+  int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
+  if (forced > 0 && *pr.status == 0)
+    ns = (forced <= pr.S_eff && V[(int64_t)(forced - 1) * lvl + (int64_t)N * DP + D - 1] != INF) ? forced : 0;
+  for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
+  if (ns == 0) return;
+  int j = N, d = D;
+  for (int s = ns; s >= 2; --s) {
+    if (tid == 0) *best_key = 0xFFFFFFFFu;
+    __syncthreads();
+    const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
+    const int jj = j - 1, c = jj >> 6;
+    const int nd = d - (s - 1);                       // d' = s-1 .. d-1
+    const int total = (j - (s - 1)) * nd;             // i = s-1 .. j-1
+    unsigned mine = 0xFFFFFFFFu;
+    for (int e = tid; e < total && mine == 0xFFFFFFFFu; e += blockDim.x) {
+      const int i = s - 1 + e / nd, dp = s - 1 + e % nd;
+      const int64_t pc = (int64_t)(s - 2) * lvl + (int64_t)i * DP + dp - 1;
+      if (V[pc] == INF) continue;
+      const int64_t u = unit_index(nch, i, c);
+      const int r = d - dp;
+      if (r < (int)pr.rmin[u * 64 + (jj & 63)]) continue;
+      const int64_t te = (u * D + (r - 1)) * 64 + (jj & 63);
+      const VT f = vmax(VF[pc], costf[te]), b = vmax(VB[pc], costb[te]);
+      if ((VT)(f + b) == v) mine = ((unsigned)i << 8) | (unsigned)dp;  // (i, d') ascends with e
+    }
+    if (mine != 0xFFFFFFFFu) atomicMin(best_key, mine);
+    __syncthreads();
+    const unsigned key = *best_key;
+    __syncthreads();
+    if (key == 0xFFFFFFFFu) {  // tables inconsistent: report no plan rather than walk on
+      for (int u = tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
+      return;
+    }
+    const int i_sel = (int)(key >> 8), d_sel = (int)(key & 255u);
+    if (tid == 0) { se[s - 1] = j; rp[s - 1] = d - d_sel; }
+    j = i_sel;
+    d = d_sel;
+  }
+  if (tid == 0) { se[0] = j; rp[0] = d; }
+}
+
+// ---------------------------------------------------------------------------------------
 // Final choice of the stage count: opt = min over s of V[s][N][D], smallest s among equals.
 // One wave per problem, lane s-1 reads V[s][N][D] (S_eff <= D <= 64).
 // ---------------------------------------------------------------------------------------
@@ -804,6 +947,11 @@ __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
     case 32: traceback_body<T, 32>(pr, plan_stride, se, rp, &best_key, forced); break;          \
     default: traceback_body<T, 64>(pr, plan_stride, se, rp, &best_key, forced); break;          \
   }
+  if (pr.VF) {  // split objective: first-match over all candidates
+    if (pr.bits == 32) traceback_split_body<uint32_t>(pr, plan_stride, se, rp, &best_key, forced);
+    else traceback_split_body<uint64_t>(pr, plan_stride, se, rp, &best_key, forced);
+    return;
+  }
   if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
 }
@@ -820,7 +968,8 @@ __global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restric
   const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   constexpr VT INF = Lim<VT>::inf;
   const bool bad = *pr.status != 0;
-  if (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_FIT) {
+  if (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_FIT || which == RANNC_DP_TABLE_COST_BWD) {
+    const VT *ctab = (const VT *)(which == RANNC_DP_TABLE_COST_BWD ? pr.costb : pr.cost);
     const int64_t total = (int64_t)N * (N + 1) / 2 * D;
     for (int64_t e = t0; e < total; e += stride) {
       const int r = (int)(e % D) + 1;
@@ -835,11 +984,12 @@ __global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restric
         ((uint8_t *)dst)[e] = bad ? 0 : (uint8_t)(r >= (int)pr.rmin[u * 64 + (jj & 63)]);
       } else {
         const bool fit = !bad && r >= (int)pr.rmin[u * 64 + (jj & 63)];
-        const VT v = fit ? ((const VT *)pr.cost)[(u * D + (r - 1)) * 64 + (jj & 63)] : INF;
+        const VT v = fit ? ctab[(u * D + (r - 1)) * 64 + (jj & 63)] : INF;
         ((int64_t *)dst)[e] = (v == INF) ? INT64_MAX : (int64_t)v;
       }
     }
-  } else if (which == RANNC_DP_TABLE_V) {
+  } else if (which == RANNC_DP_TABLE_V || which == RANNC_DP_TABLE_MAX_FWD || which == RANNC_DP_TABLE_MAX_BWD) {
+    const VT *vtab = (const VT *)(which == RANNC_DP_TABLE_V ? pr.V : which == RANNC_DP_TABLE_MAX_FWD ? pr.VF : pr.VB);
     const int64_t per = (int64_t)(N + 1) * (D + 1);
     const int64_t total = (int64_t)(pr.S_eff + 1) * per;
     const int64_t lvl = (int64_t)(N + 1) * DP;
@@ -850,7 +1000,7 @@ __global__ __launch_bounds__(256) void export_kernel(const ProblemDev *__restric
       int64_t v = INT64_MAX;
       if (s == 0) v = (j == 0 && d == 0) ? 0 : INT64_MAX;
       else if (d >= 1 && !bad) {
-        const VT u = ((const VT *)pr.V)[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
+        const VT u = vtab[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
         v = (u == INF) ? INT64_MAX : (int64_t)u;
       }
       ((int64_t *)dst)[e] = v;
@@ -1005,6 +1155,31 @@ hipError_t launch_level_scan(const ProblemDev *p, const LaunchShape &sh, int bit
   return hipGetLastError();
 }
 
+hipError_t launch_split_level1(const ProblemDev *p, const LaunchShape &sh, int bits, hipStream_t st) {
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    const dim3 grid(sh.max_nch, sh.max_D, nq);
+    if (bits == 32) hipLaunchKernelGGL((split_level1_kernel<uint32_t>), grid, dim3(64), 0, st, p + q0);
+    else hipLaunchKernelGGL((split_level1_kernel<uint64_t>), grid, dim3(64), 0, st, p + q0);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_level_split(const ProblemDev *p, const LaunchShape &sh, int bits, int s, int write_v,
+                              int32_t *arg_i, int32_t *arg_d, hipStream_t st) {
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    const dim3 grid(sh.max_nch, sh.max_D, nq);
+    if (bits == 32)
+      hipLaunchKernelGGL((level_split_kernel<uint32_t>), grid, dim3(64), 0, st, p + q0, s, write_v, arg_i,
+                         arg_d);
+    else
+      hipLaunchKernelGGL((level_split_kernel<uint64_t>), grid, dim3(64), 0, st, p + q0, s, write_v, arg_i,
+                         arg_d);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_select(const ProblemDev *p, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st) {
   hipLaunchKernelGGL(select_kernel, dim3(Q), dim3(64), 0, st, p, d_opt, d_n_stages, d_est, d_status);
@@ -1047,7 +1222,7 @@ hipError_t launch_level_values(const ProblemDev *p, int Q, int stride, int64_t *
 
 hipError_t launch_export(const ProblemDev *p, int which, int bits, void *d_dst, hipStream_t st) {
   const dim3 grid(1024), block(256);
-  if (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_FIT || which == RANNC_DP_TABLE_V) {
+  if (which != RANNC_DP_TABLE_ARG_I && which != RANNC_DP_TABLE_ARG_D) {
     if (bits == 32) hipLaunchKernelGGL((export_kernel<uint32_t>), grid, block, 0, st, p, which, d_dst);
     else hipLaunchKernelGGL((export_kernel<uint64_t>), grid, block, 0, st, p, which, d_dst);
   } else {

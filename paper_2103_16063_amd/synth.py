@@ -207,6 +207,9 @@ def concat_batch(problems):
             [pr.get("cut_bytes", np.zeros(pr["time_ns"].shape[0], np.int64)) for pr in problems]).astype(np.int64)
         extra["bandwidth_bytes_per_us"] = np.array(
             [pr.get("bandwidth_bytes_per_us", 1) for pr in problems], dtype=np.int64)
+    if any("time_bwd_ns" in pr for pr in problems):
+        assert all("time_bwd_ns" in pr for pr in problems), "split objective: every problem needs backward times"
+        extra["time_bwd_ns"] = np.concatenate([pr["time_bwd_ns"] for pr in problems]).astype(np.int64)
     return {
         **extra,
         "n_problems": Q,

@@ -43,6 +43,11 @@ def assert_tables_match(pr, sess, q, threads=0, args=True):
         bad = np.argwhere(V != o["V"])
         raise AssertionError(f"{pr['name']}: V differs at {len(bad)} cells, first (s,j,d)={bad[0]} "
                              f"gpu={V[tuple(bad[0])]} oracle={o['V'][tuple(bad[0])]}")
+    if "time_bwd_ns" in pr:  # split objective: second stage-time table and the two carried maxima
+        cb = sess.table(B.TABLE_COST_BWD, q)
+        assert np.array_equal(cb, np.where(o["fit"] != 0, o["cost_bwd"], INF)), pr["name"]
+        assert np.array_equal(sess.table(B.TABLE_MAX_FWD, q), o["TF"]), pr["name"]
+        assert np.array_equal(sess.table(B.TABLE_MAX_BWD, q), o["TB"]), pr["name"]
     if args:
         ai = sess.table(B.TABLE_ARG_I, q)
         ad = sess.table(B.TABLE_ARG_D, q)
