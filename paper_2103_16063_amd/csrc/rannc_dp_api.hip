@@ -23,11 +23,11 @@ constexpr int kStagingSlots = 2;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Sizes {  // bytes of one problem's regions inside the workspace
-  size_t prefix, wlo, runs, ufit, misc, rmin, cost, V;
+  size_t prefix, wlo, runs, ufit, misc, rmin, cost, V, keys;
   bool split;  // split objective: a fifth prefix array, a second stage-time table, two more value tables
   size_t total() const {
     return prefix * (split ? 5 : 4) + wlo + runs + ufit + misc + rmin + cost * (split ? 2 : 1) +
-           V * (split ? 3 : 1);
+           V * (split ? 3 : 1) + keys;
   }
 };
 
@@ -49,6 +49,7 @@ bool problem_sizes(int N, int D, int S_eff, int bits, bool split, Sizes *o) {
   o->cost = align_up((size_t)cost);
   o->V = align_up((size_t)V);
   o->split = split;
+  o->keys = (split && bits == 32) ? align_up((size_t)(N + 1) * (size_t)DP * 8) : 0;
   return true;
 }
 
@@ -313,6 +314,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       p.costb = base; base += sz.cost;
       p.VF = base; base += sz.V;
       p.VB = base; base += sz.V;
+      if (sz.keys) { p.keys = base; base += sz.keys; }
     }
     off += sz.total();
     for (int k = 0; k < 4; ++k)
@@ -344,6 +346,9 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   // ---- kernels ---------------------------------------------------------------------------
   const ProblemDev *dp = h->d_probs;
   const bool scan = h->lim.algo == RANNC_DP_ALGO_SCAN;
+  // split objective: packed-key kernel for 32-bit tables; RANNC_DP_ALGO_SCAN and 64-bit tables take
+  // the literal one
+  const bool split_fast = split && !scan && h->bits == 32;
   bool ok = true;
   const bool timing = h->timing;
   h->ev_valid = false;
@@ -371,7 +376,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     ok = ok && rannc::launch_fill(cp, sh.nprob, st) == hipSuccess;
     ok = ok && rannc::launch_build(cp, sh, h->bits, kClasses[k], st) == hipSuccess;
     ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
-    if (split) ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
+    if (split) {
+      ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
+      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), st) == hipSuccess;
+    }
     if (scan || split) continue;
     // One predecessor row per wave: measured best on every configuration (most waves in flight
     // to hide the latency of the row reads).  RANNC_DP_ROWS_PER_WAVE = 2 or 4 selects the variants
@@ -395,7 +403,9 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     for (int k = 0; k < 4 && ok; ++k) {
       const LaunchShape &sh = shape[k];
       if (!sh.nprob || sh.max_S_eff < s || fused[k]) continue;
-      if (split)
+      if (split_fast)
+        ok = rannc::launch_level_split_fast(dp + cls_start[k], sh, kClasses[k], s, st) == hipSuccess;
+      else if (split)
         ok = rannc::launch_level_split(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;
       else if (scan)

@@ -39,8 +39,12 @@ __host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
 }
 
 // upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
-// groups of at least 8
-__host__ __device__ inline int64_t max_runs(int nch) { return 4LL * nch * (nch + 1); }
+// groups of at least 8, or into groups of 4 while all windows together hold fewer than 8192 rows
+__host__ __device__ inline int64_t max_runs(int nch) {
+  const int64_t by8 = 4LL * nch * (nch + 1), by4 = 2 * by8, few = 2048 + nch;
+  const int64_t small = by4 < few ? by4 : few;
+  return by8 > small ? by8 : small;
+}
 
 __host__ __device__ inline int dp_class(int D) { return D <= 8 ? 8 : D <= 16 ? 16 : D <= 32 ? 32 : 64; }
 
@@ -58,6 +62,8 @@ struct ProblemDev {
   void *costb;                 // backward stage-time table, layout of cost; null when tb is null
   void *VF, *VB;               // largest forward / backward stage time of the plan behind each V entry
                                // (layout of V); null when tb is null
+  void *keys;                  // [DP][N+1] uint64: packed (value, i, d') winners of the level in flight;
+                               // only with tb and 32-bit tables, else null
   const int64_t *o;            // caller's bytes per cut (DEVICE), N entries, or null: no communication term
   int64_t bw;                  // bandwidth in bytes per microsecond (>= 1 when o is given)
   int64_t *T, *P, *A;          // prefix sums, N+1 entries each
@@ -104,6 +110,9 @@ hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int
 hipError_t launch_split_level1(const ProblemDev *probs, const LaunchShape &sh, int bits, hipStream_t st);
 hipError_t launch_level_split(const ProblemDev *probs, const LaunchShape &sh, int bits, int s, int write_v,
                               int32_t *arg_i, int32_t *arg_d, hipStream_t st);
+// 32-bit tables only; needs the work list made by launch_runs(..., split_rows_per_item(), ...)
+int split_rows_per_item();
+hipError_t launch_level_split_fast(const ProblemDev *probs, const LaunchShape &sh, int DP, int s, hipStream_t st);
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
 // d_levels: per problem (caller's order) the exact stage count to recover, 0 = the best one; or null

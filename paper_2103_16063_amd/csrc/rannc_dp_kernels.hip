@@ -139,6 +139,10 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
   const int64_t total = (int64_t)pr.S_eff * (pr.N + 1) * pr.DP;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   const int64_t t0 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (pr.keys) {  // packed winners of the split level kernel: "none"
+    const int64_t nk = (int64_t)(pr.N + 1) * pr.DP;
+    for (int64_t e = t0; e < nk; e += stride) ((unsigned long long *)pr.keys)[e] = ~0ull;
+  }
   void *tabs[3] = {pr.V, pr.VF, pr.VB};
   for (int w = 0; w < (pr.VF ? 3 : 1); ++w) {
     if (pr.bits == 32) {
@@ -269,10 +273,30 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // items of `rows` consecutive rows, listed chunk by chunk.  A compact list keeps the workgroups
 // that have work at the front of the grid.  One workgroup per problem.
 // ---------------------------------------------------------------------------------------
+constexpr int kSplitWaves = 8;
+constexpr int kSplitMinRows = 4;  // smallest work item the adaptive work list makes (rows of one chunk)
+
 __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
+  __shared__ int total_rows;
   const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
+  const bool adaptive = rows == 0;
+  if (adaptive) {
+    // adaptive (split level kernel): items of 16 rows, of 8 or 4 if that leaves too few items to
+    // fill the device; the row count of an item travels in the top bits of its descriptor
+    if (tid == 0) total_rows = 0;
+    __syncthreads();
+    int mine = 0;
+    for (int c = tid; c < nch; c += 256) {
+      const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
+      if (lo <= hi) mine += hi - lo + 1;
+    }
+    if (mine) atomicAdd(&total_rows, mine);
+    __syncthreads();
+    rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
+  }
+  const int tag = adaptive ? (rows - 1) << 26 : 0;  // fixed-size items carry no tag
   for (int c = tid; c < nch; c += 256) {
     const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
     start[c + 1] = lo <= hi ? (hi - lo + rows) / rows : 0;  // items of chunk c
@@ -286,7 +310,7 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
   __syncthreads();
   for (int c = 0; c < nch; ++c) {
     const int lo = pr.wlo[c], n = start[c + 1] - start[c];
-    for (int k = tid; k < n; k += 256) pr.runs[1 + start[c] + k] = (c << 16) | (lo + k * rows);
+    for (int k = tid; k < n; k += 256) pr.runs[1 + start[c] + k] = tag | (c << 16) | (lo + k * rows);
   }
 }
 
@@ -733,6 +757,155 @@ __global__ __launch_bounds__(64) void level_split_kernel(const ProblemDev *__res
   if (arg_d) arg_d[e] = bd;
 }
 
+// Fast form of the same level for 32-bit tables.  The kept candidate of a cell is the smallest
+// (sum, i, d') in lexicographic order, so partial results over disjoint sets of rows combine
+// with a 64-bit atomicMin on the packed triple.  Work item (one workgroup of eight waves) = 16
+// consecutive rows of one chunk's window, from the same work list as the merge kernel.  Per row the
+// two stage-time units are staged in LDS once ([r][lane], conflict-free), the eight waves share
+// them and split the device totals d between them (d = s + wave, s + wave + 8, ...): a lane keeps
+// the running best of its column for each of its wave's d in registers.  The row of the previous
+// level (values, carried maxima) is wave-uniform: scalar loads, one per d', shared by all d.
+// split_finalize_kernel then turns the packed winners of the level into V and the two carried
+// maxima, and clears the key table for the next level.
+
+// Candidates d' = lo..hi of one staged row against the device totals d_k, k >= K0, of this wave
+// (all of them lie above hi, so every (d', k) pair is a candidate).  lim[k] = d_k - rmin of the
+// lane's stage (below 0 if d_k > D or nothing fits): the stage fits iff d' <= lim[k].
+template <int DP, int K0>
+__device__ __forceinline__ void split_segment(int lo, int hi, int d0, int i, int lane,
+                                              const uint32_t RANNC_GLOBAL *__restrict__ Frow,
+                                              const uint32_t RANNC_GLOBAL *__restrict__ Brow,
+                                              const uint32_t *sf, const uint32_t *sb,
+                                              const int (&lim)[DP / kSplitWaves],
+                                              uint32_t (&best_v)[DP / kSplitWaves],
+                                              uint32_t (&best_key)[DP / kSplitWaves]) {
+  constexpr int KP = DP / kSplitWaves;
+  for (int dp = lo; dp <= hi; ++dp) {
+    const uint32_t af = Frow[dp - 1], ab = Brow[dp - 1];  // wave-uniform
+    const uint32_t key = ((uint32_t)i << 8) | (uint32_t)dp;
+#pragma unroll
+    for (int k = K0; k < KP; ++k) {
+      const int r = d0 + kSplitWaves * k - dp;  // >= 1; at most DP (rows beyond the staged ones hold
+                                                // stale values, masked by lim)
+      const uint32_t f = vmax(af, sf[(r - 1) * 64 + lane]);
+      const uint32_t b = vmax(ab, sb[(r - 1) * 64 + lane]);
+      const uint32_t v = f + b;
+      const bool ok = (dp <= lim[k]) & (v < best_v[k]);
+      best_v[k] = ok ? v : best_v[k];
+      best_key[k] = ok ? key : best_key[k];
+    }
+  }
+}
+
+template <int DP, int K0>
+__device__ __forceinline__ void split_row(int dlo, int D, int d0, int i, int lane,
+                                          const uint32_t RANNC_GLOBAL *__restrict__ Frow,
+                                          const uint32_t RANNC_GLOBAL *__restrict__ Brow,
+                                          const uint32_t *sf, const uint32_t *sb,
+                                          const int (&lim)[DP / kSplitWaves],
+                                          uint32_t (&best_v)[DP / kSplitWaves],
+                                          uint32_t (&best_key)[DP / kSplitWaves]) {
+  if constexpr (K0 < DP / kSplitWaves) {
+    // d' in [d_{K0-1}, d_{K0} - 1]: exactly the totals d_k with k >= K0 lie above it
+    const int lo = K0 == 0 ? dlo : max(dlo, d0 + kSplitWaves * (K0 - 1));
+    const int hi = min(d0 + kSplitWaves * K0 - 1, D - 1);
+    split_segment<DP, K0>(lo, hi, d0, i, lane, Frow, Brow, sf, sb, lim, best_v, best_key);
+    split_row<DP, K0 + 1>(dlo, D, d0, i, lane, Frow, Brow, sf, sb, lim, best_v, best_key);
+  }
+}
+
+template <int DP>
+__global__ __launch_bounds__(64 * kSplitWaves) void level_split_fast_kernel(
+    const ProblemDev *__restrict__ probs, const int s) {
+  using VT = uint32_t;
+  constexpr VT INF = Lim<VT>::inf;
+  constexpr int KP = DP / kSplitWaves;  // device totals per wave
+  const ProblemDev &pr = probs[blockIdx.z];
+  if (s > pr.S_eff) return;
+  const int N = pr.N, D = pr.D, nch = pr.nch;
+  const int32_t RANNC_GLOBAL *__restrict__ runs = gptr((const int32_t *)pr.runs);
+  if ((int)blockIdx.x >= runs[0]) return;
+  const unsigned desc = (unsigned)runs[1 + blockIdx.x];
+  const int c = (int)((desc >> 16) & 0x3ffu), i0 = (int)(desc & 0xffffu), rows = (int)(desc >> 26) + 1;
+  if (64 * c + 64 < s) return;  // no column j >= s in this chunk
+  const int i_hi = min(min(i0 + rows - 1, 64 * c + 63), N - 1);
+  const int i_lo = max(i0, s - 1);
+  if (i_hi < i_lo) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int jj = 64 * c + lane;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT RANNC_GLOBAL *__restrict__ Vprev = gptr((const VT *)pr.V) + (int64_t)(s - 2) * lvl;
+  const VT RANNC_GLOBAL *__restrict__ Fprev = gptr((const VT *)pr.VF) + (int64_t)(s - 2) * lvl;
+  const VT RANNC_GLOBAL *__restrict__ Bprev = gptr((const VT *)pr.VB) + (int64_t)(s - 2) * lvl;
+  const VT RANNC_GLOBAL *__restrict__ costf = gptr((const VT *)pr.cost);
+  const VT RANNC_GLOBAL *__restrict__ costb = gptr((const VT *)pr.costb);
+  const uint8_t RANNC_GLOBAL *__restrict__ rmin = gptr((const uint8_t *)pr.rmin);
+  const uint8_t RANNC_GLOBAL *__restrict__ ufit = gptr((const uint8_t *)pr.ufit);
+  const int rl = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
+  const int d0 = s + wave;   // this wave's device totals: d0, d0 + 8, ...
+  __shared__ VT sf[DP * 64], sb[DP * 64];
+
+  VT best_v[KP];
+  uint32_t best_key[KP];
+#pragma unroll
+  for (int k = 0; k < KP; ++k) { best_v[k] = INF; best_key[k] = 0xFFFFFFFFu; }
+
+  for (int i = i_lo; i <= i_hi; ++i) {  // every condition below is uniform over the workgroup
+    if (Vprev[(int64_t)i * DP + D - 2] == INF) continue;  // no (s-1)-stage plan over blocks 1..i
+    const int64_t u = unit_index(nch, i, c);
+    if (!ufit[u]) continue;  // no stage of this unit fits: its rows were never written
+    __syncthreads();  // the previous row's reads of the staged units are done
+    for (int e = tid; e < rl * 64; e += 64 * kSplitWaves) {
+      sf[e] = costf[u * 64 * D + e];
+      sb[e] = costb[u * 64 * D + e];
+    }
+    const int rmn = (jj >= i && jj < N) ? (int)rmin[u * 64 + lane] : 255;
+    // first d' with a plan (finite values are a suffix of the row)
+    const VT av = (lane < D) ? Vprev[(int64_t)i * DP + lane] : INF;
+    const unsigned long long fin = __ballot(av != INF);
+    const int dlo = max(s - 1, __ffsll((long long)fin));  // lane q holds d' = q + 1
+    int lim[KP];
+#pragma unroll
+    for (int k = 0; k < KP; ++k) lim[k] = (d0 + kSplitWaves * k <= D) ? d0 + kSplitWaves * k - rmn : -1;
+    __syncthreads();
+    split_row<DP, 0>(dlo, D, d0, i, lane, Fprev + (int64_t)i * DP, Bprev + (int64_t)i * DP, sf, sb, lim,
+                     best_v, best_key);
+  }
+  if (jj >= N || jj + 1 < s) return;
+  unsigned long long RANNC_GLOBAL *K = gptr((unsigned long long *)pr.keys);
+#pragma unroll
+  for (int k = 0; k < KP; ++k) {
+    const int dk = d0 + kSplitWaves * k;
+    if (dk <= D && best_v[k] != INF)
+      (void)__hip_atomic_fetch_min(&K[(int64_t)(dk - 1) * (N + 1) + jj + 1],
+                                   ((unsigned long long)best_v[k] << 32) | best_key[k], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+__global__ __launch_bounds__(256) void split_finalize_kernel(const ProblemDev *__restrict__ probs, const int s) {
+  using VT = uint32_t;
+  const ProblemDev &pr = probs[blockIdx.z];
+  if (s > pr.S_eff) return;
+  const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
+  const int j = blockIdx.x * 256 + threadIdx.x, d = blockIdx.y + 1;
+  if (j > N || d > D) return;
+  unsigned long long *K = (unsigned long long *)pr.keys + (int64_t)(d - 1) * (N + 1) + j;
+  const unsigned long long key = *K;
+  if (key == ~0ull) return;  // no candidate: the cell keeps "no plan"
+  *K = ~0ull;                // ready for the next level
+  const int i = (int)((key >> 8) & 0xFFFFFFull), dp = (int)(key & 0xFFull);
+  const int jj = j - 1;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const int64_t pc = (int64_t)(s - 2) * lvl + (int64_t)i * DP + dp - 1;
+  const int64_t te = (unit_index(nch, i, jj >> 6) * D + (d - dp - 1)) * 64 + (jj & 63);
+  const int64_t e = (int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1;
+  ((VT *)pr.V)[e] = (VT)(key >> 32);
+  ((VT *)pr.VF)[e] = vmax(((const VT *)pr.VF)[pc], ((const VT *)pr.cost)[te]);
+  ((VT *)pr.VB)[e] = vmax(((const VT *)pr.VB)[pc], ((const VT *)pr.costb)[te]);
+}
+
 // Plan recovery for the split objective: the candidate kept by a cell is the first one, in scan
 // order, whose sum equals the cell's value.  All threads of the workgroup evaluate the candidates
 // of one cell, numbered in scan order, and the smallest matching number wins.
@@ -1176,6 +1349,24 @@ hipError_t launch_level_split(const ProblemDev *p, const LaunchShape &sh, int bi
     else
       hipLaunchKernelGGL((level_split_kernel<uint64_t>), grid, dim3(64), 0, st, p + q0, s, write_v, arg_i,
                          arg_d);
+  }
+  return hipGetLastError();
+}
+
+int split_rows_per_item() { return 0; }  // 0 = chosen on the device from the size of the windows
+
+hipError_t launch_level_split_fast(const ProblemDev *p, const LaunchShape &sh, int DP, int s, hipStream_t st) {
+  int64_t items = 0;  // upper bound on the items of any problem of the launch
+  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + kSplitMinRows - 1) / kSplitMinRows;
+  for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
+    const int nq = min(65535, sh.nprob - q0);
+    const dim3 grid((unsigned)items, 1, nq), block(64 * kSplitWaves);
+    if (DP == 8) hipLaunchKernelGGL((level_split_fast_kernel<8>), grid, block, 0, st, p + q0, s);
+    else if (DP == 16) hipLaunchKernelGGL((level_split_fast_kernel<16>), grid, block, 0, st, p + q0, s);
+    else if (DP == 32) hipLaunchKernelGGL((level_split_fast_kernel<32>), grid, block, 0, st, p + q0, s);
+    else hipLaunchKernelGGL((level_split_fast_kernel<64>), grid, block, 0, st, p + q0, s);
+    hipLaunchKernelGGL(split_finalize_kernel, dim3((sh.max_N + 256) / 256, sh.max_D, nq), dim3(256), 0, st,
+                       p + q0, s);
   }
   return hipGetLastError();
 }

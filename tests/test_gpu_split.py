@@ -24,8 +24,10 @@ def _case(seed, N, D, S, tight, tmax, comm):
     return pr
 
 
-@pytest.mark.parametrize("width", WIDTHS)
-def test_shape_sweep_split(width):
+@pytest.mark.parametrize("width,algo", [(WIDTHS[0], B.ALGO_AUTO), (WIDTHS[0], B.ALGO_SCAN), (WIDTHS[1], B.ALGO_AUTO)])
+def test_shape_sweep_split(width, algo):
+    """32-bit tables take the packed-key level kernel, RANNC_DP_ALGO_SCAN and 64-bit tables the
+    literal one."""
     for n, (N, D, S) in enumerate(SHAPES):
         for k, tight in enumerate((1.3, 2.0, 40.0)):
             pr = _case(2900 + n, N, D, S, tight, [6, 5000][(n + k) % 2], comm=(n + k) % 3 == 0)
@@ -34,7 +36,7 @@ def test_shape_sweep_split(width):
                     pr[key] = pr[key] * (1 << 24)  # totals beyond 32 bits
                 if "cut_bytes" in pr:
                     pr["cut_bytes"] = pr["cut_bytes"] * (1 << 24)
-            res, sess = gpu_run([pr], max_total_time_ns=width)
+            res, sess = gpu_run([pr], max_total_time_ns=width, algo=algo)
             with sess:
                 assert_results_match([pr], res)
                 assert_tables_match(pr, sess, 0, args=(N <= 100))
@@ -87,11 +89,12 @@ def test_split_batch_across_device_classes():
     assert differs >= 2, differs
 
 
+@pytest.mark.parametrize("algo", [B.ALGO_AUTO, B.ALGO_SCAN])
 @pytest.mark.parametrize("k", [2, 3])
-def test_named_configs_split(k):
+def test_named_configs_split(k, algo):
     """BERT-like and ResNet-like chains with a backward pass of about twice the forward time."""
     pr = synth.with_backward_times(synth.named_config(k), 23)
-    res, sess = gpu_run([pr])
+    res, sess = gpu_run([pr], algo=algo)
     with sess:
         assert_results_match([pr], res)
         assert_tables_match(pr, sess, 0)
