@@ -76,6 +76,18 @@
 #define ORACLE_BAD_ARG (-1)
 #define ORACLE_OVERFLOW (-4)
 
+/* n_threads > 0: that many OpenMP threads; otherwise the number the process started with (an
+ * earlier call's explicit count must not stick). */
+static void set_threads(int32_t n_threads) {
+#ifdef _OPENMP
+  static int at_start = 0;
+  if (!at_start) at_start = omp_get_max_threads();
+  omp_set_num_threads(n_threads > 0 ? n_threads : at_start);
+#else
+  (void)n_threads;
+#endif
+}
+
 static int64_t ceil_div(int64_t x, int64_t r) { return (x + r - 1) / r; } /* x >= 0, r >= 1 */
 
 /* Inclusive prefix sums X[0] = 0, X[k] = x_1 + .. + x_k.  Rejects negative entries and
@@ -139,11 +151,7 @@ int rannc_oracle_dp(int32_t N, int32_t D, int32_t n_levels, const int64_t *cost,
     arg_d[e] = -1;
   }
   V[CELL(0, 0, 0)] = 0;
-#ifdef _OPENMP
-  if (n_threads > 0) omp_set_num_threads(n_threads);
-#else
-  (void)n_threads;
-#endif
+  set_threads(n_threads);
   for (int32_t s = 1; s <= n_levels; ++s) {
     /* cells (j, d) of one level depend only on level s-1 */
 #ifdef _OPENMP
@@ -195,11 +203,7 @@ int rannc_oracle_dp_split(int32_t N, int32_t D, int32_t n_levels, const int64_t 
     arg_d[e] = -1;
   }
   V[CELL(0, 0, 0)] = TF[CELL(0, 0, 0)] = TB[CELL(0, 0, 0)] = 0;
-#ifdef _OPENMP
-  if (n_threads > 0) omp_set_num_threads(n_threads);
-#else
-  (void)n_threads;
-#endif
+  set_threads(n_threads);
   for (int32_t s = 1; s <= n_levels; ++s) {
 #ifdef _OPENMP
 #pragma omp parallel for schedule(dynamic, 1)
