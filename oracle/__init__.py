@@ -50,6 +50,8 @@ def lib():
         L.rannc_oracle_dp.restype = C.c_int
         L.rannc_oracle_dp_split.argtypes = [i32, i32, i32, pi64, pi64, pu8, pi64, pi64, pi64, pi32, pi32, i32]
         L.rannc_oracle_dp_split.restype = C.c_int
+        L.rannc_oracle_dp_pruned.argtypes = [i32, i32, i32, pi64, pu8, pi64, pi64]
+        L.rannc_oracle_dp_pruned.restype = C.c_int
         L.rannc_oracle_select.argtypes = [i32, i32, i32, pi64, pi64, pi32]
         L.rannc_oracle_select.restype = C.c_int
         L.rannc_oracle_traceback.argtypes = [i32, i32, i32, pi32, pi32, i32, pi32, pi32]
@@ -127,6 +129,16 @@ def dp_split(N: int, D: int, n_levels: int, costf, costb, fit, n_threads: int = 
                                      _p(TB, C.c_int64), _p(ai, C.c_int32), _p(ad, C.c_int32),
                                      int(n_threads)), "dp_split")
     return V, TF, TB, ai, ad
+
+
+def dp_pruned(N: int, D: int, S: int, cost, fit):
+    """Algorithm 1 for exactly S stages with its printed pruning (trimmed loop ranges, d_min):
+    returns (V, cells visited, candidates scanned, final d_min).  A study; see the C source."""
+    V = np.empty((S + 1, N + 1, D + 1), dtype=np.int64)
+    stats = np.zeros(3, dtype=np.int64)
+    _chk(lib().rannc_oracle_dp_pruned(N, D, S, _p(cost, C.c_int64), _p(fit, C.c_uint8),
+                                      _p(V, C.c_int64), _p(stats, C.c_int64)), "dp_pruned")
+    return V, int(stats[0]), int(stats[1]), int(stats[2])
 
 
 def select(V):

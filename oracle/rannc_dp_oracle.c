@@ -237,6 +237,54 @@ int rannc_oracle_dp_split(int32_t N, int32_t D, int32_t n_levels, const int64_t 
   return ORACLE_OK;
 }
 
+/* Algorithm 1 for EXACTLY S stages with the search-space pruning it prints (a study, not part of
+ * the search the HIP path runs): block counts b = s .. N-S+s, device totals d descending from
+ * D-(S-s) to max(d_min, s), and the running bound d_min: the first (s, b, d) that ends without a
+ * solution sets d_min = d + 1 for everything that follows and ends that d loop.  Min-max
+ * objective, candidates scanned as in rannc_oracle_dp.  V has the shape [(S+1)][N+1][D+1]; cells
+ * that are never visited stay INF.  stats[0] = cells visited, stats[1] = candidates (b', d')
+ * scanned, stats[2] = final d_min. */
+int rannc_oracle_dp_pruned(int32_t N, int32_t D, int32_t S, const int64_t *cost, const uint8_t *fit,
+                           int64_t *V, int64_t *stats) {
+  if (N < 1 || D < 1 || S < 1 || S > N || S > D || !cost || !fit || !V || !stats) return ORACLE_BAD_ARG;
+  const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
+#define CELL(s, j, d) ((size_t)(s) * ND + (size_t)(j) * (size_t)(D + 1) + (size_t)(d))
+  for (size_t e = 0; e < ((size_t)S + 1) * ND; ++e) V[e] = ORACLE_INF;
+  V[CELL(0, 0, 0)] = 0;
+  int32_t d_min = 1;
+  int64_t cells = 0, cands = 0;
+  for (int32_t s = 1; s <= S; ++s) {
+    for (int32_t b = s; b <= N - S + s; ++b) {
+      const int32_t d_low = d_min > s ? d_min : s;
+      for (int32_t d = D - (S - s); d >= d_low; --d) {
+        int64_t best = ORACLE_INF;
+        ++cells;
+        for (int32_t bp = s - 1; bp <= b - 1; ++bp) {
+          for (int32_t dq = s - 1; dq <= d - 1; ++dq) {
+            ++cands;
+            int64_t prev = V[CELL(s - 1, bp, dq)];
+            if (prev == ORACLE_INF) continue;
+            size_t e = (size_t)(((int64_t)b * (b - 1) / 2 + bp) * D) + (size_t)(d - dq - 1);
+            if (!fit[e]) continue;
+            int64_t v = prev > cost[e] ? prev : cost[e];
+            if (v < best) best = v;
+          }
+        }
+        V[CELL(s, b, d)] = best;
+        if (best == ORACLE_INF) { /* no solution with d: nothing below it is tried any more */
+          d_min = d + 1;
+          break;
+        }
+      }
+    }
+  }
+#undef CELL
+  stats[0] = cells;
+  stats[1] = cands;
+  stats[2] = d_min;
+  return ORACLE_OK;
+}
+
 /* Best level for the full chain on all D devices; smallest s among equals. */
 int rannc_oracle_select(int32_t N, int32_t D, int32_t n_levels, const int64_t *V,
                         int64_t *opt, int32_t *n_stages) {
