@@ -250,7 +250,7 @@ int rannc_oracle_dp_pruned(int32_t N, int32_t D, int32_t S, const int64_t *cost,
   const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
 #define CELL(s, j, d) ((size_t)(s) * ND + (size_t)(j) * (size_t)(D + 1) + (size_t)(d))
   for (size_t e = 0; e < ((size_t)S + 1) * ND; ++e) V[e] = ORACLE_INF;
-  V[CELL(0, 0, 0)] = 0;
+  V[0] = 0; /* cell (0, 0, 0) */
   int32_t d_min = 1;
   int64_t cells = 0, cands = 0;
   for (int32_t s = 1; s <= S; ++s) {
@@ -262,12 +262,13 @@ int rannc_oracle_dp_pruned(int32_t N, int32_t D, int32_t S, const int64_t *cost,
         for (int32_t bp = s - 1; bp <= b - 1; ++bp) {
           for (int32_t dq = s - 1; dq <= d - 1; ++dq) {
             ++cands;
-            int64_t prev = V[CELL(s - 1, bp, dq)];
-            if (prev == ORACLE_INF) continue;
-            size_t e = (size_t)(((int64_t)b * (b - 1) / 2 + bp) * D) + (size_t)(d - dq - 1);
+            const int64_t ante = V[CELL(s - 1, bp, dq)];
+            if (ante == ORACLE_INF) continue;
+            const size_t e = (size_t)(((int64_t)b * (b - 1) / 2 + bp) * D) + (size_t)(d - dq - 1);
             if (!fit[e]) continue;
-            int64_t v = prev > cost[e] ? prev : cost[e];
-            if (v < best) best = v;
+            const int64_t h = cost[e];
+            const int64_t cand = ante > h ? ante : h;
+            if (cand < best) best = cand;
           }
         }
         V[CELL(s, b, d)] = best;
