@@ -1,6 +1,6 @@
 """Benchmark of the stage-level partition search on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c5|c3|c2|c1|c4dense]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c5|c3|c2|c1|c4dense|c4split|c4densesplit]
                     [--no-cpu-baseline] [--no-dense] [--calibration-copy]
 
 A step is one pass of the whole path over one batch of synthetic input that is already resident
@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 import numpy as np  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+# plain vector ALU rate of the chip: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# vector instructions per candidate in the split-objective level kernel's loop body (ISA of
+# level_split_fast_kernel<64>: 57 per 8 candidates: 16 max, 8 add, 16 compares, 16 selects, 1 move)
+SPLIT_VALU_PER_UPDATE = 57 / 8
 ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configurations run in
 
 # HBM bytes per level-kernel launch from the committed rocprofv3 --pmc runs (profiles/*.md):
@@ -49,6 +54,10 @@ def level_bytes(N, D, esize=ESIZE):
 
 def make_workload(name):
     from paper_2103_16063_amd import synth
+    if name.endswith("split"):
+        # Algorithm 1 as printed: separate forward / backward times, backward about twice the forward
+        probs, label = make_workload(name[:-5])
+        return [synth.with_backward_times(p, 5) for p in probs], label + ", split fwd/bwd objective"
     if name == "c5":
         probs = synth.named_config(5)
         label = "config5 batched sweep: 2048 searches, N=128, D in {8,16,32,64}, S<=16, M=16GiB"
@@ -112,6 +121,15 @@ def run_workload(name, steps, warmup, wide=False):
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
             "algorithmic_bytes_per_launch": lvl_bytes / max(launches, 1)}
+    if name.endswith("split"):
+        # every candidate is evaluated: bound by the plain vector ALU rate, not by HBM
+        U2 = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"])
+                 - updates(p["time_ns"].shape[0], p["n_devices"], 1) for p in probs)  # levels >= 2
+        ach = U2 * SPLIT_VALU_PER_UPDATE / (phase[1] * 1e-3) / 1e12
+        roof = {"bound": "alu", "kernel": "level_split_fast_kernel + split_finalize_kernel", "achieved": ach,
+                "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-op/s", "frac": ach / ALU_PEAK_TLANEOPS,
+                "traffic": None, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
+                "valu_per_candidate": SPLIT_VALU_PER_UPDATE, "candidates_levels_2_up": U2}
     return {"probs": probs, "label": label, "U": U, "ms_per_step": wall / steps * 1e3,
             "phase": phase, "launches": launches, "res": res, "roofline": roof}
 
