@@ -190,8 +190,8 @@ RANNC_DP_API int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t 
  *   out          HOST result; out->feasible == 0 means INFEASIBLE (not an error)
  *   stage_end, replicas  HOST int32[plan_stride]: the plan as in rannc_dp_traceback (replicas
  *                before the factor R: stage u runs on replicas[u] * R devices in total)
- * Errors: INVALID_ARG (bad sizes, negative inputs, a handle with RANNC_DP_FLAG_SPLIT_OBJECTIVE,
- * devices_per_node * n_max > 64,
+ * Errors: INVALID_ARG (bad sizes, negative inputs, backward times that do not match the handle's
+ * RANNC_DP_FLAG_SPLIT_OBJECTIVE, devices_per_node * n_max > 64,
  * plan_stride < min(devices_per_node * n_max, n_blocks)), OVERFLOW (scaled inputs or their sums
  * exceed the handle's value width or 2^62), LIMIT_EXCEEDED / WORKSPACE_TOO_SMALL from solve. */
 typedef struct {
@@ -208,6 +208,10 @@ typedef struct {
                                          sample (communication term of rannc_dp_batch_t; grows
                                          with the samples of a microbatch like the times) */
   int64_t bandwidth_bytes_per_us;     /* >= 1 if cut_bytes_per_sample is given, else ignored */
+  const int64_t *time_bwd_per_sample_ns; /* HOST [N]: required on a handle with
+                                         RANNC_DP_FLAG_SPLIT_OBJECTIVE (every form_stage_dp call is then
+                                         Algorithm 1 as printed, time_per_sample_ns the forward time,
+                                         stage_time_ns the sum of the two maxima), NULL otherwise */
 } rannc_dp_form_stage_in_t;
 
 typedef struct {

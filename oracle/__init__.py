@@ -207,7 +207,8 @@ def solve(problem, n_threads: int = 1, keep_tables: bool = False, max_levels=Non
 
 def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: int,
                devices_per_node: int, batch_size: int, mem_capacity: int, n_threads: int = 1,
-               cut_bytes_per_sample=None, bandwidth_bytes_per_us: int = 0):
+               cut_bytes_per_sample=None, bandwidth_bytes_per_us: int = 0,
+               time_bwd_per_sample_ns=None):
     """Outer driver of the search (Algorithm 2 "form_stage" of Sec. III-C), loops in the paper's
     order: node count n = 1, 2, 4, ... <= n_nodes; D = devices_per_node * n devices, replica factor
     R = n_nodes / n; stage count S ascending over (devices_per_node*(n-1), devices_per_node*n]; for
@@ -217,7 +218,10 @@ def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: i
 
     Readings (the paper leaves them open): a block's time and transient bytes grow linearly with
     the samples of a microbatch on one pipeline replica, b = floor(batch_size / R / MB), its
-    persistent bytes do not (the bytes crossing a cut, if given, grow the same way); "best" = smallest (MB + S - 1) * V, the time of one synchronous
+    persistent bytes do not (the bytes crossing a cut, if given, grow the same way); with
+    time_bwd_per_sample_ns every form_stage_dp call is Algorithm 1 as printed (forward and
+    backward maxima carried separately, time_per_sample_ns being the forward time) and V is the
+    sum of the two maxima; "best" = smallest (MB + S - 1) * V, the time of one synchronous
     pipeline iteration (Fig. 1), the first found among equals (smallest MB); R is the integer
     quotient.  The DP for one (n, MB) yields every exact-S value at once, so it is memoised.
 
@@ -229,6 +233,8 @@ def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: i
     pp = np.ascontiguousarray(param_bytes, dtype=np.int64)
     os_ = (None if cut_bytes_per_sample is None
            else np.ascontiguousarray(cut_bytes_per_sample, dtype=np.int64))
+    tbs = (None if time_bwd_per_sample_ns is None
+           else np.ascontiguousarray(time_bwd_per_sample_ns, dtype=np.int64))
     N = int(ts.shape[0])
     if n_nodes < 1 or devices_per_node < 1 or batch_size < 1 or mem_capacity < 0:
         raise OracleError("bad scalar argument")
@@ -242,7 +248,12 @@ def form_stage(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes: i
             T, P, A = prefix(ts * b), prefix(pp), prefix(as_ * b)
             cost, fit = tables(T, P, A, D, mem_capacity, None if os_ is None else os_ * b,
                                bandwidth_bytes_per_us)
-            memo[(n, MB)] = dp(N, D, min(D, N), cost, fit, n_threads)
+            if tbs is None:
+                memo[(n, MB)] = dp(N, D, min(D, N), cost, fit, n_threads)
+            else:
+                costb, _ = tables(prefix(tbs * b), P, A, D, mem_capacity)
+                V, _, _, ai, ad = dp_split(N, D, min(D, N), cost, costb, fit, n_threads)
+                memo[(n, MB)] = (V, ai, ad)
         return memo[(n, MB)]
 
     n = 1

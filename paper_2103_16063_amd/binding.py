@@ -56,7 +56,7 @@ class FormStageIn(C.Structure):
                 ("reserved", C.c_int32), ("batch_size", C.c_int64), ("mem_capacity", C.c_int64),
                 ("time_per_sample_ns", C.c_void_p), ("act_bytes_per_sample", C.c_void_p),
                 ("param_bytes", C.c_void_p), ("cut_bytes_per_sample", C.c_void_p),
-                ("bandwidth_bytes_per_us", C.c_int64)]
+                ("bandwidth_bytes_per_us", C.c_int64), ("time_bwd_per_sample_ns", C.c_void_p)]
 
 
 class FormStageOut(C.Structure):
@@ -201,15 +201,17 @@ class HostFormStageIn:
 
     def __init__(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes,
                  devices_per_node, batch_size, mem_capacity, cut_bytes_per_sample=None,
-                 bandwidth_bytes_per_us=0):
+                 bandwidth_bytes_per_us=0, time_bwd_per_sample_ns=None):
         self.keep = [np.ascontiguousarray(time_per_sample_ns, dtype=np.int64),
                      np.ascontiguousarray(act_bytes_per_sample, dtype=np.int64),
                      np.ascontiguousarray(param_bytes, dtype=np.int64)]
         self.cut = (None if cut_bytes_per_sample is None
                     else np.ascontiguousarray(cut_bytes_per_sample, dtype=np.int64))
+        self.bwd = (None if time_bwd_per_sample_ns is None
+                    else np.ascontiguousarray(time_bwd_per_sample_ns, dtype=np.int64))
         self.struct = FormStageIn(int(self.keep[0].shape[0]), int(n_nodes), int(devices_per_node), 0,
                                   int(batch_size), int(mem_capacity), *[_ptr(a) for a in self.keep],
-                                  _ptr(self.cut), int(bandwidth_bytes_per_us))
+                                  _ptr(self.cut), int(bandwidth_bytes_per_us), _ptr(self.bwd))
 
 
 def rannc_dp_form_stage_problems(fin: HostFormStageIn) -> int:
@@ -363,7 +365,7 @@ class FormStageSession:
     """Owns handle, workspace and scratch for rannc_dp_form_stage calls on inputs of one shape."""
 
     def __init__(self, n_blocks, n_nodes, devices_per_node, batch_size, *,
-                 max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO, device="cuda:0"):
+                 max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO, device="cuda:0", split=False):
         import torch
         self.torch = torch
         self.dev = torch.device(device)
@@ -379,7 +381,7 @@ class FormStageSession:
         self.max_D = devices_per_node * n_max
         self.plan_stride = self.max_D
         self.limits = make_limits(self.Q, n_blocks, self.max_D, min(self.max_D, n_blocks),
-                                  max_total_time_ns, algo)
+                                  max_total_time_ns, algo, FLAG_SPLIT_OBJECTIVE if split else 0)
         self.ws_bytes = rannc_dp_workspace_bytes(self.limits)
         if self.ws_bytes == 0:
             raise RanncDpError(INVALID_ARG, "workspace size query")
@@ -391,10 +393,11 @@ class FormStageSession:
         self.scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.dev)
 
     def run(self, time_per_sample_ns, act_bytes_per_sample, param_bytes, mem_capacity,
-            cut_bytes_per_sample=None, bandwidth_bytes_per_us=0):
+            cut_bytes_per_sample=None, bandwidth_bytes_per_us=0, time_bwd_per_sample_ns=None):
         n_blocks, n_nodes, dn, bs = self.shape
         fin = HostFormStageIn(time_per_sample_ns, act_bytes_per_sample, param_bytes, n_nodes, dn, bs,
-                              mem_capacity, cut_bytes_per_sample, bandwidth_bytes_per_us)
+                              mem_capacity, cut_bytes_per_sample, bandwidth_bytes_per_us,
+                              time_bwd_per_sample_ns)
         assert fin.struct.n_blocks == n_blocks
         stream = self.torch.cuda.current_stream(self.dev).cuda_stream
         return rannc_dp_form_stage(self.h, fin, stream, self.scratch, self.scratch_bytes,

@@ -493,7 +493,7 @@ bool fs_pairs(const rannc_dp_form_stage_in_t *in, std::vector<FsPair> *out, int 
 
 size_t fs_scratch(int Q, int N, int stride) {
   size_t b = 0;
-  b += 4 * align_up((size_t)Q * N * 8);       // scaled time, param, act, cut bytes
+  b += 5 * align_up((size_t)Q * N * 8);       // scaled time, param, act, cut bytes, backward time
   b += 2 * align_up((size_t)Q * 8);           // opt, (n_stages + status as int32 pairs)
   b += align_up((size_t)Q * stride * 8);      // per-level values
   b += align_up((size_t)Q * 4);               // forced levels
@@ -528,7 +528,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (!in->time_per_sample_ns || !in->act_bytes_per_sample || !in->param_bytes) return RANNC_DP_INVALID_ARG;
   std::vector<FsPair> pairs;
   int max_D = 0;
-  std::vector<int64_t> ht, hp, ha, ho, hbw, hvals, hM, hoff;
+  std::vector<int64_t> ht, hp, ha, ho, hb, hbw, hvals, hM, hoff;
   const bool comm = in->cut_bytes_per_sample != nullptr;
   std::vector<int32_t> hN, hD, hS, hMB, hlev, hns, hse, hrp;
   const int N = in->n_blocks;
@@ -539,7 +539,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   }
   const int Q = (int)pairs.size();
   if (Q == 0) return RANNC_DP_INVALID_ARG;
-  if (split_of(&h->lim)) return RANNC_DP_INVALID_ARG;  // the driver's inputs carry one time per block
+  const bool split = in->time_bwd_per_sample_ns != nullptr;
+  if (split != split_of(&h->lim)) return RANNC_DP_INVALID_ARG;
   const int stride = max_D;
   if (plan_stride < std::min(stride, N)) return RANNC_DP_INVALID_ARG;
   if (scratch_bytes < fs_scratch(Q, N, stride)) return RANNC_DP_WORKSPACE_TOO_SMALL;
@@ -547,6 +548,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   try {
     ht.resize((size_t)Q * N); hp.resize((size_t)Q * N); ha.resize((size_t)Q * N);
     if (comm) { ho.resize((size_t)Q * N); hbw.assign(Q, in->bandwidth_bytes_per_us); }
+    if (split) hb.resize((size_t)Q * N);
     hvals.resize((size_t)Q * stride); hM.assign(Q, in->mem_capacity); hoff.resize(Q + 1);
     hN.assign(Q, N); hD.resize(Q); hS.resize(Q); hMB.resize(Q); hlev.assign(Q, 0); hns.resize(2 * (size_t)Q);
     hse.resize(stride); hrp.resize(stride);
@@ -567,6 +569,12 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
       ht[(size_t)q * N + k] = ts * pairs[q].b;
       ha[(size_t)q * N + k] = as * pairs[q].b;
       hp[(size_t)q * N + k] = in->param_bytes[k];
+      if (split) {
+        const int64_t tb = in->time_bwd_per_sample_ns[k];
+        if (tb < 0) return RANNC_DP_INVALID_ARG;
+        if ((__int128)tb * pairs[q].b >= lim) return RANNC_DP_OVERFLOW;
+        hb[(size_t)q * N + k] = tb * pairs[q].b;
+      }
       if (comm) {
         const int64_t os = in->cut_bytes_per_sample[k];
         if (os < 0) return RANNC_DP_INVALID_ARG;
@@ -582,6 +590,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   int64_t *d_p = (int64_t *)base; base += align_up((size_t)Q * N * 8);
   int64_t *d_a = (int64_t *)base; base += align_up((size_t)Q * N * 8);
   int64_t *d_o = (int64_t *)base; base += align_up((size_t)Q * N * 8);
+  int64_t *d_b = (int64_t *)base; base += align_up((size_t)Q * N * 8);
   int64_t *d_opt = (int64_t *)base; base += align_up((size_t)Q * 8);
   int32_t *d_ns = (int32_t *)base;
   int32_t *d_st = d_ns + Q; base += align_up((size_t)Q * 8);
@@ -594,7 +603,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (hipMemcpyAsync(d_t, ht.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
       hipMemcpyAsync(d_p, hp.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
       hipMemcpyAsync(d_a, ha.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
-      (comm && hipMemcpyAsync(d_o, ho.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess)) {
+      (comm && hipMemcpyAsync(d_o, ho.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess) ||
+      (split && hipMemcpyAsync(d_b, hb.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess)) {
     (void)hipGetLastError();
     (void)hipStreamSynchronize(st);  // copies already enqueued must not outlive their host buffers
     return RANNC_DP_HIP_ERROR;
@@ -606,7 +616,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   b.time_ns = d_t; b.param_bytes = d_p; b.act_bytes = d_a;
   b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
   b.cut_bytes = comm ? d_o : nullptr;
-  b.time_bwd_ns = nullptr;
+  b.time_bwd_ns = split ? d_b : nullptr;
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
   if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
   if (rc != RANNC_DP_OK) {

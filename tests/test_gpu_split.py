@@ -141,3 +141,46 @@ def test_split_status_words_and_rejections():
         torch.cuda.synchronize()
     lim = B.make_limits(1, 8, 4, 4, flags=2)
     assert B.rannc_dp_workspace_bytes(lim) == 0
+
+
+FS_SPLIT = []
+for seed in range(20):
+    g = np.random.default_rng(71_000 + seed)
+    FS_SPLIT.append((seed, int(g.integers(2, 60)), int(g.choice([1, 2, 4, 8])), int(g.integers(1, 9)),
+                     int(g.choice([4, 16, 64, 256])), float(g.choice([0.6, 1.0, 2.0, 20.0])), seed % 2 == 0))
+
+
+@pytest.mark.parametrize("seed,N,n_nodes,d_node,BS,tight,comm", FS_SPLIT)
+def test_form_stage_on_a_split_handle(seed, N, n_nodes, d_node, BS, tight, comm):
+    """The outer driver (Algorithm 2) with Algorithm 1 as printed underneath, which is the paper's
+    own pipeline, with and without the send time of the cuts."""
+    if d_node * max(n for n in (1, 2, 4, 8) if n <= n_nodes) > B.MAX_DEVICES:
+        pytest.skip("more devices than the kernels are built for")
+    c = synth.form_stage_case(seed, N, n_nodes, d_node, BS, tight=tight, tmax=60)
+    g = np.random.default_rng(seed)
+    tb = g.integers(0, 120, N, endpoint=True)
+    os_, w = (g.integers(0, 40, N, endpoint=True), 1000) if comm else (None, 0)
+    want = oracle.form_stage(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"],
+                             n_nodes, d_node, BS, c["mem_capacity"], n_threads=0,
+                             cut_bytes_per_sample=os_, bandwidth_bytes_per_us=w, time_bwd_per_sample_ns=tb)
+    fs = B.FormStageSession(N, n_nodes, d_node, BS, split=True)
+    try:
+        rc, out, se, rp = fs.run(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"],
+                                 c["mem_capacity"], os_, w, tb)
+        assert rc == B.OK
+        # the same handle refuses inputs without backward times
+        rc2, *_ = fs.run(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], c["mem_capacity"])
+        assert rc2 == B.INVALID_ARG
+    finally:
+        fs.close()
+    if want is None:
+        assert out.feasible == 0 and (se == -1).all()
+        return
+    have = {"n": out.n, "devices": out.devices, "replica_factor": out.replica_factor,
+            "n_stages": out.n_stages, "n_microbatches": out.n_microbatches,
+            "stage_time_ns": out.stage_time_ns, "est_iter_ns": out.est_iter_ns}
+    for k, v in have.items():
+        assert v == want[k], (k, v, want[k])
+    S = want["n_stages"]
+    assert np.array_equal(se[:S], want["stage_end"]) and np.array_equal(rp[:S], want["replicas"])
+    assert (se[S:] == -1).all() and (rp[S:] == -1).all()

@@ -114,3 +114,62 @@ def test_form_stage_with_comm_against_enumeration(seed, N, n_nodes, d_node, BS, 
     defcheck.check_plan([int(x) * b for x in ts], pp, [int(x) * b for x in as_], D, S, M,
                         got["stage_time_ns"], S, got["stage_end"], got["replicas"],
                         ([int(x) * b for x in os_], w))
+
+
+def enumerate_form_stage_split_two_stage_bound(tf, tb, as_, pp, n_nodes, d_node, BS, M):
+    """With at most two devices per node count Algorithm 1 as printed is exact (one or two stages:
+    nothing is discarded), so the outer loops can be enumerated over the exact split objective."""
+    N = len(tf)
+    n = 1
+    while n <= n_nodes:
+        D, R = d_node * n, n_nodes // n
+        assert D <= 2
+        for S in range(d_node * (n - 1) + 1, d_node * n + 1):
+            cands = []
+            MB = 1
+            while MB <= BS // R:
+                b = BS // R // MB
+                v = defcheck.brute_force_prefix_split([int(x) * b for x in tf], [int(x) * b for x in tb], pp,
+                                                      [int(x) * b for x in as_], S, N, D, M)
+                if v != INF:
+                    cands.append(((MB + S - 1) * v, MB, v))
+                MB *= 2
+            if cands:
+                est, MB, v = min(cands)
+                return {"n": n, "n_stages": S, "n_microbatches": MB, "stage_time_ns": v, "est_iter_ns": est}
+        n *= 2
+    return None
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_form_stage_split_objective_small_clusters(seed):
+    g = np.random.default_rng(900 + seed)
+    N, n_nodes, d_node = int(g.integers(1, 7)), int(g.choice([1, 2])), 1
+    BS, tight = int(g.choice([1, 4, 8])), float(g.choice([0.4, 1.0, 3.0]))
+    tf, tb = g.integers(1, 50, N), g.integers(1, 90, N)
+    as_, pp = g.integers(1, 40, N), g.integers(1, 100, N)
+    M = int(tight * (int(pp.sum()) + int(as_.sum()) * BS) / (d_node * n_nodes)) + 1
+    want = enumerate_form_stage_split_two_stage_bound(tf, tb, as_, pp, n_nodes, d_node, BS, M)
+    got = oracle.form_stage(tf, as_, pp, n_nodes, d_node, BS, M, time_bwd_per_sample_ns=tb)
+    if want is None:
+        assert got is None
+        return
+    for k in want:
+        assert got[k] == want[k], (k, got[k], want[k])
+
+
+def test_form_stage_split_equal_halves_doubles_the_value():
+    """Backward = forward: every form_stage_dp value doubles and the same plans win, so the outer
+    loops make the same choices."""
+    for seed, N, n_nodes, d_node, BS, tight in CASES[:12]:
+        g = np.random.default_rng(seed)
+        ts, as_, pp = g.integers(1, 50, N), g.integers(1, 40, N), g.integers(1, 100, N)
+        M = int(tight * (int(pp.sum()) + int(as_.sum()) * BS) / (d_node * n_nodes)) + 1
+        a = oracle.form_stage(ts, as_, pp, n_nodes, d_node, BS, M)
+        b = oracle.form_stage(ts, as_, pp, n_nodes, d_node, BS, M, time_bwd_per_sample_ns=ts)
+        assert (a is None) == (b is None)
+        if a is not None:
+            for k in ("n", "n_stages", "n_microbatches", "devices", "replica_factor"):
+                assert a[k] == b[k]
+            assert b["stage_time_ns"] == 2 * a["stage_time_ns"] and b["est_iter_ns"] == 2 * a["est_iter_ns"]
+            assert np.array_equal(a["stage_end"], b["stage_end"]) and np.array_equal(a["replicas"], b["replicas"])
