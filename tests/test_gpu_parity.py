@@ -2,6 +2,7 @@
 seeded inputs.  Everything is integer, so every comparison is bit-exact."""
 import numpy as np
 import pytest
+import torch
 
 import oracle
 from paper_2103_16063_amd import binding as B
@@ -230,3 +231,40 @@ def test_small_search_kernel_on_and_off(mode, width, monkeypatch):
         assert_results_match(probs, res)
         for q in range(0, len(probs), 3):
             assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
+
+
+@pytest.mark.parametrize("N,M_gib,width", [(4096, 64, B.NARROW_MAX_TOTAL_TIME), (3000, 48, 1 << 50)])
+def test_large_search_prefix_parity_and_properties(N, M_gib, width):
+    """A search four times config 4's length (64 column chunks, a ragged one at N = 3000, 2 GB of
+    table), beyond what the oracle finishes in seconds.  The values of a prefix of the chain do not
+    depend on the blocks behind it, so the cells with j <= 192 are compared one by one with the
+    oracle's run on the first 192 blocks; the rest is checked by what holds at any size: the plan
+    is valid and attains the optimum, the optimum is at least the perfectly balanced time, and
+    the values do not increase with the device total."""
+    pr = synth.enlarged_transformer_chain(seed=11, N=N, D=64, S=32, MB=64, M=M_gib << 30)
+    res, sess = gpu_run([pr], max_total_time_ns=width)
+    with sess:
+        opt, ns = int(res["opt"][0]), int(res["n_stages"][0])
+        assert int(res["status"][0]) == 0 and opt != INF and 1 <= ns <= 32
+        t, p, a = pr["time_ns"], pr["param_bytes"], pr["act_bytes"]
+        defcheck.check_plan(t, p, a, 64, 32, pr["mem_capacity"], opt, ns, res["stage_end"][0], res["replicas"][0])
+        assert opt >= -(-int(t.sum()) // 64)
+        V = sess.table(B.TABLE_V, 0)
+        J = 192
+        head = dict(pr)
+        for k in ("time_ns", "param_bytes", "act_bytes"):
+            head[k] = pr[k][:J]
+        o = oracle.solve(head, n_threads=0, keep_tables=True)
+        assert np.array_equal(V[:, :J + 1, :], o["V"])
+        fin = V[1:, 1:, 1:]
+        assert (fin[:, :, 1:] <= fin[:, :, :-1]).all()          # non-increasing in d
+        col = V[1:, N, 64]
+        assert opt == int(col.min()) and ns == 1 + int(np.argmin(col))
+        # the plan of an exact stage count further down the column is valid too
+        s_other = ns + 3
+        assert int(V[s_other, N, 64]) != INF
+        lev = torch.full((1,), s_other, dtype=torch.int32, device="cuda:0")
+        assert B.rannc_dp_traceback_at(sess.h, sess.stream(), lev, sess.plan_stride, sess.d_se, sess.d_rp) == B.OK
+        torch.cuda.synchronize()
+        defcheck.check_plan(t, p, a, 64, 32, pr["mem_capacity"], int(V[s_other, N, 64]), s_other,
+                            sess.d_se.cpu().numpy()[0], sess.d_rp.cpu().numpy()[0])
