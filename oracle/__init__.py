@@ -52,6 +52,8 @@ def lib():
         L.rannc_oracle_dp_split.restype = C.c_int
         L.rannc_oracle_dp_pruned.argtypes = [i32, i32, i32, pi64, pu8, pi64, pi64]
         L.rannc_oracle_dp_pruned.restype = C.c_int
+        L.rannc_oracle_compact.argtypes = [i32, pi64, pi64, pi64, i32, i64, pi32, pi32]
+        L.rannc_oracle_compact.restype = C.c_int
         L.rannc_oracle_select.argtypes = [i32, i32, i32, pi64, pi64, pi32]
         L.rannc_oracle_select.restype = C.c_int
         L.rannc_oracle_traceback.argtypes = [i32, i32, i32, pi32, pi32, i32, pi32, pi32]
@@ -158,6 +160,24 @@ def traceback(ai, ad, n_stages: int, max_slots: int):
                                       max_slots, _p(se, C.c_int32), _p(rp, C.c_int32)),
          "traceback")
     return se, rp
+
+
+def compact(time_ns, param_bytes, act_bytes, k: int, mem_capacity: int):
+    """Compaction step of the block-level phase on a chain (Sec. III-B): returns the ends of the
+    resulting groups (1-based counts of input groups, the last one = G) and their summed time,
+    persistent and transient bytes -- the block arrays the stage-level search takes."""
+    t = np.ascontiguousarray(time_ns, dtype=np.int64)
+    p = np.ascontiguousarray(param_bytes, dtype=np.int64)
+    a = np.ascontiguousarray(act_bytes, dtype=np.int64)
+    G = int(t.shape[0])
+    end = np.empty(G, dtype=np.int32)
+    n = C.c_int32()
+    _chk(lib().rannc_oracle_compact(G, _p(t, C.c_int64), _p(p, C.c_int64), _p(a, C.c_int64), int(k),
+                                    int(mem_capacity), C.byref(n), _p(end, C.c_int32)), "compact")
+    end = end[:n.value].copy()
+    lo = np.concatenate(([0], end[:-1]))
+    T, P, A = prefix(t), prefix(p), prefix(a)
+    return end, T[end] - T[lo], P[end] - P[lo], A[end] - A[lo]
 
 
 def est_iter_ns(opt: int, n_stages: int, MB: int) -> int:

@@ -66,6 +66,7 @@
  */
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -326,6 +327,81 @@ int rannc_oracle_traceback(int32_t N, int32_t D, int32_t n_stages, const int32_t
   }
   if (n_stages > 0 && (j != 0 || d != 0)) return ORACLE_BAD_ARG;
   return ORACLE_OK;
+}
+
+/* Compaction step of the block-level phase (Sec. III-B, last paragraph before the stage-level
+ * search), on a chain: G groups in topological order with computation time t, persistent bytes p
+ * and transient bytes a each; target k blocks; device memory M.  Steps, in the paper's order:
+ * the groups are listed once by ascending computation time (equal times: by position); each
+ * listed group v that still stands alone as listed (it has not been absorbed by an earlier
+ * merge) picks, of its left and right neighbours in the chain, the one whose current computation
+ * time is smaller (equal: the left one; only one neighbour: that one); if the union fits the
+ * device memory (all persistent plus all transient bytes <= M) the two are merged into one group
+ * at their place in the chain, times and bytes added up; the pass ends when k groups are left or
+ * the list is exhausted.  A union is not put back into the list.  Readings where the text is
+ * silent: one pass; the other neighbour is not tried when the chosen one does not fit; memory
+ * of a group = p + a (one replica, the whole microbatch); a group that was merged INTO (it
+ * absorbed a neighbour on that neighbour's turn) has changed and is no longer the listed group
+ * either.
+ * Output: n_out groups, group u covering the input groups end[u-1]+1 .. end[u] (end[-1] = 0). */
+int rannc_oracle_compact(int32_t G, const int64_t *t, const int64_t *p, const int64_t *a, int32_t k,
+                         int64_t M, int32_t *n_out, int32_t *end) {
+  if (G < 1 || k < 1 || M < 0 || !t || !p || !a || !n_out || !end) return ORACLE_BAD_ARG;
+  int64_t *ct = malloc(sizeof(int64_t) * (size_t)G), *cm = malloc(sizeof(int64_t) * (size_t)G);
+  int32_t *prev = malloc(sizeof(int32_t) * (size_t)G), *next = malloc(sizeof(int32_t) * (size_t)G);
+  int32_t *order = malloc(sizeof(int32_t) * (size_t)G);
+  uint8_t *listed = malloc((size_t)G); /* still the group that was listed */
+  if (!ct || !cm || !prev || !next || !order || !listed) {
+    free(ct); free(cm); free(prev); free(next); free(order); free(listed);
+    return ORACLE_BAD_ARG;
+  }
+  const int64_t LIM = (int64_t)1 << 62;
+  int64_t st = 0, sm = 0;
+  for (int32_t g = 0; g < G; ++g) {
+    if (t[g] < 0 || p[g] < 0 || a[g] < 0 || t[g] >= LIM - st || p[g] >= LIM - sm || a[g] >= LIM - sm - p[g]) {
+      free(ct); free(cm); free(prev); free(next); free(order); free(listed);
+      return t[g] < 0 || p[g] < 0 || a[g] < 0 ? ORACLE_BAD_ARG : ORACLE_OVERFLOW;
+    }
+    st += t[g];
+    sm += p[g] + a[g];
+    ct[g] = t[g];
+    cm[g] = p[g] + a[g];
+    prev[g] = g - 1;
+    next[g] = g + 1 < G ? g + 1 : -1;
+    order[g] = g;
+    listed[g] = 1;
+  }
+  /* ascending time, equal times by position: insertion sort keeps the order of equals */
+  for (int32_t x = 1; x < G; ++x) {
+    int32_t v = order[x], y = x - 1;
+    while (y >= 0 && t[order[y]] > t[v]) { order[y + 1] = order[y]; --y; }
+    order[y + 1] = v;
+  }
+  int32_t count = G;
+  /* a group is named by its first input group; next/prev link the group heads along the chain */
+  for (int32_t x = 0; x < G && count > k; ++x) {
+    const int32_t v = order[x];
+    if (!listed[v]) continue;
+    const int32_t l = prev[v], r = next[v];
+    int32_t w;
+    if (l < 0 && r < 0) break; /* a single group */
+    if (l < 0) w = r;
+    else if (r < 0) w = l;
+    else w = ct[r] < ct[l] ? r : l;
+    if (cm[v] + cm[w] > M) continue; /* the union does not fit */
+    const int32_t first = w == l ? l : v, second = w == l ? v : r; /* chain order */
+    ct[first] += ct[second];
+    cm[first] += cm[second];
+    next[first] = next[second];
+    if (next[second] >= 0) prev[next[second]] = first;
+    listed[first] = listed[second] = 0; /* neither is the listed group any more */
+    --count;
+  }
+  int32_t n = 0;
+  for (int32_t g = 0; g >= 0; g = next[g]) end[n++] = next[g] >= 0 ? next[g] : G;
+  *n_out = n;
+  free(ct); free(cm); free(prev); free(next); free(order); free(listed);
+  return n == count ? ORACLE_OK : ORACLE_BAD_ARG;
 }
 
 /* Estimated time of one synchronous-pipeline iteration with MB microbatches over n_stages

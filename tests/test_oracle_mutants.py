@@ -9,6 +9,7 @@ import pytest
 
 import oracle
 from tests import test_oracle_comm as comm_pins
+from tests import test_oracle_compact as compact_pins
 from tests import test_oracle_pins as pins
 from tests import test_oracle_split as split_pins
 
@@ -59,6 +60,12 @@ MUTANTS = {
     "split_skips_split_at_s_minus_1": ("for (int32_t i = s - 1; i < j; ++i) {", "for (int32_t i = s; i < j; ++i) {"),
     "split_device_loop_stops_early": ("for (int32_t dp = s - 1; dp < d; ++dp) {", "for (int32_t dp = s - 1; dp < d - 1; ++dp) {"),
     "split_wrong_replica_index": ("const int32_t r = d - dp;", "const int32_t r = dp + 1;"),
+    "compact_ties_to_the_right": ("else w = ct[r] < ct[l] ? r : l;", "else w = ct[r] <= ct[l] ? r : l;"),
+    "compact_takes_the_slower_neighbour": ("else w = ct[r] < ct[l] ? r : l;", "else w = ct[r] > ct[l] ? r : l;"),
+    "compact_fit_exclusive": ("if (cm[v] + cm[w] > M) continue;", "if (cm[v] + cm[w] >= M) continue;"),
+    "compact_descending_order": ("while (y >= 0 && t[order[y]] > t[v])", "while (y >= 0 && t[order[y]] < t[v])"),
+    "compact_ignores_transient_bytes": ("cm[g] = p[g] + a[g];", "cm[g] = p[g];"),
+    "compact_neighbour_times_not_updated": ("ct[first] += ct[second];", "ct[first] += 0;"),
     "device_loop_stops_early": ("for (int32_t dp = s - 1; dp <= d - 1; ++dp)",
                                 "for (int32_t dp = s - 1; dp < d - 1; ++dp)"),
 }
@@ -84,6 +91,9 @@ def battery():
     comm_pins.test_worked_example()
     comm_pins.test_tables_against_definition_with_comm()
     comm_pins.test_comm_invariants(0)
+    compact_pins.test_worked_example_distinct_times()
+    compact_pins.test_worked_example_equal_times_pair_up()
+    compact_pins.test_memory_rule_and_no_second_choice()
     for row in split_pins.SMALL[:12]:
         split_pins.test_values_are_plan_values_bounded_by_the_exact_minimum(*row)
     split_pins.test_worked_example_where_one_pair_per_cell_loses()
@@ -109,7 +119,7 @@ def test_mutant_is_caught(name, tmp_path):
     mutant = ctypes.CDLL(str(so))
     for fn in ("rannc_oracle_prefix", "rannc_oracle_table_entries", "rannc_oracle_tables",
                "rannc_oracle_dp", "rannc_oracle_dp_split", "rannc_oracle_select", "rannc_oracle_traceback",
-               "rannc_oracle_est_iter_ns", "rannc_oracle_max_threads"):
+               "rannc_oracle_est_iter_ns", "rannc_oracle_max_threads", "rannc_oracle_compact"):
         getattr(mutant, fn).argtypes = getattr(real, fn).argtypes
         getattr(mutant, fn).restype = getattr(real, fn).restype
     oracle._lib = mutant
