@@ -32,7 +32,8 @@ EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp
            "rannc_dp_solve", "rannc_dp_traceback", "rannc_dp_read_table", "rannc_dp_destroy",
            "rannc_dp_strerror", "rannc_dp_set_timing", "rannc_dp_get_timing",
            "rannc_dp_traceback_at", "rannc_dp_level_values", "rannc_dp_form_stage_problems",
-           "rannc_dp_form_stage_scratch_bytes", "rannc_dp_form_stage"]
+           "rannc_dp_form_stage_scratch_bytes", "rannc_dp_form_stage",
+           "rannc_dp_compact_workspace_bytes", "rannc_dp_compact"]
 
 
 class Limits(C.Structure):
@@ -114,6 +115,10 @@ def lib():
         L.rannc_dp_form_stage.argtypes = [vp, C.POINTER(FormStageIn), vp, vp, sz,
                                           C.POINTER(FormStageOut), vp, vp, C.c_int32]
         L.rannc_dp_form_stage.restype = C.c_int
+        L.rannc_dp_compact_workspace_bytes.argtypes = [C.c_int32]
+        L.rannc_dp_compact_workspace_bytes.restype = sz
+        L.rannc_dp_compact.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp]
+        L.rannc_dp_compact.restype = C.c_int
         _lib = L
     return _lib
 
@@ -232,6 +237,19 @@ def rannc_dp_form_stage(handle, fin: HostFormStageIn, stream, d_scratch, scratch
                                    int(scratch_bytes), C.byref(out), _ptr(se), _ptr(rp),
                                    int(plan_stride))
     return rc, out, se, rp
+
+
+def rannc_dp_compact_workspace_bytes(n_groups: int) -> int:
+    return int(lib().rannc_dp_compact_workspace_bytes(int(n_groups)))
+
+
+def rannc_dp_compact(stream, n_groups: int, k: int, mem_capacity: int, d_time_ns, d_param_bytes, d_act_bytes,
+                     d_workspace, workspace_bytes: int, d_n_blocks, d_block_end, d_time_out, d_param_out,
+                     d_act_out, d_status) -> int:
+    return lib().rannc_dp_compact(_ptr(stream), int(n_groups), int(k), int(mem_capacity), _ptr(d_time_ns),
+                                  _ptr(d_param_bytes), _ptr(d_act_bytes), _ptr(d_workspace), int(workspace_bytes),
+                                  _ptr(d_n_blocks), _ptr(d_block_end), _ptr(d_time_out), _ptr(d_param_out),
+                                  _ptr(d_act_out), _ptr(d_status))
 
 
 def rannc_dp_read_table(handle, which: int, problem: int, d_dst, nbytes: int, stream) -> int:

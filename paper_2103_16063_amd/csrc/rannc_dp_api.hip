@@ -682,6 +682,30 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   return RANNC_DP_OK;
 }
 
+size_t rannc_dp_compact_workspace_bytes(int32_t n_groups) {
+  if (n_groups < 1 || n_groups > 65535) return 0;
+  return rannc::compact_workspace_bytes(n_groups);
+}
+
+int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k, int64_t mem_capacity,
+                     const int64_t *d_time_ns, const int64_t *d_param_bytes, const int64_t *d_act_bytes,
+                     void *d_workspace, size_t workspace_bytes, int32_t *d_n_blocks, int32_t *d_block_end,
+                     int64_t *d_time_out, int64_t *d_param_out, int64_t *d_act_out, int32_t *d_status) {
+  if (n_groups < 1 || n_groups > 65535 || k < 1 || mem_capacity < 0) return RANNC_DP_INVALID_ARG;
+  if (!d_time_ns || !d_param_bytes || !d_act_bytes || !d_workspace || !d_n_blocks || !d_block_end ||
+      !d_time_out || !d_param_out || !d_act_out || !d_status)
+    return RANNC_DP_INVALID_ARG;
+  if (((uintptr_t)d_workspace % kAlign) != 0) return RANNC_DP_INVALID_ARG;
+  if (workspace_bytes < rannc::compact_workspace_bytes(n_groups)) return RANNC_DP_WORKSPACE_TOO_SMALL;
+  if (rannc::launch_compact(n_groups, k, mem_capacity, d_time_ns, d_param_bytes, d_act_bytes, d_workspace,
+                            d_n_blocks, d_block_end, d_time_out, d_param_out, d_act_out, d_status,
+                            (hipStream_t)hip_stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  return RANNC_DP_OK;
+}
+
 int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, size_t bytes,
                         void *hip_stream) {
   if (!h || !d_dst) return RANNC_DP_INVALID_ARG;
