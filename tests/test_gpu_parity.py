@@ -45,6 +45,7 @@ SHAPES = [  # (N, D, S): edge shapes, ragged tails, several 64-column chunks, no
     (1, 1, 1), (1, 7, 3), (9, 1, 4), (3, 3, 9), (2, 64, 2), (5, 2, 5),
     (16, 4, 4), (33, 5, 5), (63, 8, 8), (64, 9, 6), (65, 12, 7), (100, 17, 9),
     (129, 24, 6), (130, 33, 5), (200, 40, 4), (70, 63, 10), (96, 64, 12),
+    (64, 64, 64), (80, 64, 64), (65, 33, 40),  # as many levels as devices
 ]
 
 

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 WIDTHS = [B.NARROW_MAX_TOTAL_TIME, 1 << 50]
 SHAPES = [(1, 1, 1), (1, 7, 3), (9, 1, 4), (5, 2, 5), (16, 4, 4), (33, 5, 5), (63, 8, 8), (64, 9, 6),
-          (65, 12, 7), (100, 17, 9), (129, 24, 6), (130, 33, 5), (70, 63, 10), (96, 64, 12)]
+          (65, 12, 7), (100, 17, 9), (129, 24, 6), (130, 33, 5), (70, 63, 10), (96, 64, 12), (72, 64, 64)]
 
 
 def _case(seed, N, D, S, tight, tmax, comm):
