@@ -73,7 +73,9 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
   int64_t *out[4] = {pr.T, pr.P, pr.A, pr.TB};
   const int nw = pr.tb ? 4 : 3;  // backward times only with the split objective
   int myflags = 0;
-  for (int w = 0; w < nw; ++w) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w >= nw) break;
     uint64_t s = 0;
     for (int k = lo; k < hi; ++k) {
       int64_t v = in[w][k];
@@ -88,15 +90,20 @@ __global__ __launch_bounds__(256) void prefix_kernel(const ProblemDev *__restric
   // inclusive scan of the 256 segment sums (saturating add is associative on [0, limit])
   for (int off = 1; off < 256; off <<= 1) {
     uint64_t add[4];
-    for (int w = 0; w < nw; ++w) add[w] = tid >= off ? part[w][tid - off] : 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) add[w] = (w < nw && tid >= off) ? part[w][tid - off] : 0;
     __syncthreads();
-    for (int w = 0; w < nw; ++w) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (w >= nw) break;
       uint64_t v = part[w][tid] + add[w];
       part[w][tid] = v > kSumLimit ? kSumLimit : v;
     }
     __syncthreads();
   }
-  for (int w = 0; w < nw; ++w) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w >= nw) break;
     uint64_t run = tid ? part[w][tid - 1] : 0;  // sum of the segments before this thread's
     if (tid == 0) out[w][0] = 0;
     for (int k = lo; k < hi; ++k) {
