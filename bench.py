@@ -85,30 +85,45 @@ def run_workload(name, steps, warmup, wide=False):
     U = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"]) for p in probs)
     sess = B.Session(synth.concat_batch(probs), max_total_time_ns=(1 << 60) if wide else B.NARROW_MAX_TOTAL_TIME)
     esize = 8 if wide else ESIZE
-    B.rannc_dp_set_timing(sess.h, True)
 
     def step():
         sess.solve()
         sess.traceback()
 
+    def timed_loop(n, with_events):
+        """Wall time of n steps, one in flight at a time; with_events: also the per-phase device
+        times (HIP events recorded by the library on the solve's stream), summed."""
+        ph, nl = np.zeros(3), 0
+        t0 = time.perf_counter()
+        for _ in range(n):
+            step()
+            if with_events:
+                rc, ms, nl = B.rannc_dp_get_timing(sess.h)  # waits for the step's last event
+                assert rc == B.OK
+                ph += ms
+            else:
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ph, nl
+
+    # A batch with several device-count classes runs them on streams of the handle unless the
+    # per-phase events are on (they time phases on one stream): then `value` comes from a loop
+    # without events and the phase times from a second, shorter one.
+    multi = len({1 << max(3, int(p["n_devices"] - 1).bit_length()) for p in probs}) > 1
+    B.rannc_dp_set_timing(sess.h, not multi)
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    phase = np.zeros(3)
-    launches = 0
-    t0 = time.perf_counter()
-    for _ in range(steps):
+    wall, phase, launches = timed_loop(steps, with_events=not multi)
+    n_phase = steps
+    if multi:
+        B.rannc_dp_set_timing(sess.h, True)
         step()
-        # per-phase device times of this step (HIP events recorded by the library on the solve's
-        # stream); waiting for them keeps one step in flight at a time: wall time = step latency
-        rc, ms, launches = B.rannc_dp_get_timing(sess.h)
-        assert rc == B.OK
-        phase += ms
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+        n_phase = min(steps, 10)
+        _, phase, launches = timed_loop(n_phase, with_events=True)
     res = sess.run()
     sess.close()
-    phase /= steps
+    phase /= n_phase
     # algorithmic bytes of all level launches of one step
     lvl_bytes = 0
     for p in probs:

@@ -112,6 +112,13 @@ struct rannc_dp {
   hipEvent_t ev[4];
   bool ev_valid;
   int level_launches;
+  // Device-count classes are independent chains of launches: with more than one class in a batch
+  // the others run on streams of the handle (default priority), forked from and joined to the
+  // caller's stream with events.  Off while per-phase timing is on (the phases are timed on the
+  // caller's stream) and with RANNC_DP_STREAMS=0.
+  hipStream_t aux[3];
+  hipEvent_t fork_ev, join_ev[3];
+  bool multi_stream;
   int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
   int fused_small;  // one-launch kernel for classes of small searches: 1 = where it pays (default),
                     // 0 = never, 2 = whenever N <= 128 (RANNC_DP_FUSED_SMALL)
@@ -181,7 +188,10 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->fused_small = 1;
   if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
-  int made_staging = 0, made_ev_s = 0, made_ev = 0;
+  h->multi_stream = true;
+  if (const char *e = std::getenv("RANNC_DP_STREAMS")) h->multi_stream = std::atoi(e) != 0;
+  int made_staging = 0, made_ev_s = 0, made_ev = 0, made_aux = 0, made_join = 0;
+  bool made_fork = false;
   bool ok = true;
   for (int k = 0; k < kStagingSlots && ok; ++k) {
     h->staging_used[k] = false;
@@ -196,7 +206,22 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
     ok = hipEventCreate(&h->ev[k]) == hipSuccess;
     if (ok) ++made_ev;
   }
+  for (int k = 0; k < 3 && ok; ++k) {
+    ok = hipStreamCreateWithFlags(&h->aux[k], hipStreamNonBlocking) == hipSuccess;
+    if (ok) ++made_aux;
+  }
+  for (int k = 0; k < 3 && ok; ++k) {
+    ok = hipEventCreateWithFlags(&h->join_ev[k], hipEventDisableTiming) == hipSuccess;
+    if (ok) ++made_join;
+  }
+  if (ok) {
+    ok = hipEventCreateWithFlags(&h->fork_ev, hipEventDisableTiming) == hipSuccess;
+    made_fork = ok;
+  }
   if (!ok) {
+    for (int k = 0; k < made_aux; ++k) (void)hipStreamDestroy(h->aux[k]);
+    for (int k = 0; k < made_join; ++k) (void)hipEventDestroy(h->join_ev[k]);
+    if (made_fork) (void)hipEventDestroy(h->fork_ev);
     for (int k = 0; k < made_staging; ++k) (void)hipHostFree(h->staging[k]);
     for (int k = 0; k < made_ev_s; ++k) (void)hipEventDestroy(h->staging_free[k]);
     for (int k = 0; k < made_ev; ++k) (void)hipEventDestroy(h->ev[k]);
@@ -216,6 +241,12 @@ void rannc_dp_destroy(rannc_dp_t *h) {
     (void)hipEventDestroy(h->staging_free[k]);
   }
   for (int k = 0; k < 4; ++k) (void)hipEventDestroy(h->ev[k]);
+  for (int k = 0; k < 3; ++k) {
+    (void)hipStreamSynchronize(h->aux[k]);
+    (void)hipStreamDestroy(h->aux[k]);
+    (void)hipEventDestroy(h->join_ev[k]);
+  }
+  (void)hipEventDestroy(h->fork_ev);
   delete h;
 }
 
@@ -354,12 +385,28 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   h->ev_valid = false;
   h->level_launches = 0;
   if (timing) ok = ok && hipEventRecord(h->ev[0], st) == hipSuccess;
+  // one stream per device-count class: the largest class stays on the caller's stream
+  hipStream_t cs[4] = {st, st, st, st};
+  int n_aux = 0;
+  if (h->multi_stream && !timing) {
+    bool first = true;
+    for (int k = 3; k >= 0; --k) {
+      if (!shape[k].nprob) continue;
+      if (first) { first = false; continue; }
+      cs[k] = h->aux[n_aux++];
+    }
+    if (n_aux > 0) {
+      ok = ok && hipEventRecord(h->fork_ev, st) == hipSuccess;  // descriptors are on the device
+      for (int a = 0; a < n_aux && ok; ++a) ok = hipStreamWaitEvent(h->aux[a], h->fork_ev, 0) == hipSuccess;
+    }
+  }
   int spw[4] = {1, 1, 1, 1};
   bool fused[4] = {false, false, false, false};
   for (int k = 0; k < 4 && ok; ++k) {
     const LaunchShape &sh = shape[k];
     if (!sh.nprob) continue;
     const ProblemDev *cp = dp + cls_start[k];
+    const hipStream_t st = cs[k];  // this class's stream
     // Small searches: everything in one launch, one workgroup per search.  Measured on MI355X:
     // it wins for batches at D <= 16 (no launch per level, levels folded in LDS) and for a lone
     // tiny search; at D >= 32 a workgroup's waves work through too many table rows one after the
@@ -393,7 +440,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   for (int k = 0; k < 4; ++k) {
     if (fused[k]) {
       ok = ok && rannc::launch_solve_small(dp + cls_start[k], shape[k].nprob, h->bits, kClasses[k], d_opt,
-                                           d_n_stages, d_est_iter_ns, d_status, st) == hipSuccess;
+                                           d_n_stages, d_est_iter_ns, d_status, cs[k]) == hipSuccess;
       h->level_launches++;
     } else {
       max_levels = std::max(max_levels, shape[k].max_S_eff);
@@ -403,6 +450,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     for (int k = 0; k < 4 && ok; ++k) {
       const LaunchShape &sh = shape[k];
       if (!sh.nprob || sh.max_S_eff < s || fused[k]) continue;
+      const hipStream_t st = cs[k];
       if (split_fast)
         ok = rannc::launch_level_split_fast(dp + cls_start[k], sh, kClasses[k], s, st) == hipSuccess;
       else if (split)
@@ -421,7 +469,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   for (int k = 0; k < 4 && ok; ++k)
     if (shape[k].nprob && !fused[k])
       ok = rannc::launch_select(dp + cls_start[k], shape[k].nprob, d_opt, d_n_stages, d_est_iter_ns,
-                                d_status, st) == hipSuccess;
+                                d_status, cs[k]) == hipSuccess;
+  for (int a = 0; a < n_aux && ok; ++a)  // join: the caller's stream continues after every class
+    ok = hipEventRecord(h->join_ev[a], h->aux[a]) == hipSuccess &&
+         hipStreamWaitEvent(st, h->join_ev[a], 0) == hipSuccess;
   if (timing) ok = ok && hipEventRecord(h->ev[3], st) == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();

@@ -269,3 +269,30 @@ def test_large_search_prefix_parity_and_properties(N, M_gib, width):
         torch.cuda.synchronize()
         defcheck.check_plan(t, p, a, 64, 32, pr["mem_capacity"], int(V[s_other, N, 64]), s_other,
                             sess.d_se.cpu().numpy()[0], sess.d_rp.cpu().numpy()[0])
+
+
+@pytest.mark.parametrize("streams", ["0", "1"])
+@pytest.mark.parametrize("timing", [False, True])
+def test_classes_on_their_own_streams(streams, timing, monkeypatch):
+    """A batch with all four device-count classes: the classes run as independent chains of
+    launches on streams of the handle (RANNC_DP_STREAMS=1, the default) or one after the other on
+    the caller's stream (0, and whenever per-phase timing is on).  Same results either way, also
+    on repeated solves of one handle and with the one-launch kernel on or off."""
+    monkeypatch.setenv("RANNC_DP_STREAMS", streams)
+    probs = []
+    for seed in range(64):
+        g = np.random.default_rng(121_000 + seed)
+        D = int(g.choice([3, 8, 11, 16, 27, 32, 50, 64]))
+        probs.append(synth.random_small(seed, int(g.integers(1, 140)), D, int(g.integers(1, 18)),
+                                        tight=float(g.choice([1.2, 2.0, 9.0])), tmax=int(g.choice([9, 4000]))))
+    for fused in ("0", "1"):
+        monkeypatch.setenv("RANNC_DP_FUSED_SMALL", fused)
+        res, sess = gpu_run(probs)
+        with sess:
+            B.rannc_dp_set_timing(sess.h, timing)
+            for _ in range(3):
+                again = sess.run()
+                for k in res:
+                    assert np.array_equal(res[k], again[k]), k
+            assert_results_match(probs, res)
+            assert_tables_match(probs[7], sess, 7, args=False)
