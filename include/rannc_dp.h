@@ -83,7 +83,8 @@ typedef enum {
  * and a second stage-time table. */
 #define RANNC_DP_FLAG_SPLIT_OBJECTIVE 1
 
-typedef struct rannc_dp rannc_dp_t; /* opaque; owns host memory only */
+typedef struct rannc_dp rannc_dp_t; /* opaque; owns host memory, a few events and three streams (default
+                                       priority), no device memory */
 
 /* Capacity of a handle. */
 typedef struct {
@@ -136,7 +137,9 @@ RANNC_DP_API size_t rannc_dp_workspace_bytes_for(const rannc_dp_limits_t *limits
 
 /* Create a handle over a caller-owned DEVICE workspace (256-byte aligned).  The workspace
  * must stay valid until destroy.  A workspace smaller than rannc_dp_workspace_bytes(limits) is
- * accepted; solve then rejects batches that do not fit.  *out is NULL on failure. */
+ * accepted; solve then rejects batches that do not fit.  *out is NULL on failure.  The handle
+ * allocates pinned host staging for the descriptors, events, and three streams on the current
+ * device; it never allocates device memory. */
 RANNC_DP_API int rannc_dp_create(const rannc_dp_limits_t *limits, void *d_workspace, size_t workspace_bytes,
                     rannc_dp_t **out);
 
@@ -148,6 +151,9 @@ RANNC_DP_API int rannc_dp_create(const rannc_dp_limits_t *limits, void *d_worksp
  *   d_est_iter_ns DEVICE int64[Q] or NULL: (MB + s* - 1) * opt, the fill-and-drain time of one
  *                synchronous pipeline iteration (Fig. 1), saturating at INT64_MAX
  *   d_status     DEVICE int32[Q] or NULL: RANNC_DP_PROBLEM_* per problem
+ * Searches of different device-count classes (D <= 8, 16, 32, 64) of one batch may run on streams
+ * of the handle; they start after the work already on hip_stream and hip_stream is made to wait
+ * for them, so for the caller everything is ordered on hip_stream as if it ran there.
  * Host-side argument errors are returned before anything is enqueued. */
 RANNC_DP_API int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *batch, void *hip_stream,
                    int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est_iter_ns,
@@ -278,7 +284,8 @@ RANNC_DP_API int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k,
 RANNC_DP_API int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, size_t bytes,
                         void *hip_stream);
 
-/* Frees host state only; the workspace remains the caller's.  NULL is allowed. */
+/* Waits for the handle's own streams, frees host state, events and streams; the workspace remains
+ * the caller's.  NULL is allowed. */
 RANNC_DP_API void rannc_dp_destroy(rannc_dp_t *h);
 
 /* Static description of a status code; never NULL. */
