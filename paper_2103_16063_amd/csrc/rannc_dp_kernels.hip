@@ -499,7 +499,7 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
 // form_stage_dp calls of Algorithm 2): one workgroup per search.
 // ---------------------------------------------------------------------------------------
 constexpr int kSmallMaxN = 128;
-constexpr int kSmallWaves = 8;
+constexpr int kSmallWaves = 16;
 
 __device__ __forceinline__ void select_finish(const ProblemDev &pr, int64_t v, int st, int64_t *d_opt,
                                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status);
