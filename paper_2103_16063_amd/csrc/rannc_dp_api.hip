@@ -410,13 +410,13 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     // Small searches: everything in one launch, one workgroup per search.  Measured on MI355X
     // (N = 16..128, D = 8..64, 1..512 searches per class): it wins whenever a workgroup has little
     // to walk through (rows x levels up to about 480: no launch per level, levels folded in LDS),
-    // and for classes of hundreds of searches at D <= 16, where the launches per level are
-    // throughput-bound as well; otherwise a workgroup's waves work through too many table rows one
+    // and for classes of hundreds of searches at D <= 16 or N <= 64, where the launches per level
+    // are throughput-bound as well; otherwise a workgroup's waves work through too many table rows one
     // after the other and the launch per level, which spreads the rows over the whole device, is
     // faster (up to 10x at N = 128, D = 64).
     {
       const int64_t rows = std::min(sh.max_N, 64) + (sh.max_nch > 1 ? sh.max_N : 0);
-      const bool batch = sh.nprob >= 256 && kClasses[k] <= 16;
+      const bool batch = sh.nprob >= 256 && (kClasses[k] <= 16 || sh.max_N <= 64);
       const bool tiny = rows * (sh.max_S_eff - 1) <= 480;
       fused[k] = !scan && !split && sh.max_N <= rannc::small_max_blocks() &&
                  (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);

@@ -611,9 +611,10 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
       unit_load<VT, DP>(x, cost + u * 64 * D + lane, act, rl);
       unit_sort<VT, DP, const VT *>(x, prev + i * LS);
       if (act && jj + 1 >= s) {
+        // unconditional: folding INF in is a no-op and costs less than testing for it
 #pragma unroll
         for (int t = 0; t < DP - 1; ++t)
-          if (t + 1 <= D - 1 && x[t] != INF) atomicMin(&cur[(jj + 1) * LS + t + 1], x[t]);
+          if (t + 1 <= D - 1) atomicMin(&cur[(jj + 1) * LS + t + 1], x[t]);
       }
     }
     __syncthreads();
