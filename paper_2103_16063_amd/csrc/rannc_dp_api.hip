@@ -479,6 +479,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   if (timing) ok = ok && hipEventRecord(h->ev[3], st) == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();
+    // nothing of this solve may still run on the handle's streams when the caller sees the error
+    for (int a = 0; a < n_aux; ++a) (void)hipStreamSynchronize(h->aux[a]);
     return RANNC_DP_HIP_ERROR;
   }
   h->ev_valid = timing;

@@ -296,3 +296,35 @@ def test_classes_on_their_own_streams(streams, timing, monkeypatch):
                     assert np.array_equal(res[k], again[k]), k
             assert_results_match(probs, res)
             assert_tables_match(probs[7], sess, 7, args=False)
+
+
+def test_solve_on_a_side_stream_and_two_handles_at_once():
+    """The caller's stream is a stream of its own (not the default one), and two handles work at
+    the same time on two such streams; each batch has several device-count classes, so each
+    handle also forks to its own streams and joins back."""
+    batches = []
+    for b in range(2):
+        probs = []
+        for seed in range(40):
+            g = np.random.default_rng(131_000 + 100 * b + seed)
+            probs.append(synth.random_small(seed + 100 * b, int(g.integers(1, 150)), int(g.integers(1, 65)),
+                                            int(g.integers(1, 14)), tight=float(g.choice([1.3, 3.0])), tmax=2000))
+        batches.append(probs)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sessions = [B.Session(synth.concat_batch(p)) for p in batches]
+    try:
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for sess, st in zip(sessions, streams):
+                with torch.cuda.stream(st):
+                    sess.solve()
+                    sess.traceback()
+        outs = []
+        for sess, st in zip(sessions, streams):
+            with torch.cuda.stream(st):
+                outs.append(sess.run())
+        for probs, res in zip(batches, outs):
+            assert_results_match(probs, res)
+    finally:
+        for sess in sessions:
+            sess.close()
