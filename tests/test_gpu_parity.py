@@ -328,3 +328,26 @@ def test_solve_on_a_side_stream_and_two_handles_at_once():
     finally:
         for sess in sessions:
             sess.close()
+
+
+@pytest.mark.parametrize("fused", ["0", "2"])
+def test_more_searches_than_one_grid_dimension_holds(fused, monkeypatch):
+    """70 000 searches in one batch (a launch covers at most 65 535 problems in a grid dimension, so
+    every kernel is launched in slices): seven distinct tiny searches, each repeated 10 000 times;
+    every copy must equal the oracle's result for its original."""
+    monkeypatch.setenv("RANNC_DP_FUSED_SMALL", fused)
+    base = [synth.random_small(4000 + k, 2 + k, 1 + (k * 5) % 9, 1 + k % 4, tight=[1.2, 2.0, 9.0][k % 3], tmax=50)
+            for k in range(7)]
+    probs = [base[q % 7] for q in range(70_000)]
+    res, sess = gpu_run(probs)
+    with sess:
+        for k, pr in enumerate(base):
+            o = oracle.solve(pr)
+            sel = slice(k, None, 7)
+            assert (res["status"][sel] == 0).all()
+            assert (res["opt"][sel] == o["opt"]).all() and (res["n_stages"][sel] == o["n_stages"]).all()
+            assert (res["est_iter_ns"][sel] == o["est_iter_ns"]).all()
+            w = min(res["stage_end"].shape[1], len(o["stage_end"]))
+            assert (res["stage_end"][sel, :w] == o["stage_end"][:w]).all()
+            assert (res["replicas"][sel, :w] == o["replicas"][:w]).all()
+            assert (res["stage_end"][sel, w:] == -1).all()
