@@ -86,3 +86,42 @@ def test_null_handle_calls():
     assert B.rannc_dp_read_table(None, 0, 0, None, 0, None) == B.INVALID_ARG
     assert B.rannc_dp_set_timing(None, True) == B.INVALID_ARG
     B.rannc_dp_destroy(None)
+
+
+def test_form_stage_host_queries():
+    """Number of searches the outer driver issues = the (node count, microbatch count) pairs
+    Algorithm 2 can visit: n = 1, 2, 4, ... <= n_nodes, MB = 1, 2, 4, ... <= floor(BS / (n_nodes / n))."""
+    z = np.zeros(8, dtype=np.int64)
+
+    def pairs(n_nodes, d_node, BS):
+        return B.rannc_dp_form_stage_problems(B.HostFormStageIn(z, z, z, n_nodes, d_node, BS, 1))
+
+    assert pairs(1, 8, 1) == 1
+    assert pairs(1, 8, 256) == 9                      # MB = 1 .. 256
+    assert pairs(4, 8, 256) == 7 + 8 + 9              # R = 4, 2, 1 -> BS/R = 64, 128, 256
+    assert pairs(3, 2, 8) == 2 + 4                    # n = 1 (R = 3, MB <= 2), n = 2 (R = 1, MB = 1, 2, 4, 8)
+    assert pairs(4, 8, 2) == 0 + 1 + 2                # BS / R = 0 for n = 1: no microbatch count at all
+    assert pairs(16, 8, 64) == 0                      # 8 * 16 devices: more than the kernels hold
+    assert pairs(0, 8, 64) == 0 and pairs(2, 0, 64) == 0 and pairs(2, 8, 0) == 0
+    small = B.rannc_dp_form_stage_scratch_bytes(B.HostFormStageIn(z, z, z, 1, 8, 1, 1))
+    big = B.rannc_dp_form_stage_scratch_bytes(B.HostFormStageIn(z, z, z, 4, 8, 256, 1))
+    assert 0 < small < big and small % 256 == 0 and big % 256 == 0
+    assert B.rannc_dp_form_stage_scratch_bytes(B.HostFormStageIn(z, z, z, 16, 8, 64, 1)) == 0
+    # a communication term needs a bandwidth
+    assert B.rannc_dp_form_stage_problems(B.HostFormStageIn(z, z, z, 2, 4, 8, 1, z, 0)) == 0
+    assert B.rannc_dp_form_stage_problems(B.HostFormStageIn(z, z, z, 2, 4, 8, 1, z, 5)) == 3 + 4
+
+
+def test_split_and_compact_host_queries():
+    plain = B.rannc_dp_workspace_bytes(B.make_limits(1, 256, 32, 16))
+    split = B.rannc_dp_workspace_bytes(B.make_limits(1, 256, 32, 16, flags=B.FLAG_SPLIT_OBJECTIVE))
+    assert split > 2 * plain - (1 << 16)              # a second table, two more value tables, the keys
+    assert B.rannc_dp_workspace_bytes(B.make_limits(1, 256, 32, 16, flags=4)) == 0
+    assert B.rannc_dp_compact_workspace_bytes(1) > 0
+    assert B.rannc_dp_compact_workspace_bytes(1600) < B.rannc_dp_compact_workspace_bytes(1601)  # state leaves LDS
+    assert B.rannc_dp_compact_workspace_bytes(65535) > 0 and B.rannc_dp_compact_workspace_bytes(65536) == 0
+    assert B.rannc_dp_compact(None, 0, 1, 1, None, None, None, None, 0, None, None, None, None, None, None) == B.INVALID_ARG
+    assert B.rannc_dp_form_stage(None, B.HostFormStageIn(np.zeros(2), np.zeros(2), np.zeros(2), 1, 1, 1, 1),
+                                 None, None, 0, 4)[0] == B.INVALID_ARG
+    assert B.rannc_dp_level_values(None, None, 4, None) == B.INVALID_ARG
+    assert B.rannc_dp_traceback_at(None, None, None, 4, None, None) == B.INVALID_ARG
