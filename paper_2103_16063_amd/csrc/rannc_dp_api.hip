@@ -32,7 +32,7 @@ struct Sizes {  // bytes of one problem's regions inside the workspace
 };
 
 // false on arithmetic overflow
-bool problem_sizes(int N, int D, int S_eff, int bits, bool split, Sizes *o) {
+bool problem_sizes(int N, int D, int S_eff, int bits, bool split, bool packed, Sizes *o) {
   const int nch = (N + 63) / 64;
   const int DP = rannc::dp_class(D);
   const size_t esz = bits / 8;
@@ -49,7 +49,7 @@ bool problem_sizes(int N, int D, int S_eff, int bits, bool split, Sizes *o) {
   o->cost = align_up((size_t)cost);
   o->V = align_up((size_t)V);
   o->split = split;
-  o->keys = (split && bits == 32) ? align_up((size_t)(N + 1) * (size_t)DP * 8) : 0;
+  o->keys = (split && packed) ? align_up((size_t)(N + 1) * (size_t)DP * 8) : 0;
   return true;
 }
 
@@ -61,6 +61,8 @@ bool limits_ok(const rannc_dp_limits_t *l) {
 }
 
 bool split_of(const rannc_dp_limits_t *l) { return (l->flags & RANNC_DP_FLAG_SPLIT_OBJECTIVE) != 0; }
+// split objective: can the winners of a level be packed into 64-bit words (see the level kernel)
+bool packed_of(const rannc_dp_limits_t *l) { return l->max_total_time_ns <= rannc::kSplitPackedMax; }
 int bits_of(const rannc_dp_limits_t *l) { return l->max_total_time_ns <= kNarrowMax ? 32 : 64; }
 
 size_t header_bytes(int Q) { return align_up((size_t)Q * sizeof(ProblemDev)); }
@@ -144,7 +146,7 @@ size_t rannc_dp_workspace_bytes(const rannc_dp_limits_t *l) {
   if (!limits_ok(l)) return 0;
   Sizes sz;
   const int S_eff = std::min(l->max_stages, std::min(l->max_blocks, l->max_devices));
-  if (!problem_sizes(l->max_blocks, l->max_devices, S_eff, bits_of(l), split_of(l), &sz)) return 0;
+  if (!problem_sizes(l->max_blocks, l->max_devices, S_eff, bits_of(l), split_of(l), packed_of(l), &sz)) return 0;
   const unsigned __int128 tot =
       (unsigned __int128)sz.total() * (unsigned)l->max_problems + header_bytes(l->max_problems);
   if (tot > ((unsigned __int128)1 << 47)) return 0;
@@ -157,7 +159,7 @@ size_t rannc_dp_workspace_bytes_for(const rannc_dp_limits_t *l, const rannc_dp_b
   for (int q = 0; q < b->n_problems; ++q) {
     Sizes sz;
     const int S_eff = std::min(b->max_stages[q], std::min(b->n_blocks[q], b->n_devices[q]));
-    if (!problem_sizes(b->n_blocks[q], b->n_devices[q], S_eff, bits_of(l), split_of(l), &sz)) return 0;
+    if (!problem_sizes(b->n_blocks[q], b->n_devices[q], S_eff, bits_of(l), split_of(l), packed_of(l), &sz)) return 0;
     tot += sz.total();
     if (tot > ((size_t)1 << 47)) return 0;
   }
@@ -308,7 +310,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     const int N = b->n_blocks[q], D = b->n_devices[q];
     const int S_eff = std::min(b->max_stages[q], std::min(N, D));
     Sizes sz;
-    if (!problem_sizes(N, D, S_eff, h->bits, split, &sz)) return RANNC_DP_OVERFLOW;
+    if (!problem_sizes(N, D, S_eff, h->bits, split, packed_of(&h->lim), &sz)) return RANNC_DP_OVERFLOW;
     if (off + sz.total() > h->ws_bytes) return RANNC_DP_WORKSPACE_TOO_SMALL;
     ProblemDev &p = probs[pos_of[q]];
     std::memset(&p, 0, sizeof(p));
@@ -377,9 +379,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   // ---- kernels ---------------------------------------------------------------------------
   const ProblemDev *dp = h->d_probs;
   const bool scan = h->lim.algo == RANNC_DP_ALGO_SCAN;
-  // split objective: packed-key kernel for 32-bit tables; RANNC_DP_ALGO_SCAN and 64-bit tables take
-  // the literal one
-  const bool split_fast = split && !scan && h->bits == 32;
+  // split objective: packed-key kernel wherever a cell's winner fits a 64-bit word (all 32-bit
+  // handles, 64-bit ones up to 2^42 - 2 ns); RANNC_DP_ALGO_SCAN and larger time bounds take the
+  // literal one
+  const bool split_fast = split && !scan && packed_of(&h->lim);
   bool ok = true;
   const bool timing = h->timing;
   h->ev_valid = false;
@@ -455,7 +458,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       if (!sh.nprob || sh.max_S_eff < s || fused[k]) continue;
       const hipStream_t st = cs[k];
       if (split_fast)
-        ok = rannc::launch_level_split_fast(dp + cls_start[k], sh, kClasses[k], s, st) == hipSuccess;
+        ok = rannc::launch_level_split_fast(dp + cls_start[k], sh, h->bits, kClasses[k], s, st) == hipSuccess;
       else if (split)
         ok = rannc::launch_level_split(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;

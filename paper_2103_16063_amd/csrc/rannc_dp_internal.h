@@ -63,7 +63,7 @@ struct ProblemDev {
   void *VF, *VB;               // largest forward / backward stage time of the plan behind each V entry
                                // (layout of V); null when tb is null
   void *keys;                  // [DP][N+1] uint64: packed (value, i, d') winners of the level in flight;
-                               // only with tb and 32-bit tables, else null
+                               // only with tb and a time bound the packing can hold, else null
   const int64_t *o;            // caller's bytes per cut (DEVICE), N entries, or null: no communication term
   int64_t bw;                  // bandwidth in bytes per microsecond (>= 1 when o is given)
   int64_t *T, *P, *A;          // prefix sums, N+1 entries each
@@ -110,9 +110,12 @@ hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int
 hipError_t launch_split_level1(const ProblemDev *probs, const LaunchShape &sh, int bits, hipStream_t st);
 hipError_t launch_level_split(const ProblemDev *probs, const LaunchShape &sh, int bits, int s, int write_v,
                               int32_t *arg_i, int32_t *arg_d, hipStream_t st);
-// 32-bit tables only; needs the work list made by launch_runs(..., split_rows_per_item(), ...)
+// needs the key table and the work list made by launch_runs(..., split_rows_per_item(), ...); with
+// 64-bit tables only for time bounds up to kSplitPackedMax (the packed winner holds 42 value bits)
+constexpr int64_t kSplitPackedMax = (1LL << 42) - 2;
 int split_rows_per_item();
-hipError_t launch_level_split_fast(const ProblemDev *probs, const LaunchShape &sh, int DP, int s, hipStream_t st);
+hipError_t launch_level_split_fast(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
+                                   hipStream_t st);
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
 // d_levels: per problem (caller's order) the exact stage count to recover, 0 = the best one; or null

@@ -779,25 +779,46 @@ __global__ __launch_bounds__(64) void level_split_kernel(const ProblemDev *__res
 // Candidates d' = lo..hi of one staged row against the device totals d_k, k >= K0, of this wave
 // (all of them lie above hi, so every (d', k) pair is a candidate).  lim[k] = d_k - rmin of the
 // lane's stage (below 0 if d_k > D or nothing fits): the stage fits iff d' <= lim[k].
-template <int DP, int K0>
+// Packed winner of a cell: (sum, i, d') in one 64-bit word whose unsigned order is the lexicographic
+// order of the triple.  32-bit tables: 32 + 24 + 8 bits.  64-bit tables: 42 + 16 + 6 bits, which is
+// why the packed kernel serves 64-bit handles only up to a time bound of 2^42 - 2 ns (73 minutes);
+// the 32-bit key of the running best is always (i << 8) | d'.
+template <typename VT> __device__ __forceinline__ unsigned long long split_pack(VT v, uint32_t key);
+template <> __device__ __forceinline__ unsigned long long split_pack<uint32_t>(uint32_t v, uint32_t key) {
+  return ((unsigned long long)v << 32) | key;
+}
+template <> __device__ __forceinline__ unsigned long long split_pack<uint64_t>(uint64_t v, uint32_t key) {
+  return (v << 22) | ((unsigned long long)(key >> 8) << 6) | (key & 63u);
+}
+template <typename VT> __device__ __forceinline__ int split_key_i(unsigned long long k) {
+  return sizeof(VT) == 4 ? (int)((k >> 8) & 0xFFFFFFull) : (int)((k >> 6) & 0xFFFFull);
+}
+template <typename VT> __device__ __forceinline__ int split_key_d(unsigned long long k) {
+  return sizeof(VT) == 4 ? (int)(k & 0xFFull) : (int)(k & 63ull);
+}
+template <typename VT> __device__ __forceinline__ VT split_key_v(unsigned long long k) {
+  return sizeof(VT) == 4 ? (VT)(k >> 32) : (VT)(k >> 22);
+}
+
+template <typename VT, int DP, int K0>
 __device__ __forceinline__ void split_segment(int lo, int hi, int d0, int i, int lane,
-                                              const uint32_t RANNC_GLOBAL *__restrict__ Frow,
-                                              const uint32_t RANNC_GLOBAL *__restrict__ Brow,
-                                              const uint32_t *sf, const uint32_t *sb,
+                                              const VT RANNC_GLOBAL *__restrict__ Frow,
+                                              const VT RANNC_GLOBAL *__restrict__ Brow,
+                                              const VT *sf, const VT *sb,
                                               const int (&lim)[DP / kSplitWaves],
-                                              uint32_t (&best_v)[DP / kSplitWaves],
+                                              VT (&best_v)[DP / kSplitWaves],
                                               uint32_t (&best_key)[DP / kSplitWaves]) {
   constexpr int KP = DP / kSplitWaves;
   for (int dp = lo; dp <= hi; ++dp) {
-    const uint32_t af = Frow[dp - 1], ab = Brow[dp - 1];  // wave-uniform
+    const VT af = Frow[dp - 1], ab = Brow[dp - 1];  // wave-uniform
     const uint32_t key = ((uint32_t)i << 8) | (uint32_t)dp;
 #pragma unroll
     for (int k = K0; k < KP; ++k) {
       const int r = d0 + kSplitWaves * k - dp;  // >= 1; at most DP (rows beyond the staged ones hold
                                                 // stale values, masked by lim)
-      const uint32_t f = vmax(af, sf[(r - 1) * 64 + lane]);
-      const uint32_t b = vmax(ab, sb[(r - 1) * 64 + lane]);
-      const uint32_t v = f + b;
+      const VT f = vmax(af, sf[(r - 1) * 64 + lane]);
+      const VT b = vmax(ab, sb[(r - 1) * 64 + lane]);
+      const VT v = f + b;
       const bool ok = (dp <= lim[k]) & (v < best_v[k]);
       best_v[k] = ok ? v : best_v[k];
       best_key[k] = ok ? key : best_key[k];
@@ -805,27 +826,26 @@ __device__ __forceinline__ void split_segment(int lo, int hi, int d0, int i, int
   }
 }
 
-template <int DP, int K0>
+template <typename VT, int DP, int K0>
 __device__ __forceinline__ void split_row(int dlo, int D, int d0, int i, int lane,
-                                          const uint32_t RANNC_GLOBAL *__restrict__ Frow,
-                                          const uint32_t RANNC_GLOBAL *__restrict__ Brow,
-                                          const uint32_t *sf, const uint32_t *sb,
+                                          const VT RANNC_GLOBAL *__restrict__ Frow,
+                                          const VT RANNC_GLOBAL *__restrict__ Brow,
+                                          const VT *sf, const VT *sb,
                                           const int (&lim)[DP / kSplitWaves],
-                                          uint32_t (&best_v)[DP / kSplitWaves],
+                                          VT (&best_v)[DP / kSplitWaves],
                                           uint32_t (&best_key)[DP / kSplitWaves]) {
   if constexpr (K0 < DP / kSplitWaves) {
     // d' in [d_{K0-1}, d_{K0} - 1]: exactly the totals d_k with k >= K0 lie above it
     const int lo = K0 == 0 ? dlo : max(dlo, d0 + kSplitWaves * (K0 - 1));
     const int hi = min(d0 + kSplitWaves * K0 - 1, D - 1);
-    split_segment<DP, K0>(lo, hi, d0, i, lane, Frow, Brow, sf, sb, lim, best_v, best_key);
-    split_row<DP, K0 + 1>(dlo, D, d0, i, lane, Frow, Brow, sf, sb, lim, best_v, best_key);
+    split_segment<VT, DP, K0>(lo, hi, d0, i, lane, Frow, Brow, sf, sb, lim, best_v, best_key);
+    split_row<VT, DP, K0 + 1>(dlo, D, d0, i, lane, Frow, Brow, sf, sb, lim, best_v, best_key);
   }
 }
 
-template <int DP>
+template <typename VT, int DP>
 __global__ __launch_bounds__(64 * kSplitWaves) void level_split_fast_kernel(
     const ProblemDev *__restrict__ probs, const int s) {
-  using VT = uint32_t;
   constexpr VT INF = Lim<VT>::inf;
   constexpr int KP = DP / kSplitWaves;  // device totals per wave
   const ProblemDev &pr = probs[blockIdx.z];
@@ -877,7 +897,7 @@ __global__ __launch_bounds__(64 * kSplitWaves) void level_split_fast_kernel(
 #pragma unroll
     for (int k = 0; k < KP; ++k) lim[k] = (d0 + kSplitWaves * k <= D) ? d0 + kSplitWaves * k - rmn : -1;
     __syncthreads();
-    split_row<DP, 0>(dlo, D, d0, i, lane, Fprev + (int64_t)i * DP, Bprev + (int64_t)i * DP, sf, sb, lim,
+    split_row<VT, DP, 0>(dlo, D, d0, i, lane, Fprev + (int64_t)i * DP, Bprev + (int64_t)i * DP, sf, sb, lim,
                      best_v, best_key);
   }
   if (jj >= N || jj + 1 < s) return;
@@ -886,14 +906,13 @@ __global__ __launch_bounds__(64 * kSplitWaves) void level_split_fast_kernel(
   for (int k = 0; k < KP; ++k) {
     const int dk = d0 + kSplitWaves * k;
     if (dk <= D && best_v[k] != INF)
-      (void)__hip_atomic_fetch_min(&K[(int64_t)(dk - 1) * (N + 1) + jj + 1],
-                                   ((unsigned long long)best_v[k] << 32) | best_key[k], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+      (void)__hip_atomic_fetch_min(&K[(int64_t)(dk - 1) * (N + 1) + jj + 1], split_pack<VT>(best_v[k], best_key[k]),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
+template <typename VT>
 __global__ __launch_bounds__(256) void split_finalize_kernel(const ProblemDev *__restrict__ probs, const int s) {
-  using VT = uint32_t;
   const ProblemDev &pr = probs[blockIdx.z];
   if (s > pr.S_eff) return;
   const int N = pr.N, D = pr.D, DP = pr.DP, nch = pr.nch;
@@ -903,13 +922,13 @@ __global__ __launch_bounds__(256) void split_finalize_kernel(const ProblemDev *_
   const unsigned long long key = *K;
   if (key == ~0ull) return;  // no candidate: the cell keeps "no plan"
   *K = ~0ull;                // ready for the next level
-  const int i = (int)((key >> 8) & 0xFFFFFFull), dp = (int)(key & 0xFFull);
+  const int i = split_key_i<VT>(key), dp = split_key_d<VT>(key);
   const int jj = j - 1;
   const int64_t lvl = (int64_t)(N + 1) * DP;
   const int64_t pc = (int64_t)(s - 2) * lvl + (int64_t)i * DP + dp - 1;
   const int64_t te = (unit_index(nch, i, jj >> 6) * D + (d - dp - 1)) * 64 + (jj & 63);
   const int64_t e = (int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1;
-  ((VT *)pr.V)[e] = (VT)(key >> 32);
+  ((VT *)pr.V)[e] = split_key_v<VT>(key);
   ((VT *)pr.VF)[e] = vmax(((const VT *)pr.VF)[pc], ((const VT *)pr.cost)[te]);
   ((VT *)pr.VB)[e] = vmax(((const VT *)pr.VB)[pc], ((const VT *)pr.costb)[te]);
 }
@@ -1496,19 +1515,26 @@ hipError_t launch_level_split(const ProblemDev *p, const LaunchShape &sh, int bi
 
 int split_rows_per_item() { return 0; }  // 0 = chosen on the device from the size of the windows
 
-hipError_t launch_level_split_fast(const ProblemDev *p, const LaunchShape &sh, int DP, int s, hipStream_t st) {
-  int64_t items = 0;  // upper bound on the items of any problem of the launch
-  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + kSplitMinRows - 1) / kSplitMinRows;
+template <typename VT>
+static void split_fast_go(const ProblemDev *p, const LaunchShape &sh, int DP, int s, int64_t items, hipStream_t st) {
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
     const dim3 grid((unsigned)items, 1, nq), block(64 * kSplitWaves);
-    if (DP == 8) hipLaunchKernelGGL((level_split_fast_kernel<8>), grid, block, 0, st, p + q0, s);
-    else if (DP == 16) hipLaunchKernelGGL((level_split_fast_kernel<16>), grid, block, 0, st, p + q0, s);
-    else if (DP == 32) hipLaunchKernelGGL((level_split_fast_kernel<32>), grid, block, 0, st, p + q0, s);
-    else hipLaunchKernelGGL((level_split_fast_kernel<64>), grid, block, 0, st, p + q0, s);
-    hipLaunchKernelGGL(split_finalize_kernel, dim3((sh.max_N + 256) / 256, sh.max_D, nq), dim3(256), 0, st,
+    if (DP == 8) hipLaunchKernelGGL((level_split_fast_kernel<VT, 8>), grid, block, 0, st, p + q0, s);
+    else if (DP == 16) hipLaunchKernelGGL((level_split_fast_kernel<VT, 16>), grid, block, 0, st, p + q0, s);
+    else if (DP == 32) hipLaunchKernelGGL((level_split_fast_kernel<VT, 32>), grid, block, 0, st, p + q0, s);
+    else hipLaunchKernelGGL((level_split_fast_kernel<VT, 64>), grid, block, 0, st, p + q0, s);
+    hipLaunchKernelGGL((split_finalize_kernel<VT>), dim3((sh.max_N + 256) / 256, sh.max_D, nq), dim3(256), 0, st,
                        p + q0, s);
   }
+}
+
+hipError_t launch_level_split_fast(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s,
+                                   hipStream_t st) {
+  int64_t items = 0;  // upper bound on the items of any problem of the launch
+  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + kSplitMinRows - 1) / kSplitMinRows;
+  if (bits == 32) split_fast_go<uint32_t>(p, sh, DP, s, items, st);
+  else split_fast_go<uint64_t>(p, sh, DP, s, items, st);
   return hipGetLastError();
 }
 

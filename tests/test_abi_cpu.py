@@ -24,7 +24,7 @@ def test_library_is_built():
 def test_exports_every_declared_symbol():
     names = _declared()
     assert len(names) >= 10 and set(names) == set(B.EXPORTS)
-    L = C.CDLL(B.LIB_PATH)
+    L = C.CDLL(B.LIB_PATH, mode=os.RTLD_NOW)  # resolve everything now: an undefined symbol fails here
     for n in names:
         assert hasattr(L, n), n
 

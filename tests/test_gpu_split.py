@@ -24,18 +24,20 @@ def _case(seed, N, D, S, tight, tmax, comm):
     return pr
 
 
-@pytest.mark.parametrize("width,algo", [(WIDTHS[0], B.ALGO_AUTO), (WIDTHS[0], B.ALGO_SCAN), (WIDTHS[1], B.ALGO_AUTO)])
+@pytest.mark.parametrize("width,algo", [(WIDTHS[0], B.ALGO_AUTO), (WIDTHS[0], B.ALGO_SCAN), (WIDTHS[1], B.ALGO_AUTO),
+                                        (1 << 41, B.ALGO_AUTO), (1 << 41, B.ALGO_SCAN)])
 def test_shape_sweep_split(width, algo):
-    """32-bit tables take the packed-key level kernel, RANNC_DP_ALGO_SCAN and 64-bit tables the
-    literal one."""
+    """32-bit tables and 64-bit tables with a time bound up to 2^42 - 2 take the packed-key level
+    kernel, RANNC_DP_ALGO_SCAN and larger bounds the literal one."""
     for n, (N, D, S) in enumerate(SHAPES):
         for k, tight in enumerate((1.3, 2.0, 40.0)):
             pr = _case(2900 + n, N, D, S, tight, [6, 5000][(n + k) % 2], comm=(n + k) % 3 == 0)
             if width > B.NARROW_MAX_TOTAL_TIME:
+                up = 1 << (24 if width > (1 << 42) else 20)   # totals beyond 32 bits, within the bound
                 for key in ("time_ns", "time_bwd_ns"):
-                    pr[key] = pr[key] * (1 << 24)  # totals beyond 32 bits
+                    pr[key] = pr[key] * up
                 if "cut_bytes" in pr:
-                    pr["cut_bytes"] = pr["cut_bytes"] * (1 << 24)
+                    pr["cut_bytes"] = pr["cut_bytes"] * up
             res, sess = gpu_run([pr], max_total_time_ns=width, algo=algo)
             with sess:
                 assert_results_match([pr], res)
@@ -184,3 +186,18 @@ def test_form_stage_on_a_split_handle(seed, N, n_nodes, d_node, BS, tight, comm)
     S = want["n_stages"]
     assert np.array_equal(se[:S], want["stage_end"]) and np.array_equal(rp[:S], want["replicas"])
     assert (se[S:] == -1).all() and (rp[S:] == -1).all()
+
+
+def test_split_64bit_packed_at_size():
+    """The ResNet-like chain with times in units that need 64-bit tables, through the packed-key
+    kernel of a handle whose time bound is 2^41, and through the literal kernel of a wider one."""
+    pr = synth.with_backward_times(synth.named_config(3), 23)
+    for key in ("time_ns", "time_bwd_ns"):
+        pr[key] = pr[key] * 4096
+    ra, sa = gpu_run([pr], max_total_time_ns=1 << 41)
+    rb, sb = gpu_run([pr], max_total_time_ns=1 << 50)
+    with sa, sb:
+        assert_results_match([pr], ra)
+        for k in ra:
+            assert np.array_equal(ra[k], rb[k]), k
+        assert_tables_match(pr, sa, 0, args=False)
