@@ -189,7 +189,8 @@ RANNC_DP_API int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t 
  * and transient bytes are linear in the b = floor(batch_size / R / MB) samples of a microbatch on
  * one pipeline replica (inputs are per sample), persistent bytes are not scaled; "best" is the
  * smallest (MB + S - 1) * V (one synchronous pipeline iteration, Fig. 1), the smallest MB among
- * equals.  This call is synchronous: it waits for the stream twice.
+ * equals.  This call is synchronous: it waits for the stream twice.  Its first use on a handle
+ * (and any later use with larger inputs) allocates pinned host memory, freed by destroy.
  *   h            handle whose limits cover rannc_dp_form_stage_problems(in) problems of n_blocks
  *                blocks, devices_per_node * n_max devices and as many stages
  *   d_scratch    DEVICE memory, 256-byte aligned, rannc_dp_form_stage_scratch_bytes(in) bytes

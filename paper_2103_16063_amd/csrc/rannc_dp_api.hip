@@ -118,6 +118,8 @@ struct rannc_dp {
   // the others run on streams of the handle (default priority), forked from and joined to the
   // caller's stream with events.  Off while per-phase timing is on (the phases are timed on the
   // caller's stream) and with RANNC_DP_STREAMS=0.
+  char *fs_pin;          // pinned host mirror of the outer driver's device scratch (grown on demand)
+  size_t fs_pin_bytes;
   hipStream_t aux[3];
   hipEvent_t fork_ev, join_ev[3];
   bool multi_stream;
@@ -190,6 +192,8 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->fused_small = 1;
   if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
+  h->fs_pin = nullptr;
+  h->fs_pin_bytes = 0;
   h->multi_stream = true;
   if (const char *e = std::getenv("RANNC_DP_STREAMS")) h->multi_stream = std::atoi(e) != 0;
   int made_staging = 0, made_ev_s = 0, made_ev = 0, made_aux = 0, made_join = 0;
@@ -249,6 +253,7 @@ void rannc_dp_destroy(rannc_dp_t *h) {
     (void)hipEventDestroy(h->join_ev[k]);
   }
   (void)hipEventDestroy(h->fork_ev);
+  if (h->fs_pin) (void)hipHostFree(h->fs_pin);
   delete h;
 }
 
@@ -587,9 +592,9 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (!in->time_per_sample_ns || !in->act_bytes_per_sample || !in->param_bytes) return RANNC_DP_INVALID_ARG;
   std::vector<FsPair> pairs;
   int max_D = 0;
-  std::vector<int64_t> ht, hp, ha, ho, hb, hbw, hvals, hM, hoff;
+  std::vector<int64_t> hbw, hM, hoff;
   const bool comm = in->cut_bytes_per_sample != nullptr;
-  std::vector<int32_t> hN, hD, hS, hMB, hlev, hns, hse, hrp;
+  std::vector<int32_t> hN, hD, hS, hMB;
   const int N = in->n_blocks;
   try {
     if (!fs_pairs(in, &pairs, &max_D)) return RANNC_DP_INVALID_ARG;
@@ -602,18 +607,44 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (split != split_of(&h->lim)) return RANNC_DP_INVALID_ARG;
   const int stride = max_D;
   if (plan_stride < std::min(stride, N)) return RANNC_DP_INVALID_ARG;
-  if (scratch_bytes < fs_scratch(Q, N, stride)) return RANNC_DP_WORKSPACE_TOO_SMALL;
+  const size_t need = fs_scratch(Q, N, stride);
+  if (scratch_bytes < need) return RANNC_DP_WORKSPACE_TOO_SMALL;
   if (((uintptr_t)d_scratch % kAlign) != 0) return RANNC_DP_INVALID_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  // pinned host mirror of the device scratch: same layout, so inputs go up and results come down
+  // in one copy each
+  if (h->fs_pin_bytes < need) {
+    if (h->fs_pin) {
+      if (hipStreamSynchronize(st) != hipSuccess) return RANNC_DP_HIP_ERROR;  // an earlier call's copies
+      (void)hipHostFree(h->fs_pin);
+      h->fs_pin = nullptr;
+      h->fs_pin_bytes = 0;
+    }
+    if (hipHostMalloc((void **)&h->fs_pin, need, hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      h->fs_pin = nullptr;
+      return RANNC_DP_NO_HOST_MEMORY;
+    }
+    h->fs_pin_bytes = need;
+  }
   try {
-    ht.resize((size_t)Q * N); hp.resize((size_t)Q * N); ha.resize((size_t)Q * N);
-    if (comm) { ho.resize((size_t)Q * N); hbw.assign(Q, in->bandwidth_bytes_per_us); }
-    if (split) hb.resize((size_t)Q * N);
-    hvals.resize((size_t)Q * stride); hM.assign(Q, in->mem_capacity); hoff.resize(Q + 1);
-    hN.assign(Q, N); hD.resize(Q); hS.resize(Q); hMB.resize(Q); hlev.assign(Q, 0); hns.resize(2 * (size_t)Q);
-    hse.resize(stride); hrp.resize(stride);
+    if (comm) hbw.assign(Q, in->bandwidth_bytes_per_us);
+    hM.assign(Q, in->mem_capacity); hoff.resize(Q + 1);
+    hN.assign(Q, N); hD.resize(Q); hS.resize(Q); hMB.resize(Q);
   } catch (...) {
     return RANNC_DP_NO_HOST_MEMORY;
   }
+  // layout of the scratch (device) and of its mirror (host)
+  const size_t a_in = align_up((size_t)Q * N * 8);
+  const size_t o_t = 0, o_p = a_in, o_a = 2 * a_in, o_o = 3 * a_in, o_b = 4 * a_in, o_opt = 5 * a_in;
+  const size_t o_ns = o_opt + align_up((size_t)Q * 8);
+  const size_t o_vals = o_ns + align_up((size_t)Q * 8);
+  const size_t o_lev = o_vals + align_up((size_t)Q * stride * 8);
+  const size_t o_se = o_lev + align_up((size_t)Q * 4);
+  const size_t o_rp = o_se + align_up((size_t)Q * stride * 4);
+  char *dev = (char *)d_scratch, *pin = h->fs_pin;
+  int64_t *ht = (int64_t *)(pin + o_t), *hp = (int64_t *)(pin + o_p), *ha = (int64_t *)(pin + o_a);
+  int64_t *ho = (int64_t *)(pin + o_o), *hb = (int64_t *)(pin + o_b);
   // per-microbatch inputs of every (n, MB): b samples on one pipeline replica
   const __int128 lim = (__int128)1 << 62;
   for (int q = 0; q < Q; ++q) {
@@ -643,51 +674,38 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
     }
   }
   hoff[Q] = (int64_t)Q * N;
-  // scratch layout
-  char *base = (char *)d_scratch;
-  int64_t *d_t = (int64_t *)base; base += align_up((size_t)Q * N * 8);
-  int64_t *d_p = (int64_t *)base; base += align_up((size_t)Q * N * 8);
-  int64_t *d_a = (int64_t *)base; base += align_up((size_t)Q * N * 8);
-  int64_t *d_o = (int64_t *)base; base += align_up((size_t)Q * N * 8);
-  int64_t *d_b = (int64_t *)base; base += align_up((size_t)Q * N * 8);
-  int64_t *d_opt = (int64_t *)base; base += align_up((size_t)Q * 8);
-  int32_t *d_ns = (int32_t *)base;
-  int32_t *d_st = d_ns + Q; base += align_up((size_t)Q * 8);
-  int64_t *d_vals = (int64_t *)base; base += align_up((size_t)Q * stride * 8);
-  int32_t *d_lev = (int32_t *)base; base += align_up((size_t)Q * 4);
-  int32_t *d_se = (int32_t *)base; base += align_up((size_t)Q * stride * 4);
-  int32_t *d_rp = (int32_t *)base;
-  hipStream_t st = (hipStream_t)hip_stream;
-  const size_t nb = (size_t)Q * N * 8;
-  if (hipMemcpyAsync(d_t, ht.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
-      hipMemcpyAsync(d_p, hp.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
-      hipMemcpyAsync(d_a, ha.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess ||
-      (comm && hipMemcpyAsync(d_o, ho.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess) ||
-      (split && hipMemcpyAsync(d_b, hb.data(), nb, hipMemcpyHostToDevice, st) != hipSuccess)) {
+  const size_t in_bytes = (split ? 5 : comm ? 4 : 3) * a_in;  // the regions in use are contiguous
+  if (hipMemcpyAsync(dev, pin, in_bytes, hipMemcpyHostToDevice, st) != hipSuccess) {
     (void)hipGetLastError();
-    (void)hipStreamSynchronize(st);  // copies already enqueued must not outlive their host buffers
     return RANNC_DP_HIP_ERROR;
   }
+  int64_t *d_opt = (int64_t *)(dev + o_opt);
+  int32_t *d_ns = (int32_t *)(dev + o_ns), *d_st = d_ns + Q;
+  int64_t *d_vals = (int64_t *)(dev + o_vals);
+  int32_t *d_lev = (int32_t *)(dev + o_lev), *d_se = (int32_t *)(dev + o_se), *d_rp = (int32_t *)(dev + o_rp);
   rannc_dp_batch_t b;
   b.n_problems = Q;
   b.n_blocks = hN.data(); b.n_devices = hD.data(); b.max_stages = hS.data();
   b.n_microbatches = hMB.data(); b.mem_capacity = hM.data(); b.block_offset = hoff.data();
-  b.time_ns = d_t; b.param_bytes = d_p; b.act_bytes = d_a;
+  b.time_ns = (const int64_t *)(dev + o_t); b.param_bytes = (const int64_t *)(dev + o_p);
+  b.act_bytes = (const int64_t *)(dev + o_a);
   b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
-  b.cut_bytes = comm ? d_o : nullptr;
-  b.time_bwd_ns = split ? d_b : nullptr;
+  b.cut_bytes = comm ? (const int64_t *)(dev + o_o) : nullptr;
+  b.time_bwd_ns = split ? (const int64_t *)(dev + o_b) : nullptr;
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
   if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
   if (rc != RANNC_DP_OK) {
-    (void)hipStreamSynchronize(st);  // the host copies above must not outlive their buffers
+    (void)hipStreamSynchronize(st);  // the mirror may be refilled by the next call
     return rc;
   }
-  if (hipMemcpyAsync(hvals.data(), d_vals, (size_t)Q * stride * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
-      hipMemcpyAsync(hns.data(), d_ns, (size_t)Q * 8, hipMemcpyDeviceToHost, st) != hipSuccess ||
+  // stage counts, status words and per-level values are adjacent: one copy down
+  if (hipMemcpyAsync(pin + o_ns, dev + o_ns, o_lev - o_ns, hipMemcpyDeviceToHost, st) != hipSuccess ||
       hipStreamSynchronize(st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
   }
+  const int32_t *hns = (const int32_t *)(pin + o_ns);
+  const int64_t *hvals = (const int64_t *)(pin + o_vals);
   for (int q = 0; q < Q; ++q) {
     const int stq = hns[Q + q];
     if (stq == RANNC_DP_PROBLEM_NEGATIVE_INPUT) return RANNC_DP_INVALID_ARG;
@@ -713,8 +731,11 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
     }
   }
   if (q_sel < 0) return RANNC_DP_OK;  // infeasible: out->feasible = 0
+  const int64_t v_sel = hvals[(size_t)q_sel * stride + S_sel - 1];  // the mirror is reused below
+  int32_t *hlev = (int32_t *)(pin + o_lev);
+  for (int q = 0; q < Q; ++q) hlev[q] = 0;
   hlev[q_sel] = S_sel;
-  if (hipMemcpyAsync(d_lev, hlev.data(), (size_t)Q * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
+  if (hipMemcpyAsync(d_lev, hlev, (size_t)Q * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
   }
@@ -723,8 +744,9 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
     (void)hipStreamSynchronize(st);
     return rc;
   }
-  if (hipMemcpyAsync(hse.data(), d_se + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
-      hipMemcpyAsync(hrp.data(), d_rp + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+  int32_t *hse = (int32_t *)(pin + o_se), *hrp = (int32_t *)(pin + o_rp);
+  if (hipMemcpyAsync(hse, d_se + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipMemcpyAsync(hrp, d_rp + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
       hipStreamSynchronize(st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
@@ -735,7 +757,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   out->replica_factor = in->n_nodes / pairs[q_sel].n;
   out->n_stages = S_sel;
   out->n_microbatches = pairs[q_sel].MB;
-  out->stage_time_ns = hvals[(size_t)q_sel * stride + S_sel - 1];
+  out->stage_time_ns = v_sel;
   out->est_iter_ns = est_sel;
   for (int u = 0; u < std::min(stride, (int)plan_stride); ++u) { stage_end[u] = hse[u]; replicas[u] = hrp[u]; }
   return RANNC_DP_OK;
