@@ -475,8 +475,7 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
   if (__syncthreads_or(any) == 0) return;
   if (any) {
 #pragma unroll
-    for (int t = 0; t < DP; ++t)
-      if (acc[t] != INF) atomicMin(&tile[lane * (DP + 1) + t], acc[t]);
+    for (int t = 0; t < DP; ++t) atomicMin(&tile[lane * (DP + 1) + t], acc[t]);  // folding INF in is a no-op
   }
   __syncthreads();
   constexpr int RPP = 64 * kMergeWaves / DP;  // rows per pass
