@@ -32,9 +32,9 @@ ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configuratio
 # HBM bytes per level-kernel launch from the committed rocprofv3 --pmc runs (profiles/*.md):
 # FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB (factors from the 256 MiB copy of the same runs).
 PMC_TRAFFIC_BYTES = {
-    "c4": 26.97e6,        # profiles/level_merge_config4.md: 24.41 MB fetched + 2.56 MB written
-    "c4dense": 115.86e6,  # profiles/level_merge_config4_dense.md: 102.51 MB + 13.35 MB
-    "c5": 811.8e6,        # profiles/level_merge_config5_batched.md: 25 978 MB per step over its 32 launches
+    "c4": 26.94e6,        # profiles/level_merge_config4.md: 24.38 MB fetched + 2.56 MB written
+    "c4dense": 115.83e6,  # profiles/level_merge_config4_dense.md: 102.48 MB + 13.35 MB
+    "c5": 805.9e6,        # profiles/level_merge_config5_batched.md: 25 790 MB per step over its 32 launches
                           # (30 level launches at D = 32, 64 and the two one-launch kernels at D = 8, 16)
 }
 
@@ -160,6 +160,9 @@ def main():
                     help="skip the extra roofline_dense measurement (c4 workload only)")
     ap.add_argument("--wide", action="store_true",
                     help="use a 64-bit handle (tables of 8-byte values) for the same inputs")
+    ap.add_argument("--one-stream", action="store_true",
+                    help="keep the device-count classes of a batch on the caller's stream (sets "
+                         "RANNC_DP_STREAMS=0), so that a kernel trace shows each kernel on its own")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy first: the dispatch of known "
                          "size against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled")
@@ -169,6 +172,8 @@ def main():
               "count); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
+    if args.one_stream:
+        os.environ["RANNC_DP_STREAMS"] = "0"
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     if args.calibration_copy:
