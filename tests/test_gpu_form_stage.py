@@ -182,3 +182,20 @@ def test_level_values_and_traceback_at(monkeypatch, fused):
         assert bad == B.INVALID_ARG
     finally:
         sess.close()
+
+
+def test_one_handle_serves_inputs_of_growing_size():
+    """The driver keeps a pinned host mirror of its scratch on the handle and grows it on demand:
+    a small search first, then larger ones, then the small one again, all on one handle."""
+    big = B.FormStageSession(64, 4, 8, 256)
+    try:
+        stream = torch.cuda.current_stream().cuda_stream
+        for (seed, N, nn, dn, BS) in [(1, 6, 1, 2, 4), (2, 20, 2, 4, 32), (3, 64, 4, 8, 256), (1, 6, 1, 2, 4)]:
+            c = synth.form_stage_case(seed, N, nn, dn, BS, tight=1.5, tmax=60)
+            fin = B.HostFormStageIn(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], nn, dn, BS,
+                                    c["mem_capacity"])
+            assert B.rannc_dp_form_stage_scratch_bytes(fin) <= big.scratch_bytes
+            got = B.rannc_dp_form_stage(big.h, fin, stream, big.scratch, big.scratch_bytes, big.plan_stride)
+            _assert_same(c, got, _oracle_form_stage(c), big.plan_stride)
+    finally:
+        big.close()
