@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librannc_dp.so")
-SOURCES = ["rannc_dp_kernels.hip", "rannc_dp_api.hip"]
+SOURCES = ["rannc_dp_kernels.hip", "rannc_dp_split.hip", "rannc_dp_compact.hip", "rannc_dp_api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

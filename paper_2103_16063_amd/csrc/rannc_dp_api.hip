@@ -1,7 +1,7 @@
 // Host orchestration behind the C ABI of include/rannc_dp.h: argument checks, workspace
 // layout, and the sequence of kernel launches of one search (prefix sums and tables, one
 // launch per DP level, final selection, plan recovery).  Nothing here computes any part of the
-// recurrence; that is all in rannc_dp_kernels.hip.
+// recurrence; that is all in the kernel files (rannc_dp_kernels.hip, rannc_dp_split.hip, rannc_dp_compact.hip).
 #include "../../include/rannc_dp.h"
 #include "rannc_dp_internal.h"
 

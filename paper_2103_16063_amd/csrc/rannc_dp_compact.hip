@@ -1,0 +1,153 @@
+// gfx950 kernel of the compaction step of RaNNC's block-level phase (Sec. III-B) on a chain, and
+// its launcher.
+#include "rannc_dp_device.h"
+
+namespace rannc {
+
+// ---------------------------------------------------------------------------------------
+// Compaction step of the block-level phase (Sec. III-B, last step before the stage-level search),
+// on a chain of G groups: one pass over the groups listed by ascending computation time; a
+// listed group that is still as listed merges with the neighbour whose current time is smaller
+// if the union fits the device memory, until k groups are left.  Every merge changes what the
+// following groups see, so the pass itself is sequential (one lane walks the list; the state lives
+// in LDS for chains of up to kCompactLds groups, in the workspace beyond that); the listing (a
+// rank sort), the validation and the compaction of the result into the block arrays of the
+// search are parallel.  The kernel exists so that the chain stays on the device between the two
+// phases.  One workgroup.
+// ---------------------------------------------------------------------------------------
+constexpr int kCompactThreads = 1024;
+constexpr int kCompactLds = 1600;
+
+__global__ __launch_bounds__(kCompactThreads) void compact_kernel(
+    int G, int k, int64_t M, const int64_t *__restrict__ t, const int64_t *__restrict__ p,
+    const int64_t *__restrict__ a, char *__restrict__ ws, int32_t *n_out, int32_t *block_end,
+    int64_t *t_out, int64_t *p_out, int64_t *a_out, int32_t *status) {
+  __shared__ int64_t l_ct[kCompactLds], l_cp[kCompactLds], l_ca[kCompactLds];
+  __shared__ int32_t l_prev[kCompactLds], l_next[kCompactLds];
+  __shared__ uint8_t l_listed[kCompactLds], l_alive[kCompactLds];
+  __shared__ unsigned long long sum_t, sum_m;
+  __shared__ int flags, scan[kCompactThreads];
+  const int tid = threadIdx.x;
+  // state arrays: LDS for short chains, the workspace otherwise (same code through generic pointers)
+  int64_t *ct = l_ct, *cp = l_cp, *ca = l_ca;
+  int32_t *prev = l_prev, *next = l_next, *order = (int32_t *)ws;
+  uint8_t *listed = l_listed, *alive = l_alive;
+  if (G > kCompactLds) {
+    char *w = ws + (((size_t)G * 4 + 255) / 256) * 256;
+    const size_t a8 = (((size_t)G * 8 + 255) / 256) * 256, a4 = (((size_t)G * 4 + 255) / 256) * 256;
+    ct = (int64_t *)w; w += a8;
+    cp = (int64_t *)w; w += a8;
+    ca = (int64_t *)w; w += a8;
+    prev = (int32_t *)w; w += a4;
+    next = (int32_t *)w; w += a4;
+    listed = (uint8_t *)w; w += a4;
+    alive = (uint8_t *)w;
+  }
+  if (tid == 0) { sum_t = 0ull; sum_m = 0ull; flags = 0; }
+  __syncthreads();
+  // ---- validation and initial state ----
+  {
+    unsigned long long st = 0ull, sm = 0ull;
+    int myflags = 0;
+    for (int g = tid; g < G; g += kCompactThreads) {
+      int64_t tv = t[g], pv = p[g], av = a[g];
+      if (tv < 0 || pv < 0 || av < 0) { myflags |= 1; tv = pv = av = 0; }
+      if ((uint64_t)tv >= kSumLimit || (uint64_t)pv >= kSumLimit || (uint64_t)av >= kSumLimit) {
+        myflags |= 2; tv = pv = av = 0;
+      }
+      st += (uint64_t)tv; if (st > kSumLimit) st = kSumLimit;
+      sm += (uint64_t)pv; if (sm > kSumLimit) sm = kSumLimit;
+      sm += (uint64_t)av; if (sm > kSumLimit) sm = kSumLimit;
+      ct[g] = tv; cp[g] = pv; ca[g] = av;
+      prev[g] = g - 1;
+      next[g] = g + 1 < G ? g + 1 : -1;
+      listed[g] = 1;
+      alive[g] = 1;
+    }
+    // totals, saturating (a few hundred adds on two LDS words)
+    unsigned long long old = atomicAdd(&sum_t, st);
+    if (old + st >= kSumLimit) myflags |= 2;
+    old = atomicAdd(&sum_m, sm);
+    if (old + sm >= kSumLimit) myflags |= 2;
+    if (myflags) atomicOr(&flags, myflags);
+  }
+  __syncthreads();
+  if (flags) {
+    if (tid == 0) {
+      *status = (flags & 1) ? RANNC_DP_PROBLEM_NEGATIVE_INPUT : RANNC_DP_PROBLEM_SUM_OVERFLOW;
+      *n_out = 0;
+    }
+    return;
+  }
+  // ---- listing: position of every group in the order (time, position) ----
+  for (int g = tid; g < G; g += kCompactThreads) {
+    const int64_t tg = ct[g];
+    int rank = 0;
+    for (int h = 0; h < G; ++h) {
+      const int64_t th = ct[h];
+      rank += (th < tg) || (th == tg && h < g);
+    }
+    order[rank] = g;
+  }
+  __syncthreads();
+  // ---- the pass ----
+  if (tid == 0) {
+    int count = G;
+    for (int x = 0; x < G && count > k; ++x) {
+      const int v = order[x];
+      if (!listed[v]) continue;
+      const int l = prev[v], r = next[v];
+      if (l < 0 && r < 0) break;
+      int w;
+      if (l < 0) w = r;
+      else if (r < 0) w = l;
+      else w = ct[r] < ct[l] ? r : l;
+      if (cp[v] + ca[v] + cp[w] + ca[w] > M) continue;  // totals stay below 2^62: no overflow
+      const int first = (w == l) ? l : v, second = (w == l) ? v : r;
+      ct[first] += ct[second]; cp[first] += cp[second]; ca[first] += ca[second];
+      const int nx = next[second];
+      next[first] = nx;
+      if (nx >= 0) prev[nx] = first;
+      listed[first] = 0; listed[second] = 0;
+      alive[second] = 0;
+      --count;
+    }
+  }
+  __syncthreads();
+  // ---- result: the surviving group heads in chain order ----
+  const int per = (G + kCompactThreads - 1) / kCompactThreads;
+  const int lo = min(tid * per, G), hi = min(lo + per, G);
+  int mine = 0;
+  for (int g = lo; g < hi; ++g) mine += alive[g];
+  scan[tid] = mine;
+  __syncthreads();
+  for (int off = 1; off < kCompactThreads; off <<= 1) {
+    const int add = tid >= off ? scan[tid - off] : 0;
+    __syncthreads();
+    scan[tid] += add;
+    __syncthreads();
+  }
+  int u = scan[tid] - mine;
+  for (int g = lo; g < hi; ++g) {
+    if (!alive[g]) continue;
+    block_end[u] = next[g] >= 0 ? next[g] : G;
+    t_out[u] = ct[g]; p_out[u] = cp[g]; a_out[u] = ca[g];
+    ++u;
+  }
+  if (tid == kCompactThreads - 1) { *n_out = scan[tid]; *status = RANNC_DP_PROBLEM_OK; }
+}
+
+size_t compact_workspace_bytes(int G) {
+  const size_t a8 = (((size_t)G * 8 + 255) / 256) * 256, a4 = (((size_t)G * 4 + 255) / 256) * 256;
+  return a4 + (G > kCompactLds ? 3 * a8 + 4 * a4 : 0);
+}
+
+hipError_t launch_compact(int G, int k, int64_t M, const int64_t *t, const int64_t *p, const int64_t *a, void *ws,
+                          int32_t *n_out, int32_t *block_end, int64_t *t_out, int64_t *p_out, int64_t *a_out,
+                          int32_t *status, hipStream_t st) {
+  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kCompactThreads), 0, st, G, k, M, t, p, a, (char *)ws, n_out,
+                     block_end, t_out, p_out, a_out, status);
+  return hipGetLastError();
+}
+
+}  // namespace rannc

@@ -88,7 +88,7 @@ struct LaunchShape {
   int max_S_eff;
 };
 
-// Kernel launchers (rannc_dp_kernels.hip).  All enqueue on `st` and return the launch status.
+// Kernel launchers (rannc_dp_kernels.hip, rannc_dp_split.hip, rannc_dp_compact.hip).  All enqueue on `st` and return the launch status.
 // `probs` points at the first ProblemDev of the launch; problems of one launch are contiguous.
 hipError_t launch_prefix(const ProblemDev *probs, int Q, hipStream_t st);
 hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st);
