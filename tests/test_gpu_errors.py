@@ -112,3 +112,22 @@ def test_timing_events():
         sess.run()
         rc, ms, n = B.rannc_dp_get_timing(sess.h)
         assert rc == B.OK and n >= 1 and all(m >= 0 for m in ms) and ms[1] > 0
+
+
+def test_totals_at_the_edge_of_32_bit_tables():
+    """A total time of exactly 2^32 - 2 ns still fits 32-bit tables (2^32 - 1 is the "no plan" mark);
+    one more nanosecond is reported as too large.  Same with a send time on top."""
+    edge = synth.random_small(9, 6, 4, 3, tight=4.0)
+    edge["time_ns"] = np.array([B.NARROW_MAX_TOTAL_TIME - 5, 1, 1, 1, 1, 1], dtype=np.int64)
+    over = dict(edge)
+    over["time_ns"] = edge["time_ns"].copy(); over["time_ns"][3] = 2
+    comm_edge = synth.with_cut_bytes(dict(edge), 1, 1000, lo=0, hi=0)
+    comm_edge["time_ns"] = edge["time_ns"].copy(); comm_edge["time_ns"][0] -= 7
+    comm_edge["cut_bytes"] = np.array([0, 7, 3, 0, 1, 10**9], dtype=np.int64)   # longest send: 7 ns; last cut unused
+    comm_over = dict(comm_edge); comm_over["cut_bytes"] = np.array([0, 8, 3, 0, 1, 0], dtype=np.int64)
+    res, sess = gpu_run([edge, over, comm_edge, comm_over])
+    with sess:
+        assert list(res["status"]) == [B.PROBLEM_OK, B.PROBLEM_TIME_TOO_LARGE, B.PROBLEM_OK, B.PROBLEM_TIME_TOO_LARGE]
+        assert_results_match([edge], {k: v[[0]] for k, v in res.items()})
+        assert_results_match([comm_edge], {k: v[[2]] for k, v in res.items()})
+        assert int(res["opt"][0]) != INF
