@@ -607,6 +607,10 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   if (split != split_of(&h->lim)) return RANNC_DP_INVALID_ARG;
   const int stride = max_D;
   if (plan_stride < std::min(stride, N)) return RANNC_DP_INVALID_ARG;
+  // before anything is sized by them (the batched solve would refuse the same)
+  if (N > h->lim.max_blocks || max_D > h->lim.max_devices || Q > h->lim.max_problems ||
+      std::min(N, max_D) > h->lim.max_stages)
+    return RANNC_DP_LIMIT_EXCEEDED;
   const size_t need = fs_scratch(Q, N, stride);
   if (scratch_bytes < need) return RANNC_DP_WORKSPACE_TOO_SMALL;
   if (((uintptr_t)d_scratch % kAlign) != 0) return RANNC_DP_INVALID_ARG;

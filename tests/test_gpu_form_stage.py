@@ -113,8 +113,8 @@ def test_form_stage_rejects_bad_arguments():
                                        fs.scratch_bytes, fs.plan_stride)
         assert rc == B.INVALID_ARG
         big = B.HostFormStageIn(t, a, p, 4, 2, 8, M)  # more searches than the handle was made for
-        rc, *_ = B.rannc_dp_form_stage(fs.h, big, stream, fs.scratch, 1 << 30, 8)
-        assert rc in (B.LIMIT_EXCEEDED, B.WORKSPACE_TOO_SMALL)
+        rc, *_ = B.rannc_dp_form_stage(fs.h, big, stream, fs.scratch, fs.scratch_bytes, 8)
+        assert rc == B.LIMIT_EXCEEDED  # checked before anything is sized or copied
         assert B.rannc_dp_form_stage_problems(B.HostFormStageIn(t, a, p, 64, 2, 8, M)) == 0  # D > 64
         # the handle still works afterwards
         rc, out, se, rp = fs.run(t, a, p, M)
