@@ -16,7 +16,7 @@ SOURCES = ["rannc_dp_kernels.hip", "rannc_dp_split.hip", "rannc_dp_compact.hip",
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-    "-fvisibility=hidden", "-fgpu-rdc" if False else "-fno-gpu-rdc",
+    "-fvisibility=hidden", "-fno-gpu-rdc",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
