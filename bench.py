@@ -2,6 +2,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4|c5|c3|c2|c1|c4dense|c4split|c4densesplit]
                     [--no-cpu-baseline] [--no-dense] [--calibration-copy]
+    python bench.py --workload formstage32|formstage128|formstage512[split]   (outer driver, Algorithm 2)
 
 A step is one pass of the whole path over one batch of synthetic input that is already resident
 in HBM: prefix sums, stage-time / fit tables, every DP level, the choice of the stage count and
@@ -149,6 +150,67 @@ def run_workload(name, steps, warmup, wide=False):
             "phase": phase, "launches": launches, "res": res, "roofline": roof}
 
 
+def run_form_stage(name, steps, warmup, cpu_baseline):
+    """Outer driver (Algorithm 2) end to end: host arrays in, chosen plan on the host, at the
+    paper's cluster shape (4 nodes x 8 devices, batch 256, Sec. IV-A).  A step is one call:
+    24 searches in three device-count classes plus the host's loops over their results."""
+    import torch
+    from paper_2103_16063_amd import binding as B
+    from paper_2103_16063_amd import synth
+
+    split = name.endswith("split")
+    N = int(name[len("formstage"):-5] if split else name[len("formstage"):])
+    nn, dn, BS = 4, 8, 256
+    c = synth.form_stage_case(7, N, nn, dn, BS, tight=1.3, tmax=2000, layered=True)
+    kw = {}
+    if split:
+        kw["time_bwd_per_sample_ns"] = synth.with_backward_times(
+            {"time_ns": c["time_per_sample_ns"], "name": c["name"]}, 5)["time_bwd_ns"]
+    fs = B.FormStageSession(N, nn, dn, BS, split=split)
+    args = (c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], c["mem_capacity"])
+    for _ in range(warmup):
+        fs.run(*args, **kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        rc, out, se, rp = fs.run(*args, **kw)
+        assert rc == B.OK
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    Q = fs.Q
+    fs.close()
+    # definitional updates of the searches of one call: n = 1, 2, 4 nodes, every MB = 1, 2, 4, ...
+    U, n = 0, 1
+    while n <= nn:
+        D, mb = dn * n, 1
+        while mb <= BS // (nn // n):
+            U += updates(N, D, D)
+            mb *= 2
+        n *= 2
+    line = {
+        "metric": "DP cell-updates/sec (definitional count, outer driver end to end, host arrays in, plan out)",
+        "value": U / (ms * 1e-3) / 1e9, "unit": "G cell-updates/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": {"workload": f"outer driver: {nn} nodes x {dn} devices, batch {BS}, N={N} blocks"
+                               + (", split fwd/bwd objective" if split else ""),
+                   "n_problems": Q, "cell_updates": U},
+        "result": {"feasible": int(out.feasible), "n": int(out.n), "n_stages": int(out.n_stages),
+                   "n_microbatches": int(out.n_microbatches), "est_iter_ns": int(out.est_iter_ns)},
+        "roofline": None,  # bound by launch and copy latency: a few dozen dependent launches of small kernels
+    }
+    if cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        o = oracle.form_stage(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], nn, dn, BS,
+                              c["mem_capacity"], time_bwd_per_sample_ns=kw.get("time_bwd_per_sample_ns"))
+        dt = time.perf_counter() - t0
+        assert (o is not None) == bool(out.feasible)
+        assert o is None or (o["n_stages"] == out.n_stages and o["est_iter_ns"] == out.est_iter_ns)
+        line["cpu_baseline"] = {"value": U / dt / 1e9, "unit": "G cell-updates/s", "cores": 1, "kind": "oracle",
+                                "sample": "the whole call once", "seconds": dt}
+    return line
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +246,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.workload.startswith("formstage"):
+        print(json.dumps(run_form_stage(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)),
+              flush=True)
+        return
     m = run_workload(args.workload, args.steps, args.warmup, args.wide)
     probs, res, phase = m["probs"], m["res"], m["phase"]
     out = {
