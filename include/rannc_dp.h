@@ -200,7 +200,9 @@ RANNC_DP_API int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t 
  * Errors: INVALID_ARG (bad sizes, negative inputs, backward times that do not match the handle's
  * RANNC_DP_FLAG_SPLIT_OBJECTIVE, devices_per_node * n_max > 64,
  * plan_stride < min(devices_per_node * n_max, n_blocks)), OVERFLOW (scaled inputs or their sums
- * exceed the handle's value width or 2^62), LIMIT_EXCEEDED / WORKSPACE_TOO_SMALL from solve. */
+ * exceed the handle's value width or 2^62), LIMIT_EXCEEDED (more searches, blocks, devices or
+ * stages than the handle was created for; checked before anything is copied),
+ * WORKSPACE_TOO_SMALL (scratch_bytes, or the handle's workspace for this batch). */
 typedef struct {
   int32_t n_blocks;                   /* N >= 1 */
   int32_t n_nodes;                    /* >= 1; only n = 1, 2, 4, ... <= n_nodes are visited */
