@@ -122,7 +122,14 @@ def run_workload(name, steps, warmup, wide=False):
         step()
         n_phase = min(steps, 10)
         _, phase, launches = timed_loop(n_phase, with_events=True)
-    res = sess.run()
+    # latency of one search as a caller sees it: solve call to plan bytes on the host (six small
+    # device-to-host copies included), median of 20
+    lat = []
+    for _ in range(20):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        res = sess.run()
+        lat.append(time.perf_counter() - t0)
     sess.close()
     phase /= n_phase
     # algorithmic bytes of all level launches of one step
@@ -147,6 +154,7 @@ def run_workload(name, steps, warmup, wide=False):
                 "traffic": None, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
                 "valu_per_candidate": SPLIT_VALU_PER_UPDATE, "candidates_levels_2_up": U2}
     return {"probs": probs, "label": label, "U": U, "ms_per_step": wall / steps * 1e3,
+            "latency_ms": float(np.median(lat)) * 1e3,
             "phase": phase, "launches": launches, "res": res, "roofline": roof}
 
 
@@ -265,6 +273,7 @@ def main():
         "phases_ms": {"prefix_and_tables": float(phase[0]), "dp_levels": float(phase[1]),
                       "select": float(phase[2]), "level_launches": int(m["launches"])},
         "level_updates_per_s_G": m["U"] / (phase[1] * 1e-3) / 1e9 if phase[1] > 0 else None,
+        "latency_to_host_plan_ms": m["latency_ms"],
         "roofline": m["roofline"],
     }
     if args.workload == "c4" and not args.no_dense and not args.wide:
