@@ -30,14 +30,19 @@ ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 SPLIT_VALU_PER_UPDATE = 57 / 8
 ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configurations run in
 
-# HBM bytes per level-kernel launch from the committed rocprofv3 --pmc runs (profiles/*.md):
-# FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB (factors from the 256 MiB copy of the same runs).
-PMC_TRAFFIC_BYTES = {
-    "c4": 26.94e6,        # profiles/level_merge_config4.md: 24.38 MB fetched + 2.56 MB written
-    "c4dense": 115.83e6,  # profiles/level_merge_config4_dense.md: 102.48 MB + 13.35 MB
-    "c5": 805.9e6,        # profiles/level_merge_config5_batched.md: 25 790 MB per step over its 32 launches
-                          # (30 level launches at D = 32, 64 and the two one-launch kernels at D = 8, 16)
+# HBM bytes per level-kernel launch as rocprofv3 --pmc measured them (FETCH_SIZE x 2.000 + WRITE_SIZE x
+# 1.000 KiB per dispatch, factors from the 256 MiB copy of the same runs).  These are NOT measured by
+# this script: each entry names the committed summary it was copied from, and the JSON line repeats
+# that name next to the number, so a reader can see where it comes from and whether it is stale.
+PMC_TRAFFIC = {
+    "c4": (26.94e6, "profiles/level_merge_config4.md"),
+    "c4dense": (115.83e6, "profiles/level_merge_config4_dense.md"),
+    "c5": (805.9e6, "profiles/level_merge_config5_batched.md"),
 }
+# useful vector instructions of the sorted-merge level kernel per (i, j) stage: DP maxima that form
+# the bitonic sequence, then log2(DP) compare-exchange stages of DP/2 (max, min) pairs
+def merge_valu_per_stage(DP):
+    return DP * (DP.bit_length() - 1 + 1)
 
 
 def updates(N, D, S):
@@ -48,9 +53,63 @@ def updates(N, D, S):
 
 
 def level_bytes(N, D, esize=ESIZE):
-    """Algorithmic bytes of one DP level: every stage-time entry (i,j,r) read once (entries of
-    `esize` bytes), V[s-1] read, V[s] written."""
+    """Dense equivalent of one DP level: every stage-time entry (i,j,r) of `esize` bytes once, V[s-1]
+    read, V[s] written.  What a level would move if nothing could be skipped; never compared with
+    the HBM peak (the kernel skips what the method itself skips)."""
     return esize * D * N * (N + 1) // 2 + 2 * esize * (N + 1) * D
+
+
+def method_work(sess, q, N, D, S_eff, esize, split):
+    """The method's own work per DP level of problem q, from the library's table exports of the
+    finished solve (fits-in-memory table and value table), in the terms of Algorithm 1: a stage
+    (i, j) is visited at level s only if a plan of s-1 stages covers blocks 1..i (the first
+    `continue` of the loop body) and the stage fits memory with at most D-s+1 replicas (the second
+    one; s-1 devices are spent on the earlier stages); of its stage-time entries only those with
+    r <= D-s+1 can be used.  Returns per level s = 2..S_eff:
+      entries  stage-time entries (i, j, r) the level has to read, stage by stage
+      unit_entries  the same at the granularity the table is stored, skipped and read in: every
+               existing column of a (row i, 64-column chunk) unit that holds at least one such stage
+      stages   stages (i, j) it has to merge (min-max search) -- lanes with work
+      units    (row i, 64-column chunk) pairs with at least one such stage -- waves with work
+      rows     rows i of V[s-1] read, cells of V[s] written
+      cands    candidates (i, j, d, d') with a finite predecessor and a fitting stage (what the
+               split objective must evaluate one by one)"""
+    from paper_2103_16063_amd import binding as B
+    INF = np.iinfo(np.int64).max
+    V = sess.table(B.TABLE_V, q)                      # [S_eff+1][N+1][D+1]
+    fit = sess.table(B.TABLE_FIT, q).reshape(-1, D)   # [(j(j-1)/2 + i)][r-1]
+    j_of = np.repeat(np.arange(1, N + 1), np.arange(1, N + 1))
+    i_of = np.arange(fit.shape[0]) - j_of * (j_of - 1) // 2
+    chunk_of = (j_of - 1) >> 6
+    out = []
+    for s in range(2, S_eff + 1):
+        rl = D - s + 1
+        row_ok = V[s - 1, :N, D] != INF               # the kernel's test: V[s-1][i][D] finite
+        act = row_ok[i_of] & (i_of >= s - 1) & (fit[:, rl - 1] != 0)
+        n_act = int(act.sum())
+        units, unit_entries, rows = 0, 0, 0
+        if n_act:
+            ia, ca = i_of[act].astype(np.int64), chunk_of[act].astype(np.int64)
+            uid = np.unique(ia * 1024 + ca)
+            ui, uc = uid // 1024, uid % 1024
+            units = int(uid.shape[0])
+            # columns of the unit that exist: j-1 in [max(i, 64c), min(64c+63, N-1)]
+            lanes = np.minimum(64 * uc + 63, N - 1) - np.maximum(ui, 64 * uc) + 1
+            unit_entries = int(lanes.sum()) * rl
+            rows = int(np.unique(ia).shape[0])
+        cands = 0
+        if split and n_act:
+            # per active stage: pairs (d', d) with V[s-1][i][d'] finite, d' < d <= D, d - d' >= rmin
+            rmin = D - fit[act].sum(axis=1).astype(np.int64) + 1          # fit is monotone in r
+            dlo = np.argmax(V[s - 1, :N, 1:] != INF, axis=1) + 1           # first finite d' per row
+            lo = np.maximum(dlo[i_of[act]], s - 1)
+            n = D - rmin - lo + 1                                          # d' = lo .. D - rmin
+            n = np.maximum(n, 0)
+            cands = int((n * (n + 1) // 2).sum())
+        out.append({"s": s, "entries": n_act * rl, "unit_entries": unit_entries, "stages": n_act,
+                    "units": units, "rows": rows,
+                    "cells": (N - s + 1) * (D - s + 1), "cands": cands})
+    return out
 
 
 def make_workload(name):
@@ -122,37 +181,72 @@ def run_workload(name, steps, warmup, wide=False):
         step()
         n_phase = min(steps, 10)
         _, phase, launches = timed_loop(n_phase, with_events=True)
-    # latency of one search as a caller sees it: solve call to plan bytes on the host (six small
-    # device-to-host copies included), median of 20
+    # latency of one search as a caller sees it: solve call to plan bytes on the host, median of 20
     lat = []
     for _ in range(20):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         res = sess.run()
         lat.append(time.perf_counter() - t0)
-    sess.close()
     phase /= n_phase
-    # algorithmic bytes of all level launches of one step
-    lvl_bytes = 0
-    for p in probs:
+    launches = max(int(launches), 1)
+    per_launch_ms = phase[1] / launches
+    # ---- the method's own work in the level phase (not timed): from the exports of this solve ----
+    split = name.endswith("split")
+    tot = {"entries": 0, "unit_entries": 0, "stages": 0, "units": 0, "rows_bytes": 0, "cells_bytes": 0,
+           "cands": 0, "valu": 0}
+    dense_bytes = 0
+    for q, p in enumerate(probs):
         N, D = p["time_ns"].shape[0], p["n_devices"]
-        lvl_bytes += (min(p["max_stages"], N, D) - 1) * level_bytes(N, D, esize)
-    per_launch_ms = phase[1] / max(launches, 1)
-    achieved = lvl_bytes / max(launches, 1) / (per_launch_ms * 1e-3) / 1e9
-    traffic = None if wide else PMC_TRAFFIC_BYTES.get(name)
-    roof = {"bound": "hbm", "kernel": "level_merge_kernel (%d-bit values)" % (8 * esize), "achieved": achieved,
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": traffic, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
-            "algorithmic_bytes_per_launch": lvl_bytes / max(launches, 1)}
-    if name.endswith("split"):
-        # every candidate is evaluated: bound by the plain vector ALU rate, not by HBM
-        U2 = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"])
-                 - updates(p["time_ns"].shape[0], p["n_devices"], 1) for p in probs)  # levels >= 2
-        ach = U2 * SPLIT_VALU_PER_UPDATE / (phase[1] * 1e-3) / 1e12
-        roof = {"bound": "alu", "kernel": "level_split_fast_kernel + split_finalize_kernel", "achieved": ach,
-                "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-op/s", "frac": ach / ALU_PEAK_TLANEOPS,
-                "traffic": None, "avg_launch_ms": per_launch_ms, "launches_per_step": int(launches),
-                "valu_per_candidate": SPLIT_VALU_PER_UPDATE, "candidates_levels_2_up": U2}
+        S_eff = min(p["max_stages"], N, D)
+        DP = 1 << max(3, int(D - 1).bit_length())
+        dense_bytes += (S_eff - 1) * level_bytes(N, D, esize)
+        for lv in method_work(sess, q, N, D, S_eff, esize, split):
+            tot["entries"] += lv["entries"]
+            tot["unit_entries"] += lv["unit_entries"]
+            tot["stages"] += lv["stages"]
+            tot["units"] += lv["units"]
+            tot["rows_bytes"] += lv["rows"] * D * esize
+            tot["cells_bytes"] += lv["cells"] * esize
+            tot["cands"] += lv["cands"]
+            tot["valu"] += lv["stages"] * merge_valu_per_stage(DP)
+    sess.close()
+    n_tables = 2 if split else 1                  # the split objective reads a backward table too
+    n_vals = 3 if split else 1                    # ... and carries two maxima beside each value
+    v_bytes = (tot["rows_bytes"] + tot["cells_bytes"]) * n_vals
+    own_bytes = esize * tot["unit_entries"] * n_tables + v_bytes
+    strict_bytes = esize * tot["entries"] * n_tables + v_bytes
+    t_levels = phase[1] * 1e-3
+    hbm = own_bytes / t_levels / 1e9
+    traffic, traffic_src = (None, None) if wide else PMC_TRAFFIC.get(name, (None, None))
+    if split:
+        useful = tot["cands"] * SPLIT_VALU_PER_UPDATE
+        alu = useful / t_levels / 1e12
+        kernel = "level_split_fast_kernel + split_finalize_kernel (%d-bit values)" % (8 * esize)
+    else:
+        alu = tot["valu"] / t_levels / 1e12
+        kernel = "level_merge_kernel (%d-bit values)" % (8 * esize)
+    frac_hbm, frac_valu = hbm / HBM_PEAK_GBS, alu / ALU_PEAK_TLANEOPS
+    bound = "alu" if frac_valu > frac_hbm else "hbm"
+    roof = {"bound": bound, "kernel": kernel,
+            "achieved": alu if bound == "alu" else hbm,
+            "peak": ALU_PEAK_TLANEOPS if bound == "alu" else HBM_PEAK_GBS,
+            "unit": "T lane-op/s" if bound == "alu" else "GB/s",
+            "frac": max(frac_hbm, frac_valu),
+            "frac_hbm": frac_hbm, "frac_valu": frac_valu,
+            "traffic": traffic, "traffic_source": traffic_src,
+            "avg_launch_ms": per_launch_ms, "launches_per_step": launches,
+            "algorithmic_bytes_per_launch": own_bytes / launches,
+            "algorithmic_bytes_stage_granularity_per_launch": strict_bytes / launches,
+            "frac_hbm_traffic": (traffic / (per_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS) if traffic else None,
+            "algorithmic_lane_ops_per_launch": (tot["cands"] * SPLIT_VALU_PER_UPDATE if split else tot["valu"]) / launches,
+            "stages_visited_per_step": tot["stages"], "table_units_read_per_step": tot["units"],
+            "dense_equivalent_bytes_per_launch": dense_bytes / launches,
+            "note": "achieved = the method's own bytes (table units that hold a stage Algorithm 1 visits at "
+                    "the level, entries r <= D-s+1; rows of V[s-1] read; V[s] written) or useful lane-ops, "
+                    "per level launch, over the measured launch time; stage granularity counts only the "
+                    "visited stages' own entries; the dense equivalent counts every (i,j,r) and is not "
+                    "compared with a peak; traffic is the rocprofv3 counter figure of the named summary"}
     return {"probs": probs, "label": label, "U": U, "ms_per_step": wall / steps * 1e3,
             "latency_ms": float(np.median(lat)) * 1e3,
             "phase": phase, "launches": launches, "res": res, "roofline": roof}
@@ -228,6 +322,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the extra roofline_dense measurement (c4 workload only)")
+    ap.add_argument("--no-wide", action="store_true",
+                    help="skip the extra measurement of the same workload on 64-bit tables")
     ap.add_argument("--wide", action="store_true",
                     help="use a 64-bit handle (tables of 8-byte values) for the same inputs")
     ap.add_argument("--one-stream", action="store_true",
@@ -277,35 +373,66 @@ def main():
         "roofline": m["roofline"],
     }
     if args.workload == "c4" and not args.no_dense and not args.wide:
-        # the same kernel where nothing can be pruned: achieved ~ real traffic
+        # the same kernel where nothing can be pruned (every stage fits): the streaming case
         dm = run_workload("c4dense", max(5, args.steps // 5), 2)
         out["roofline_dense"] = dict(dm["roofline"], workload=dm["label"],
                                      ms_per_step=dm["ms_per_step"])
+    if not args.no_wide and not args.wide and not args.workload.endswith("split"):
+        # the same workload on a handle with 64-bit tables (the path inputs with totals above
+        # 2^32 - 2 ns take, e.g. the outer driver at the paper's cluster shape)
+        wm = run_workload(args.workload, max(5, args.steps // 5), 2, wide=True)
+        assert int(wm["res"]["opt"][0]) == int(res["opt"][0])
+        out["wide_u64"] = {"dtype": "u64", "ms_per_step": wm["ms_per_step"],
+                           "value": wm["U"] / (wm["ms_per_step"] * 1e-3) / 1e9,
+                           "dp_levels_ms": float(wm["phase"][1]),
+                           "slowdown_vs_u32": wm["ms_per_step"] / m["ms_per_step"],
+                           "roofline": wm["roofline"]}
 
     if not args.no_cpu_baseline:
         import oracle
+        ncpu = os.cpu_count()
         threads = min(oracle.max_threads(), 16)
-        if len(probs) == 1:
-            pr = probs[0]
-            t0 = time.perf_counter()
-            o = oracle.solve(pr, n_threads=threads)
-            dt = time.perf_counter() - t0
-            Ucpu = m["U"]
-            sample = "the whole workload once (tables, all levels, traceback)"
-            assert o["opt"] == int(res["opt"][0]) and o["n_stages"] == int(res["n_stages"][0])
-        else:
-            idx = list(range(0, len(probs), len(probs) // 32))[:32]
+
+        def time_oracle(n_threads, idx, max_levels=None):
             t0 = time.perf_counter()
             for q in idx:
-                o = oracle.solve(probs[q], n_threads=threads)
-                assert o["opt"] == int(res["opt"][q])
-            dt = time.perf_counter() - t0
-            Ucpu = sum(updates(probs[q]["time_ns"].shape[0], probs[q]["n_devices"],
-                               probs[q]["max_stages"]) for q in idx)
-            sample = f"{len(idx)} of the {len(probs)} searches (every {len(probs) // 32}th)"
+                o = oracle.solve(probs[q], n_threads=n_threads, max_levels=max_levels)
+                if max_levels is None:
+                    assert o["opt"] == int(res["opt"][q]) and o["n_stages"] == int(res["n_stages"][q])
+            return time.perf_counter() - t0
+
+        if len(probs) == 1:
+            idx, sample = [0], "the whole workload once (tables, all levels, traceback)"
+        else:
+            idx = list(range(0, len(probs), len(probs) // 32))[:32]
+            sample = f"{len(idx)} of the {len(probs)} searches (every {len(probs) // 32}th), each whole"
+        dt = time_oracle(threads, idx)
+        Ucpu = sum(updates(probs[q]["time_ns"].shape[0], probs[q]["n_devices"], probs[q]["max_stages"])
+                   for q in idx)
         out["cpu_baseline"] = {"value": Ucpu / dt / 1e9, "unit": "G cell-updates/s",
                                "cores": threads, "kind": "oracle", "sample": sample,
-                               "seconds": dt}
+                               "seconds": dt, "host_cpus": ncpu}
+        # single thread: bounded to about 20 s by the number of levels (one search) or of searches
+        rate = Ucpu / dt / threads            # optimistic per-thread rate, only to size the sample
+        if len(probs) == 1:
+            pr = probs[0]
+            N, D = pr["time_ns"].shape[0], pr["n_devices"]
+            L, Lmax = 1, min(pr["max_stages"], N, D)
+            while L < Lmax and updates(N, D, L + 1) / rate < 20.0:
+                L += 1
+            dt1 = time_oracle(1, [0], max_levels=None if L == Lmax else L)
+            U1 = updates(N, D, L)
+            sample1 = ("the whole workload once" if L == Lmax else
+                       f"tables and the first {L} of {Lmax} levels of the workload")
+        else:
+            idx1 = idx[:max(1, int(len(idx) * 20.0 * rate / max(Ucpu, 1)))]
+            dt1 = time_oracle(1, idx1)
+            U1 = sum(updates(probs[q]["time_ns"].shape[0], probs[q]["n_devices"], probs[q]["max_stages"])
+                     for q in idx1)
+            sample1 = f"{len(idx1)} of the {len(probs)} searches, each whole"
+        out["cpu_baseline_1thread"] = {"value": U1 / dt1 / 1e9, "unit": "G cell-updates/s", "cores": 1,
+                                       "kind": "oracle", "sample": sample1, "seconds": dt1,
+                                       "host_cpus": ncpu}
     print(json.dumps(out), flush=True)
 
 

@@ -15,9 +15,18 @@ def gpu_run(problems, **kw):
     return sess.run(), sess
 
 
-def assert_results_match(problems, res, threads=0):
+def oracle_solve_many(problems, workers=None):
+    """oracle.solve of every problem, one search per host thread (the C calls release the GIL)."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    workers = workers or min(16, os.cpu_count() or 1)
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        return list(ex.map(lambda pr: oracle.solve(pr, n_threads=1), problems))
+
+
+def assert_results_match(problems, res, threads=0, oracle_results=None):
     for q, pr in enumerate(problems):
-        o = oracle.solve(pr, n_threads=threads)
+        o = oracle_results[q] if oracle_results is not None else oracle.solve(pr, n_threads=threads)
         S_eff = o["n_levels"]
         assert int(res["status"][q]) == 0, (q, pr["name"])
         assert int(res["opt"][q]) == o["opt"], (q, pr["name"], int(res["opt"][q]), o["opt"])

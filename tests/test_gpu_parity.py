@@ -8,7 +8,7 @@ import oracle
 from paper_2103_16063_amd import binding as B
 from paper_2103_16063_amd import synth
 from tests import defcheck
-from tests.gpu_util import INF, assert_results_match, assert_tables_match, gpu_run
+from tests.gpu_util import INF, assert_results_match, assert_tables_match, gpu_run, oracle_solve_many
 
 pytestmark = pytest.mark.gpu
 
@@ -28,13 +28,14 @@ def test_configs_1_to_3_tables_and_plan(k, algo, width):
 
 
 def test_config4_full_size():
-    """N=1024, D=64, S<=32 in the launch configuration the benchmark times: optimum, plan and
-    the whole value table against the oracle (a few seconds of CPU with all cores)."""
+    """N=1024, D=64, S<=32 in the launch configuration the benchmark times: optimum, plan, the whole
+    value table and the whole (i, d') tables of every cell against the oracle (a few seconds of
+    CPU with all cores)."""
     pr = synth.named_config(4)
     res, sess = gpu_run([pr])
     with sess:
         assert_results_match([pr], res)
-        o = assert_tables_match(pr, sess, 0, args=False)
+        o = assert_tables_match(pr, sess, 0, args=True)
         t, p, a = pr["time_ns"], pr["param_bytes"], pr["act_bytes"]
         defcheck.check_plan(t, p, a, 64, 32, pr["mem_capacity"], int(res["opt"][0]),
                             int(res["n_stages"][0]), res["stage_end"][0], res["replicas"][0])
@@ -121,26 +122,23 @@ def test_batched_mixed_shapes(algo):
 
 
 def test_config5_batched_sweep_full_size():
-    """All 2048 searches in one batch.  The oracle checks a sample one by one; every plan is
-    checked from the definition (fits, covers the chain, replicas sum to D, attains opt), and
-    opt respects the lower bound ceil(T_total / D)."""
+    """All 2048 searches in one batch, in the launch configuration the benchmark times.  The oracle
+    solves every one of them (one search per host thread): optimum, stage count, estimated iteration
+    time and the canonical plan must agree for all 2048; the tables of a few are compared cell by
+    cell; every plan is also checked from the definition."""
     probs = synth.named_config(5)
     res, sess = gpu_run(probs)
     with sess:
         assert (res["status"] == 0).all()
-        sample = list(range(0, 2048, 43)) + [1, 2, 3, 2047]
-        assert_results_match([probs[q] for q in sample],
-                             {k: v[sample] for k, v in res.items()})
-        for q in (0, 1000):
+        assert_results_match(probs, res, oracle_results=oracle_solve_many(probs))
+        for q in (0, 1, 2, 3, 1000, 2047):  # covers the four device-count classes
             assert_tables_match(probs[q], sess, q, args=False)
+        assert {probs[q]["n_devices"] for q in (0, 1, 2, 3, 1000, 2047)} == {8, 16, 32, 64}
         for q, pr in enumerate(probs):
             D = pr["n_devices"]
             opt, ns = int(res["opt"][q]), int(res["n_stages"][q])
             defcheck.check_plan(pr["time_ns"], pr["param_bytes"], pr["act_bytes"], D, 16,
                                 pr["mem_capacity"], opt, ns, res["stage_end"][q], res["replicas"][q])
-            if opt != INF:
-                assert opt >= defcheck.cdiv(int(pr["time_ns"].sum()), D)
-                assert int(res["est_iter_ns"][q]) == (pr["n_microbatches"] + ns - 1) * opt
         assert (res["opt"] != INF).sum() > 1500
 
 
