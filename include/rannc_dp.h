@@ -243,12 +243,18 @@ RANNC_DP_API int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in
 
 /* Compaction step of the block-level phase (Sec. III-B: the step that hands k blocks to the
  * stage-level search), on a chain of G groups in topological order, each with a computation time,
- * persistent and transient bytes.  The groups are listed once by ascending computation time (equal
- * times by position); a listed group that is still as listed picks the neighbour in the chain
- * whose current computation time is smaller (equal: the left one) and merges with it if the
- * union fits the device memory (all persistent + all transient bytes <= mem_capacity; the other
- * neighbour is not tried); a union is not listed again; the pass stops at k groups or at the end
- * of the list.  Enqueued on the stream, no synchronisation, no handle.
+ * persistent and transient bytes.  A walk: the groups as they stand are listed by ascending
+ * computation time (equal times by position); a listed group that is still as listed (neither
+ * absorbed nor grown since) picks the neighbour in the chain whose current computation time is
+ * smaller (equal: the left one) and merges with it if the union fits the device memory (all
+ * persistent + all transient bytes <= mem_capacity; the other neighbour is not tried); a union is
+ * not listed again in the walk that formed it; everything stops as soon as k groups are left.
+ * Sec. III-B repeats this "until |G| = k" and does not say what happens when the list runs out
+ * first: with max_walks = 0 the groups are then listed again by their current times and walked
+ * again, until k groups are left or a walk merges nothing (every chosen union then exceeds the
+ * memory, so further walks could not differ); max_walks = n > 0 stops after n walks (1: a single
+ * walk over the initial list, which at most about halves the number of groups).
+ * Enqueued on the stream, no synchronisation, no handle.
  *   d_time_ns, d_param_bytes, d_act_bytes  DEVICE int64[G], >= 0, totals below 2^62
  *   d_workspace   DEVICE, 256-byte aligned, rannc_dp_compact_workspace_bytes(G) bytes
  *   d_n_blocks    DEVICE int32[1]: number n of resulting blocks (>= min(k, G)); 0 on bad inputs
@@ -257,10 +263,10 @@ RANNC_DP_API int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in
  *   d_time_out, d_param_out, d_act_out  DEVICE int64[G]: summed time and bytes of the n blocks, in
  *                 the form rannc_dp_batch_t takes as block arrays
  *   d_status      DEVICE int32[1]: RANNC_DP_PROBLEM_OK / _NEGATIVE_INPUT / _SUM_OVERFLOW
- * G <= 65535.  Errors: INVALID_ARG, WORKSPACE_TOO_SMALL, HIP_ERROR. */
+ * G <= 65535.  Errors: INVALID_ARG (also max_walks < 0), WORKSPACE_TOO_SMALL, HIP_ERROR. */
 RANNC_DP_API size_t rannc_dp_compact_workspace_bytes(int32_t n_groups); /* 0 if n_groups is out of range */
-RANNC_DP_API int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k, int64_t mem_capacity,
-                                  const int64_t *d_time_ns, const int64_t *d_param_bytes,
+RANNC_DP_API int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k, int32_t max_walks,
+                                  int64_t mem_capacity, const int64_t *d_time_ns, const int64_t *d_param_bytes,
                                   const int64_t *d_act_bytes, void *d_workspace, size_t workspace_bytes,
                                   int32_t *d_n_blocks, int32_t *d_block_end, int64_t *d_time_out,
                                   int64_t *d_param_out, int64_t *d_act_out, int32_t *d_status);

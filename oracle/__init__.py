@@ -52,7 +52,7 @@ def lib():
         L.rannc_oracle_dp_split.restype = C.c_int
         L.rannc_oracle_dp_pruned.argtypes = [i32, i32, i32, pi64, pu8, pi64, pi64]
         L.rannc_oracle_dp_pruned.restype = C.c_int
-        L.rannc_oracle_compact.argtypes = [i32, pi64, pi64, pi64, i32, i64, pi32, pi32]
+        L.rannc_oracle_compact.argtypes = [i32, pi64, pi64, pi64, i32, i64, i32, pi32, pi32]
         L.rannc_oracle_compact.restype = C.c_int
         L.rannc_oracle_select.argtypes = [i32, i32, i32, pi64, pi64, pi32]
         L.rannc_oracle_select.restype = C.c_int
@@ -162,10 +162,12 @@ def traceback(ai, ad, n_stages: int, max_slots: int):
     return se, rp
 
 
-def compact(time_ns, param_bytes, act_bytes, k: int, mem_capacity: int):
+def compact(time_ns, param_bytes, act_bytes, k: int, mem_capacity: int, max_passes: int = 0):
     """Compaction step of the block-level phase on a chain (Sec. III-B): returns the ends of the
     resulting groups (1-based counts of input groups, the last one = G) and their summed time,
-    persistent and transient bytes -- the block arrays the stage-level search takes."""
+    persistent and transient bytes -- the block arrays the stage-level search takes.
+    max_passes = 0: the walk over the groups listed by time is repeated (on the groups as they
+    then stand) until k groups are left or a walk merges nothing; n > 0: at most n walks."""
     t = np.ascontiguousarray(time_ns, dtype=np.int64)
     p = np.ascontiguousarray(param_bytes, dtype=np.int64)
     a = np.ascontiguousarray(act_bytes, dtype=np.int64)
@@ -173,7 +175,8 @@ def compact(time_ns, param_bytes, act_bytes, k: int, mem_capacity: int):
     end = np.empty(G, dtype=np.int32)
     n = C.c_int32()
     _chk(lib().rannc_oracle_compact(G, _p(t, C.c_int64), _p(p, C.c_int64), _p(a, C.c_int64), int(k),
-                                    int(mem_capacity), C.byref(n), _p(end, C.c_int32)), "compact")
+                                    int(mem_capacity), int(max_passes), C.byref(n), _p(end, C.c_int32)),
+         "compact")
     end = end[:n.value].copy()
     lo = np.concatenate(([0], end[:-1]))
     T, P, A = prefix(t), prefix(p), prefix(a)

@@ -332,20 +332,25 @@ int rannc_oracle_traceback(int32_t N, int32_t D, int32_t n_stages, const int32_t
 /* Compaction step of the block-level phase (Sec. III-B, last paragraph before the stage-level
  * search), on a chain: G groups in topological order with computation time t, persistent bytes p
  * and transient bytes a each; target k blocks; device memory M.  Steps, in the paper's order:
- * the groups are listed once by ascending computation time (equal times: by position); each
- * listed group v that still stands alone as listed (it has not been absorbed by an earlier
- * merge) picks, of its left and right neighbours in the chain, the one whose current computation
- * time is smaller (equal: the left one; only one neighbour: that one); if the union fits the
- * device memory (all persistent plus all transient bytes <= M) the two are merged into one group
- * at their place in the chain, times and bytes added up; the pass ends when k groups are left or
- * the list is exhausted.  A union is not put back into the list.  Readings where the text is
- * silent: one pass; the other neighbour is not tried when the chosen one does not fit; memory
- * of a group = p + a (one replica, the whole microbatch); a group that was merged INTO (it
- * absorbed a neighbour on that neighbour's turn) has changed and is no longer the listed group
- * either.
+ * the current groups are listed by ascending computation time (equal times: by position); each
+ * listed group v that still stands as listed (it has neither been absorbed nor grown since) picks,
+ * of its left and right neighbours in the chain, the one whose current computation time is
+ * smaller (equal: the left one; only one neighbour: that one); if the union fits the device
+ * memory (all persistent plus all transient bytes <= M) the two are merged into one group at
+ * their place in the chain, times and bytes added up; the procedure ends as soon as k groups are
+ * left.  A union is not put back into the list it was formed from.
+ * Readings where the text is silent: the other neighbour is not tried when the chosen one does
+ * not fit; memory of a group = p + a (one replica, the whole microbatch); a group that was merged
+ * INTO (it absorbed a neighbour on that neighbour's turn) has changed and is no longer the listed
+ * group either.  "Repeats this process for every v in the sorted list until |G| = k" leaves open
+ * what happens when the list runs out above k groups: with max_passes <= 0 the groups that now
+ * exist are listed again by their current times and the walk repeats, until k groups are left or a
+ * whole walk merges nothing (then every group's chosen union exceeds M and no further walk could
+ * differ); max_passes = n > 0 stops after n walks (n = 1: one walk over the initial list, which at
+ * most about halves the number of groups).
  * Output: n_out groups, group u covering the input groups end[u-1]+1 .. end[u] (end[-1] = 0). */
 int rannc_oracle_compact(int32_t G, const int64_t *t, const int64_t *p, const int64_t *a, int32_t k,
-                         int64_t M, int32_t *n_out, int32_t *end) {
+                         int64_t M, int32_t max_passes, int32_t *n_out, int32_t *end) {
   if (G < 1 || k < 1 || M < 0 || !t || !p || !a || !n_out || !end) return ORACLE_BAD_ARG;
   int64_t *ct = malloc(sizeof(int64_t) * (size_t)G), *cm = malloc(sizeof(int64_t) * (size_t)G);
   int32_t *prev = malloc(sizeof(int32_t) * (size_t)G), *next = malloc(sizeof(int32_t) * (size_t)G);
@@ -368,34 +373,43 @@ int rannc_oracle_compact(int32_t G, const int64_t *t, const int64_t *p, const in
     cm[g] = p[g] + a[g];
     prev[g] = g - 1;
     next[g] = g + 1 < G ? g + 1 : -1;
-    order[g] = g;
-    listed[g] = 1;
-  }
-  /* ascending time, equal times by position: insertion sort keeps the order of equals */
-  for (int32_t x = 1; x < G; ++x) {
-    int32_t v = order[x], y = x - 1;
-    while (y >= 0 && t[order[y]] > t[v]) { order[y + 1] = order[y]; --y; }
-    order[y + 1] = v;
   }
   int32_t count = G;
   /* a group is named by its first input group; next/prev link the group heads along the chain */
-  for (int32_t x = 0; x < G && count > k; ++x) {
-    const int32_t v = order[x];
-    if (!listed[v]) continue;
-    const int32_t l = prev[v], r = next[v];
-    int32_t w;
-    if (l < 0 && r < 0) break; /* a single group */
-    if (l < 0) w = r;
-    else if (r < 0) w = l;
-    else w = ct[r] < ct[l] ? r : l;
-    if (cm[v] + cm[w] > M) continue; /* the union does not fit */
-    const int32_t first = w == l ? l : v, second = w == l ? v : r; /* chain order */
-    ct[first] += ct[second];
-    cm[first] += cm[second];
-    next[first] = next[second];
-    if (next[second] >= 0) prev[next[second]] = first;
-    listed[first] = listed[second] = 0; /* neither is the listed group any more */
-    --count;
+  for (int32_t pass = 1; count > k && (max_passes <= 0 || pass <= max_passes); ++pass) {
+    /* the groups as they stand, by ascending time, equal times by position: the heads are met in
+     * chain order and the insertion sort keeps the order of equals */
+    int32_t n = 0;
+    for (int32_t g = 0; g >= 0; g = next[g]) {
+      order[n++] = g;
+      listed[g] = 1;
+    }
+    for (int32_t x = 1; x < n; ++x) {
+      int32_t v = order[x], y = x - 1;
+      while (y >= 0 && ct[order[y]] > ct[v]) { order[y + 1] = order[y]; --y; }
+      order[y + 1] = v;
+    }
+    int32_t merged = 0;
+    for (int32_t x = 0; x < n && count > k; ++x) {
+      const int32_t v = order[x];
+      if (!listed[v]) continue;
+      const int32_t l = prev[v], r = next[v];
+      int32_t w;
+      if (l < 0 && r < 0) break; /* a single group */
+      if (l < 0) w = r;
+      else if (r < 0) w = l;
+      else w = ct[r] < ct[l] ? r : l;
+      if (cm[v] + cm[w] > M) continue; /* the union does not fit */
+      const int32_t first = w == l ? l : v, second = w == l ? v : r; /* chain order */
+      ct[first] += ct[second];
+      cm[first] += cm[second];
+      next[first] = next[second];
+      if (next[second] >= 0) prev[next[second]] = first;
+      listed[first] = listed[second] = 0; /* neither is the listed group any more */
+      --count;
+      ++merged;
+    }
+    if (!merged) break;
   }
   int32_t n = 0;
   for (int32_t g = 0; g >= 0; g = next[g]) end[n++] = next[g] >= 0 ? next[g] : G;

@@ -117,7 +117,8 @@ def lib():
         L.rannc_dp_form_stage.restype = C.c_int
         L.rannc_dp_compact_workspace_bytes.argtypes = [C.c_int32]
         L.rannc_dp_compact_workspace_bytes.restype = sz
-        L.rannc_dp_compact.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp]
+        L.rannc_dp_compact.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp, vp, sz, vp, vp, vp,
+                                       vp, vp, vp]
         L.rannc_dp_compact.restype = C.c_int
         _lib = L
     return _lib
@@ -243,10 +244,10 @@ def rannc_dp_compact_workspace_bytes(n_groups: int) -> int:
     return int(lib().rannc_dp_compact_workspace_bytes(int(n_groups)))
 
 
-def rannc_dp_compact(stream, n_groups: int, k: int, mem_capacity: int, d_time_ns, d_param_bytes, d_act_bytes,
-                     d_workspace, workspace_bytes: int, d_n_blocks, d_block_end, d_time_out, d_param_out,
-                     d_act_out, d_status) -> int:
-    return lib().rannc_dp_compact(_ptr(stream), int(n_groups), int(k), int(mem_capacity), _ptr(d_time_ns),
+def rannc_dp_compact(stream, n_groups: int, k: int, max_walks: int, mem_capacity: int, d_time_ns, d_param_bytes,
+                     d_act_bytes, d_workspace, workspace_bytes: int, d_n_blocks, d_block_end, d_time_out,
+                     d_param_out, d_act_out, d_status) -> int:
+    return lib().rannc_dp_compact(_ptr(stream), int(n_groups), int(k), int(max_walks), int(mem_capacity), _ptr(d_time_ns),
                                   _ptr(d_param_bytes), _ptr(d_act_bytes), _ptr(d_workspace), int(workspace_bytes),
                                   _ptr(d_n_blocks), _ptr(d_block_end), _ptr(d_time_out), _ptr(d_param_out),
                                   _ptr(d_act_out), _ptr(d_status))

@@ -772,18 +772,18 @@ size_t rannc_dp_compact_workspace_bytes(int32_t n_groups) {
   return rannc::compact_workspace_bytes(n_groups);
 }
 
-int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k, int64_t mem_capacity,
+int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k, int32_t max_walks, int64_t mem_capacity,
                      const int64_t *d_time_ns, const int64_t *d_param_bytes, const int64_t *d_act_bytes,
                      void *d_workspace, size_t workspace_bytes, int32_t *d_n_blocks, int32_t *d_block_end,
                      int64_t *d_time_out, int64_t *d_param_out, int64_t *d_act_out, int32_t *d_status) {
-  if (n_groups < 1 || n_groups > 65535 || k < 1 || mem_capacity < 0) return RANNC_DP_INVALID_ARG;
+  if (n_groups < 1 || n_groups > 65535 || k < 1 || max_walks < 0 || mem_capacity < 0) return RANNC_DP_INVALID_ARG;
   if (!d_time_ns || !d_param_bytes || !d_act_bytes || !d_workspace || !d_n_blocks || !d_block_end ||
       !d_time_out || !d_param_out || !d_act_out || !d_status)
     return RANNC_DP_INVALID_ARG;
   if (((uintptr_t)d_workspace % kAlign) != 0) return RANNC_DP_INVALID_ARG;
   if (workspace_bytes < rannc::compact_workspace_bytes(n_groups)) return RANNC_DP_WORKSPACE_TOO_SMALL;
-  if (rannc::launch_compact(n_groups, k, mem_capacity, d_time_ns, d_param_bytes, d_act_bytes, d_workspace,
-                            d_n_blocks, d_block_end, d_time_out, d_param_out, d_act_out, d_status,
+  if (rannc::launch_compact(n_groups, k, mem_capacity, max_walks, d_time_ns, d_param_bytes, d_act_bytes,
+                            d_workspace, d_n_blocks, d_block_end, d_time_out, d_param_out, d_act_out, d_status,
                             (hipStream_t)hip_stream) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;

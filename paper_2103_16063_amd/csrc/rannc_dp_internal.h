@@ -122,11 +122,23 @@ hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t
 hipError_t launch_traceback(const ProblemDev *probs, int Q, int plan_stride, int32_t *d_stage_end,
                             int32_t *d_replicas, const int32_t *d_levels, hipStream_t st);
 hipError_t launch_level_values(const ProblemDev *probs, int Q, int stride, int64_t *d_out, hipStream_t st);
-// compaction step of the block-level phase on a chain of G groups (one workgroup)
-size_t compact_workspace_bytes(int G);
-hipError_t launch_compact(int G, int k, int64_t M, const int64_t *t, const int64_t *p, const int64_t *a, void *ws,
-                          int32_t *n_out, int32_t *block_end, int64_t *t_out, int64_t *p_out, int64_t *a_out,
-                          int32_t *status, hipStream_t st);
+// compaction step of the block-level phase on a chain of G groups (one workgroup).  Chains whose
+// state fits LDS (kCompactLds groups) need only the listing in the workspace, longer ones keep
+// their whole state there.
+constexpr int kCompactLds = 1600;
+// bytes of one index list: room for the next power of two above G (the bitonic listing pads to it)
+constexpr size_t compact_order_bytes(int G) {
+  size_t P = 1;
+  while (P < (size_t)G) P <<= 1;
+  return (P * 4 + 255) / 256 * 256;
+}
+constexpr size_t compact_workspace_bytes(int G) {
+  const size_t a8 = (((size_t)G * 8 + 255) / 256) * 256, a4 = (((size_t)G * 4 + 255) / 256) * 256;
+  return 2 * compact_order_bytes(G) + (G > kCompactLds ? 3 * a8 + 4 * a4 : 0);
+}
+hipError_t launch_compact(int G, int k, int64_t M, int max_walks, const int64_t *t, const int64_t *p,
+                          const int64_t *a, void *ws, int32_t *n_out, int32_t *block_end, int64_t *t_out,
+                          int64_t *p_out, int64_t *a_out, int32_t *status, hipStream_t st);
 hipError_t launch_export(const ProblemDev *prob, int which, int bits, void *d_dst, hipStream_t st);
 
 

@@ -222,32 +222,38 @@ def split_steps(tf, tb, p, a, D, M, n_levels, comm=None):
 
 
 # ---- compaction step of the block-level phase on a chain (Sec. III-B) ----------------------------
-def compact_steps(t, p, a, k, M):
-    """The compaction pass written out with Python lists of groups (a second, separately written
-    run of the same steps).  Returns the ends of the resulting groups."""
-    groups = [{"lo": g, "hi": g + 1, "t": int(t[g]), "m": int(p[g]) + int(a[g]), "listed": True}
-              for g in range(len(t))]
-    order = sorted(range(len(t)), key=lambda g: (int(t[g]), g))
-    for v in order:
-        if len(groups) <= k:
+def compact_steps(t, p, a, k, M, max_passes=0):
+    """The compaction procedure written out with Python lists of groups (a second, separately
+    written run of the same steps).  Returns the ends of the resulting groups."""
+    groups = [{"lo": g, "hi": g + 1, "t": int(t[g]), "m": int(p[g]) + int(a[g])} for g in range(len(t))]
+    walks = 0
+    while len(groups) > k and (max_passes <= 0 or walks < max_passes):
+        walks += 1
+        # the list of this walk: (lo, hi) names a group as it stood when listed
+        listing = sorted(((gr["t"], gr["lo"], gr["hi"]) for gr in groups))
+        before = len(groups)
+        for _, lo, hi in listing:
+            if len(groups) <= k:
+                break
+            pos = next((x for x, gr in enumerate(groups) if gr["lo"] == lo and gr["hi"] == hi), None)
+            if pos is None:
+                continue  # absorbed or grown since it was listed
+            left = pos - 1 if pos > 0 else None
+            right = pos + 1 if pos + 1 < len(groups) else None
+            if left is None and right is None:
+                break
+            if left is None:
+                w = right
+            elif right is None:
+                w = left
+            else:
+                w = right if groups[right]["t"] < groups[left]["t"] else left
+            if groups[pos]["m"] + groups[w]["m"] > M:
+                continue
+            x, y = min(pos, w), max(pos, w)
+            groups[x] = {"lo": groups[x]["lo"], "hi": groups[y]["hi"], "t": groups[x]["t"] + groups[y]["t"],
+                         "m": groups[x]["m"] + groups[y]["m"]}
+            del groups[y]
+        if len(groups) == before:
             break
-        pos = next((x for x, gr in enumerate(groups) if gr["listed"] and gr["lo"] == v and gr["hi"] == v + 1), None)
-        if pos is None:
-            continue
-        left = pos - 1 if pos > 0 else None
-        right = pos + 1 if pos + 1 < len(groups) else None
-        if left is None and right is None:
-            break
-        if left is None:
-            w = right
-        elif right is None:
-            w = left
-        else:
-            w = right if groups[right]["t"] < groups[left]["t"] else left
-        if groups[pos]["m"] + groups[w]["m"] > M:
-            continue
-        x, y = min(pos, w), max(pos, w)
-        groups[x] = {"lo": groups[x]["lo"], "hi": groups[y]["hi"], "t": groups[x]["t"] + groups[y]["t"],
-                     "m": groups[x]["m"] + groups[y]["m"], "listed": False}
-        del groups[y]
     return [gr["hi"] for gr in groups]

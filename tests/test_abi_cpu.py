@@ -120,7 +120,7 @@ def test_split_and_compact_host_queries():
     assert B.rannc_dp_compact_workspace_bytes(1) > 0
     assert B.rannc_dp_compact_workspace_bytes(1600) < B.rannc_dp_compact_workspace_bytes(1601)  # state leaves LDS
     assert B.rannc_dp_compact_workspace_bytes(65535) > 0 and B.rannc_dp_compact_workspace_bytes(65536) == 0
-    assert B.rannc_dp_compact(None, 0, 1, 1, None, None, None, None, 0, None, None, None, None, None, None) == B.INVALID_ARG
+    assert B.rannc_dp_compact(None, 0, 1, 0, 1, None, None, None, None, 0, None, None, None, None, None, None) == B.INVALID_ARG
     assert B.rannc_dp_form_stage(None, B.HostFormStageIn(np.zeros(2), np.zeros(2), np.zeros(2), 1, 1, 1, 1),
                                  None, None, 0, 4)[0] == B.INVALID_ARG
     assert B.rannc_dp_level_values(None, None, 4, None) == B.INVALID_ARG

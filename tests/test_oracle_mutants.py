@@ -63,7 +63,13 @@ MUTANTS = {
     "compact_ties_to_the_right": ("else w = ct[r] < ct[l] ? r : l;", "else w = ct[r] <= ct[l] ? r : l;"),
     "compact_takes_the_slower_neighbour": ("else w = ct[r] < ct[l] ? r : l;", "else w = ct[r] > ct[l] ? r : l;"),
     "compact_fit_exclusive": ("if (cm[v] + cm[w] > M) continue;", "if (cm[v] + cm[w] >= M) continue;"),
-    "compact_descending_order": ("while (y >= 0 && t[order[y]] > t[v])", "while (y >= 0 && t[order[y]] < t[v])"),
+    "compact_descending_order": ("while (y >= 0 && ct[order[y]] > ct[v])", "while (y >= 0 && ct[order[y]] < ct[v])"),
+    "compact_lists_by_the_input_times": ("while (y >= 0 && ct[order[y]] > ct[v])", "while (y >= 0 && t[order[y]] > t[v])"),
+    "compact_single_walk_only": ("    if (!merged) break;\n", "    break;\n"),
+    "compact_union_keeps_its_turn": ("listed[first] = listed[second] = 0;", "listed[second] = 0;"),
+    "compact_count_checked_between_walks_only": ("for (int32_t x = 0; x < n && count > k; ++x) {",
+                                                 "for (int32_t x = 0; x < n; ++x) {"),
+    "compact_walk_limit_off_by_one": ("(max_passes <= 0 || pass <= max_passes)", "(max_passes <= 0 || pass < max_passes)"),
     "compact_ignores_transient_bytes": ("cm[g] = p[g] + a[g];", "cm[g] = p[g];"),
     "compact_neighbour_times_not_updated": ("ct[first] += ct[second];", "ct[first] += 0;"),
     "device_loop_stops_early": ("for (int32_t dp = s - 1; dp <= d - 1; ++dp)",
@@ -94,6 +100,10 @@ def battery():
     compact_pins.test_worked_example_distinct_times()
     compact_pins.test_worked_example_equal_times_pair_up()
     compact_pins.test_memory_rule_and_no_second_choice()
+    compact_pins.test_worked_example_repeated_walks()
+    compact_pins.test_worked_example_grown_group_loses_its_turn()
+    compact_pins.test_worked_example_second_walk_lists_by_current_times()
+    compact_pins.test_worked_example_walks_end_when_nothing_fits()
     for row in split_pins.SMALL[:12]:
         split_pins.test_values_are_plan_values_bounded_by_the_exact_minimum(*row)
     split_pins.test_worked_example_where_one_pair_per_cell_loses()
