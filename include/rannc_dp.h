@@ -271,6 +271,23 @@ RANNC_DP_API int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k,
                                   int32_t *d_n_blocks, int32_t *d_block_end, int64_t *d_time_out,
                                   int64_t *d_param_out, int64_t *d_act_out, int32_t *d_status);
 
+/* rannc_dp_compact for callers that cannot allocate device memory or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernel, same
+ * arguments and results, but its workspace is a fixed array inside the library's device image
+ * (rannc_dp_compact_workspace_bytes(RANNC_DP_COMPACT_STATIC_MAX_GROUPS) = 786 432 bytes per device,
+ * held until the process ends).  The call allocates nothing on host or device; its first use on a
+ * device looks the array's address up once.  n_groups > RANNC_DP_COMPACT_STATIC_MAX_GROUPS returns
+ * RANNC_DP_LIMIT_EXCEEDED.  All calls on one device share the array: two calls that may overlap on
+ * the device (different streams, no ordering between them) race; calls on one stream, or ordered by
+ * events, are safe.  The array keeps the previous call's contents; the kernel writes every word
+ * before reading it, so nothing is cleared. */
+#define RANNC_DP_COMPACT_STATIC_MAX_GROUPS 16384
+RANNC_DP_API int rannc_dp_compact_static(void *hip_stream, int32_t n_groups, int32_t k, int32_t max_walks,
+                                         int64_t mem_capacity, const int64_t *d_time_ns,
+                                         const int64_t *d_param_bytes, const int64_t *d_act_bytes,
+                                         int32_t *d_n_blocks, int32_t *d_block_end, int64_t *d_time_out,
+                                         int64_t *d_param_out, int64_t *d_act_out, int32_t *d_status);
+
 /* Export one table of one problem of the last solve in a layout-independent form, for parity
  * checks and inspection (not part of the timed path).  d_dst is DEVICE memory of `bytes`
  * bytes; with D = D_q, N = N_q, L = min(S_q,N_q,D_q):

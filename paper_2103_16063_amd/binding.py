@@ -33,7 +33,7 @@ EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp
            "rannc_dp_strerror", "rannc_dp_set_timing", "rannc_dp_get_timing",
            "rannc_dp_traceback_at", "rannc_dp_level_values", "rannc_dp_form_stage_problems",
            "rannc_dp_form_stage_scratch_bytes", "rannc_dp_form_stage",
-           "rannc_dp_compact_workspace_bytes", "rannc_dp_compact"]
+           "rannc_dp_compact_workspace_bytes", "rannc_dp_compact", "rannc_dp_compact_static"]
 
 
 class Limits(C.Structure):
@@ -120,6 +120,9 @@ def lib():
         L.rannc_dp_compact.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp, vp, sz, vp, vp, vp,
                                        vp, vp, vp]
         L.rannc_dp_compact.restype = C.c_int
+        L.rannc_dp_compact_static.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp, vp, vp, vp,
+                                              vp, vp, vp]
+        L.rannc_dp_compact_static.restype = C.c_int
         _lib = L
     return _lib
 
@@ -251,6 +254,18 @@ def rannc_dp_compact(stream, n_groups: int, k: int, max_walks: int, mem_capacity
                                   _ptr(d_param_bytes), _ptr(d_act_bytes), _ptr(d_workspace), int(workspace_bytes),
                                   _ptr(d_n_blocks), _ptr(d_block_end), _ptr(d_time_out), _ptr(d_param_out),
                                   _ptr(d_act_out), _ptr(d_status))
+
+
+COMPACT_STATIC_MAX_GROUPS = 16384
+
+
+def rannc_dp_compact_static(stream, n_groups: int, k: int, max_walks: int, mem_capacity: int, d_time_ns,
+                            d_param_bytes, d_act_bytes, d_n_blocks, d_block_end, d_time_out, d_param_out,
+                            d_act_out, d_status) -> int:
+    return lib().rannc_dp_compact_static(_ptr(stream), int(n_groups), int(k), int(max_walks), int(mem_capacity),
+                                         _ptr(d_time_ns), _ptr(d_param_bytes), _ptr(d_act_bytes), _ptr(d_n_blocks),
+                                         _ptr(d_block_end), _ptr(d_time_out), _ptr(d_param_out), _ptr(d_act_out),
+                                         _ptr(d_status))
 
 
 def rannc_dp_read_table(handle, which: int, problem: int, d_dst, nbytes: int, stream) -> int:

@@ -6,6 +6,7 @@
 #include "rannc_dp_internal.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -784,6 +785,61 @@ int rannc_dp_compact(void *hip_stream, int32_t n_groups, int32_t k, int32_t max_
   if (workspace_bytes < rannc::compact_workspace_bytes(n_groups)) return RANNC_DP_WORKSPACE_TOO_SMALL;
   if (rannc::launch_compact(n_groups, k, mem_capacity, max_walks, d_time_ns, d_param_bytes, d_act_bytes,
                             d_workspace, d_n_blocks, d_block_end, d_time_out, d_param_out, d_act_out, d_status,
+                            (hipStream_t)hip_stream) != hipSuccess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  return RANNC_DP_OK;
+}
+
+// ---- compaction for callers that cannot allocate: workspace in a static device array ----------
+namespace {
+
+constexpr size_t kCompactStaticBytes = rannc::compact_workspace_bytes(RANNC_DP_COMPACT_STATIC_MAX_GROUPS);
+// Workspace of rannc_dp_compact_static.  Every device the library runs on holds its own copy at its
+// own address until the process ends; host code never uses this name as an address (it is only a
+// handle for hipGetSymbolAddress), kernels get the looked-up pointer as an argument.
+static __device__ __align__(256) unsigned char scratch[kCompactStaticBytes];
+
+constexpr int kMaxDevicesPerProcess = 64;
+std::atomic<void *> scratch_of_device[kMaxDevicesPerProcess];
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevicesPerProcess) {
+    (void)hipGetLastError();
+    return RANNC_DP_HIP_ERROR;
+  }
+  void *ptr = scratch_of_device[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return RANNC_DP_HIP_ERROR;
+    }
+    scratch_of_device[dev].store(ptr, std::memory_order_release);  // two racing threads store the same address
+  }
+  *out = ptr;
+  return RANNC_DP_OK;
+}
+
+}  // namespace
+
+int rannc_dp_compact_static(void *hip_stream, int32_t n_groups, int32_t k, int32_t max_walks, int64_t mem_capacity,
+                            const int64_t *d_time_ns, const int64_t *d_param_bytes, const int64_t *d_act_bytes,
+                            int32_t *d_n_blocks, int32_t *d_block_end, int64_t *d_time_out, int64_t *d_param_out,
+                            int64_t *d_act_out, int32_t *d_status) {
+  if (n_groups < 1 || k < 1 || max_walks < 0 || mem_capacity < 0) return RANNC_DP_INVALID_ARG;
+  if (n_groups > RANNC_DP_COMPACT_STATIC_MAX_GROUPS) return RANNC_DP_LIMIT_EXCEEDED;
+  if (!d_time_ns || !d_param_bytes || !d_act_bytes || !d_n_blocks || !d_block_end || !d_time_out ||
+      !d_param_out || !d_act_out || !d_status)
+    return RANNC_DP_INVALID_ARG;
+  void *ws = nullptr;
+  const int rc = static_scratch(&ws);
+  if (rc != RANNC_DP_OK) return rc;
+  // the kernel initialises every word of the workspace it later reads, so nothing has to be cleared
+  if (rannc::launch_compact(n_groups, k, mem_capacity, max_walks, d_time_ns, d_param_bytes, d_act_bytes, ws,
+                            d_n_blocks, d_block_end, d_time_out, d_param_out, d_act_out, d_status,
                             (hipStream_t)hip_stream) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
