@@ -125,6 +125,7 @@ struct rannc_dp {
   hipEvent_t fork_ev, join_ev[3];
   bool multi_stream;
   int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
+  int tune_rows8, tune_rows16;  // > 0: thresholds of that heuristic (experiments)
   int fused_small;  // one-launch kernel for classes of small searches: 1 = where it pays (default),
                     // 0 = never, 2 = whenever N <= 128 (RANNC_DP_FUSED_SMALL)
 };
@@ -190,6 +191,9 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->level_launches = 0;
   h->tune_spw = 0;
   if (const char *e = std::getenv("RANNC_DP_ROWS_PER_WAVE")) h->tune_spw = std::atoi(e);
+  h->tune_rows8 = h->tune_rows16 = 0;
+  if (const char *e = std::getenv("RANNC_DP_ROWS8_FROM")) h->tune_rows8 = std::atoi(e);
+  if (const char *e = std::getenv("RANNC_DP_ROWS16_FROM")) h->tune_rows16 = std::atoi(e);
   h->fused_small = 1;
   if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
@@ -409,7 +413,6 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       for (int a = 0; a < n_aux && ok; ++a) ok = hipStreamWaitEvent(h->aux[a], h->fork_ev, 0) == hipSuccess;
     }
   }
-  int spw[4] = {1, 1, 1, 1};
   bool fused[4] = {false, false, false, false};
   for (int k = 0; k < 4 && ok; ++k) {
     const LaunchShape &sh = shape[k];
@@ -440,12 +443,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), st) == hipSuccess;
     }
     if (scan || split) continue;
-    // One predecessor row per wave: measured best on every configuration (most waves in flight
-    // to hide the latency of the row reads).  RANNC_DP_ROWS_PER_WAVE = 2 or 4 selects the variants
-    // that keep several rows per wave with double-buffered reads.
-    spw[k] = 1;
-    if (h->tune_spw > 0) spw[k] = h->tune_spw;
-    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(spw[k]), st) == hipSuccess;
+    // Rows per wave of the level kernel: chosen on the device from the size of the windows unless
+    // the handle fixes it (1, 2 or 4).
+    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), st, h->tune_rows8,
+                                  h->tune_rows16) == hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;
@@ -472,8 +473,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
         ok = rannc::launch_level_scan(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;
       else
-        ok = rannc::launch_level_merge(dp + cls_start[k], sh, h->bits, kClasses[k], s, spw[k], st) ==
-             hipSuccess;
+        ok = rannc::launch_level_merge(dp + cls_start[k], sh, h->bits, kClasses[k], s, st) == hipSuccess;
       h->level_launches++;
     }
   }

@@ -40,6 +40,7 @@ __host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
 
 // upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
 // groups of at least 8, or into groups of 4 while all windows together hold fewer than 8192 rows
+// (the split-objective kernel) or 6144 rows (the sorted-merge kernel)
 __host__ __device__ inline int64_t max_runs(int nch) {
   const int64_t by8 = 4LL * nch * (nch + 1), by4 = 2 * by8, few = 2048 + nch;
   const int64_t small = by4 < few ? by4 : few;
@@ -94,10 +95,11 @@ hipError_t launch_prefix(const ProblemDev *probs, int Q, hipStream_t st);
 hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st);
 hipError_t launch_build(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, hipStream_t st);
 hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStream_t st);
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st);
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st, int rows8_from = 0,
+                       int rows16_from = 0);
 int merge_rows_per_item(int rows_per_wave);
 hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
-                              int rows_per_wave, hipStream_t st);
+                              hipStream_t st);
 // whole search of problems with N <= small_max_blocks() in one launch, one workgroup each
 int small_max_blocks();
 hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, int64_t *d_opt,

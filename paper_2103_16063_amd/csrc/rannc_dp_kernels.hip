@@ -233,19 +233,23 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 }
 
 // ---------------------------------------------------------------------------------------
-// Work list of the merge level kernel: the rows wlo[c] .. min(64c+63, N-1) of every chunk, cut into
-// items of `rows` consecutive rows, listed chunk by chunk.  A compact list keeps the workgroups
-// that have work at the front of the grid.  One workgroup per problem.
+// Work list of the level kernels: the rows wlo[c] .. min(64c+63, N-1) of every chunk, cut into
+// items of consecutive rows, listed chunk by chunk.  A compact list keeps the workgroups that have
+// work at the front of the grid.  The number of rows of an item travels in the top bits of its
+// descriptor: (rows - 1) << 26 | c << 16 | first row.  rows > 0: items of that many rows;
+// rows = 0 / -1: chosen here from the size of all windows together, for the split-objective /
+// the sorted-merge level kernel: large items where there is enough work to fill the device with
+// them (fewer folds and atomics per row), small ones otherwise (more workgroups, shorter critical
+// path).  The sorted-merge kernel counts the rows of all `batch` searches of the launch.  One
+// workgroup per problem.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows) {
+__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int batch,
+                                                    int rows8_from, int rows16_from) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
   __shared__ int total_rows;
   const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
-  const bool adaptive = rows == 0;
-  if (adaptive) {
-    // adaptive (split level kernel): items of 16 rows, of 8 or 4 if that leaves too few items to
-    // fill the device; the row count of an item travels in the top bits of its descriptor
+  if (rows <= 0) {
     if (tid == 0) total_rows = 0;
     __syncthreads();
     int mine = 0;
@@ -255,9 +259,13 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
     }
     if (mine) atomicAdd(&total_rows, mine);
     __syncthreads();
-    rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
+    // the searches of one launch are alike (one device-count class of one batch): this search's
+    // rows times their number stands for the rows of the whole launch
+    const long long all_rows = (long long)total_rows * batch;
+    if (rows == 0) rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
+    else rows = all_rows >= rows16_from ? 16 : all_rows >= rows8_from ? 8 : kMergeMinRows;
   }
-  const int tag = adaptive ? (rows - 1) << 26 : 0;  // fixed-size items carry no tag
+  const int tag = (rows - 1) << 26;
   for (int c = tid; c < nch; c += 256) {
     const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
     start[c + 1] = lo <= hi ? (hi - lo + rows) / rows : 0;  // items of chunk c
@@ -293,35 +301,40 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
 // Only replica counts r <= D-s+1 can occur at level s (s-1 devices are spent on the earlier
 // stages); the larger ones rank below position D-1 of the merge, so they are not read.
 //
-// Work item (one workgroup of eight waves) = `8*SPW` consecutive rows of one chunk's window, taken
-// from the work list;
-// wave w takes rows i0+w, i0+w+8, ...  A lane owns column jj = 64c + lane.  a[] is
-// wave-uniform (one row of V[s-1]), c[] comes from coalesced reads of one contiguous unit.  The
-// reads of the next row are issued before the current row is merged (two register buffers).
-// The eight waves fold their running minima together in LDS; partial minima of different items
-// are combined with atomicMin into V[s] (pre-filled with INF): min is order-independent, so the
-// result is deterministic.
+// Work item (one workgroup of four waves) = 4, 8 or 16 consecutive rows of one chunk's window,
+// taken from the work list; wave w takes rows i0+w, i0+w+4, ... one after the other and keeps the
+// running minimum over them in registers (one value array for the row in flight, one for the
+// minimum: three waves per SIMD, i.e. three workgroups per compute unit, whose memory, merge and
+// fold phases overlap).  A lane owns column jj = 64c + lane.  a[] is wave-uniform (one row of
+// V[s-1], scalar loads), c[] comes from coalesced reads of one contiguous unit; the flags of the
+// next row are fetched while the current one is merged.  The four waves then fold their minima
+// together in LDS, and one transposed pass of device-scope atomicMin into V[s] (pre-filled with
+// INF) combines the items of a chunk: min is order-independent, so the result is deterministic.
 // ---------------------------------------------------------------------------------------
-constexpr int kMergeWaves = 8;
-
-template <typename VT, int DP>
-__device__ __forceinline__ void unit_load(VT (&x)[DP], const VT RANNC_GLOBAL *__restrict__ unit, bool act,
-                                          int rl) {
-  // x[DP-1-m] = c[m+1]: reversed, so that max(a, x) is a bitonic sequence
+// One row's sorted merge: x := the DP largest elements of merge(a, c), sorted descending, for the
+// lane's stage; all INF for a lane without work (`off` = INF there, 0 elsewhere).
+//
+// x[DP-1-m] = c[m+1]: reversed, so that max(a, x) is a bitonic sequence; then log2(DP) compare-
+// exchange stages.  Replica counts beyond rl cannot occur at this level and rank below everything
+// that matters in the merge.  NG = ceil(rl / 8) is a compile-time number, so that the reads of a
+// row are one straight run of independent loads: the groups of eight rows beyond it are taken as
+// 0, and inside the last group the row index is clamped to rl-1 (the repeated value keeps the
+// sequence sorted, stays below rank D-1, and costs no memory traffic).  `unit` points at the
+// lane's column, or for a lane without work at the column of a lane that has some (every load
+// instruction then touches only lines that are needed); such a lane is switched off by folding
+// `off` into the first maximum, which makes its whole result INF.
+template <typename VT, int DP, int NG, typename AP>
+__device__ __forceinline__ void row_merge(VT (&x)[DP], const VT RANNC_GLOBAL *__restrict__ unit, AP arow,
+                                          VT off, int rl) {
 #pragma unroll
   for (int m = 0; m < DP; ++m) {
-    const int mr = (m < rl) ? m : (rl - 1);  // clamp keeps the address inside the unit
-    VT cv = Lim<VT>::inf;
-    if (act) cv = unit[mr * 64];
-    x[DP - 1 - m] = (m < rl) ? cv : (VT)0;   // unread entries rank below everything that matters
+    if (m < 8 * (NG - 1)) x[DP - 1 - m] = unit[m * 64];
+    else if (m == 8 * (NG - 1)) x[DP - 1 - m] = unit[m * 64];       // 8(NG-1) <= rl-1: never clamped
+    else if (m < 8 * NG) x[DP - 1 - m] = unit[min(m, rl - 1) * 64];  // wave-uniform clamp
+    else x[DP - 1 - m] = (VT)0;
   }
-}
-
-// x := the DP largest elements of merge(a, c), sorted descending (x holds c reversed on entry)
-template <typename VT, int DP, typename AP>
-__device__ __forceinline__ void unit_sort(VT (&x)[DP], AP arow) {
 #pragma unroll
-  for (int q = 0; q < DP; ++q) x[q] = vmax(arow[q], x[q]);
+  for (int q = 0; q < DP; ++q) x[q] = vmax(vmax(arow[q], x[q]), off);
 #pragma unroll
   for (int h = DP / 2; h >= 1; h >>= 1) {
 #pragma unroll
@@ -336,91 +349,95 @@ __device__ __forceinline__ void unit_sort(VT (&x)[DP], AP arow) {
   }
 }
 
-template <typename VT, int DP>
-__device__ __forceinline__ void unit_merge(VT (&acc)[DP], VT (&x)[DP],
-                                           const VT RANNC_GLOBAL *__restrict__ arow) {
-  unit_sort<VT, DP, const VT RANNC_GLOBAL *>(x, arow);
-#pragma unroll
-  for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
-}
+// Waves per SIMD the level kernel is compiled for: the two value arrays of the widest 32-bit case
+// fit the 168 registers of three waves per SIMD (the compiler left alone takes one more).
+template <typename VT, int DP> constexpr int merge_waves_per_simd() { return (sizeof(VT) == 4 && DP == 64) ? 3 : 1; }
 
-template <typename VT, int DP, int SPW>
-__global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
-    const ProblemDev *__restrict__ probs, const int s) {
-  const ProblemDev &pr = probs[blockIdx.z];
-  if (s > pr.S_eff) return;
-  const int N = pr.N, D = pr.D, nch = pr.nch;
-  constexpr int R = kMergeWaves * SPW;
-  const int32_t RANNC_GLOBAL *__restrict__ runs = gptr((const int32_t *)pr.runs);
-  if ((int)blockIdx.x >= runs[0]) return;
-  const int desc = runs[1 + blockIdx.x];
-  const int c = desc >> 16, i0 = desc & 0xffff;
-  if (64 * c + 64 < s) return;  // no column j >= s in this chunk
-  const int i_hi = min(min(i0 + R - 1, 64 * c + 63), N - 1);
-  if (i_hi < s - 1) return;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int jj = 64 * c + lane;
+// The rows i0+wave, i0+wave+4, ... <= i_hi of one work item, folded into acc (running minimum of the
+// sorted merges).  Returns whether any row had work.
+template <typename VT, int DP, int NG>
+__device__ __forceinline__ bool merge_rows(VT (&acc)[DP], const ProblemDev &pr, const int s, const int c,
+                                           const int i0, const int i_hi, const int lane, const int wave) {
   constexpr VT INF = Lim<VT>::inf;
+  const int N = pr.N, D = pr.D, nch = pr.nch;
+  const int jj = 64 * c + lane;
   const int64_t lvl = (int64_t)(N + 1) * DP;
   const VT RANNC_GLOBAL *__restrict__ Vprev = gptr((const VT *)pr.V) + (int64_t)(s - 2) * lvl;
-  VT RANNC_GLOBAL *Vcur = gptr((VT *)pr.V) + (int64_t)(s - 1) * lvl;
   const VT RANNC_GLOBAL *__restrict__ cost = gptr((const VT *)pr.cost);
   const uint8_t RANNC_GLOBAL *__restrict__ rmin = gptr((const uint8_t *)pr.rmin);
   const int rl = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
-
-  // Which of this wave's rows can contribute: the row of V[s-1] must hold a finite plan and the
-  // lane's stage must fit with at most rl replicas.  All loads issued together.
-  bool act[SPW];
-  int64_t ubase[SPW];
-  {
-    VT alast[SPW];
-    int rmn[SPW];
-#pragma unroll
-    for (int k = 0; k < SPW; ++k) {
-      const int i = i0 + wave + kMergeWaves * k;
-      alast[k] = INF;
-      rmn[k] = 255;
-      ubase[k] = 0;
-      if (i >= s - 1 && i <= i_hi) {
-        ubase[k] = unit_index(nch, i, c);
-        alast[k] = Vprev[(int64_t)i * DP + D - 1];
-        if (jj >= i && jj < N) rmn[k] = rmin[ubase[k] * 64 + lane];
-      }
+  // Flags of a row: it can contribute if its row of V[s-1] holds a finite plan and the lane's
+  // stage fits with at most rl replicas.
+  auto row_flags = [&](int i, int64_t &ubase) -> bool {
+    VT alast = INF;
+    int rmn = 255;
+    ubase = 0;
+    if (i >= s - 1 && i <= i_hi) {
+      ubase = unit_index(nch, i, c);
+      alast = Vprev[(int64_t)i * DP + D - 1];
+      if (jj >= i && jj < N) rmn = rmin[ubase * 64 + lane];
     }
+    return (alast != INF) && (rmn <= rl);
+  };
+  bool any = false;
+  int i = i0 + wave;
+  int64_t ubase;
+  bool act = row_flags(i, ubase);
+  while (i <= i_hi) {  // wave-uniform
+    // the next row's flags are fetched while this row is merged
+    int64_t ubase_next = 0;
+    const bool act_next = (i + kMergeWaves <= i_hi) ? row_flags(i + kMergeWaves, ubase_next) : false;
+    const unsigned long long work = __ballot(act);
+    if (work != 0ull) {
+      any = true;
+      VT x[DP];
+      const int col = act ? lane : __ffsll((long long)work) - 1;  // a lane without work reads a needed column
+      row_merge<VT, DP, NG, const VT RANNC_GLOBAL *>(x, cost + ubase * 64 * D + col, Vprev + (int64_t)i * DP,
+                                                     act ? (VT)0 : INF, rl);
 #pragma unroll
-    for (int k = 0; k < SPW; ++k) act[k] = (alast[k] != INF) && (rmn[k] <= rl);
+      for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+    }
+    act = act_next;
+    ubase = ubase_next;
+    i += kMergeWaves;
   }
+  return any;
+}
+
+template <typename VT, int DP>
+__global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP>())))
+void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
+  const ProblemDev &pr = probs[blockIdx.z];
+  if (s > pr.S_eff) return;
+  const int N = pr.N, D = pr.D;
+  const int32_t RANNC_GLOBAL *__restrict__ runs = gptr((const int32_t *)pr.runs);
+  if ((int)blockIdx.x >= runs[0]) return;
+  const unsigned desc = (unsigned)runs[1 + blockIdx.x];
+  const int c = (int)((desc >> 16) & 0x3ffu), i0 = (int)(desc & 0xffffu), rows = (int)(desc >> 26) + 1;
+  if (64 * c + 64 < s) return;  // no column j >= s in this chunk
+  const int i_hi = min(min(i0 + rows - 1, 64 * c + 63), N - 1);
+  if (i_hi < s - 1) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  constexpr VT INF = Lim<VT>::inf;
+  VT RANNC_GLOBAL *Vcur = gptr((VT *)pr.V) + (int64_t)(s - 1) * (int64_t)(N + 1) * DP;
 
   // acc[t] = running minimum over this wave's rows of the sorted merge
   VT acc[DP];
+#pragma unroll
+  for (int t = 0; t < DP; ++t) acc[t] = INF;
   bool any = false;
-  if constexpr (SPW == 1) {  // one row: its sorted merge is the result, no second array
-    unit_load<VT, DP>(acc, cost + ubase[0] * 64 * D + lane, act[0], rl);
-    if (__ballot(act[0]) != 0ull) {
-      any = true;
-      unit_sort<VT, DP, const VT RANNC_GLOBAL *>(acc, Vprev + (int64_t)(i0 + wave) * DP);
-    }
-  } else {
-#pragma unroll
-    for (int t = 0; t < DP; ++t) acc[t] = INF;
-    VT xa[DP], xb[DP];
-    unit_load<VT, DP>(xa, cost + ubase[0] * 64 * D + lane, act[0], rl);
-#pragma unroll
-    for (int k = 0; k < SPW; ++k) {
-      // issue the next row's reads into the idle buffer, then merge the current one
-      if (k + 1 < SPW) {
-        if ((k & 1) == 0) unit_load<VT, DP>(xb, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
-        else unit_load<VT, DP>(xa, cost + ubase[k + 1] * 64 * D + lane, act[k + 1], rl);
-      }
-      if (__ballot(act[k]) != 0ull) {
-        any = true;
-        const VT RANNC_GLOBAL *__restrict__ arow = Vprev + (int64_t)(i0 + wave + kMergeWaves * k) * DP;
-        if ((k & 1) == 0) unit_merge<VT, DP>(acc, xa, arow);
-        else unit_merge<VT, DP>(acc, xb, arow);
-      }
-    }
+  const int ng = (D - s + 1 + 7) >> 3;  // eight-row groups of a unit that this level reads
+#define RANNC_ROWS(K)                                                                     \
+  case K:                                                                                 \
+    if constexpr (8 * K <= DP) any = merge_rows<VT, DP, K>(acc, pr, s, c, i0, i_hi, lane, wave); \
+    break;
+  switch (ng) {
+    RANNC_ROWS(1) RANNC_ROWS(2) RANNC_ROWS(3) RANNC_ROWS(4)
+    RANNC_ROWS(5) RANNC_ROWS(6) RANNC_ROWS(7) RANNC_ROWS(8)
+    default: break;
   }
+#undef RANNC_ROWS
 
   // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Fold the waves in LDS, then
   // write transposed so that one atomic instruction covers consecutive d of one column.
@@ -444,7 +461,7 @@ __global__ __launch_bounds__(64 * kMergeWaves) void level_merge_kernel(
 // ---------------------------------------------------------------------------------------
 // Whole search of a SMALL problem (N <= 128, i.e. at most two column chunks) in one workgroup and
 // one launch: prefix sums, tables, every level, choice of the stage count.  Same arithmetic as the
-// kernels above (the same build_unit / unit_load / unit_sort), but two consecutive levels of V
+// kernels above (the same build_unit / row_merge), but two consecutive levels of V
 // live in LDS, so the waves of the workgroup fold their merges with LDS atomics and meet at
 // workgroup barriers: no launch per level, no global atomics.  Every level is also copied to the
 // V table in memory (plan recovery and export read it there).  Meant for searches at the
@@ -561,8 +578,22 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
       const bool act = rmn <= rl;
       if (__ballot(act) == 0ull) continue;
       VT x[DP];
-      unit_load<VT, DP>(x, cost + u * 64 * D + lane, act, rl);
-      unit_sort<VT, DP, const VT *>(x, prev + i * LS);
+      {
+        const int col = act ? lane : __ffsll((long long)__ballot(act)) - 1;
+        const VT RANNC_GLOBAL *unit = cost + u * 64 * D + col;
+        const VT *arow = prev + i * LS;
+        const VT off = act ? (VT)0 : INF;
+#define RANNC_ROW(K)                                                                   \
+  case K:                                                                              \
+    if constexpr (8 * K <= DP) row_merge<VT, DP, K, const VT *>(x, unit, arow, off, rl); \
+    break;
+        switch ((rl + 7) >> 3) {
+          RANNC_ROW(1) RANNC_ROW(2) RANNC_ROW(3) RANNC_ROW(4)
+          RANNC_ROW(5) RANNC_ROW(6) RANNC_ROW(7) RANNC_ROW(8)
+          default: break;
+        }
+#undef RANNC_ROW
+      }
       if (act && jj + 1 >= s) {
         // unconditional: folding INF in is a no-op and costs less than testing for it
 #pragma unroll
@@ -952,11 +983,14 @@ hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st) {
 }
 
 int merge_rows_per_item(int rows_per_wave) {
+  if (rows_per_wave <= 0) return -1;  // chosen on the device from the size of the windows
   return kMergeWaves * (rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : 4);
 }
 
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st) {
-  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item);
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st, int rows8_from,
+                       int rows16_from) {
+  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, Q,
+                     rows8_from > 0 ? rows8_from : kMergeRows8From, rows16_from > 0 ? rows16_from : kMergeRows16From);
   return hipGetLastError();
 }
 
@@ -993,35 +1027,28 @@ hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, in
   return hipGetLastError();
 }
 
-template <typename VT, int DP, int SPW>
+template <typename VT, int DP>
 static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, hipStream_t st) {
-  // upper bound on the items of any problem of the launch: every chunk's rows, none pruned
-  // upper bound on the items of any problem of the launch: every chunk's rows, none pruned
+  // upper bound on the items of any problem of the launch: every chunk's rows, none pruned, in the
+  // smallest items the work list makes; never more than the list can hold
   int64_t items = 0;
-  const int rows = kMergeWaves * SPW;
-  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + rows - 1) / rows;
+  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + kMergeMinRows - 1) / kMergeMinRows;
+  items = std::min<int64_t>(items, max_runs(sh.max_nch));
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((level_merge_kernel<VT, DP, SPW>), dim3((unsigned)items, 1, nq),
-                       dim3(64 * kMergeWaves), 0, st, p + q0, s);
+    hipLaunchKernelGGL((level_merge_kernel<VT, DP>), dim3((unsigned)items, 1, nq), dim3(64 * kMergeWaves), 0, st,
+                       p + q0, s);
   }
 }
 
-template <typename VT, int DP>
-static void merge_spw(const ProblemDev *p, const LaunchShape &sh, int s, int spw, hipStream_t st) {
-  if (spw <= 1) merge_go<VT, DP, 1>(p, sh, s, st);
-  else if (spw <= 2) merge_go<VT, DP, 2>(p, sh, s, st);
-  else merge_go<VT, DP, 4>(p, sh, s, st);
-}
-
 hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s,
-                              int spw, hipStream_t st) {
-#define GO(B, T)                                                  \
-  if (bits == B) {                                                \
-    if (DP == 8) merge_spw<T, 8>(p, sh, s, spw, st);              \
-    else if (DP == 16) merge_spw<T, 16>(p, sh, s, spw, st);       \
-    else if (DP == 32) merge_spw<T, 32>(p, sh, s, spw, st);       \
-    else merge_spw<T, 64>(p, sh, s, spw, st);                     \
+                              hipStream_t st) {
+#define GO(B, T)                                             \
+  if (bits == B) {                                           \
+    if (DP == 8) merge_go<T, 8>(p, sh, s, st);               \
+    else if (DP == 16) merge_go<T, 16>(p, sh, s, st);        \
+    else if (DP == 32) merge_go<T, 32>(p, sh, s, st);        \
+    else merge_go<T, 64>(p, sh, s, st);                      \
   }
   GO(32, uint32_t)
   GO(64, uint64_t)
