@@ -135,16 +135,22 @@ def make_workload(name):
     return probs, label
 
 
-def run_workload(name, steps, warmup, wide=False):
-    """Times `steps` solve+traceback passes of one workload; returns the measurements."""
+def run_workload(name, steps, warmup, wide=False, algo="auto"):
+    """Times `steps` solve+traceback passes of one workload; returns the measurements.  algo: "auto"
+    (the library's choice: stage times recomputed inside the level kernel where that applies),
+    "table" (the level kernel reads the stage-time table), "recompute"."""
     import torch
     from paper_2103_16063_amd import binding as B
     from paper_2103_16063_amd import synth
 
     probs, label = make_workload(name)
     U = sum(updates(p["time_ns"].shape[0], p["n_devices"], p["max_stages"]) for p in probs)
-    sess = B.Session(synth.concat_batch(probs), max_total_time_ns=(1 << 60) if wide else B.NARROW_MAX_TOTAL_TIME)
+    algo_id = {"auto": B.ALGO_AUTO, "table": B.ALGO_MERGE, "recompute": B.ALGO_RECOMPUTE}[algo]
+    sess = B.Session(synth.concat_batch(probs), algo=algo_id,
+                     max_total_time_ns=(1 << 60) if wide else B.NARROW_MAX_TOTAL_TIME)
     esize = 8 if wide else ESIZE
+    split = name.endswith("split")
+    DP_of = lambda D: 1 << max(3, int(D - 1).bit_length())
 
     def step():
         sess.solve()
@@ -192,14 +198,18 @@ def run_workload(name, steps, warmup, wide=False):
     launches = max(int(launches), 1)
     per_launch_ms = phase[1] / launches
     # ---- the method's own work in the level phase (not timed): from the exports of this solve ----
-    split = name.endswith("split")
+    rc, info = B.rannc_dp_solve_info(sess.h)   # which level kernel each device-count class ran
+    assert rc == B.OK
+    kernel_of = {8 << k: info.level_kernel[k] for k in range(4)}
+    recompute_any = any(kernel_of[DP_of(p["n_devices"])] == B.KERNEL_MERGE_RECOMPUTE for p in probs)
     tot = {"entries": 0, "unit_entries": 0, "stages": 0, "units": 0, "rows_bytes": 0, "cells_bytes": 0,
-           "cands": 0, "valu": 0}
+           "cands": 0, "valu": 0, "table_bytes": 0, "table_bytes_strict": 0}
     dense_bytes = 0
     for q, p in enumerate(probs):
         N, D = p["time_ns"].shape[0], p["n_devices"]
         S_eff = min(p["max_stages"], N, D)
-        DP = 1 << max(3, int(D - 1).bit_length())
+        DP = DP_of(D)
+        recompute = kernel_of[DP] == B.KERNEL_MERGE_RECOMPUTE
         dense_bytes += (S_eff - 1) * level_bytes(N, D, esize)
         for lv in method_work(sess, q, N, D, S_eff, esize, split):
             tot["entries"] += lv["entries"]
@@ -208,24 +218,32 @@ def run_workload(name, steps, warmup, wide=False):
             tot["units"] += lv["units"]
             tot["rows_bytes"] += lv["rows"] * D * esize
             tot["cells_bytes"] += lv["cells"] * esize
+            # stage-time table bytes the level has to read (none where the times are recomputed: then one
+            # fits-in-memory byte per stage)
+            tot["table_bytes"] += 64 * lv["units"] if recompute else esize * lv["unit_entries"]
+            tot["table_bytes_strict"] += lv["stages"] if recompute else esize * lv["entries"]
             tot["cands"] += lv["cands"]
-            tot["valu"] += lv["stages"] * merge_valu_per_stage(DP)
+            # sorted merge per stage; when the stage times are recomputed, two more instructions for
+            # each of the D-s+1 replica counts the level can use
+            tot["valu"] += lv["stages"] * merge_valu_per_stage(DP) + (2 * lv["entries"] if recompute else 0)
     sess.close()
     n_tables = 2 if split else 1                  # the split objective reads a backward table too
     n_vals = 3 if split else 1                    # ... and carries two maxima beside each value
     v_bytes = (tot["rows_bytes"] + tot["cells_bytes"]) * n_vals
-    own_bytes = esize * tot["unit_entries"] * n_tables + v_bytes
-    strict_bytes = esize * tot["entries"] * n_tables + v_bytes
+    own_bytes = tot["table_bytes"] * n_tables + v_bytes
+    strict_bytes = tot["table_bytes_strict"] * n_tables + v_bytes
+    recompute = recompute_any
     t_levels = phase[1] * 1e-3
     hbm = own_bytes / t_levels / 1e9
-    traffic, traffic_src = (None, None) if wide else PMC_TRAFFIC.get(name, (None, None))
+    traffic, traffic_src = (None, None) if (wide or recompute) else PMC_TRAFFIC.get(name, (None, None))
     if split:
         useful = tot["cands"] * SPLIT_VALU_PER_UPDATE
         alu = useful / t_levels / 1e12
         kernel = "level_split_fast_kernel + split_finalize_kernel (%d-bit values)" % (8 * esize)
     else:
         alu = tot["valu"] / t_levels / 1e12
-        kernel = "level_merge_kernel (%d-bit values)" % (8 * esize)
+        kernel = "level_merge_kernel (%d-bit values, %s)" % (
+            8 * esize, "stage times recomputed" if recompute else "stage times read from their table")
     frac_hbm, frac_valu = hbm / HBM_PEAK_GBS, alu / ALU_PEAK_TLANEOPS
     bound = "alu" if frac_valu > frac_hbm else "hbm"
     roof = {"bound": bound, "kernel": kernel,
@@ -247,7 +265,7 @@ def run_workload(name, steps, warmup, wide=False):
                     "per level launch, over the measured launch time; stage granularity counts only the "
                     "visited stages' own entries; the dense equivalent counts every (i,j,r) and is not "
                     "compared with a peak; traffic is the rocprofv3 counter figure of the named summary"}
-    return {"probs": probs, "label": label, "U": U, "ms_per_step": wall / steps * 1e3,
+    return {"probs": probs, "label": label, "U": U, "ms_per_step": wall / steps * 1e3, "recompute": recompute,
             "latency_ms": float(np.median(lat)) * 1e3,
             "phase": phase, "launches": launches, "res": res, "roofline": roof}
 
@@ -322,6 +340,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true",
                     help="skip the extra roofline_dense measurement (c4 workload only)")
+    ap.add_argument("--algo", default="auto", choices=["auto", "table", "recompute"],
+                    help="level kernel: the library's choice, stage times read from their table, or recomputed")
     ap.add_argument("--no-wide", action="store_true",
                     help="skip the extra measurement of the same workload on 64-bit tables")
     ap.add_argument("--wide", action="store_true",
@@ -354,7 +374,7 @@ def main():
         print(json.dumps(run_form_stage(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)),
               flush=True)
         return
-    m = run_workload(args.workload, args.steps, args.warmup, args.wide)
+    m = run_workload(args.workload, args.steps, args.warmup, args.wide, args.algo)
     probs, res, phase = m["probs"], m["res"], m["phase"]
     out = {
         "metric": "DP cell-updates/sec (definitional count, whole solve incl. table build and traceback)",
@@ -372,11 +392,18 @@ def main():
         "latency_to_host_plan_ms": m["latency_ms"],
         "roofline": m["roofline"],
     }
+    out["level_kernel"] = "stage times recomputed" if m["recompute"] else "stage times read from their table"
+    if m["recompute"] and args.algo == "auto" and not args.no_dense:
+        # the same workload with the level kernel that reads the stage-time table (HBM-bound form)
+        tm = run_workload(args.workload, max(5, args.steps // 3), 2, algo="table")
+        assert int(tm["res"]["opt"][0]) == int(res["opt"][0])
+        out["table_mode"] = {"ms_per_step": tm["ms_per_step"], "dp_levels_ms": float(tm["phase"][1]),
+                             "prefix_and_tables_ms": float(tm["phase"][0]), "roofline": tm["roofline"]}
     if args.workload == "c4" and not args.no_dense and not args.wide:
-        # the same kernel where nothing can be pruned (every stage fits): the streaming case
-        dm = run_workload("c4dense", max(5, args.steps // 5), 2)
-        out["roofline_dense"] = dict(dm["roofline"], workload=dm["label"],
-                                     ms_per_step=dm["ms_per_step"])
+        # the same kernels where nothing can be pruned (every stage fits): the streaming case
+        for key, algo in (("roofline_dense", "table"), ("roofline_dense_recompute", "recompute")):
+            dm = run_workload("c4dense", max(5, args.steps // 5), 2, algo=algo)
+            out[key] = dict(dm["roofline"], workload=dm["label"], ms_per_step=dm["ms_per_step"])
     if not args.no_wide and not args.wide and not args.workload.endswith("split"):
         # the same workload on a handle with 64-bit tables (the path inputs with totals above
         # 2^32 - 2 ns take, e.g. the outer driver at the paper's cluster shape)

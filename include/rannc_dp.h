@@ -67,9 +67,16 @@ typedef enum {
 #define RANNC_DP_MAX_DEVICES 64   /* largest D the kernels are built for */
 
 /* Level kernels (Sec. III-C recurrence, one stage count s per launch). */
-#define RANNC_DP_ALGO_AUTO 0
-#define RANNC_DP_ALGO_MERGE 1 /* sorted-merge form of the (min,max) convolution over d' */
-#define RANNC_DP_ALGO_SCAN 2  /* literal scan of every (i, d') candidate per cell */
+#define RANNC_DP_ALGO_AUTO 0      /* the fastest applicable of the following */
+#define RANNC_DP_ALGO_MERGE 1     /* sorted-merge form of the (min,max) convolution over d'; the stage
+                                     times h(i,j,r) are read from the table that solve builds */
+#define RANNC_DP_ALGO_SCAN 2      /* literal scan of every (i, d') candidate per cell (reads the table) */
+#define RANNC_DP_ALGO_RECOMPUTE 3 /* sorted-merge form with h(i,j,r) recomputed from the prefix sums
+                                     inside the level kernel: solve then builds only the fits-in-memory
+                                     table, and the stage-time table is built when rannc_dp_read_table
+                                     asks for it.  Applies to 32-bit handles (max_total_time_ns up to
+                                     4294967294) and batches without a communication term; elsewhere
+                                     this value behaves as RANNC_DP_ALGO_MERGE.  Same results. */
 
 /* Handle flag: run Algorithm 1 as printed, with separate forward and backward block times.  A
  * cell of the search then keeps, besides its value, the largest forward and the largest backward
@@ -97,6 +104,19 @@ typedef struct {
                                 traffic); above it 64-bit.  Results are the same int64. */
   int32_t algo;              /* RANNC_DP_ALGO_* */
   int32_t flags;             /* RANNC_DP_FLAG_* or 0 */
+  /* Tuning; 0 everywhere = the library's own choices.  None of them changes a result. */
+  int32_t rows_per_wave;     /* sorted-merge level kernel: predecessor rows a wave takes one after the
+                                other before the workgroup folds (1, 2, 4 or 8); 0 = by the size of the
+                                launch.  Environment override: RANNC_DP_ROWS_PER_WAVE */
+  int32_t one_launch_small;  /* searches of at most 128 blocks can run as ONE launch with one workgroup
+                                per search: 0 = where it measured faster (few rows x levels, or
+                                classes of >= 256 searches with D <= 16 or N <= 64), 1 = never,
+                                2 = whenever N <= 128.  Environment override: RANNC_DP_FUSED_SMALL
+                                (0 = never, 1 = where faster, 2 = always) */
+  int32_t single_stream;     /* 0 = the device-count classes of a batch run on streams of the handle,
+                                1 = everything on the caller's stream.  Environment override:
+                                RANNC_DP_STREAMS (0 = caller's stream only) */
+  int32_t reserved;          /* must be 0 */
 } rannc_dp_limits_t;
 
 /* A batch of Q independent searches (Algorithm 2 of Sec. III-C issues many form_stage_dp
@@ -309,6 +329,21 @@ RANNC_DP_API int rannc_dp_compact_static(void *hip_stream, int32_t n_groups, int
 #define RANNC_DP_TABLE_MAX_BWD 7
 RANNC_DP_API int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, size_t bytes,
                         void *hip_stream);
+
+/* Which level kernel the last solve ran for each device-count class (D <= 8, 16, 32, 64) of its batch. */
+#define RANNC_DP_KERNEL_NONE 0            /* no search of that class in the batch */
+#define RANNC_DP_KERNEL_MERGE_TABLE 1     /* sorted merge, stage times read from their table */
+#define RANNC_DP_KERNEL_MERGE_RECOMPUTE 2 /* sorted merge, stage times recomputed */
+#define RANNC_DP_KERNEL_ONE_LAUNCH 3      /* whole search in one launch, one workgroup per search */
+#define RANNC_DP_KERNEL_SCAN 4            /* literal scan */
+#define RANNC_DP_KERNEL_SPLIT 5           /* split objective, packed winners */
+#define RANNC_DP_KERNEL_SPLIT_SCAN 6      /* split objective, literal scan */
+typedef struct {
+  int32_t n_problems[4];
+  int32_t level_kernel[4];  /* RANNC_DP_KERNEL_* */
+} rannc_dp_solve_info_t;
+/* RANNC_DP_BAD_STATE before the first successful solve. */
+RANNC_DP_API int rannc_dp_solve_info(rannc_dp_t *h, rannc_dp_solve_info_t *out);
 
 /* Waits for the handle's own streams, frees host state, events and streams; the workspace remains
  * the caller's.  NULL is allowed. */

@@ -21,7 +21,7 @@ INT64_MAX = (1 << 63) - 1
 OK, INVALID_ARG, LIMIT_EXCEEDED, WORKSPACE_TOO_SMALL, OVERFLOW, HIP_ERROR, BAD_STATE, NO_HOST_MEMORY = \
     0, -1, -2, -3, -4, -5, -6, -7
 PROBLEM_OK, PROBLEM_NEGATIVE_INPUT, PROBLEM_SUM_OVERFLOW, PROBLEM_TIME_TOO_LARGE = 0, 1, 2, 3
-ALGO_AUTO, ALGO_MERGE, ALGO_SCAN = 0, 1, 2
+ALGO_AUTO, ALGO_MERGE, ALGO_SCAN, ALGO_RECOMPUTE = 0, 1, 2, 3
 TABLE_COST, TABLE_FIT, TABLE_V, TABLE_ARG_I, TABLE_ARG_D = 0, 1, 2, 3, 4
 TABLE_COST_BWD, TABLE_MAX_FWD, TABLE_MAX_BWD = 5, 6, 7
 FLAG_SPLIT_OBJECTIVE = 1
@@ -33,13 +33,24 @@ EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp
            "rannc_dp_strerror", "rannc_dp_set_timing", "rannc_dp_get_timing",
            "rannc_dp_traceback_at", "rannc_dp_level_values", "rannc_dp_form_stage_problems",
            "rannc_dp_form_stage_scratch_bytes", "rannc_dp_form_stage",
-           "rannc_dp_compact_workspace_bytes", "rannc_dp_compact", "rannc_dp_compact_static"]
+           "rannc_dp_compact_workspace_bytes", "rannc_dp_compact", "rannc_dp_compact_static",
+           "rannc_dp_solve_info"]
 
 
 class Limits(C.Structure):
     _fields_ = [("max_problems", C.c_int32), ("max_blocks", C.c_int32),
                 ("max_devices", C.c_int32), ("max_stages", C.c_int32),
-                ("max_total_time_ns", C.c_int64), ("algo", C.c_int32), ("flags", C.c_int32)]
+                ("max_total_time_ns", C.c_int64), ("algo", C.c_int32), ("flags", C.c_int32),
+                ("rows_per_wave", C.c_int32), ("one_launch_small", C.c_int32),
+                ("single_stream", C.c_int32), ("reserved", C.c_int32)]
+
+
+class SolveInfo(C.Structure):
+    _fields_ = [("n_problems", C.c_int32 * 4), ("level_kernel", C.c_int32 * 4)]
+
+
+KERNEL_NONE, KERNEL_MERGE_TABLE, KERNEL_MERGE_RECOMPUTE, KERNEL_ONE_LAUNCH, KERNEL_SCAN, KERNEL_SPLIT, \
+    KERNEL_SPLIT_SCAN = range(7)
 
 
 class Batch(C.Structure):
@@ -115,6 +126,8 @@ def lib():
         L.rannc_dp_form_stage.argtypes = [vp, C.POINTER(FormStageIn), vp, vp, sz,
                                           C.POINTER(FormStageOut), vp, vp, C.c_int32]
         L.rannc_dp_form_stage.restype = C.c_int
+        L.rannc_dp_solve_info.argtypes = [vp, C.POINTER(SolveInfo)]
+        L.rannc_dp_solve_info.restype = C.c_int
         L.rannc_dp_compact_workspace_bytes.argtypes = [C.c_int32]
         L.rannc_dp_compact_workspace_bytes.restype = sz
         L.rannc_dp_compact.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int64, vp, vp, vp, vp, sz, vp, vp, vp,
@@ -143,9 +156,18 @@ def _ptr(x):
 
 
 def make_limits(max_problems, max_blocks, max_devices, max_stages,
-                max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO, flags=0) -> Limits:
+                max_total_time_ns=NARROW_MAX_TOTAL_TIME, algo=ALGO_AUTO, flags=0, rows_per_wave=0,
+                one_launch_small=0, single_stream=0) -> Limits:
     return Limits(int(max_problems), int(max_blocks), int(max_devices), int(max_stages),
-                  int(max_total_time_ns), int(algo), int(flags))
+                  int(max_total_time_ns), int(algo), int(flags), int(rows_per_wave), int(one_launch_small),
+                  int(single_stream), 0)
+
+
+def rannc_dp_solve_info(handle):
+    """Returns (status, SolveInfo)."""
+    info = SolveInfo()
+    rc = lib().rannc_dp_solve_info(handle, C.byref(info))
+    return rc, info
 
 
 class HostBatch:
@@ -295,7 +317,7 @@ def rannc_dp_get_timing(handle):
 # ---------------------------------------------------------------------------------------------
 class Session:
     def __init__(self, batch_np: dict, *, algo=ALGO_AUTO, max_total_time_ns=NARROW_MAX_TOTAL_TIME,
-                 device="cuda:0", exact_workspace=True):
+                 device="cuda:0", exact_workspace=True, rows_per_wave=0, one_launch_small=0, single_stream=0):
         import torch
         self.torch = torch
         self.dev = torch.device(device)
@@ -306,7 +328,8 @@ class Session:
         self.split = "time_bwd_ns" in b
         self.limits = make_limits(self.Q, int(b["n_blocks"].max()), int(b["n_devices"].max()),
                                   int(self.S_eff.max()), max_total_time_ns, algo,
-                                  FLAG_SPLIT_OBJECTIVE if self.split else 0)
+                                  FLAG_SPLIT_OBJECTIVE if self.split else 0, rows_per_wave, one_launch_small,
+                                  single_stream)
         self.d_in = [torch.from_numpy(np.ascontiguousarray(b[k], dtype=np.int64)).to(self.dev)
                      for k in ("time_ns", "param_bytes", "act_bytes")]
         self.d_bwd = None

@@ -58,7 +58,9 @@ bool limits_ok(const rannc_dp_limits_t *l) {
   return l && l->max_problems >= 1 && l->max_blocks >= 1 && l->max_blocks <= 65535 &&
          l->max_devices >= 1 && l->max_devices <= RANNC_DP_MAX_DEVICES && l->max_stages >= 1 &&
          l->max_total_time_ns >= 0 && (l->flags & ~RANNC_DP_FLAG_SPLIT_OBJECTIVE) == 0 && l->algo >= RANNC_DP_ALGO_AUTO &&
-         l->algo <= RANNC_DP_ALGO_SCAN;
+         l->algo <= RANNC_DP_ALGO_RECOMPUTE && l->rows_per_wave >= 0 && l->rows_per_wave <= 8 &&
+         l->one_launch_small >= 0 && l->one_launch_small <= 2 && l->single_stream >= 0 && l->single_stream <= 1 &&
+         l->reserved == 0;
 }
 
 bool split_of(const rannc_dp_limits_t *l) { return (l->flags & RANNC_DP_FLAG_SPLIT_OBJECTIVE) != 0; }
@@ -124,8 +126,9 @@ struct rannc_dp {
   hipStream_t aux[3];
   hipEvent_t fork_ev, join_ev[3];
   bool multi_stream;
+  rannc_dp_solve_info_t info;  // of the last successful solve
+  bool no_times[4];  // per device-count class of the last solve: the stage-time table was not built
   int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
-  int tune_rows8, tune_rows16;  // > 0: thresholds of that heuristic (experiments)
   int fused_small;  // one-launch kernel for classes of small searches: 1 = where it pays (default),
                     // 0 = never, 2 = whenever N <= 128 (RANNC_DP_FUSED_SMALL)
 };
@@ -189,17 +192,15 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->timing = false;
   h->ev_valid = false;
   h->level_launches = 0;
-  h->tune_spw = 0;
+  h->tune_spw = l->rows_per_wave;
+  for (int k = 0; k < 4; ++k) h->no_times[k] = false;
   if (const char *e = std::getenv("RANNC_DP_ROWS_PER_WAVE")) h->tune_spw = std::atoi(e);
-  h->tune_rows8 = h->tune_rows16 = 0;
-  if (const char *e = std::getenv("RANNC_DP_ROWS8_FROM")) h->tune_rows8 = std::atoi(e);
-  if (const char *e = std::getenv("RANNC_DP_ROWS16_FROM")) h->tune_rows16 = std::atoi(e);
-  h->fused_small = 1;
+  h->fused_small = l->one_launch_small == 1 ? 0 : l->one_launch_small == 2 ? 2 : 1;
   if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
   h->fs_pin = nullptr;
   h->fs_pin_bytes = 0;
-  h->multi_stream = true;
+  h->multi_stream = l->single_stream == 0;
   if (const char *e = std::getenv("RANNC_DP_STREAMS")) h->multi_stream = std::atoi(e) != 0;
   int made_staging = 0, made_ev_s = 0, made_ev = 0, made_aux = 0, made_join = 0;
   bool made_fork = false;
@@ -393,6 +394,15 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   // handles, 64-bit ones up to 2^42 - 2 ns); RANNC_DP_ALGO_SCAN and larger time bounds take the
   // literal one
   const bool split_fast = split && !scan && packed_of(&h->lim);
+  // stage times recomputed inside the level kernel instead of read from their table: where it
+  // applies, on request, or (AUTO) for the classes whose launches are large enough to be bound by
+  // throughput
+  const bool can_recompute = !scan && !split && h->bits == 32 && !b->cut_bytes;
+  bool recompute_cls[4];
+  for (int k = 0; k < 4; ++k)
+    recompute_cls[k] = can_recompute && (h->lim.algo == RANNC_DP_ALGO_RECOMPUTE ||
+                                         (h->lim.algo == RANNC_DP_ALGO_AUTO &&
+                                          rannc::merge_launch_rows(shape[k]) >= rannc::kRecomputeRowsFrom));
   bool ok = true;
   const bool timing = h->timing;
   h->ev_valid = false;
@@ -414,6 +424,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     }
   }
   bool fused[4] = {false, false, false, false};
+  int merge_items[4] = {1, 1, 1, 1};
   for (int k = 0; k < 4 && ok; ++k) {
     const LaunchShape &sh = shape[k];
     if (!sh.nprob) continue;
@@ -436,17 +447,18 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     if (fused[k]) continue;
     ok = rannc::launch_prefix(cp, sh.nprob, st) == hipSuccess;
     ok = ok && rannc::launch_fill(cp, sh.nprob, st) == hipSuccess;
-    ok = ok && rannc::launch_build(cp, sh, h->bits, kClasses[k], st) == hipSuccess;
+    ok = ok && rannc::launch_build(cp, sh, h->bits, kClasses[k], recompute_cls[k] ? 1 : 3, st) == hipSuccess;
     ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
     if (split) {
       ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
-      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), st) == hipSuccess;
+      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, st) == hipSuccess;
     }
     if (scan || split) continue;
     // Rows per wave of the level kernel: chosen on the device from the size of the windows unless
     // the handle fixes it (1, 2 or 4).
-    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), st, h->tune_rows8,
-                                  h->tune_rows16) == hipSuccess;
+    merge_items[k] = rannc::merge_grid_items(sh, rannc::merge_rows_per_item(h->tune_spw));
+    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), merge_items[k], st) ==
+                   hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;
@@ -473,7 +485,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
         ok = rannc::launch_level_scan(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;
       else
-        ok = rannc::launch_level_merge(dp + cls_start[k], sh, h->bits, kClasses[k], s, st) == hipSuccess;
+        ok = rannc::launch_level_merge(dp + cls_start[k], sh, h->bits, kClasses[k], s, recompute_cls[k], merge_items[k],
+                                       st) == hipSuccess;
       h->level_launches++;
     }
   }
@@ -493,10 +506,28 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     return RANNC_DP_HIP_ERROR;
   }
   h->ev_valid = timing;
+  for (int k = 0; k < 4; ++k) {
+    h->no_times[k] = recompute_cls[k] && !fused[k];
+    h->info.n_problems[k] = shape[k].nprob;
+    h->info.level_kernel[k] = !shape[k].nprob ? RANNC_DP_KERNEL_NONE
+                              : fused[k]      ? RANNC_DP_KERNEL_ONE_LAUNCH
+                              : split_fast    ? RANNC_DP_KERNEL_SPLIT
+                              : split         ? RANNC_DP_KERNEL_SPLIT_SCAN
+                              : scan          ? RANNC_DP_KERNEL_SCAN
+                              : recompute_cls[k] ? RANNC_DP_KERNEL_MERGE_RECOMPUTE
+                                                 : RANNC_DP_KERNEL_MERGE_TABLE;
+  }
   h->host_probs.swap(probs);
   h->pos_of.swap(pos_of);
   h->Q = Q;
   h->solved = true;
+  return RANNC_DP_OK;
+}
+
+int rannc_dp_solve_info(rannc_dp_t *h, rannc_dp_solve_info_t *out) {
+  if (!h || !out) return RANNC_DP_INVALID_ARG;
+  if (!h->solved) return RANNC_DP_BAD_STATE;
+  *out = h->info;
   return RANNC_DP_OK;
 }
 
@@ -876,7 +907,16 @@ int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, void *d_dst, 
   }
   if (bytes != want) return RANNC_DP_INVALID_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
-  bool ok = rannc::launch_export(h->d_probs + pos, which, p.bits, d_dst, st) == hipSuccess;
+  bool ok = true;
+  int cls = 0;
+  while (cls < 3 && p.DP != (8 << cls)) ++cls;
+  if (h->no_times[cls] && (which == RANNC_DP_TABLE_COST || which == RANNC_DP_TABLE_ARG_I || which == RANNC_DP_TABLE_ARG_D)) {
+    // the solve recomputed the stage times instead of tabulating them: tabulate this search's now
+    LaunchShape one;
+    one.nprob = 1; one.max_N = p.N; one.max_nch = p.nch; one.max_D = p.D; one.max_S_eff = p.S_eff;
+    ok = rannc::launch_build(h->d_probs + pos, one, p.bits, p.DP, 2, st) == hipSuccess;
+  }
+  ok = ok && rannc::launch_export(h->d_probs + pos, which, p.bits, d_dst, st) == hipSuccess;
   if (which == RANNC_DP_TABLE_ARG_I || which == RANNC_DP_TABLE_ARG_D) {
     LaunchShape sh;
     sh.nprob = 1; sh.max_N = p.N; sh.max_nch = p.nch; sh.max_D = p.D; sh.max_S_eff = p.S_eff;

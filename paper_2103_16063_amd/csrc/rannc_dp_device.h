@@ -52,14 +52,6 @@ static constexpr int kNoRow = 0x7fffffff;
 
 // Split-objective level kernel: waves per workgroup, and the smallest work item the adaptive work
 // list makes for it (rows of one chunk); the work-list kernel needs both.
-// Sorted-merge level kernel: waves per work item; a wave takes 1, 2 or 4 of the item's rows.  The
-// work list makes items of 16 rows when all windows of a search together hold at least
-// kMergeRows16From rows, of 8 from kMergeRows8From, of 4 below.
-constexpr int kMergeWaves = 4;
-constexpr int kMergeMinRows = 4;
-constexpr int kMergeRows8From = 6144;
-constexpr int kMergeRows16From = 16384;
-
 constexpr int kSplitWaves = 8;
 constexpr int kSplitMinRows = 4;  // smallest work item the adaptive work list makes (rows of one chunk)
 

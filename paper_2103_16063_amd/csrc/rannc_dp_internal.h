@@ -39,13 +39,21 @@ __host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
 }
 
 // upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
-// groups of at least 8, or into groups of 4 while all windows together hold fewer than 8192 rows
-// (the split-objective kernel) or 6144 rows (the sorted-merge kernel)
-__host__ __device__ inline int64_t max_runs(int nch) {
-  const int64_t by8 = 4LL * nch * (nch + 1), by4 = 2 * by8, few = 2048 + nch;
-  const int64_t small = by4 < few ? by4 : few;
-  return by8 > small ? by8 : small;
-}
+// groups of at least 4 rows (chunk c has at most 64(c+1) rows)
+__host__ __device__ inline int64_t max_runs(int nch) { return 8LL * nch * (nch + 1); }
+
+// Sorted-merge level kernel: waves per work item; a wave takes 1, 2, 4, ... of the item's rows.  The
+// host sizes the grid for items of 16 rows when the searches of a launch together hold at least
+// kMergeRows16From rows (unpruned), of 8 from kMergeRows8From, of 4 below.
+constexpr int kMergeWaves = 4;
+constexpr int kMergeMinRows = 4;
+constexpr int kMergeRows8From = 6144;
+constexpr int kMergeRows16From = 16384;
+// From this many rows in a launch on, a 32-bit search without a communication term has its stage
+// times recomputed in the level kernel (RANNC_DP_ALGO_AUTO): the launch then runs many rounds of
+// workgroups and is bound by throughput, where recomputing beats reading the table; below, the
+// level is a single round bound by latency, where the shorter table kernel wins.
+constexpr int kRecomputeRowsFrom = 32768;
 
 __host__ __device__ inline int dp_class(int D) { return D <= 8 ? 8 : D <= 16 ? 16 : D <= 32 ? 32 : 64; }
 
@@ -93,13 +101,21 @@ struct LaunchShape {
 // `probs` points at the first ProblemDev of the launch; problems of one launch are contiguous.
 hipError_t launch_prefix(const ProblemDev *probs, int Q, hipStream_t st);
 hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st);
-hipError_t launch_build(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, hipStream_t st);
+// parts: 1 = fits-in-memory tables (rmin, ufit) and level 1 of V, 2 = the stage-time table, 3 = both
+hipError_t launch_build(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int parts, hipStream_t st);
 hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStream_t st);
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st, int rows8_from = 0,
-                       int rows16_from = 0);
+// rows_per_item: > 0 fixed, 0 chosen on the device for the split-objective kernel, -1 for the
+// sorted-merge kernel (then the smallest item size whose item count fits max_items)
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, hipStream_t st);
 int merge_rows_per_item(int rows_per_wave);
+int merge_grid_items(const LaunchShape &sh, int rows_per_item);
+// rows of the searches of a launch if nothing is pruned (every chunk c holds rows 0 .. 64c+63)
+int64_t merge_launch_rows(const LaunchShape &sh);
+// recompute: the level kernel computes the stage times from the prefix sums instead of reading
+// their table (32-bit values only)
+// items: merge_grid_items of the launch, the value launch_runs was given
 hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
-                              hipStream_t st);
+                              bool recompute, int items, hipStream_t st);
 // whole search of problems with N <= small_max_blocks() in one launch, one workgroup each
 int small_max_blocks();
 hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, int64_t *d_opt,

@@ -148,7 +148,7 @@ __device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RA
       h += qc + (VT)(qc * (VT)r != cj);
     }
     const VT v = (r >= rmin) ? h : Lim<VT>::inf;
-    crow[(r - 1) * 64] = v;
+    if (crow) crow[(r - 1) * 64] = v;
     if (v1) v1[r - 1] = v;
     if (lds1) lds1[r - 1] = v;
   }
@@ -157,11 +157,14 @@ __device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RA
 // One unit (row i, chunk c) of the tables, by one wave.  T, P, A, Cc may live in global memory or in
 // LDS; Cc (per-cut send time at one replica, Cc[N] = 0) is null when there is no communication
 // term.  Returns whether any stage of the unit fits.  If lds_level1 is given, row 0's entries
-// (= level 1 of V) are also written there with row stride ls.
+// (= level 1 of V) are also written there with row stride ls.  with_times = false: only the
+// fits-in-memory part (rmin, ufit) and level 1 of V are written, for searches whose level kernel
+// recomputes the stage times (level 1 already written: only the stage-time rows, for an export).
 template <typename VT, int DP>
 __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *T, const int64_t *P,
                                            const int64_t *A, const int64_t *Cc, int i, int c, int lane,
-                                           VT *lds_level1, int ls, const int64_t *TBp = nullptr) {
+                                           VT *lds_level1, int ls, const int64_t *TBp = nullptr,
+                                           const bool with_times = true, const bool with_level1 = true) {
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
@@ -188,27 +191,32 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
   // A unit in which no stage fits for any r is never read (every reader consults ufit or rmin
   // first): only those are written.  Row 0 also carries level 1 and is always written.
   if (!unit_fits && i != 0) return unit_fits;
-  VT RANNC_GLOBAL *crow = gptr((VT *)pr.cost) + u * 64 * D + lane;
-  VT RANNC_GLOBAL *v1 = gptr((VT *)pr.V) + (int64_t)j * DP;
+  if (!with_times && i != 0) return unit_fits;
+  VT RANNC_GLOBAL *crow = with_times ? gptr((VT *)pr.cost) + u * 64 * D + lane : nullptr;
+  VT RANNC_GLOBAL *v1 = (i == 0 && with_level1) ? gptr((VT *)pr.V) + (int64_t)j * DP : nullptr;
   const VT tij = (VT)Tij;
   if (Cc)  // wave-uniform: with the stage's own send time at one replica (0 for j = N)
-    build_rows<VT, DP, true>(tij, (VT)Cc[j], rmin, D, crow, i == 0 ? v1 : nullptr,
+    build_rows<VT, DP, true>(tij, (VT)Cc[j], rmin, D, crow, v1,
                              (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
   else
-    build_rows<VT, DP, false>(tij, (VT)0, rmin, D, crow, i == 0 ? v1 : nullptr,
+    build_rows<VT, DP, false>(tij, (VT)0, rmin, D, crow, v1,
                               (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
-  if (TBp)  // split objective: the backward times get a table of their own (never a send time)
+  if (TBp && with_times)  // split objective: the backward times get a table of their own (never a send time)
     build_rows<VT, DP, false>((VT)(TBp[j] - TBp[i]), (VT)0, rmin, D,
                               gptr((VT *)pr.costb) + u * 64 * D + lane, nullptr, nullptr);
   return unit_fits;
 }
 
+// parts: 1 = fits-in-memory tables and level 1 of V only, 3 = those and the stage-time table,
+// 2 = the stage-time table alone (added later to a search that was solved without it)
 template <typename VT, int DP>
-__global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs) {
+__global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs,
+                                                                 const int parts) {
   const ProblemDev &pr = probs[blockIdx.z];
   const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
   if (i >= pr.N || c >= pr.nch || c < (i >> 6)) return;
-  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, pr.C, i, c, threadIdx.x & 63, nullptr, 0, pr.TB);
+  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, pr.C, i, c, threadIdx.x & 63, nullptr, 0, pr.TB,
+                           (parts & 2) != 0, (parts & 1) != 0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -236,34 +244,45 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // Work list of the level kernels: the rows wlo[c] .. min(64c+63, N-1) of every chunk, cut into
 // items of consecutive rows, listed chunk by chunk.  A compact list keeps the workgroups that have
 // work at the front of the grid.  The number of rows of an item travels in the top bits of its
-// descriptor: (rows - 1) << 26 | c << 16 | first row.  rows > 0: items of that many rows;
-// rows = 0 / -1: chosen here from the size of all windows together, for the split-objective /
-// the sorted-merge level kernel: large items where there is enough work to fill the device with
-// them (fewer folds and atomics per row), small ones otherwise (more workgroups, shorter critical
-// path).  The sorted-merge kernel counts the rows of all `batch` searches of the launch.  One
-// workgroup per problem.
+// descriptor: (rows - 1) << 26 | c << 16 | first row.  rows > 0: items of that many rows.
+// rows = 0 (split-objective level kernel): 16, 8 or 4 rows, from the size of all windows together.
+// rows = -1 (sorted-merge level kernel): the smallest of 4, 8, 16, 32, 64 rows whose item count
+// fits max_items, the grid the host launches (sized for the rows of an unpruned search: small
+// items, i.e. many workgroups and a short critical path, when pruning leaves few rows; large ones,
+// i.e. fewer folds and atomics per row, when the launch is full anyway; and never a workgroup
+// without an item in a launch over many searches).  One workgroup per problem.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int batch,
-                                                    int rows8_from, int rows16_from) {
+__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int max_items) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
-  __shared__ int total_rows;
+  __shared__ int total_rows, count[5];
   const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
   if (rows <= 0) {
+    if (tid < 5) count[tid] = 0;
     if (tid == 0) total_rows = 0;
     __syncthreads();
-    int mine = 0;
+    int mine = 0, cnt[5] = {0, 0, 0, 0, 0};
     for (int c = tid; c < nch; c += 256) {
       const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
-      if (lo <= hi) mine += hi - lo + 1;
+      if (lo <= hi) {
+        mine += hi - lo + 1;
+#pragma unroll
+        for (int k = 0; k < 5; ++k) cnt[k] += (hi - lo + (4 << k)) / (4 << k);
+      }
     }
-    if (mine) atomicAdd(&total_rows, mine);
+    if (mine) {
+      atomicAdd(&total_rows, mine);
+#pragma unroll
+      for (int k = 0; k < 5; ++k) atomicAdd(&count[k], cnt[k]);
+    }
     __syncthreads();
-    // the searches of one launch are alike (one device-count class of one batch): this search's
-    // rows times their number stands for the rows of the whole launch
-    const long long all_rows = (long long)total_rows * batch;
-    if (rows == 0) rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
-    else rows = all_rows >= rows16_from ? 16 : all_rows >= rows8_from ? 8 : kMergeMinRows;
+    if (rows == 0) {
+      rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
+    } else {
+      rows = 64;
+      for (int k = 4; k >= 0; --k)
+        if (count[k] <= max_items) rows = 4 << k;
+    }
   }
   const int tag = (rows - 1) << 26;
   for (int c = tid; c < nch; c += 256) {
@@ -349,9 +368,136 @@ __device__ __forceinline__ void row_merge(VT (&x)[DP], const VT RANNC_GLOBAL *__
   }
 }
 
+// The same for a level kernel that recomputes the stage times instead of reading their table (32-bit
+// values, no communication term): the lane's stage has total time tij, fits from rmn replicas on
+// (255: never, or a lane without work), and c[r] = ceil(tij / r), INF for r < rmn.
+//
+// ceil(x / r) for 0 <= x < 2^32 and odd r <= 63 without an integer division, in double precision:
+//     t = x + (r/2 - 1 + r * 2^-18)            exact (a multiple of 2^-18 below 2^33)
+//     y = t * (1/r) + 1.5 * 2^52               one fused multiply-add
+// t / r = (x + r - 1)/r - 1/2 + 2^-18; the fraction of (x + r - 1)/r is a multiple of 1/r, at most
+// 62/63, and the rounded 1/r puts the product off by less than 2^-21, so t * (1/r) lies strictly
+// between k - 1/2 and k + 1/2 for k = floor((x + r - 1) / r): the addition of 1.5 * 2^52 rounds it to
+// that integer and leaves k in the low word of the sum.  Even replica counts follow from
+// ceil(x / 2r) = ceil(ceil(x / r) / 2): an add and a shift.  Two full-rate instructions per entry.
+// The 32 reciprocals and 1.5 * 2^52 live in vector registers for the whole kernel (as immediate
+// operands they would need one scalar register pair each, which do not exist in that number).
+// The INF below rmn comes from a per-lane bit mask (bit r-1 set for r < rmn), one bit-field extract
+// per entry, folded into the first maximum of the merge together with a[].
+struct DirectConsts {
+  double inv[32];  // 1 / (2k + 1)
+  double magic;    // 1.5 * 2^52
+};
+__device__ __forceinline__ void direct_consts_init(DirectConsts &k) {
+#pragma unroll
+  for (int q = 0; q < 32; ++q) {
+    k.inv[q] = 1.0 / (double)(2 * q + 1);
+    asm("" : "+v"(k.inv[q]));  // a register, not an immediate (not volatile: no memory effects)
+  }
+  k.magic = 0x1.8p52;
+  asm("" : "+v"(k.magic));
+}
+
+// entry r = ODD << SH and the ones it is the parent of
+template <int DP, int NG, int ODD, int SH>
+__device__ __forceinline__ void direct_chain(uint32_t (&x)[DP], const uint32_t RANNC_GLOBAL *__restrict__ arow,
+                                             uint32_t q_odd, int mlo, int mhi) {
+  constexpr int R = ODD << SH, M = R - 1;
+  if constexpr (R <= 8 * NG && R <= DP) {
+    const uint32_t h = SH == 0 ? q_odd : (q_odd + ((1u << SH) - 1u)) >> SH;
+    const uint32_t inf = (uint32_t)__builtin_amdgcn_sbfe(M < 32 ? mlo : mhi, M & 31, 1);  // 0 or 0xFFFFFFFF
+    x[DP - 1 - M] = vmax(vmax(arow[DP - 1 - M], h), inf);
+    direct_chain<DP, NG, ODD, SH + 1>(x, arow, q_odd, mlo, mhi);
+  }
+}
+
+template <int DP, int NG, int K = 0>
+__device__ __forceinline__ void direct_entries(uint32_t (&x)[DP], const uint32_t RANNC_GLOBAL *__restrict__ arow,
+                                               double tf, const DirectConsts &k, int mlo, int mhi) {
+  constexpr int ODD = 2 * K + 1;
+  if constexpr (ODD <= 8 * NG && ODD <= DP) {
+    constexpr double add = (double)ODD / 2.0 - 1.0 + (double)ODD * 0x1p-18;
+    const double y = __builtin_fma(tf + add, k.inv[K], k.magic);
+    direct_chain<DP, NG, ODD, 0>(x, arow, (uint32_t)__double_as_longlong(y), mlo, mhi);
+    direct_entries<DP, NG, K + 1>(x, arow, tf, k, mlo, mhi);
+  }
+}
+
+template <int DP, int NG>
+__device__ __forceinline__ void row_merge_direct(uint32_t (&x)[DP], const uint32_t RANNC_GLOBAL *__restrict__ arow,
+                                                 uint32_t tij, int rmn, const DirectConsts &k) {
+  // bit r-1 set for r < rmn: these replica counts do not fit (all of them for rmn = 255)
+  const unsigned long long below = rmn > 64 ? ~0ull : ((1ull << (rmn - 1)) - 1ull);
+#pragma unroll
+  for (int m = 8 * NG; m < DP; ++m) x[DP - 1 - m] = arow[DP - 1 - m];  // max(a, 0): replica counts not needed
+  direct_entries<DP, NG>(x, arow, (double)tij, k, (int)(uint32_t)below, (int)(uint32_t)(below >> 32));
+#pragma unroll
+  for (int h = DP / 2; h >= 1; h >>= 1) {
+#pragma unroll
+    for (int q = 0; q < DP; ++q) {
+      if ((q & h) == 0) {
+        const uint32_t hi = vmax(x[q], x[q + h]);
+        const uint32_t lo = vmin(x[q], x[q + h]);
+        x[q] = hi;
+        x[q + h] = lo;
+      }
+    }
+  }
+}
+
+// merge_rows for the recomputing level kernel: no table reads; per row one scalar read of T[i], the
+// lane's rmin byte and the a[] row.
+template <int DP, int NG>
+__device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], const ProblemDev &pr, const int s, const int c,
+                                                  const int i0, const int i_hi, const int lane, const int wave,
+                                                  const DirectConsts &k) {
+  using VT = uint32_t;
+  constexpr VT INF = Lim<VT>::inf;
+  const int N = pr.N, D = pr.D, nch = pr.nch;
+  const int jj = 64 * c + lane;
+  const int64_t lvl = (int64_t)(N + 1) * DP;
+  const VT RANNC_GLOBAL *__restrict__ Vprev = gptr((const VT *)pr.V) + (int64_t)(s - 2) * lvl;
+  const uint8_t RANNC_GLOBAL *__restrict__ rmin = gptr((const uint8_t *)pr.rmin);
+  const int64_t RANNC_GLOBAL *__restrict__ T = gptr((const int64_t *)pr.T);
+  const int rl = D - s + 1;
+  const int64_t Tj = T[min(jj + 1, N)];  // the lane's column (clamped: lanes beyond N have no work)
+  // only the loads happen here, unconditionally; the values are looked at one iteration later (see
+  // merge_rows)
+  struct Row { VT alast; int rmn; int64_t Ti; };
+  auto load_flags = [&](int i) -> Row {
+    const int ic = min(max(i, s - 1), i_hi);
+    Row r;
+    r.alast = Vprev[(int64_t)ic * DP + D - 1];
+    r.Ti = T[ic];
+    r.rmn = rmin[unit_index(nch, ic, c) * 64 + lane];
+    return r;
+  };
+  bool any = false;
+  int i = i0 + wave;
+  Row cur = load_flags(i);
+  while (i <= i_hi) {  // wave-uniform
+    const bool act = i >= s - 1 && cur.alast != INF && jj >= i && jj < N && cur.rmn <= rl;
+    const uint32_t tij = (uint32_t)(Tj - cur.Ti);
+    const int rmn = act ? cur.rmn : 255;
+    cur = load_flags(i + kMergeWaves);  // the next row's
+    if (__ballot(act) != 0ull) {
+      any = true;
+      VT x[DP];
+      row_merge_direct<DP, NG>(x, Vprev + (int64_t)i * DP, tij, rmn, k);
+#pragma unroll
+      for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+    }
+    i += kMergeWaves;
+  }
+  return any;
+}
+
 // Waves per SIMD the level kernel is compiled for: the two value arrays of the widest 32-bit case
-// fit the 168 registers of three waves per SIMD (the compiler left alone takes one more).
-template <typename VT, int DP> constexpr int merge_waves_per_simd() { return (sizeof(VT) == 4 && DP == 64) ? 3 : 1; }
+// fit the 168 registers of three waves per SIMD (the compiler left alone takes one more); the
+// recomputing kernel also keeps 32 reciprocals in registers and runs two waves per SIMD.
+template <typename VT, int DP, bool DIRECT> constexpr int merge_waves_per_simd() {
+  return (sizeof(VT) == 4 && DP == 64) ? (DIRECT ? 2 : 3) : 1;
+}
 
 // The rows i0+wave, i0+wave+4, ... <= i_hi of one work item, folded into acc (running minimum of the
 // sorted merges).  Returns whether any row had work.
@@ -367,26 +513,27 @@ __device__ __forceinline__ bool merge_rows(VT (&acc)[DP], const ProblemDev &pr, 
   const uint8_t RANNC_GLOBAL *__restrict__ rmin = gptr((const uint8_t *)pr.rmin);
   const int rl = D - s + 1;  // replicas left for stage s when s-1 devices are spent earlier
   // Flags of a row: it can contribute if its row of V[s-1] holds a finite plan and the lane's
-  // stage fits with at most rl replicas.
-  auto row_flags = [&](int i, int64_t &ubase) -> bool {
-    VT alast = INF;
-    int rmn = 255;
-    ubase = 0;
-    if (i >= s - 1 && i <= i_hi) {
-      ubase = unit_index(nch, i, c);
-      alast = Vprev[(int64_t)i * DP + D - 1];
-      if (jj >= i && jj < N) rmn = rmin[ubase * 64 + lane];
-    }
-    return (alast != INF) && (rmn <= rl);
+  // stage fits with at most rl replicas.  Only the loads happen here; the values are looked at one
+  // iteration later, so that the wait for them never stands between a row and its own unit reads.
+  // The loads are unconditional (rows outside the item are clamped to a row inside it, every column
+  // of a unit has its rmin byte in memory): a load inside a branch would be waited for where the
+  // branch ends.
+  struct Flags { VT alast; int rmn; int64_t ubase; };
+  auto load_flags = [&](int i) -> Flags {
+    const int ic = min(max(i, s - 1), i_hi);
+    Flags f;
+    f.ubase = unit_index(nch, ic, c);
+    f.alast = Vprev[(int64_t)ic * DP + D - 1];
+    f.rmn = rmin[f.ubase * 64 + lane];
+    return f;
   };
   bool any = false;
   int i = i0 + wave;
-  int64_t ubase;
-  bool act = row_flags(i, ubase);
+  Flags cur = load_flags(i);
   while (i <= i_hi) {  // wave-uniform
-    // the next row's flags are fetched while this row is merged
-    int64_t ubase_next = 0;
-    const bool act_next = (i + kMergeWaves <= i_hi) ? row_flags(i + kMergeWaves, ubase_next) : false;
+    const bool act = i >= s - 1 && cur.alast != INF && jj >= i && jj < N && cur.rmn <= rl;
+    const int64_t ubase = cur.ubase;
+    cur = load_flags(i + kMergeWaves);  // the next row's
     const unsigned long long work = __ballot(act);
     if (work != 0ull) {
       any = true;
@@ -397,15 +544,13 @@ __device__ __forceinline__ bool merge_rows(VT (&acc)[DP], const ProblemDev &pr, 
 #pragma unroll
       for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
     }
-    act = act_next;
-    ubase = ubase_next;
     i += kMergeWaves;
   }
   return any;
 }
 
-template <typename VT, int DP>
-__global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP>())))
+template <typename VT, int DP, bool DIRECT>
+__global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP, DIRECT>())))
 void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
   const ProblemDev &pr = probs[blockIdx.z];
   if (s > pr.S_eff) return;
@@ -427,17 +572,33 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
 #pragma unroll
   for (int t = 0; t < DP; ++t) acc[t] = INF;
   bool any = false;
-  const int ng = (D - s + 1 + 7) >> 3;  // eight-row groups of a unit that this level reads
+  const int ng = (D - s + 1 + 7) >> 3;  // eight-row groups of a unit that this level needs
+  if constexpr (DIRECT) {
+    // stage times recomputed: groups in pairs (fewer variants; a group more costs a few instructions)
+    DirectConsts k;
+    direct_consts_init(k);
+#define RANNC_ROWS(K)                                                                              \
+  case K:                                                                                          \
+    if constexpr (8 * K <= DP || (K == 1 && DP == 8))                                              \
+      any = merge_rows_direct<DP, (8 * K <= DP ? K : 1)>(acc, pr, s, c, i0, i_hi, lane, wave, k);  \
+    break;
+    switch (DP == 8 ? 1 : ((ng + 1) & ~1)) {
+      RANNC_ROWS(1) RANNC_ROWS(2) RANNC_ROWS(4) RANNC_ROWS(6) RANNC_ROWS(8)
+      default: break;
+    }
+#undef RANNC_ROWS
+  } else {
 #define RANNC_ROWS(K)                                                                     \
   case K:                                                                                 \
     if constexpr (8 * K <= DP) any = merge_rows<VT, DP, K>(acc, pr, s, c, i0, i_hi, lane, wave); \
     break;
-  switch (ng) {
-    RANNC_ROWS(1) RANNC_ROWS(2) RANNC_ROWS(3) RANNC_ROWS(4)
-    RANNC_ROWS(5) RANNC_ROWS(6) RANNC_ROWS(7) RANNC_ROWS(8)
-    default: break;
-  }
+    switch (ng) {
+      RANNC_ROWS(1) RANNC_ROWS(2) RANNC_ROWS(3) RANNC_ROWS(4)
+      RANNC_ROWS(5) RANNC_ROWS(6) RANNC_ROWS(7) RANNC_ROWS(8)
+      default: break;
+    }
 #undef RANNC_ROWS
+  }
 
   // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Fold the waves in LDS, then
   // write transposed so that one atomic instruction covers consecutive d of one column.
@@ -493,12 +654,16 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
   // ---- prefix sums and validation (as prefix_kernel) ----
-  if (tid == 0) { s_flags = 0; s_wlo[0] = kNoRow; s_wlo[1] = kNoRow; s_max_cut = 0ull; sC[0] = 0; }
+  if (tid == 0) {
+    s_flags = 0; s_wlo[0] = kNoRow; s_wlo[1] = kNoRow; s_max_cut = 0ull; sC[0] = 0;
+    if (pr.o) pr.C[0] = 0;
+  }
   int myflags = 0;
   __syncthreads();
   if (tid < N && pr.o) {  // per-cut send time (as prefix_kernel)
     const uint64_t c = cut_time(pr.o[tid], pr.bw, myflags);
     sC[tid + 1] = (tid + 1 < N) ? (int64_t)c : 0;
+    pr.C[tid + 1] = sC[tid + 1];  // plan recovery values the stages from the prefix sums in memory
     if (tid + 1 < N && c) atomicMax(&s_max_cut, (unsigned long long)c);
   }
   if (tid < N) {
@@ -783,7 +948,7 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
 // A wave owns a split point i and reads the row V[s-1][i][.] with one coalesced request (lane =
 // d'-1).  Both that row and h(i,j,.) are non-increasing (the property the merge kernel rests on),
 // so in row i the only candidate is the smallest d' whose earlier-stages value is <= the cell's
-// value: one row read and one table read per split point, and the reads of one pass (192 rows)
+// value: one row read and one division per split point, and the reads of one pass (192 rows)
 // do not depend on each other.
 // ---------------------------------------------------------------------------------------
 template <typename VT, int DP>
@@ -803,13 +968,15 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
     ns = (forced <= pr.S_eff && V[(int64_t)(forced - 1) * lvl + (int64_t)N * DP + D - 1] != INF) ? forced : 0;
   for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
   if (ns == 0) return;
-  const VT RANNC_GLOBAL *cost = gptr((const VT *)pr.cost);
+  const int64_t RANNC_GLOBAL *T = gptr((const int64_t *)pr.T);
   const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
   const int32_t RANNC_GLOBAL *wlo = gptr((const int32_t *)pr.wlo);
   int j = N, d = D;
   for (int s = ns; s >= 2; --s) {
     const VT RANNC_GLOBAL *Vp = V + (int64_t)(s - 2) * lvl;
     const int jj = j - 1, c = jj >> 6;
+    const int64_t Tj = T[j];
+    const uint64_t Cj = pr.C ? (uint64_t)pr.C[j] : 0ull;  // send time of the cut after block j (0 for j = N)
     if (tid == 0) *best_key = 0xFFFFFFFFu;
     __syncthreads();
     // the cell's value, the window bound and the first pass of rows are read together
@@ -843,8 +1010,10 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
         const int64_t u = unit_index(nch, i, c);
         const int r = d - my_d;
         const int rmn = (int)rmin[u * 64 + (jj & 63)];
-        const VT h = cost[(u * D + (r - 1)) * 64 + (jj & 63)];  // garbage where r < rmin
-        if (r >= rmn && vmax(my_a, h) == v) mine = min(mine, ((unsigned)i << 8) | (unsigned)my_d);
+        // the stage's time from the prefix sums (the table may not have been built)
+        uint64_t h = ((uint64_t)(Tj - T[i]) + (uint64_t)(r - 1)) / (uint64_t)r;
+        if (Cj) h += (Cj + (uint64_t)(r - 1)) / (uint64_t)r;
+        if (r >= rmn && vmax(my_a, (VT)h) == v) mine = min(mine, ((unsigned)i << 8) | (unsigned)my_d);
       }
       if (top - nw * KB < first) break;  // the remaining rows lie below the window
     }
@@ -983,14 +1152,34 @@ hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st) {
 }
 
 int merge_rows_per_item(int rows_per_wave) {
-  if (rows_per_wave <= 0) return -1;  // chosen on the device from the size of the windows
-  return kMergeWaves * (rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : 4);
+  if (rows_per_wave <= 0) return -1;  // chosen on the device
+  return kMergeWaves * (rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : rows_per_wave <= 4 ? 4 : 8);
 }
 
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, hipStream_t st, int rows8_from,
-                       int rows16_from) {
-  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, Q,
-                     rows8_from > 0 ? rows8_from : kMergeRows8From, rows16_from > 0 ? rows16_from : kMergeRows16From);
+// Grid of the sorted-merge level kernel = items of the largest search of the launch if nothing is
+// pruned.  rows_per_item > 0: in items of that size.  Otherwise in the size that suits the launch
+// as a whole: 4-row items (most workgroups) while that leaves the device short of work, larger ones
+// (fewer folds and atomics per row) when the launch is full anyway.  The work list then takes the
+// smallest item size that fits this grid.
+int64_t merge_launch_rows(const LaunchShape &sh) {
+  int64_t all_rows = 0;
+  for (int c = 0; c < sh.max_nch; ++c) all_rows += min(64 * c + 64, sh.max_N);
+  return all_rows * sh.nprob;
+}
+
+int merge_grid_items(const LaunchShape &sh, int rows_per_item) {
+  int rows = rows_per_item;
+  if (rows <= 0) {
+    const int64_t launch_rows = merge_launch_rows(sh);
+    rows = launch_rows >= kMergeRows16From ? 16 : launch_rows >= kMergeRows8From ? 8 : kMergeMinRows;
+  }
+  int64_t items = 0;
+  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + rows - 1) / rows;
+  return (int)std::max<int64_t>(1, items);
+}
+
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, hipStream_t st) {
+  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, max_items);
   return hipGetLastError();
 }
 
@@ -1003,23 +1192,23 @@ hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStr
 }
 
 template <typename VT, int DP>
-static void build_go(const ProblemDev *p, const LaunchShape &sh, hipStream_t st) {
+static void build_go(const ProblemDev *p, const LaunchShape &sh, int parts, hipStream_t st) {
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
     hipLaunchKernelGGL((build_kernel<VT, DP>),
                        dim3(sh.max_nch, (sh.max_N + kBuildWaves - 1) / kBuildWaves, nq),
-                       dim3(64 * kBuildWaves), 0, st, p + q0);
+                       dim3(64 * kBuildWaves), 0, st, p + q0, parts);
   }
 }
 
-hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, hipStream_t st) {
+hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int parts, hipStream_t st) {
   if (sh.max_N > 65535) return hipErrorInvalidValue;
-#define GO(B, T)                                            \
-  if (bits == B) {                                          \
-    if (DP == 8) build_go<T, 8>(p, sh, st);                 \
-    else if (DP == 16) build_go<T, 16>(p, sh, st);          \
-    else if (DP == 32) build_go<T, 32>(p, sh, st);          \
-    else build_go<T, 64>(p, sh, st);                        \
+#define GO(B, T)                                                   \
+  if (bits == B) {                                                 \
+    if (DP == 8) build_go<T, 8>(p, sh, parts, st);                 \
+    else if (DP == 16) build_go<T, 16>(p, sh, parts, st);          \
+    else if (DP == 32) build_go<T, 32>(p, sh, parts, st);          \
+    else build_go<T, 64>(p, sh, parts, st);                        \
   }
   GO(32, uint32_t)
   GO(64, uint64_t)
@@ -1027,31 +1216,28 @@ hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, in
   return hipGetLastError();
 }
 
-template <typename VT, int DP>
-static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, hipStream_t st) {
-  // upper bound on the items of any problem of the launch: every chunk's rows, none pruned, in the
-  // smallest items the work list makes; never more than the list can hold
-  int64_t items = 0;
-  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + kMergeMinRows - 1) / kMergeMinRows;
-  items = std::min<int64_t>(items, max_runs(sh.max_nch));
+template <typename VT, int DP, bool DIRECT>
+static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, int items, hipStream_t st) {
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((level_merge_kernel<VT, DP>), dim3((unsigned)items, 1, nq), dim3(64 * kMergeWaves), 0, st,
-                       p + q0, s);
+    hipLaunchKernelGGL((level_merge_kernel<VT, DP, DIRECT>), dim3((unsigned)items, 1, nq), dim3(64 * kMergeWaves), 0,
+                       st, p + q0, s);
   }
 }
 
-hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s,
-                              hipStream_t st) {
-#define GO(B, T)                                             \
-  if (bits == B) {                                           \
-    if (DP == 8) merge_go<T, 8>(p, sh, s, st);               \
-    else if (DP == 16) merge_go<T, 16>(p, sh, s, st);        \
-    else if (DP == 32) merge_go<T, 32>(p, sh, s, st);        \
-    else merge_go<T, 64>(p, sh, s, st);                      \
+hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s, bool recompute,
+                              int items, hipStream_t st) {
+  if (recompute && bits != 32) return hipErrorInvalidValue;
+#define GO(B, T, X)                                                            \
+  if (bits == B && recompute == X) {                                           \
+    if (DP == 8) merge_go<T, 8, X>(p, sh, s, items, st);               \
+    else if (DP == 16) merge_go<T, 16, X>(p, sh, s, items, st);        \
+    else if (DP == 32) merge_go<T, 32, X>(p, sh, s, items, st);        \
+    else merge_go<T, 64, X>(p, sh, s, items, st);                      \
   }
-  GO(32, uint32_t)
-  GO(64, uint64_t)
+  GO(32, uint32_t, false)
+  GO(32, uint32_t, true)
+  GO(64, uint64_t, false)
 #undef GO
   return hipGetLastError();
 }

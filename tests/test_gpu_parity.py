@@ -12,7 +12,7 @@ from tests.gpu_util import INF, assert_results_match, assert_tables_match, gpu_r
 
 pytestmark = pytest.mark.gpu
 
-ALGOS = [B.ALGO_MERGE, B.ALGO_SCAN]
+ALGOS = [B.ALGO_MERGE, B.ALGO_SCAN, B.ALGO_RECOMPUTE]  # RECOMPUTE acts as MERGE on 64-bit handles
 WIDTHS = [B.NARROW_MAX_TOTAL_TIME, 1 << 50]
 
 
@@ -27,12 +27,14 @@ def test_configs_1_to_3_tables_and_plan(k, algo, width):
         assert_tables_match(pr, sess, 0)
 
 
-def test_config4_full_size():
-    """N=1024, D=64, S<=32 in the launch configuration the benchmark times: optimum, plan, the whole
-    value table and the whole (i, d') tables of every cell against the oracle (a few seconds of
-    CPU with all cores)."""
+@pytest.mark.parametrize("algo", [B.ALGO_AUTO, B.ALGO_MERGE])
+def test_config4_full_size(algo):
+    """N=1024, D=64, S<=32 in the launch configuration the benchmark times (AUTO: stage times
+    recomputed in the level kernel, the stage-time table built for the export) and with the table
+    read by the level kernel (MERGE): optimum, plan, the whole value table and the whole (i, d')
+    tables of every cell against the oracle (a few seconds of CPU with all cores)."""
     pr = synth.named_config(4)
-    res, sess = gpu_run([pr])
+    res, sess = gpu_run([pr], algo=algo)
     with sess:
         assert_results_match([pr], res)
         o = assert_tables_match(pr, sess, 0, args=True)
@@ -121,16 +123,23 @@ def test_batched_mixed_shapes(algo):
             assert np.array_equal(r1["replicas"][0], res["replicas"][q][:k])
 
 
-def test_config5_batched_sweep_full_size():
-    """All 2048 searches in one batch, in the launch configuration the benchmark times.  The oracle
-    solves every one of them (one search per host thread): optimum, stage count, estimated iteration
-    time and the canonical plan must agree for all 2048; the tables of a few are compared cell by
-    cell; every plan is also checked from the definition."""
+_C5_ORACLE = []
+
+
+@pytest.mark.parametrize("algo", [B.ALGO_AUTO, B.ALGO_MERGE])
+def test_config5_batched_sweep_full_size(algo):
+    """All 2048 searches in one batch, in the launch configuration the benchmark times (AUTO) and
+    with the stage-time tables read by the level kernels (MERGE).  The oracle solves every one of
+    them (one search per host thread): optimum, stage count, estimated iteration time and the
+    canonical plan must agree for all 2048; the tables of a few are compared cell by cell; every
+    plan is also checked from the definition."""
     probs = synth.named_config(5)
-    res, sess = gpu_run(probs)
+    if not _C5_ORACLE:
+        _C5_ORACLE.extend(oracle_solve_many(probs))
+    res, sess = gpu_run(probs, algo=algo)
     with sess:
         assert (res["status"] == 0).all()
-        assert_results_match(probs, res, oracle_results=oracle_solve_many(probs))
+        assert_results_match(probs, res, oracle_results=_C5_ORACLE)
         for q in (0, 1, 2, 3, 1000, 2047):  # covers the four device-count classes
             assert_tables_match(probs[q], sess, q, args=False)
         assert {probs[q]["n_devices"] for q in (0, 1, 2, 3, 1000, 2047)} == {8, 16, 32, 64}
@@ -156,29 +165,75 @@ def test_deterministic_across_runs():
     assert np.array_equal(V1, V2)
 
 
-def test_merge_and_scan_levels_agree_at_medium_size():
+def test_merge_recompute_and_scan_levels_agree_at_medium_size():
     pr = synth.enlarged_transformer_chain(seed=11, N=300, D=48, S=20, M=24 * synth.GiB)
     rm, sm = gpu_run([pr], algo=B.ALGO_MERGE)
     rs, ss = gpu_run([pr], algo=B.ALGO_SCAN)
-    with sm, ss:
+    rr, sr = gpu_run([pr], algo=B.ALGO_RECOMPUTE)
+    with sm, ss, sr:
         assert np.array_equal(sm.table(B.TABLE_V, 0), ss.table(B.TABLE_V, 0))
+        assert np.array_equal(sm.table(B.TABLE_V, 0), sr.table(B.TABLE_V, 0))
+        assert np.array_equal(sm.table(B.TABLE_COST, 0), sr.table(B.TABLE_COST, 0))  # built for the export
         for k in rm:
             assert np.array_equal(rm[k], rs[k]), k
+            assert np.array_equal(rm[k], rr[k]), k
         assert_results_match([pr], rm)
 
 
-@pytest.mark.parametrize("rows", ["1", "2", "4"])
-def test_rows_per_wave_variants(rows, monkeypatch):
-    """The merge level kernel exists in three shapes (1, 2 or 4 predecessor rows per wave, the
-    latter two with double-buffered reads); the library reads the choice when a handle is created.
-    All must give the oracle's tables."""
-    monkeypatch.setenv("RANNC_DP_ROWS_PER_WAVE", rows)
+def test_recomputed_stage_times_at_the_edges_of_the_value_range():
+    """The level kernel that recomputes ceil(T / r) without an integer division, on totals that sit
+    at exact multiples of r, one above and one below them, at the top of the 32-bit range, and at
+    0: every stage time it forms is one the table builder forms too, so the value tables of the two
+    level kernels must be identical (and equal the oracle's)."""
+    g = np.random.default_rng(4242)
+    probs = []
+    for case in range(24):
+        N = int(g.integers(40, 130))
+        D = int(g.choice([7, 8, 16, 31, 32, 33, 63, 64]))
+        pr = synth.random_small(9100 + case, N, D, int(g.integers(2, 14)), tight=float(g.choice([1.3, 3.0, 60.0])), tmax=9)
+        kind = case % 4
+        if kind == 0:      # stage totals are multiples of 720720 = lcm(1..16): exact quotients for many r
+            pr["time_ns"] = np.full(N, 720720, dtype=np.int64) * g.integers(0, 3, N)
+        elif kind == 1:    # one off the multiples
+            pr["time_ns"] = np.full(N, 720720, dtype=np.int64) * g.integers(0, 3, N) + g.integers(-1, 2, N) * (g.random(N) < 0.2)
+            pr["time_ns"] = np.maximum(pr["time_ns"], 0)
+        elif kind == 2:    # the whole chain just fits the 32-bit range
+            t = g.integers(0, 1 << 20, N).astype(np.int64)
+            t[int(g.integers(0, N))] += (B.NARROW_MAX_TOTAL_TIME - int(t.sum()))
+            pr["time_ns"] = t
+        else:              # powers of two and their neighbours
+            pr["time_ns"] = (1 << g.integers(0, 24, N)).astype(np.int64) + g.integers(-1, 2, N)
+        probs.append(pr)
+    rm, sm = gpu_run(probs, algo=B.ALGO_MERGE)
+    rr, sr = gpu_run(probs, algo=B.ALGO_RECOMPUTE)
+    with sm, sr:
+        for k in rm:
+            assert np.array_equal(rm[k], rr[k]), k
+        assert (rm["status"] == 0).all()
+        for q in range(len(probs)):
+            assert np.array_equal(sm.table(B.TABLE_V, q), sr.table(B.TABLE_V, q)), q
+        assert_results_match(probs, rr)
+        for q in (2, 6, 10):
+            assert_tables_match(probs[q], sr, q, args=False)
+
+
+@pytest.mark.parametrize("algo", [B.ALGO_MERGE, B.ALGO_RECOMPUTE])
+@pytest.mark.parametrize("rows", [1, 2, 4, 8])
+def test_rows_per_wave_variants(rows, algo):
+    """A wave of the merge level kernel takes 1, 2, 4 or 8 predecessor rows one after the other
+    (work items of 4, 8, 16 or 32 rows); the handle's limits fix the choice.  All must give the
+    oracle's tables, with the stage times read from their table and recomputed."""
     probs = [synth.enlarged_transformer_chain(seed=21, N=333, D=64, S=12, M=24 * synth.GiB),
              synth.random_small(77, 150, 40, 9, tight=1.3, tmax=5000),
              synth.random_small(78, 65, 7, 7, tight=1.1, tmax=50)]
     for width in WIDTHS:
-        res, sess = gpu_run(probs, max_total_time_ns=width)
+        res, sess = gpu_run(probs, max_total_time_ns=width, rows_per_wave=rows, algo=algo, one_launch_small=1)
         with sess:
+            rc, info = B.rannc_dp_solve_info(sess.h)
+            want = B.KERNEL_MERGE_RECOMPUTE if (algo == B.ALGO_RECOMPUTE and width == B.NARROW_MAX_TOTAL_TIME) \
+                else B.KERNEL_MERGE_TABLE
+            assert rc == B.OK and list(info.n_problems) == [1, 0, 0, 2]
+            assert [info.level_kernel[k] for k in (0, 3)] == [want, want]
             assert_results_match(probs, res)
             for q in range(3):
                 assert_tables_match(probs[q], sess, q, args=False)
@@ -209,13 +264,12 @@ def test_random_batches_against_oracle(width):
                 assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 80))
 
 
-@pytest.mark.parametrize("mode", ["0", "2"])
+@pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("width", WIDTHS)
-def test_small_search_kernel_on_and_off(mode, width, monkeypatch):
+def test_small_search_kernel_on_and_off(mode, width):
     """Searches of at most 128 blocks can run as one launch with one workgroup per search (levels
     folded in LDS) or through the per-level launches; the library chooses by batch shape.  Both
-    are forced here (0 = never, 2 = always) on the same inputs: identical tables, optimum, plan."""
-    monkeypatch.setenv("RANNC_DP_FUSED_SMALL", mode)
+    are forced here (1 = never, 2 = always) on the same inputs: identical tables, optimum, plan."""
     g = np.random.default_rng(99)
     probs = [synth.named_config(1), synth.named_config(2)]
     for q in range(30):
@@ -225,8 +279,11 @@ def test_small_search_kernel_on_and_off(mode, width, monkeypatch):
                                         tight=float(g.choice([0.9, 1.2, 2.0, 50.0])),
                                         tmax=int(g.choice([2, 1000, 10 ** 6])),
                                         zero_time_frac=float(g.choice([0.0, 0.25]))))
-    res, sess = gpu_run(probs, max_total_time_ns=width)
+    res, sess = gpu_run(probs, max_total_time_ns=width, one_launch_small=mode)
     with sess:
+        rc, info = B.rannc_dp_solve_info(sess.h)
+        kinds = {info.level_kernel[k] for k in range(4) if info.n_problems[k]}
+        assert rc == B.OK and (kinds == {B.KERNEL_ONE_LAUNCH} if mode == 2 else B.KERNEL_ONE_LAUNCH not in kinds)
         assert_results_match(probs, res)
         for q in range(0, len(probs), 3):
             assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
@@ -269,23 +326,21 @@ def test_large_search_prefix_parity_and_properties(N, M_gib, width):
                             sess.d_se.cpu().numpy()[0], sess.d_rp.cpu().numpy()[0])
 
 
-@pytest.mark.parametrize("streams", ["0", "1"])
+@pytest.mark.parametrize("single_stream", [0, 1])
 @pytest.mark.parametrize("timing", [False, True])
-def test_classes_on_their_own_streams(streams, timing, monkeypatch):
+def test_classes_on_their_own_streams(single_stream, timing):
     """A batch with all four device-count classes: the classes run as independent chains of
-    launches on streams of the handle (RANNC_DP_STREAMS=1, the default) or one after the other on
-    the caller's stream (0, and whenever per-phase timing is on).  Same results either way, also
+    launches on streams of the handle (the default) or one after the other on the caller's stream
+    (limits.single_stream = 1, and whenever per-phase timing is on).  Same results either way, also
     on repeated solves of one handle and with the one-launch kernel on or off."""
-    monkeypatch.setenv("RANNC_DP_STREAMS", streams)
     probs = []
     for seed in range(64):
         g = np.random.default_rng(121_000 + seed)
         D = int(g.choice([3, 8, 11, 16, 27, 32, 50, 64]))
         probs.append(synth.random_small(seed, int(g.integers(1, 140)), D, int(g.integers(1, 18)),
                                         tight=float(g.choice([1.2, 2.0, 9.0])), tmax=int(g.choice([9, 4000]))))
-    for fused in ("0", "1"):
-        monkeypatch.setenv("RANNC_DP_FUSED_SMALL", fused)
-        res, sess = gpu_run(probs)
+    for fused in (1, 0):
+        res, sess = gpu_run(probs, single_stream=single_stream, one_launch_small=fused)
         with sess:
             B.rannc_dp_set_timing(sess.h, timing)
             for _ in range(3):
@@ -328,16 +383,15 @@ def test_solve_on_a_side_stream_and_two_handles_at_once():
             sess.close()
 
 
-@pytest.mark.parametrize("fused", ["0", "2"])
-def test_more_searches_than_one_grid_dimension_holds(fused, monkeypatch):
+@pytest.mark.parametrize("fused", [1, 2])
+def test_more_searches_than_one_grid_dimension_holds(fused):
     """70 000 searches in one batch (a launch covers at most 65 535 problems in a grid dimension, so
     every kernel is launched in slices): seven distinct tiny searches, each repeated 10 000 times;
     every copy must equal the oracle's result for its original."""
-    monkeypatch.setenv("RANNC_DP_FUSED_SMALL", fused)
     base = [synth.random_small(4000 + k, 2 + k, 1 + (k * 5) % 9, 1 + k % 4, tight=[1.2, 2.0, 9.0][k % 3], tmax=50)
             for k in range(7)]
     probs = [base[q % 7] for q in range(70_000)]
-    res, sess = gpu_run(probs)
+    res, sess = gpu_run(probs, one_launch_small=fused)
     with sess:
         for k, pr in enumerate(base):
             o = oracle.solve(pr)
@@ -349,3 +403,36 @@ def test_more_searches_than_one_grid_dimension_holds(fused, monkeypatch):
             assert (res["stage_end"][sel, :w] == o["stage_end"][:w]).all()
             assert (res["replicas"][sel, :w] == o["replicas"][:w]).all()
             assert (res["stage_end"][sel, w:] == -1).all()
+
+
+def test_environment_overrides_and_automatic_choice_of_the_level_kernel(monkeypatch):
+    """What rannc_dp_solve_info reports: a large class of a 32-bit batch has its stage times
+    recomputed, a small one reads the table, 64-bit handles and batches with a communication term
+    always read the table; the documented environment variables override the limits' tuning."""
+    big = synth.batched_sweep(Q=1000)
+    big = [p for p in big if p["n_devices"] == 64][:200] + [p for p in big if p["n_devices"] == 32][:2]
+    res, sess = gpu_run(big)
+    with sess:
+        rc, info = B.rannc_dp_solve_info(sess.h)
+        assert rc == B.OK and list(info.n_problems) == [0, 0, 2, 200]
+        assert info.level_kernel[3] == B.KERNEL_MERGE_RECOMPUTE and info.level_kernel[2] == B.KERNEL_MERGE_TABLE
+        assert_results_match(big[:6] + big[-2:], {k: np.concatenate([v[:6], v[-2:]]) for k, v in res.items()})
+    res, sess = gpu_run(big, max_total_time_ns=1 << 50)
+    with sess:
+        rc, info = B.rannc_dp_solve_info(sess.h)
+        assert [info.level_kernel[k] for k in (2, 3)] == [B.KERNEL_MERGE_TABLE] * 2
+    comm = [synth.with_cut_bytes(p, 5, 100_000) for p in big]
+    res, sess = gpu_run(comm, algo=B.ALGO_RECOMPUTE)
+    with sess:
+        rc, info = B.rannc_dp_solve_info(sess.h)
+        assert [info.level_kernel[k] for k in (2, 3)] == [B.KERNEL_MERGE_TABLE] * 2
+        assert_results_match(comm[:3], {k: v[:3] for k, v in res.items()})
+    small = [synth.random_small(5, 40, 8, 4, tight=2.0), synth.random_small(6, 90, 30, 6, tight=2.0)]
+    monkeypatch.setenv("RANNC_DP_FUSED_SMALL", "2")
+    monkeypatch.setenv("RANNC_DP_ROWS_PER_WAVE", "2")
+    monkeypatch.setenv("RANNC_DP_STREAMS", "0")
+    res, sess = gpu_run(small, one_launch_small=1)
+    with sess:
+        rc, info = B.rannc_dp_solve_info(sess.h)
+        assert [info.level_kernel[k] for k in (0, 2)] == [B.KERNEL_ONE_LAUNCH] * 2
+        assert_results_match(small, res)
