@@ -126,6 +126,7 @@ struct rannc_dp {
   hipStream_t aux[3];
   hipEvent_t fork_ev, join_ev[3];
   bool multi_stream;
+  int n_cus;  // compute units of the device the handle was created on
   rannc_dp_solve_info_t info;  // of the last successful solve
   bool no_times[4];  // per device-count class of the last solve: the stage-time table was not built
   int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
@@ -194,6 +195,15 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->level_launches = 0;
   h->tune_spw = l->rows_per_wave;
   for (int k = 0; k < 4; ++k) h->no_times[k] = false;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+      (void)hipGetLastError();
+      cus = 256;
+    }
+    h->n_cus = cus;
+  }
   if (const char *e = std::getenv("RANNC_DP_ROWS_PER_WAVE")) h->tune_spw = std::atoi(e);
   h->fused_small = l->one_launch_small == 1 ? 0 : l->one_launch_small == 2 ? 2 : 1;
   if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
@@ -451,14 +461,15 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
     if (split) {
       ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
-      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, st) == hipSuccess;
+      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, 0, st) == hipSuccess;
     }
     if (scan || split) continue;
     // Rows per wave of the level kernel: chosen on the device from the size of the windows unless
     // the handle fixes it (1, 2 or 4).
     merge_items[k] = rannc::merge_grid_items(sh, rannc::merge_rows_per_item(h->tune_spw));
-    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), merge_items[k], st) ==
-                   hipSuccess;
+    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), merge_items[k],
+                                  h->n_cus * rannc::merge_workgroups_per_cu(h->bits, kClasses[k], recompute_cls[k]),
+                                  st) == hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;

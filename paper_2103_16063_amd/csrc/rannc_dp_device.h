@@ -10,10 +10,35 @@ namespace rannc {
 
 template <typename VT> struct Lim;
 template <> struct Lim<uint32_t> { static constexpr uint32_t inf = 0xFFFFFFFFu; };
-template <> struct Lim<uint64_t> { static constexpr uint64_t inf = 0x7FFFFFFFFFFFFFFFull; };
+// 64-bit tables: "no plan" is the bit pattern of +infinity in double precision, above every value
+// a search can form (they stay below 2^62).  Bit patterns below it, read as doubles, are
+// non-negative finite numbers (normal or denormal, never NaN) whose order is the order of the
+// integers, so the maximum and minimum of two 64-bit values are ONE double-precision instruction
+// each instead of a 64-bit compare and four selects.  The boundary still reports INT64_MAX.
+template <> struct Lim<uint64_t> { static constexpr uint64_t inf = 0x7FF0000000000000ull; };
 
 template <typename VT> __device__ __forceinline__ VT vmax(VT a, VT b) { return a > b ? a : b; }
 template <typename VT> __device__ __forceinline__ VT vmin(VT a, VT b) { return a < b ? a : b; }
+// (inline assembly: the compiler's own double-precision maximum first rewrites each operand to
+// quiet signalling NaNs, which cannot occur here, at three instructions instead of one; double
+// precision denormals are always enabled on this target)
+template <> __device__ __forceinline__ uint64_t vmax<uint64_t>(uint64_t a, uint64_t b) {
+  uint64_t r;
+  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+template <> __device__ __forceinline__ uint64_t vmin<uint64_t>(uint64_t a, uint64_t b) {
+  uint64_t r;
+  asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// maximum with a wave-uniform first operand that lives in scalar registers
+template <typename VT> __device__ __forceinline__ VT vmax_su(VT a_uniform, VT b) { return vmax(a_uniform, b); }
+template <> __device__ __forceinline__ uint64_t vmax_su<uint64_t>(uint64_t a_uniform, uint64_t b) {
+  uint64_t r;
+  asm("v_max_f64 %0, %1, %2" : "=v"(r) : "s"(a_uniform), "v"(b));
+  return r;
+}
 
 // Pointers that are read out of a descriptor in memory are generic to the compiler, and generic
 // (FLAT) loads count against the 4-bit LDS/scalar counter: at most 15 of them can be in flight per

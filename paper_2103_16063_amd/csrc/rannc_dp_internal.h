@@ -106,7 +106,9 @@ hipError_t launch_build(const ProblemDev *probs, const LaunchShape &sh, int bits
 hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStream_t st);
 // rows_per_item: > 0 fixed, 0 chosen on the device for the split-objective kernel, -1 for the
 // sorted-merge kernel (then the smallest item size whose item count fits max_items)
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, hipStream_t st);
+// slots: workgroups of the level kernel that the device holds at a time
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, hipStream_t st);
+int merge_workgroups_per_cu(int bits, int DP, bool recompute);
 int merge_rows_per_item(int rows_per_wave);
 int merge_grid_items(const LaunchShape &sh, int rows_per_item);
 // rows of the searches of a launch if nothing is pruned (every chunk c holds rows 0 .. 64c+63)

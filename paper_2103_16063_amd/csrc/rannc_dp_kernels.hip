@@ -9,8 +9,9 @@
 // reported (the final selection, the plan recovery and the exports check the status word).
 #include "rannc_dp_device.h"
 
-namespace rannc {
+#include <type_traits>
 
+namespace rannc {
 
 // ---------------------------------------------------------------------------------------
 // Prefix sums T, P, A of the block inputs (the sums over a stage's members that stand in
@@ -250,9 +251,12 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // fits max_items, the grid the host launches (sized for the rows of an unpruned search: small
 // items, i.e. many workgroups and a short critical path, when pruning leaves few rows; large ones,
 // i.e. fewer folds and atomics per row, when the launch is full anyway; and never a workgroup
-// without an item in a launch over many searches).  One workgroup per problem.
+// without an item in a launch over many searches).  One step larger if that brings a launch that
+// needs a little more than one round of workgroups (`slots` run at a time, `batch` searches in the
+// launch) down to one round that still fills half the device.  One workgroup per problem.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int max_items) {
+__global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int max_items,
+                                                    int batch, int slots) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
   __shared__ int total_rows, count[5];
@@ -279,9 +283,14 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
     if (rows == 0) {
       rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
     } else {
-      rows = 64;
+      int pick = 4;
       for (int k = 4; k >= 0; --k)
-        if (count[k] <= max_items) rows = 4 << k;
+        if (count[k] <= max_items) pick = k;
+      if (pick < 4) {
+        const long long now = (long long)count[pick] * batch, then = (long long)count[pick + 1] * batch;
+        if (now > slots && then <= slots && 2 * then >= slots) ++pick;
+      }
+      rows = 4 << pick;
     }
   }
   const int tag = (rows - 1) << 26;
@@ -353,7 +362,10 @@ __device__ __forceinline__ void row_merge(VT (&x)[DP], const VT RANNC_GLOBAL *__
     else x[DP - 1 - m] = (VT)0;
   }
 #pragma unroll
-  for (int q = 0; q < DP; ++q) x[q] = vmax(vmax(arow[q], x[q]), off);
+  for (int q = 0; q < DP; ++q) {
+    if constexpr (std::is_same<AP, const VT RANNC_GLOBAL *>::value) x[q] = vmax(vmax_su(arow[q], x[q]), off);
+    else x[q] = vmax(vmax(arow[q], x[q]), off);
+  }
 #pragma unroll
   for (int h = DP / 2; h >= 1; h >>= 1) {
 #pragma unroll
@@ -496,14 +508,18 @@ __device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], const Pro
 // fit the 168 registers of three waves per SIMD (the compiler left alone takes one more); the
 // recomputing kernel also keeps 32 reciprocals in registers and runs two waves per SIMD.
 template <typename VT, int DP, bool DIRECT> constexpr int merge_waves_per_simd() {
-  return (sizeof(VT) == 4 && DP == 64) ? (DIRECT ? 2 : 3) : 1;
+  return DP == 64 ? (sizeof(VT) == 4 ? (DIRECT ? 2 : 3) : 2) : 1;
 }
 
 // The rows i0+wave, i0+wave+4, ... <= i_hi of one work item, folded into acc (running minimum of the
 // sorted merges).  Returns whether any row had work.
-template <typename VT, int DP, int NG>
-__device__ __forceinline__ bool merge_rows(VT (&acc)[DP], const ProblemDev &pr, const int s, const int c,
-                                           const int i0, const int i_hi, const int lane, const int wave) {
+// ROWFOLD: the sorted merge of every row goes straight into the lane's row of the workgroup's LDS
+// tile instead of a running minimum in registers (64-bit values at DP = 64: two value arrays would
+// take all 256 registers of a wave and leave one wave per SIMD).
+template <typename VT, int DP, int NG, bool ROWFOLD>
+__device__ __forceinline__ bool merge_rows(VT (&acc)[DP], VT *tile_lane, const ProblemDev &pr, const int s,
+                                           const int c, const int i0, const int i_hi, const int lane,
+                                           const int wave) {
   constexpr VT INF = Lim<VT>::inf;
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int jj = 64 * c + lane;
@@ -541,8 +557,15 @@ __device__ __forceinline__ bool merge_rows(VT (&acc)[DP], const ProblemDev &pr, 
       const int col = act ? lane : __ffsll((long long)work) - 1;  // a lane without work reads a needed column
       row_merge<VT, DP, NG, const VT RANNC_GLOBAL *>(x, cost + ubase * 64 * D + col, Vprev + (int64_t)i * DP,
                                                      act ? (VT)0 : INF, rl);
+      if constexpr (ROWFOLD) {
+        if (act) {
 #pragma unroll
-      for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+          for (int t = 0; t < DP; ++t) atomicMin(&tile_lane[t], x[t]);
+        }
+      } else {
+#pragma unroll
+        for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+      }
     }
     i += kMergeWaves;
   }
@@ -568,9 +591,16 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
   VT RANNC_GLOBAL *Vcur = gptr((VT *)pr.V) + (int64_t)(s - 1) * (int64_t)(N + 1) * DP;
 
   // acc[t] = running minimum over this wave's rows of the sorted merge
-  VT acc[DP];
+  constexpr bool ROWFOLD = sizeof(VT) == 8 && DP == 64;
+  __shared__ VT tile[64 * (DP + 1)];
+  [[maybe_unused]] VT acc[DP];
+  if constexpr (ROWFOLD) {
+    for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
+    __syncthreads();
+  } else {
 #pragma unroll
-  for (int t = 0; t < DP; ++t) acc[t] = INF;
+    for (int t = 0; t < DP; ++t) acc[t] = INF;
+  }
   bool any = false;
   const int ng = (D - s + 1 + 7) >> 3;  // eight-row groups of a unit that this level needs
   if constexpr (DIRECT) {
@@ -590,7 +620,8 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
   } else {
 #define RANNC_ROWS(K)                                                                     \
   case K:                                                                                 \
-    if constexpr (8 * K <= DP) any = merge_rows<VT, DP, K>(acc, pr, s, c, i0, i_hi, lane, wave); \
+    if constexpr (8 * K <= DP)                                                            \
+      any = merge_rows<VT, DP, K, ROWFOLD>(acc, tile + lane * (DP + 1), pr, s, c, i0, i_hi, lane, wave); \
     break;
     switch (ng) {
       RANNC_ROWS(1) RANNC_ROWS(2) RANNC_ROWS(3) RANNC_ROWS(4)
@@ -602,14 +633,17 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
 
   // acc[t] is W[d = t+2]; V rows are indexed by d-1 = t+1.  Fold the waves in LDS, then
   // write transposed so that one atomic instruction covers consecutive d of one column.
-  __shared__ VT tile[64 * (DP + 1)];
-  for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
-  if (__syncthreads_or(any) == 0) return;
-  if (any) {
+  if constexpr (ROWFOLD) {
+    if (__syncthreads_or(any) == 0) return;
+  } else {
+    for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
+    if (__syncthreads_or(any) == 0) return;
+    if (any) {
 #pragma unroll
-    for (int t = 0; t < DP; ++t) atomicMin(&tile[lane * (DP + 1) + t], acc[t]);  // folding INF in is a no-op
+      for (int t = 0; t < DP; ++t) atomicMin(&tile[lane * (DP + 1) + t], acc[t]);  // folding INF in is a no-op
+    }
+    __syncthreads();
   }
-  __syncthreads();
   constexpr int RPP = 64 * kMergeWaves / DP;  // rows per pass
   const int t = threadIdx.x & (DP - 1);
   for (int row = threadIdx.x / DP; row < 64; row += RPP) {
@@ -934,7 +968,8 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
       const uint32_t u = ((const uint32_t *)pr.V)[lane * lvl + cell];
       v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
     } else {
-      v = (int64_t)((const uint64_t *)pr.V)[lane * lvl + cell];
+      const uint64_t u = ((const uint64_t *)pr.V)[lane * lvl + cell];
+      v = (u == Lim<uint64_t>::inf) ? INT64_MAX : (int64_t)u;
     }
   }
   select_finish(pr, v, st, d_opt, d_n_stages, d_est, d_status);
@@ -1178,9 +1213,19 @@ int merge_grid_items(const LaunchShape &sh, int rows_per_item) {
   return (int)std::max<int64_t>(1, items);
 }
 
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, hipStream_t st) {
-  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, max_items);
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, hipStream_t st) {
+  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, max_items, Q, slots);
   return hipGetLastError();
+}
+
+// Workgroups of the sorted-merge level kernel that one compute unit holds at a time (by the
+// registers of its four waves, one per SIMD; see the kernel's resource usage).
+int merge_workgroups_per_cu(int bits, int DP, bool recompute) {
+  if (bits == 32) {
+    if (recompute) return DP == 64 ? 2 : DP == 32 ? 3 : DP == 16 ? 5 : 8;
+    return DP == 64 ? 3 : DP == 32 ? 4 : DP == 16 ? 6 : 8;
+  }
+  return DP == 64 ? 2 : DP == 32 ? 3 : DP == 16 ? 4 : 8;
 }
 
 hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStream_t st) {
@@ -1299,7 +1344,8 @@ __global__ __launch_bounds__(64) void level_values_kernel(const ProblemDev *__re
         const uint32_t u = ((const uint32_t *)pr.V)[k * lvl + cell];
         v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
       } else {
-        v = (int64_t)((const uint64_t *)pr.V)[k * lvl + cell];
+        const uint64_t u = ((const uint64_t *)pr.V)[k * lvl + cell];
+        v = (u == Lim<uint64_t>::inf) ? INT64_MAX : (int64_t)u;
       }
     }
     out[(int64_t)pr.q * stride + k] = v;
