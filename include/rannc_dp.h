@@ -205,11 +205,12 @@ RANNC_DP_API int rannc_dp_level_values(rannc_dp_t *h, void *hip_stream, int32_t 
  * microbatch counts MB = 1, 2, 4, ... <= floor(batch_size / R), form_stage_dp is asked for a plan
  * of exactly S stages; the first S with any feasible MB returns the best of its solutions.
  * All these searches run as ONE batch through rannc_dp_solve on the given handle; the loops then
- * run over the per-level values on the host.  Readings where the paper is silent: a block's time
+ * run over the per-level values in a small kernel, the chosen plan is recovered on the device and
+ * one copy brings the result to the host.  Readings where the paper is silent: a block's time
  * and transient bytes are linear in the b = floor(batch_size / R / MB) samples of a microbatch on
  * one pipeline replica (inputs are per sample), persistent bytes are not scaled; "best" is the
  * smallest (MB + S - 1) * V (one synchronous pipeline iteration, Fig. 1), the smallest MB among
- * equals.  This call is synchronous: it waits for the stream twice.  Its first use on a handle
+ * equals.  This call is synchronous: it waits for the stream once, at its end.  Its first use on a handle
  * (and any later use with larger inputs) allocates pinned host memory, freed by destroy.
  *   h            handle whose limits cover rannc_dp_form_stage_problems(in) problems of n_blocks
  *                blocks, devices_per_node * n_max devices and as many stages

@@ -351,12 +351,20 @@ class Session:
         if rc != OK:
             raise RanncDpError(rc, "rannc_dp_create")
         self.plan_stride = int(self.S_eff.max())
-        self.d_opt = torch.empty(self.Q, dtype=torch.int64, device=self.dev)
-        self.d_ns = torch.empty(self.Q, dtype=torch.int32, device=self.dev)
-        self.d_est = torch.empty(self.Q, dtype=torch.int64, device=self.dev)
-        self.d_status = torch.empty(self.Q, dtype=torch.int32, device=self.dev)
-        self.d_se = torch.empty((self.Q, self.plan_stride), dtype=torch.int32, device=self.dev)
-        self.d_rp = torch.empty((self.Q, self.plan_stride), dtype=torch.int32, device=self.dev)
+        # every output of solve and traceback in ONE device buffer (and one pinned host buffer of
+        # the same layout), so that the results come to the host in a single copy
+        Q, PS = self.Q, self.plan_stride
+        sizes = [8 * Q, 8 * Q, 4 * Q, 4 * Q, 4 * Q * PS, 4 * Q * PS]  # opt, est, n_stages, status, ends, replicas
+        offs = np.concatenate(([0], np.cumsum([(x + 7) // 8 * 8 for x in sizes]))).astype(int)
+        self._out_dev = torch.empty(int(offs[-1]), dtype=torch.uint8, device=self.dev)
+        self._out_host = torch.empty(int(offs[-1]), dtype=torch.uint8, pin_memory=True)
+
+        def views(buf):
+            cut = lambda k, dt, shape: buf[int(offs[k]):int(offs[k]) + sizes[k]].view(dt).view(shape)
+            return (cut(0, torch.int64, (Q,)), cut(1, torch.int64, (Q,)), cut(2, torch.int32, (Q,)),
+                    cut(3, torch.int32, (Q,)), cut(4, torch.int32, (Q, PS)), cut(5, torch.int32, (Q, PS)))
+        self.d_opt, self.d_est, self.d_ns, self.d_status, self.d_se, self.d_rp = views(self._out_dev)
+        self._h_views = views(self._out_host)
 
     def stream(self):
         return self.torch.cuda.current_stream(self.dev).cuda_stream
@@ -373,13 +381,13 @@ class Session:
             raise RanncDpError(rc, "rannc_dp_traceback")
 
     def run(self):
-        """solve + traceback + copy the results to the host."""
+        """solve + traceback + ONE copy of all results to (pinned) host memory."""
         self.solve()
         self.traceback()
-        self.torch.cuda.synchronize(self.dev)
-        return {"opt": self.d_opt.cpu().numpy(), "n_stages": self.d_ns.cpu().numpy(),
-                "est_iter_ns": self.d_est.cpu().numpy(), "status": self.d_status.cpu().numpy(),
-                "stage_end": self.d_se.cpu().numpy(), "replicas": self.d_rp.cpu().numpy()}
+        self._out_host.copy_(self._out_dev, non_blocking=True)
+        self.torch.cuda.current_stream(self.dev).synchronize()
+        opt, est, ns, status, se, rp = (v.numpy().copy() for v in self._h_views)
+        return {"opt": opt, "n_stages": ns, "est_iter_ns": est, "status": status, "stage_end": se, "replicas": rp}
 
     def table(self, which: int, q: int) -> np.ndarray:
         torch = self.torch

@@ -601,10 +601,12 @@ bool fs_pairs(const rannc_dp_form_stage_in_t *in, std::vector<FsPair> *out, int 
 size_t fs_scratch(int Q, int N, int stride) {
   size_t b = 0;
   b += 5 * align_up((size_t)Q * N * 8);       // scaled time, param, act, cut bytes, backward time
+  b += align_up((size_t)Q * 8);               // n and MB of every search (int32 each; travels up with the inputs)
   b += 2 * align_up((size_t)Q * 8);           // opt, (n_stages + status as int32 pairs)
   b += align_up((size_t)Q * stride * 8);      // per-level values
   b += align_up((size_t)Q * 4);               // forced levels
-  b += 2 * align_up((size_t)Q * stride * 4);  // plan
+  b += 2 * align_up((size_t)Q * stride * 4);  // plans of the batch
+  b += align_up(6 * 8 + (size_t)stride * 8);  // result record and the chosen plan (travels down)
   return b;
 }
 
@@ -683,21 +685,28 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   }
   // layout of the scratch (device) and of its mirror (host)
   const size_t a_in = align_up((size_t)Q * N * 8);
-  const size_t o_t = 0, o_p = a_in, o_a = 2 * a_in, o_o = 3 * a_in, o_b = 4 * a_in, o_opt = 5 * a_in;
+  const size_t o_pair = 0, o_t = align_up((size_t)Q * 8);
+  const size_t o_p = o_t + a_in, o_a = o_t + 2 * a_in, o_o = o_t + 3 * a_in, o_b = o_t + 4 * a_in;
+  const size_t o_opt = o_t + 5 * a_in;
   const size_t o_ns = o_opt + align_up((size_t)Q * 8);
   const size_t o_vals = o_ns + align_up((size_t)Q * 8);
   const size_t o_lev = o_vals + align_up((size_t)Q * stride * 8);
   const size_t o_se = o_lev + align_up((size_t)Q * 4);
   const size_t o_rp = o_se + align_up((size_t)Q * stride * 4);
+  const size_t o_rec = o_rp + align_up((size_t)Q * stride * 4);
+  const size_t rec_bytes = 6 * 8 + (size_t)stride * 8;
   char *dev = (char *)d_scratch, *pin = h->fs_pin;
   int64_t *ht = (int64_t *)(pin + o_t), *hp = (int64_t *)(pin + o_p), *ha = (int64_t *)(pin + o_a);
   int64_t *ho = (int64_t *)(pin + o_o), *hb = (int64_t *)(pin + o_b);
+  int32_t *hpn = (int32_t *)(pin + o_pair), *hpm = hpn + Q;
   // per-microbatch inputs of every (n, MB): b samples on one pipeline replica
   const __int128 lim = (__int128)1 << 62;
   for (int q = 0; q < Q; ++q) {
     hD[q] = in->devices_per_node * pairs[q].n;
     hS[q] = hD[q];
     hMB[q] = pairs[q].MB;
+    hpn[q] = pairs[q].n;
+    hpm[q] = pairs[q].MB;
     hoff[q] = (int64_t)q * N;
     for (int k = 0; k < N; ++k) {
       const int64_t ts = in->time_per_sample_ns[k], as = in->act_bytes_per_sample[k];
@@ -721,7 +730,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
     }
   }
   hoff[Q] = (int64_t)Q * N;
-  const size_t in_bytes = (split ? 5 : comm ? 4 : 3) * a_in;  // the regions in use are contiguous
+  // one copy up: the (n, MB) of every search and the block arrays in use are contiguous
+  const size_t in_bytes = o_t + (split ? 5 : comm ? 4 : 3) * a_in;
   if (hipMemcpyAsync(dev, pin, in_bytes, hipMemcpyHostToDevice, st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
@@ -730,6 +740,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   int32_t *d_ns = (int32_t *)(dev + o_ns), *d_st = d_ns + Q;
   int64_t *d_vals = (int64_t *)(dev + o_vals);
   int32_t *d_lev = (int32_t *)(dev + o_lev), *d_se = (int32_t *)(dev + o_se), *d_rp = (int32_t *)(dev + o_rp);
+  const int32_t *d_pn = (const int32_t *)(dev + o_pair), *d_pm = d_pn + Q;
+  int64_t *d_rec = (int64_t *)(dev + o_rec);
   rannc_dp_batch_t b;
   b.n_problems = Q;
   b.n_blocks = hN.data(); b.n_devices = hD.data(); b.max_stages = hS.data();
@@ -739,73 +751,49 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
   b.cut_bytes = comm ? (const int64_t *)(dev + o_o) : nullptr;
   b.time_bwd_ns = split ? (const int64_t *)(dev + o_b) : nullptr;
+  // Everything on the device, in stream order: the batched search, V[S][N][D] of every S, Algorithm
+  // 2's loops over those values (first n, then first S with a feasible MB; among those the smallest
+  // (MB + S - 1) * V, the first found among equals), the plan of the chosen (n, MB, S), and the
+  // record with that plan packed behind it.  One copy down, one wait.
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
   if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
+  if (rc == RANNC_DP_OK &&
+      rannc::launch_form_stage_select(Q, stride, N, in->n_nodes, in->devices_per_node, d_vals, d_st, d_pn, d_pm,
+                                      d_lev, d_rec, st) != hipSuccess) {
+    (void)hipGetLastError();
+    rc = RANNC_DP_HIP_ERROR;
+  }
+  if (rc == RANNC_DP_OK) rc = rannc_dp_traceback_at(h, hip_stream, d_lev, stride, d_se, d_rp);
+  if (rc == RANNC_DP_OK && rannc::launch_form_stage_pack(stride, d_se, d_rp, d_rec, st) != hipSuccess) {
+    (void)hipGetLastError();
+    rc = RANNC_DP_HIP_ERROR;
+  }
   if (rc != RANNC_DP_OK) {
     (void)hipStreamSynchronize(st);  // the mirror may be refilled by the next call
     return rc;
   }
-  // stage counts, status words and per-level values are adjacent: one copy down
-  if (hipMemcpyAsync(pin + o_ns, dev + o_ns, o_lev - o_ns, hipMemcpyDeviceToHost, st) != hipSuccess ||
+  if (hipMemcpyAsync(pin + o_rec, dev + o_rec, rec_bytes, hipMemcpyDeviceToHost, st) != hipSuccess ||
       hipStreamSynchronize(st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
   }
-  const int32_t *hns = (const int32_t *)(pin + o_ns);
-  const int64_t *hvals = (const int64_t *)(pin + o_vals);
-  for (int q = 0; q < Q; ++q) {
-    const int stq = hns[Q + q];
-    if (stq == RANNC_DP_PROBLEM_NEGATIVE_INPUT) return RANNC_DP_INVALID_ARG;
-    if (stq != RANNC_DP_PROBLEM_OK) return RANNC_DP_OVERFLOW;  // sums or times beyond the handle's width
-  }
-  // Algorithm 2's loops over the values of the solved batch: first n, then first S with a
-  // feasible MB; among those the smallest (MB + S - 1) * V, first found among equals
+  const int64_t *rec = (const int64_t *)(pin + o_rec);
+  const int stq = (int)rec[2];
+  if (stq == RANNC_DP_PROBLEM_NEGATIVE_INPUT) return RANNC_DP_INVALID_ARG;
+  if (stq != RANNC_DP_PROBLEM_OK) return RANNC_DP_OVERFLOW;  // sums or times beyond the handle's width
   std::memset(out, 0, sizeof(*out));
   for (int u = 0; u < plan_stride; ++u) stage_end[u] = replicas[u] = -1;
-  int q_sel = -1, S_sel = 0;
-  int64_t est_sel = 0;
-  for (int64_t n = 1; n <= in->n_nodes && q_sel < 0; n *= 2) {
-    const int dn = in->devices_per_node;
-    for (int S = dn * ((int)n - 1) + 1; S <= dn * (int)n && q_sel < 0; ++S) {
-      for (int q = 0; q < Q; ++q) {
-        if (pairs[q].n != n || S > std::min(N, hD[q])) continue;
-        const int64_t v = hvals[(size_t)q * stride + S - 1];
-        if (v == INT64_MAX) continue;
-        const __int128 e128 = (__int128)(pairs[q].MB + S - 1) * v;
-        const int64_t est = e128 > (__int128)INT64_MAX ? INT64_MAX : (int64_t)e128;
-        if (q_sel < 0 || est < est_sel) { q_sel = q; S_sel = S; est_sel = est; }
-      }
-    }
-  }
+  const int q_sel = (int)rec[0], S_sel = (int)rec[1];
   if (q_sel < 0) return RANNC_DP_OK;  // infeasible: out->feasible = 0
-  const int64_t v_sel = hvals[(size_t)q_sel * stride + S_sel - 1];  // the mirror is reused below
-  int32_t *hlev = (int32_t *)(pin + o_lev);
-  for (int q = 0; q < Q; ++q) hlev[q] = 0;
-  hlev[q_sel] = S_sel;
-  if (hipMemcpyAsync(d_lev, hlev, (size_t)Q * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
-    (void)hipGetLastError();
-    return RANNC_DP_HIP_ERROR;
-  }
-  rc = rannc_dp_traceback_at(h, hip_stream, d_lev, stride, d_se, d_rp);
-  if (rc != RANNC_DP_OK) {
-    (void)hipStreamSynchronize(st);
-    return rc;
-  }
-  int32_t *hse = (int32_t *)(pin + o_se), *hrp = (int32_t *)(pin + o_rp);
-  if (hipMemcpyAsync(hse, d_se + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
-      hipMemcpyAsync(hrp, d_rp + (size_t)q_sel * stride, (size_t)stride * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
-      hipStreamSynchronize(st) != hipSuccess) {
-    (void)hipGetLastError();
-    return RANNC_DP_HIP_ERROR;
-  }
+  const int32_t *hse = (const int32_t *)(rec + 6), *hrp = hse + stride;
   out->feasible = 1;
   out->n = pairs[q_sel].n;
   out->devices = hD[q_sel];
   out->replica_factor = in->n_nodes / pairs[q_sel].n;
   out->n_stages = S_sel;
   out->n_microbatches = pairs[q_sel].MB;
-  out->stage_time_ns = v_sel;
-  out->est_iter_ns = est_sel;
+  out->stage_time_ns = rec[4];
+  out->est_iter_ns = rec[5];
   for (int u = 0; u < std::min(stride, (int)plan_stride); ++u) { stage_end[u] = hse[u]; replicas[u] = hrp[u]; }
   return RANNC_DP_OK;
 }

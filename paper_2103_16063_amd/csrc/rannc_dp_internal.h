@@ -159,6 +159,13 @@ constexpr size_t compact_workspace_bytes(int G) {
 hipError_t launch_compact(int G, int k, int64_t M, int max_walks, const int64_t *t, const int64_t *p,
                           const int64_t *a, void *ws, int32_t *n_out, int32_t *block_end, int64_t *t_out,
                           int64_t *p_out, int64_t *a_out, int32_t *status, hipStream_t st);
+// outer driver: Algorithm 2's loops over the values of a solved batch, and the chosen plan packed
+// behind the result record (rec: 6 int64 {q, S, bad status, 0, V, estimate}, then 2*stride int32)
+hipError_t launch_form_stage_select(int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *vals,
+                                    const int32_t *status, const int32_t *pair_n, const int32_t *pair_mb,
+                                    int32_t *levels, int64_t *rec, hipStream_t st);
+hipError_t launch_form_stage_pack(int stride, const int32_t *stage_end, const int32_t *replicas, int64_t *rec,
+                                  hipStream_t st);
 hipError_t launch_export(const ProblemDev *prob, int which, int bits, void *d_dst, hipStream_t st);
 
 

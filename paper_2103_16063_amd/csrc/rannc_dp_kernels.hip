@@ -1357,6 +1357,97 @@ hipError_t launch_level_values(const ProblemDev *p, int Q, int stride, int64_t *
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Outer driver (Algorithm 2 "form_stage" of Sec. III-C), the loops over the solved batch: node
+// counts n = 1, 2, 4, ... in turn, for each the stage counts S ascending over
+// (devices_per_node*(n-1), devices_per_node*n], and for the first S that any search of that n can
+// realise (V[S][N][D] finite), the search with the smallest (MB + S - 1) * V, the first one in
+// batch order among equals.  One wave: a lane per search of the batch (in rounds of 64), the
+// candidates of one (n, S) reduced with the lexicographic minimum of (estimate, search index).
+// Writes the record {q, S, first bad status or 0, 0, V, estimate} and the forced-level array of
+// the plan recovery (S at the chosen search, 0 elsewhere).  q = -1: infeasible.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void form_stage_select_kernel(
+    int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *__restrict__ vals,
+    const int32_t *__restrict__ status, const int32_t *__restrict__ pair_n, const int32_t *__restrict__ pair_mb,
+    int32_t *__restrict__ levels, int64_t *__restrict__ rec) {
+  const int lane = threadIdx.x;
+  int bad = 0;
+  for (int q = lane; q < Q; q += 64) {
+    levels[q] = 0;
+    const int st = status[q];
+    if (st != 0 && bad == 0) bad = st;
+  }
+  // first bad status in batch order
+  unsigned long long m = __ballot(bad != 0);
+  int bad_all = 0;
+  if (m != 0ull) bad_all = __shfl(bad, __ffsll((long long)m) - 1);
+  int q_sel = -1, S_sel = 0;
+  int64_t v_sel = 0, est_sel = 0;
+  if (bad_all == 0) {
+    for (int n = 1; n <= n_nodes && q_sel < 0; n *= 2) {
+      const int D = devices_per_node * n;
+      for (int S = devices_per_node * (n - 1) + 1; S <= D && q_sel < 0; ++S) {
+        if (S > min(N, D)) break;  // no search of this n has that many levels
+        int64_t best_e = INT64_MAX, best_v = 0;
+        int best_q = 0x7fffffff;
+        for (int q = lane; q < Q; q += 64) {
+          if (pair_n[q] != n) continue;
+          const int64_t v = vals[(int64_t)q * stride + S - 1];
+          if (v == INT64_MAX) continue;
+          const int64_t f = (int64_t)pair_mb[q] + S - 1;
+          const int64_t e = (v != 0 && f > INT64_MAX / v) ? INT64_MAX : f * v;
+          if (best_q == 0x7fffffff || e < best_e) { best_e = e; best_v = v; best_q = q; }  // q ascends per lane
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+          const int64_t oe = __shfl_xor(best_e, o), ov = __shfl_xor(best_v, o);
+          const int oq = __shfl_xor(best_q, o);
+          if (oq != 0x7fffffff && (best_q == 0x7fffffff || oe < best_e || (oe == best_e && oq < best_q))) {
+            best_e = oe; best_v = ov; best_q = oq;
+          }
+        }
+        if (best_q != 0x7fffffff) { q_sel = best_q; S_sel = S; v_sel = best_v; est_sel = best_e; }
+      }
+    }
+  }
+  if (lane == 0) {
+    if (q_sel >= 0) levels[q_sel] = S_sel;
+    rec[0] = q_sel;
+    rec[1] = S_sel;
+    rec[2] = bad_all;
+    rec[3] = 0;
+    rec[4] = v_sel;
+    rec[5] = est_sel;
+  }
+}
+
+// The chosen search's plan, copied behind the record so that one copy brings everything to the host.
+__global__ __launch_bounds__(64) void form_stage_pack_kernel(int stride, const int32_t *__restrict__ stage_end,
+                                                             const int32_t *__restrict__ replicas,
+                                                             int64_t *__restrict__ rec) {
+  const int q = (int)rec[0];
+  int32_t *plan = (int32_t *)(rec + 6);
+  for (int u = threadIdx.x; u < stride; u += 64) {
+    plan[u] = q >= 0 ? stage_end[(int64_t)q * stride + u] : -1;
+    plan[stride + u] = q >= 0 ? replicas[(int64_t)q * stride + u] : -1;
+  }
+}
+
+hipError_t launch_form_stage_select(int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *vals,
+                                    const int32_t *status, const int32_t *pair_n, const int32_t *pair_mb,
+                                    int32_t *levels, int64_t *rec, hipStream_t st) {
+  hipLaunchKernelGGL(form_stage_select_kernel, dim3(1), dim3(64), 0, st, Q, stride, N, n_nodes, devices_per_node, vals,
+                     status, pair_n, pair_mb, levels, rec);
+  return hipGetLastError();
+}
+
+hipError_t launch_form_stage_pack(int stride, const int32_t *stage_end, const int32_t *replicas, int64_t *rec,
+                                  hipStream_t st) {
+  hipLaunchKernelGGL(form_stage_pack_kernel, dim3(1), dim3(64), 0, st, stride, stage_end, replicas, rec);
+  return hipGetLastError();
+}
+
 hipError_t launch_export(const ProblemDev *p, int which, int bits, void *d_dst, hipStream_t st) {
   const dim3 grid(1024), block(256);
   if (which != RANNC_DP_TABLE_ARG_I && which != RANNC_DP_TABLE_ARG_D) {
