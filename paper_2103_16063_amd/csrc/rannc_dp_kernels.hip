@@ -986,6 +986,24 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
 // value: one row read and one division per split point, and the reads of one pass (192 rows)
 // do not depend on each other.
 // ---------------------------------------------------------------------------------------
+// Whether max(a, h) == v for the stage time h = ceil(x/r) + ceil(C/r) of Sec. III-C, given a <= v.
+// The stage's time comes from the prefix sums (the table may not have been built); x is compared
+// with multiples of r instead of being divided by it (a 64-bit division costs far more than the
+// rest of a pass).  C is the same for every lane, so its branch does not diverge.
+__device__ __forceinline__ bool stage_time_completes(uint64_t x, uint64_t C, int r, uint64_t a, uint64_t v) {
+  uint64_t w = v;  // what ceil(x/r) may reach at most, and has to reach when a < v
+  if (C) {
+    const uint64_t hc = (C + (uint64_t)(r - 1)) / (uint64_t)r;
+    if (hc > v) return false;
+    w = v - hc;
+  }
+  // ceil(x/r) <= w  <=>  x <= w r
+  if (__umul64hi(w, (uint64_t)r) == 0 && x > w * (uint64_t)r) return false;
+  if (a == v || w == 0) return true;
+  // ceil(x/r) >= w  <=>  x > (w-1) r
+  return __umul64hi(w - 1, (uint64_t)r) == 0 && x > (w - 1) * (uint64_t)r;
+}
+
 template <typename VT, int DP>
 __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
                                unsigned int *best_key, int forced) {
@@ -1025,9 +1043,20 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
         const int i = top - (wave + nw * k);
         a[k] = (i >= s - 1 && lane < DP) ? Vp[(int64_t)i * DP + lane] : INF;  // lane = d'-1
       }
+      // the row lane < KB is responsible for: its fits-in-memory byte and prefix sum are read in the
+      // same round trip as the rows (their addresses depend on nothing that is loaded; a row
+      // outside the range is clamped into it and ignored below)
+      const int i = top - (wave + nw * lane);
+      const int ic = min(max(i, s - 1), j - 1);
+      int rmn = 0;
+      int64_t Ti = 0;
+      if (lane < KB) {  // the other lanes would only fetch lines nobody needs
+        rmn = (int)rmin[unit_index(nch, ic, c) * 64 + (jj & 63)];
+        Ti = T[ic];
+      }
       // per row: smallest d' in [s-1, d-1] with a[d'] <= v (smaller d' cannot match, and if this
       // one does not match no larger one does: c only grows as r = d - d' shrinks); lane k then
-      // checks row k against the table
+      // checks row k against the stage time
       int my_d = 0;
       VT my_a = INF;
 #pragma unroll
@@ -1040,15 +1069,10 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
           if (lane == k) { my_d = q + 1; my_a = aq; }
         }
       }
-      const int i = top - (wave + nw * lane);  // the row lane < KB is responsible for
       if (lane < KB && my_d != 0 && i >= first && v != INF) {
-        const int64_t u = unit_index(nch, i, c);
         const int r = d - my_d;
-        const int rmn = (int)rmin[u * 64 + (jj & 63)];
-        // the stage's time from the prefix sums (the table may not have been built)
-        uint64_t h = ((uint64_t)(Tj - T[i]) + (uint64_t)(r - 1)) / (uint64_t)r;
-        if (Cj) h += (Cj + (uint64_t)(r - 1)) / (uint64_t)r;
-        if (r >= rmn && vmax(my_a, (VT)h) == v) mine = min(mine, ((unsigned)i << 8) | (unsigned)my_d);
+        if (r >= rmn && stage_time_completes((uint64_t)(Tj - Ti), Cj, r, (uint64_t)my_a, (uint64_t)v))
+          mine = min(mine, ((unsigned)i << 8) | (unsigned)my_d);
       }
       if (top - nw * KB < first) break;  // the remaining rows lie below the window
     }
