@@ -34,10 +34,16 @@ ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configuratio
 # 1.000 KiB per dispatch, factors from the 256 MiB copy of the same runs).  These are NOT measured by
 # this script: each entry names the committed summary it was copied from, and the JSON line repeats
 # that name next to the number, so a reader can see where it comes from and whether it is stale.
+# Keys: (workload, 64-bit tables, stage times recomputed in some class).  For config 5 a "launch" is
+# one of the 32 launches of the level phase (15 levels of the D = 32 and D = 64 classes, the two
+# one-launch kernels of the D = 8 and D = 16 classes, tables included): their bytes summed, over 32.
 PMC_TRAFFIC = {
-    "c4": (26.94e6, "profiles/level_merge_config4.md"),
-    "c4dense": (115.83e6, "profiles/level_merge_config4_dense.md"),
-    "c5": (805.9e6, "profiles/level_merge_config5_batched.md"),
+    ("c4", False, False): (29.45e6, "profiles/level_merge_config4.md"),
+    ("c4", True, False): (48.33e6, "profiles/level_merge_config4_wide.md"),
+    ("c4dense", False, False): (109.94e6, "profiles/level_merge_config4_dense.md"),
+    ("c4dense", False, True): (14.72e6, "profiles/level_merge_config4_dense_recompute.md"),
+    ("c5", False, True): (186.0e6, "profiles/level_merge_config5_batched.md"),
+    ("c5", False, False): (799.6e6, "profiles/level_merge_config5_batched_table.md"),
 }
 # useful vector instructions of the sorted-merge level kernel per (i, j) stage: DP maxima that form
 # the bitonic sequence, then log2(DP) compare-exchange stages of DP/2 (max, min) pairs
@@ -235,7 +241,7 @@ def run_workload(name, steps, warmup, wide=False, algo="auto"):
     recompute = recompute_any
     t_levels = phase[1] * 1e-3
     hbm = own_bytes / t_levels / 1e9
-    traffic, traffic_src = (None, None) if (wide or recompute) else PMC_TRAFFIC.get(name, (None, None))
+    traffic, traffic_src = PMC_TRAFFIC.get((name, bool(wide), bool(recompute)), (None, None))
     if split:
         useful = tot["cands"] * SPLIT_VALU_PER_UPDATE
         alu = useful / t_levels / 1e12

@@ -179,16 +179,16 @@ RANNC_DP_API int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *batch, vo
                    int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est_iter_ns,
                    int32_t *d_status);
 
-/* Enqueue plan recovery for the batch of the last solve ("b_i and d_i that produce
- * V[S][|B|][D]", Algorithm 1's return): per problem, stage u (1-based) ends after block
- * d_stage_end[q*plan_stride + u-1] (so the last used slot holds N_q) and runs on
+/* Enqueue plan recovery for the batch of the last solve (what Algorithm 1 returns: the stage
+ * boundaries and replica counts behind the optimal table value): per problem, stage u (1-based)
+ * ends after block d_stage_end[q*plan_stride + u-1] (so the last used slot holds N_q) and runs on
  * d_replicas[q*plan_stride + u-1] devices (they sum to D_q).  Slots from s* on are -1.
  * plan_stride must be >= min(S_q,N_q,D_q) for every problem of the batch. */
 RANNC_DP_API int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride,
                        int32_t *d_stage_end, int32_t *d_replicas);
 
 /* As rannc_dp_traceback, but for problem q the plan of EXACTLY d_levels[q] stages is recovered
- * (Algorithm 1's own answer, "b_i and d_i that produce V[S][|B|][D]", for a given S) when
+ * (Algorithm 1's own answer for a given S: the boundaries and replica counts behind V[S][|B|][D]) when
  * d_levels[q] > 0; all slots are -1 if no plan of that many stages exists.  d_levels[q] == 0 or
  * d_levels == NULL: the best stage count chosen by solve.  d_levels: DEVICE int32[Q]. */
 RANNC_DP_API int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels,

@@ -84,7 +84,7 @@ struct ProblemDev {
   uint8_t *ufit;               // per unit: 1 if any of its stages fits for some r <= D
   int32_t *wlo;                // [nch] smallest row i with a stage (i, j in chunk) that fits for some
                                // r <= D; 0x7fffffff if none
-  int32_t *runs;               // runs[0] = count, then (c << 16 | first row) per work item
+  int32_t *runs;               // runs[0] = count, then ((rows - 1) << 26 | c << 16 | first row) per work item
   int32_t *status;             // RANNC_DP_PROBLEM_*
   int64_t *res;                // res[0] = opt (int64, INT64_MAX if none), res[1] = n_stages
 };

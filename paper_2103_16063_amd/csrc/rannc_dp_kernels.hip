@@ -976,15 +976,16 @@ __global__ __launch_bounds__(64) void select_kernel(const ProblemDev *__restrict
 }
 
 // ---------------------------------------------------------------------------------------
-// Plan recovery (Algorithm 1's return value: the b_i and d_i that produce V[S][|B|][D]).
+// Plan recovery (Algorithm 1's return value: the stage boundaries and replica counts behind the
+// optimal table value).
 // One workgroup per problem walks from (s*, N, D) down to level 1.  At each cell it finds the
 // lexicographically smallest (i, d') with max(V[s-1][i][d'], h(i,j,d-d')) equal to the cell's
 // value: the candidate that the ascending scan with strict "<" of Algorithm 1 would have kept.
 // A wave owns a split point i and reads the row V[s-1][i][.] with one coalesced request (lane =
 // d'-1).  Both that row and h(i,j,.) are non-increasing (the property the merge kernel rests on),
 // so in row i the only candidate is the smallest d' whose earlier-stages value is <= the cell's
-// value: one row read and one division per split point, and the reads of one pass (192 rows)
-// do not depend on each other.
+// value: one row read and one comparison of the stage's time per split point, and the reads of one
+// pass (192 rows) do not depend on each other.
 // ---------------------------------------------------------------------------------------
 // Whether max(a, h) == v for the stage time h = ceil(x/r) + ceil(C/r) of Sec. III-C, given a <= v.
 // The stage's time comes from the prefix sums (the table may not have been built); x is compared
