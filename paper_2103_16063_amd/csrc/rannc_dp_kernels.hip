@@ -134,38 +134,80 @@ __global__ __launch_bounds__(256) void fill_kernel(const ProblemDev *__restrict_
 // ---------------------------------------------------------------------------------------
 constexpr int kBuildWaves = 4;
 
-// The D entries of one stage (i,j): ceil(tij / r) (+ ceil(cj / r) with the communication term), INF
-// below rmin.  r is a compile-time constant after unrolling, so the divisions are multiplications.
-template <typename VT, int DP, bool COMM>
-__device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RANNC_GLOBAL *crow,
-                                           VT RANNC_GLOBAL *v1, VT *lds1) {
+// ceil(x / r) for every r = 1..DP of a 32-bit x, without integer division: for odd r one
+// double-precision add and one fused multiply-add whose low word is the quotient (the derivation
+// stands at DirectConsts below), for even r an add and a shift from ceil(x / (r/2)).
+template <int DP>
+__device__ __forceinline__ void ceil_div_all(uint32_t x, uint32_t (&q)[DP + 1]) {
+  const double xf = (double)x;
+  double magic = 0x1.8p52;
+  asm("" : "+v"(magic));  // one register for all entries instead of a literal per instruction
 #pragma unroll
   for (int r = 1; r <= DP; ++r) {
-    if (r > D) break;
-    const VT q = tij / (VT)r;
-    VT h = q + (VT)(q * (VT)r != tij);  // ceil
-    if (COMM) {
-      const VT qc = cj / (VT)r;
-      h += qc + (VT)(qc * (VT)r != cj);
+    if (r & 1) {
+      const double add = (double)r / 2.0 - 1.0 + (double)r * 0x1p-18;
+      const double y = __builtin_fma(xf + add, 1.0 / (double)r, magic);
+      q[r] = (uint32_t)__double_as_longlong(y);
+    } else {
+      q[r] = (q[r / 2] + 1u) >> 1;
     }
-    const VT v = (r >= rmin) ? h : Lim<VT>::inf;
-    if (crow) crow[(r - 1) * 64] = v;
-    if (v1) v1[r - 1] = v;
-    if (lds1) lds1[r - 1] = v;
+  }
+}
+
+// The D entries of one stage (i,j): ceil(tij / r) (+ ceil(cj / r) with the communication term), INF
+// below rmin.  NODIV: 32-bit values take the division-free form above (the table builder was bound
+// by the quarter-rate integer multiplies of 64 divisions by constants per stage, not by its stores;
+// the one-launch kernel, which has 128 registers per lane, keeps the integer form).  Otherwise r is
+// a compile-time constant after unrolling, so the divisions are multiplications.
+template <typename VT, int DP, bool COMM, bool NODIV>
+__device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RANNC_GLOBAL *crow, VT *lds1) {
+  constexpr bool FAST = NODIV && sizeof(VT) == 4;
+  [[maybe_unused]] uint32_t qt[DP + 1], qc[DP + 1];
+  if constexpr (FAST) {
+    ceil_div_all<DP>((uint32_t)tij, qt);
+    if (COMM) ceil_div_all<DP>((uint32_t)cj, qc);
+  }
+  auto entry = [&](const int r) -> VT {  // r is a compile-time number wherever this is called
+    VT h;
+    if constexpr (FAST) {
+      h = qt[r];
+      if (COMM) h += qc[r];
+    } else {
+      const VT q = tij / (VT)r;
+      h = q + (VT)(q * (VT)r != tij);  // ceil
+      if (COMM) {
+        const VT qq = cj / (VT)r;
+        h += qq + (VT)(qq * (VT)r != cj);
+      }
+    }
+    return (r >= rmin) ? h : Lim<VT>::inf;
+  };
+  // one straight run of stores per destination; r <= D is a scalar test (every r keeps its own
+  // code: the quotient arrays stay in registers only with compile-time indices)
+  if (crow) {
+#pragma unroll
+    for (int r = 1; r <= DP; ++r)
+      if (r <= D) crow[(r - 1) * 64] = entry(r);
+  }
+  if (lds1) {
+#pragma unroll
+    for (int r = 1; r <= DP; ++r)
+      if (r <= D) lds1[r - 1] = entry(r);
   }
 }
 
 // One unit (row i, chunk c) of the tables, by one wave.  T, P, A, Cc may live in global memory or in
 // LDS; Cc (per-cut send time at one replica, Cc[N] = 0) is null when there is no communication
-// term.  Returns whether any stage of the unit fits.  If lds_level1 is given, row 0's entries
-// (= level 1 of V) are also written there with row stride ls.  with_times = false: only the
-// fits-in-memory part (rmin, ufit) and level 1 of V are written, for searches whose level kernel
-// recomputes the stage times (level 1 already written: only the stage-time rows, for an export).
-template <typename VT, int DP>
+// term.  Returns whether any stage of the unit fits.  Row 0's entries are level 1 of V: with
+// lds_level1 given they go to LDS, row (j - row0) with row stride ls, and the caller copies them to
+// the value table (a lane's D values are a row of V, so writing them from here would scatter every
+// store instruction over 64 cache lines).  with_times = false: only the fits-in-memory part (rmin,
+// ufit) and level 1 are produced, for searches whose level kernel recomputes the stage times.
+template <typename VT, int DP, bool NODIV = false>
 __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *T, const int64_t *P,
                                            const int64_t *A, const int64_t *Cc, int i, int c, int lane,
-                                           VT *lds_level1, int ls, const int64_t *TBp = nullptr,
-                                           const bool with_times = true, const bool with_level1 = true) {
+                                           VT *lds_level1, int ls, int row0, const int64_t *TBp = nullptr,
+                                           const bool with_times = true) {
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
@@ -192,32 +234,61 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
   // A unit in which no stage fits for any r is never read (every reader consults ufit or rmin
   // first): only those are written.  Row 0 also carries level 1 and is always written.
   if (!unit_fits && i != 0) return unit_fits;
-  if (!with_times && i != 0) return unit_fits;
+  if (!with_times && !(i == 0 && lds_level1)) return unit_fits;
   VT RANNC_GLOBAL *crow = with_times ? gptr((VT *)pr.cost) + u * 64 * D + lane : nullptr;
-  VT RANNC_GLOBAL *v1 = (i == 0 && with_level1) ? gptr((VT *)pr.V) + (int64_t)j * DP : nullptr;
+  VT *lds1 = (i == 0 && lds_level1) ? lds_level1 + (j - row0) * ls : nullptr;
   const VT tij = (VT)Tij;
   if (Cc)  // wave-uniform: with the stage's own send time at one replica (0 for j = N)
-    build_rows<VT, DP, true>(tij, (VT)Cc[j], rmin, D, crow, v1,
-                             (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
+    build_rows<VT, DP, true, NODIV>(tij, (VT)Cc[j], rmin, D, crow, lds1);
   else
-    build_rows<VT, DP, false>(tij, (VT)0, rmin, D, crow, v1,
-                              (i == 0 && lds_level1) ? lds_level1 + j * ls : nullptr);
+    build_rows<VT, DP, false, NODIV>(tij, (VT)0, rmin, D, crow, lds1);
   if (TBp && with_times)  // split objective: the backward times get a table of their own (never a send time)
-    build_rows<VT, DP, false>((VT)(TBp[j] - TBp[i]), (VT)0, rmin, D,
-                              gptr((VT *)pr.costb) + u * 64 * D + lane, nullptr, nullptr);
+    build_rows<VT, DP, false, NODIV>((VT)(TBp[j] - TBp[i]), (VT)0, rmin, D,
+                              gptr((VT *)pr.costb) + u * 64 * D + lane, nullptr);
   return unit_fits;
 }
 
 // parts: 1 = fits-in-memory tables and level 1 of V only, 3 = those and the stage-time table,
 // 2 = the stage-time table alone (added later to a search that was solved without it)
-template <typename VT, int DP>
+// A wave takes `rows` consecutive rows of one chunk, one after the other: one row when the
+// stage-time table is written (64 row stores per unit keep it busy), several when only the
+// fits-in-memory part is (a unit is then 65 bytes of output, and a launch of one wave per unit is
+// bound by the rate at which waves can be started).
+template <typename VT, int DP, int ROWS>
 __global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs,
                                                                  const int parts) {
   const ProblemDev &pr = probs[blockIdx.z];
-  const int i = blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6), c = blockIdx.x;
-  if (i >= pr.N || c >= pr.nch || c < (i >> 6)) return;
-  (void)build_unit<VT, DP>(pr, pr.T, pr.P, pr.A, pr.C, i, c, threadIdx.x & 63, nullptr, 0, pr.TB,
-                           (parts & 2) != 0, (parts & 1) != 0);
+  const int lane = threadIdx.x & 63;
+  const int i0 = (blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6)) * ROWS, c = blockIdx.x;
+  __shared__ VT tile[64 * (DP + 1)];  // level 1 of this chunk (only the wave that holds row 0 uses it)
+  if (c >= pr.nch) return;
+  auto one_row = [&](const int i) {
+    const bool level1 = i == 0 && (parts & 1);
+    (void)build_unit<VT, DP, true>(pr, pr.T, pr.P, pr.A, pr.C, i, c, lane, level1 ? tile : nullptr, DP + 1, 64 * c + 1,
+                                   pr.TB, (parts & 2) != 0);
+    if (level1) {
+      // rows j = 64c+1 .. of level 1 are contiguous in V: written with consecutive lanes on
+      // consecutive words (columns d > D keep the zeros of the fill)
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      const int D = pr.D, nrow = min(64, pr.N - 64 * c);
+      VT RANNC_GLOBAL *v1 = gptr((VT *)pr.V) + (int64_t)(64 * c + 1) * DP;
+      for (int e = lane; e < nrow * DP; e += 64) {
+        const int row = e / DP, col = e % DP;
+        if (col < D) v1[e] = tile[row * (DP + 1) + col];
+      }
+    }
+  };
+  if constexpr (ROWS == 1) {
+    // straight-line: the wave ends behind its last store without waiting for it
+    if (i0 < pr.N && c >= (i0 >> 6)) one_row(i0);
+  } else {
+#pragma unroll 1
+    for (int i = i0; i < min(i0 + ROWS, pr.N); ++i) {
+      if (c < (i >> 6)) break;  // the rows from here on have no column in this chunk
+      one_row(i);
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -743,7 +814,7 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   const int R0 = min(64, N), RT = R0 + (nch > 1 ? N : 0);
   for (int f = wave; f < RT; f += kSmallWaves) {
     const int c = f >= R0, i = c ? f - R0 : f;
-    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, pr.o ? sC : nullptr, i, c, lane, lv[0], LS);
+    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, pr.o ? sC : nullptr, i, c, lane, lv[0], LS, 0);
     if (fits && lane == 0) atomicMin(&s_wlo[c], i);
   }
   __syncthreads();
@@ -752,11 +823,8 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   VT RANNC_GLOBAL *Vg = gptr((VT *)pr.V);
   const VT RANNC_GLOBAL *cost = gptr((const VT *)pr.cost);
   const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
-  // level 1, rows that build_unit did not touch (j = 0) and the padding columns, to memory
-  for (int e = tid; e < (N + 1) * DP; e += NT) {
-    const int j = e / DP, k = e % DP;
-    if (j == 0 || k >= D) Vg[e] = lv[0][j * LS + k];
-  }
+  // level 1 to memory
+  for (int e = tid; e < (N + 1) * DP; e += NT) Vg[e] = lv[0][(e / DP) * LS + (e % DP)];
   if (tid == 0) s_top[0] = lv[0][N * LS + D - 1];
 
   // ---- levels 2..S_eff ----
@@ -1261,13 +1329,17 @@ hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStr
   return hipGetLastError();
 }
 
+constexpr int kBuildRowsFitOnly = 8;  // rows per wave when only the fits-in-memory part is built
+
 template <typename VT, int DP>
 static void build_go(const ProblemDev *p, const LaunchShape &sh, int parts, hipStream_t st) {
+  const int rows = (parts & 2) ? 1 : kBuildRowsFitOnly;
+  const int per_group = kBuildWaves * rows;
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((build_kernel<VT, DP>),
-                       dim3(sh.max_nch, (sh.max_N + kBuildWaves - 1) / kBuildWaves, nq),
-                       dim3(64 * kBuildWaves), 0, st, p + q0, parts);
+    const dim3 grid(sh.max_nch, (sh.max_N + per_group - 1) / per_group, nq), block(64 * kBuildWaves);
+    if (rows == 1) hipLaunchKernelGGL((build_kernel<VT, DP, 1>), grid, block, 0, st, p + q0, parts);
+    else hipLaunchKernelGGL((build_kernel<VT, DP, kBuildRowsFitOnly>), grid, block, 0, st, p + q0, parts);
   }
 }
 

@@ -213,8 +213,9 @@ def test_recomputed_stage_times_at_the_edges_of_the_value_range():
         for q in range(len(probs)):
             assert np.array_equal(sm.table(B.TABLE_V, q), sr.table(B.TABLE_V, q)), q
         assert_results_match(probs, rr)
-        for q in (2, 6, 10):
+        for q in (0, 1, 2, 3, 5, 10, 15, 20):   # every kind of total; the table builder divides the same way
             assert_tables_match(probs[q], sr, q, args=False)
+            assert_tables_match(probs[q], sm, q, args=False)
 
 
 @pytest.mark.parametrize("algo", [B.ALGO_MERGE, B.ALGO_RECOMPUTE])
