@@ -318,50 +318,60 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // work at the front of the grid.  The number of rows of an item travels in the top bits of its
 // descriptor: (rows - 1) << 26 | c << 16 | first row.  rows > 0: items of that many rows.
 // rows = 0 (split-objective level kernel): 16, 8 or 4 rows, from the size of all windows together.
-// rows = -1 (sorted-merge level kernel): the smallest of 4, 8, 16, 32, 64 rows whose item count
+// rows = -1 (sorted-merge level kernel): the smallest multiple of 4 (up to 64) whose item count
 // fits max_items, the grid the host launches (sized for the rows of an unpruned search: small
 // items, i.e. many workgroups and a short critical path, when pruning leaves few rows; large ones,
 // i.e. fewer folds and atomics per row, when the launch is full anyway; and never a workgroup
-// without an item in a launch over many searches).  One step larger if that brings a launch that
-// needs a little more than one round of workgroups (`slots` run at a time, `batch` searches in the
-// launch) down to one round that still fills half the device.  One workgroup per problem.
+// without an item in a launch over many searches).  If that launch needs more than one round of
+// workgroups (`slots` run at a time, `batch` searches in the launch), the smallest item size that
+// brings it down to one round is taken instead, provided the round still fills half the device:
+// the round is then as full as it can be, and no compute unit is left with one workgroup more
+// than its neighbours.  One workgroup per problem.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int max_items,
                                                     int batch, int slots) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
-  __shared__ int total_rows, count[5];
+  constexpr int NC = 16;  // candidate item sizes 4, 8, ..., 64 rows
+  __shared__ int total_rows, count[NC];
   const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
   if (rows <= 0) {
-    if (tid < 5) count[tid] = 0;
+    if (tid < NC) count[tid] = 0;
     if (tid == 0) total_rows = 0;
     __syncthreads();
-    int mine = 0, cnt[5] = {0, 0, 0, 0, 0};
+    int mine = 0, cnt[NC];
+#pragma unroll
+    for (int k = 0; k < NC; ++k) cnt[k] = 0;
     for (int c = tid; c < nch; c += 256) {
       const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
       if (lo <= hi) {
         mine += hi - lo + 1;
 #pragma unroll
-        for (int k = 0; k < 5; ++k) cnt[k] += (hi - lo + (4 << k)) / (4 << k);
+        for (int k = 0; k < NC; ++k) cnt[k] += (hi - lo + 4 * (k + 1)) / (4 * (k + 1));
       }
     }
     if (mine) {
       atomicAdd(&total_rows, mine);
 #pragma unroll
-      for (int k = 0; k < 5; ++k) atomicAdd(&count[k], cnt[k]);
+      for (int k = 0; k < NC; ++k) atomicAdd(&count[k], cnt[k]);
     }
     __syncthreads();
     if (rows == 0) {
       rows = total_rows >= 16 * 1024 ? 16 : total_rows >= 8 * 1024 ? 8 : kSplitMinRows;
     } else {
-      int pick = 4;
-      for (int k = 4; k >= 0; --k)
+      int pick = NC - 1;
+      for (int k = NC - 1; k >= 0; --k)
         if (count[k] <= max_items) pick = k;
-      if (pick < 4) {
-        const long long now = (long long)count[pick] * batch, then = (long long)count[pick + 1] * batch;
-        if (now > slots && then <= slots && 2 * then >= slots) ++pick;
+      if ((long long)count[pick] * batch > slots) {
+        for (int k = pick + 1; k < NC; ++k) {
+          const long long then = (long long)count[k] * batch;
+          if (then <= slots) {
+            if (2 * then >= slots) pick = k;
+            break;
+          }
+        }
       }
-      rows = 4 << pick;
+      rows = 4 * (pick + 1);
     }
   }
   const int tag = (rows - 1) << 26;
