@@ -190,7 +190,9 @@ RANNC_DP_API int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t pla
 /* As rannc_dp_traceback, but for problem q the plan of EXACTLY d_levels[q] stages is recovered
  * (Algorithm 1's own answer for a given S: the boundaries and replica counts behind V[S][|B|][D]) when
  * d_levels[q] > 0; all slots are -1 if no plan of that many stages exists.  d_levels[q] == 0 or
- * d_levels == NULL: the best stage count chosen by solve.  d_levels: DEVICE int32[Q]. */
+ * d_levels == NULL: the best stage count chosen by solve.  d_levels[q] < 0: no plan is recovered for
+ * problem q (all its slots are -1; a caller that wants one plan out of a batch pays for one walk).
+ * d_levels: DEVICE int32[Q]. */
 RANNC_DP_API int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels,
                                        int32_t plan_stride, int32_t *d_stage_end, int32_t *d_replicas);
 
@@ -339,6 +341,7 @@ RANNC_DP_API int rannc_dp_read_table(rannc_dp_t *h, int which, int32_t problem, 
 #define RANNC_DP_KERNEL_SCAN 4            /* literal scan */
 #define RANNC_DP_KERNEL_SPLIT 5           /* split objective, packed winners */
 #define RANNC_DP_KERNEL_SPLIT_SCAN 6      /* split objective, literal scan */
+#define RANNC_DP_KERNEL_ONE_LAUNCH_RECOMPUTE 7 /* one launch per search, stage times recomputed */
 typedef struct {
   int32_t n_problems[4];
   int32_t level_kernel[4];  /* RANNC_DP_KERNEL_* */

@@ -50,7 +50,7 @@ class SolveInfo(C.Structure):
 
 
 KERNEL_NONE, KERNEL_MERGE_TABLE, KERNEL_MERGE_RECOMPUTE, KERNEL_ONE_LAUNCH, KERNEL_SCAN, KERNEL_SPLIT, \
-    KERNEL_SPLIT_SCAN = range(7)
+    KERNEL_SPLIT_SCAN, KERNEL_ONE_LAUNCH_RECOMPUTE = range(8)
 
 
 class Batch(C.Structure):

@@ -434,6 +434,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     }
   }
   bool fused[4] = {false, false, false, false};
+  bool fused_direct[4] = {false, false, false, false};  // one-launch kernel that recomputes the stage times
   int merge_items[4] = {1, 1, 1, 1};
   for (int k = 0; k < 4 && ok; ++k) {
     const LaunchShape &sh = shape[k];
@@ -449,10 +450,21 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     // faster (up to 10x at N = 128, D = 64).
     {
       const int64_t rows = std::min(sh.max_N, 64) + (sh.max_nch > 1 ? sh.max_N : 0);
+      const int levels = sh.max_S_eff - 1;
       const bool batch = sh.nprob >= 256 && (kClasses[k] <= 16 || sh.max_N <= 64);
-      const bool tiny = rows * (sh.max_S_eff - 1) <= 480;
+      // the one-launch kernel that recomputes the stage times reads nothing from memory in its
+      // levels: a level costs it (rows / 16 waves) passes of 0.75 / 1.25 / 1.7 us (8 / 16 / 32
+      // devices; four waves share a SIMD), a level launch costs 4.5 us and the launches in front of
+      // the levels 27 us (N = 32, D = 32, 31 levels: 111 against 172 us; N = 96, D = 16, 7 levels:
+      // 94 against 49 us)
+      const bool direct_ok = can_recompute && h->lim.algo != RANNC_DP_ALGO_MERGE &&
+                             rannc::small_can_recompute(h->bits, kClasses[k]);
+      const double pass_us = kClasses[k] <= 8 ? 0.75 : kClasses[k] <= 16 ? 1.25 : 1.7;
+      const bool tiny = direct_ok ? (double)((rows + 15) / 16) * pass_us * levels <= 4.5 * levels + 27.0
+                                  : rows * levels <= 480;
       fused[k] = !scan && !split && sh.max_N <= rannc::small_max_blocks() &&
                  (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);
+      fused_direct[k] = fused[k] && direct_ok;
     }
     if (fused[k]) continue;
     ok = rannc::launch_prefix(cp, sh.nprob, st) == hipSuccess;
@@ -475,7 +487,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   int max_levels = 0;
   for (int k = 0; k < 4; ++k) {
     if (fused[k]) {
-      ok = ok && rannc::launch_solve_small(dp + cls_start[k], shape[k].nprob, h->bits, kClasses[k], d_opt,
+      ok = ok && rannc::launch_solve_small(dp + cls_start[k], shape[k].nprob, h->bits, kClasses[k], fused_direct[k], d_opt,
                                            d_n_stages, d_est_iter_ns, d_status, cs[k]) == hipSuccess;
       h->level_launches++;
     } else {
@@ -518,10 +530,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   }
   h->ev_valid = timing;
   for (int k = 0; k < 4; ++k) {
-    h->no_times[k] = recompute_cls[k] && !fused[k];
+    h->no_times[k] = fused[k] ? fused_direct[k] : recompute_cls[k];
     h->info.n_problems[k] = shape[k].nprob;
     h->info.level_kernel[k] = !shape[k].nprob ? RANNC_DP_KERNEL_NONE
-                              : fused[k]      ? RANNC_DP_KERNEL_ONE_LAUNCH
+                              : fused[k]      ? (fused_direct[k] ? RANNC_DP_KERNEL_ONE_LAUNCH_RECOMPUTE : RANNC_DP_KERNEL_ONE_LAUNCH)
                               : split_fast    ? RANNC_DP_KERNEL_SPLIT
                               : split         ? RANNC_DP_KERNEL_SPLIT_SCAN
                               : scan          ? RANNC_DP_KERNEL_SCAN
@@ -535,6 +547,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   return RANNC_DP_OK;
 }
 
+constexpr int kTracebackStagedMaxProblems = 64;
+
 int rannc_dp_solve_info(rannc_dp_t *h, rannc_dp_solve_info_t *out) {
   if (!h || !out) return RANNC_DP_INVALID_ARG;
   if (!h->solved) return RANNC_DP_BAD_STATE;
@@ -546,9 +560,20 @@ int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_leve
                           int32_t *d_stage_end, int32_t *d_replicas) {
   if (!h || !d_stage_end || !d_replicas || plan_stride < 1) return RANNC_DP_INVALID_ARG;
   if (!h->solved) return RANNC_DP_BAD_STATE;
-  for (int q = 0; q < h->Q; ++q)
-    if (h->host_probs[q].S_eff > plan_stride) return RANNC_DP_INVALID_ARG;
-  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas, d_levels,
+  // A few small min-max searches: the walk runs out of LDS (one round of reads instead of one
+  // memory round trip per stage).  Many searches fill the device anyway, and a workgroup that holds
+  // most of a compute unit's LDS would then only lower the number in flight.
+  int64_t lds_bytes = 0;
+  bool staged = h->Q <= kTracebackStagedMaxProblems;
+  for (int q = 0; q < h->Q; ++q) {
+    const ProblemDev &p = h->host_probs[q];
+    if (p.S_eff > plan_stride) return RANNC_DP_INVALID_ARG;
+    const int64_t need = rannc::traceback_lds_bytes(p.N, p.DP, p.S_eff, p.bits);
+    staged = staged && !p.VF && need <= rannc::kTracebackLdsMax;
+    lds_bytes = std::max(lds_bytes, need);
+  }
+  if (!staged) lds_bytes = 0;
+  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas, d_levels, lds_bytes,
                               (hipStream_t)hip_stream) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;

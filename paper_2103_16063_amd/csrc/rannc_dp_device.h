@@ -51,6 +51,11 @@ template <typename VT> __device__ __forceinline__ void global_min(VT RANNC_GLOBA
   (void)__hip_atomic_fetch_min(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every global load
+// and store the wave has in flight (its fence covers global memory); where the waves exchange data
+// through LDS alone, that wait puts a memory round trip in front of every barrier.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 __device__ __forceinline__ uint32_t lane_bcast(uint32_t v, int q) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, q);
 }

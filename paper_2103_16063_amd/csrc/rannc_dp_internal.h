@@ -120,7 +120,10 @@ hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, in
                               bool recompute, int items, hipStream_t st);
 // whole search of problems with N <= small_max_blocks() in one launch, one workgroup each
 int small_max_blocks();
-hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, int64_t *d_opt,
+// direct: the stage times are recomputed from the prefix sums and no table is written (only where
+// small_can_recompute says so, and only for searches without a communication term)
+bool small_can_recompute(int bits, int DP);
+hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, bool direct, int64_t *d_opt,
                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st);
 hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int bits, int s,
                              int write_v, int32_t *arg_i, int32_t *arg_d, hipStream_t st);
@@ -139,8 +142,12 @@ hipError_t launch_level_split_fast(const ProblemDev *probs, const LaunchShape &s
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
 // d_levels: per problem (caller's order) the exact stage count to recover, 0 = the best one; or null
+// lds_bytes > 0: the kernel that first copies what the walk reads into LDS; every problem of the
+// launch must be a min-max search with traceback_lds_bytes(...) <= lds_bytes <= kTracebackLdsMax
+constexpr int kTracebackLdsMax = 150 * 1024;
+int64_t traceback_lds_bytes(int N, int DP, int S_eff, int bits);
 hipError_t launch_traceback(const ProblemDev *probs, int Q, int plan_stride, int32_t *d_stage_end,
-                            int32_t *d_replicas, const int32_t *d_levels, hipStream_t st);
+                            int32_t *d_replicas, const int32_t *d_levels, int64_t lds_bytes, hipStream_t st);
 hipError_t launch_level_values(const ProblemDev *probs, int Q, int stride, int64_t *d_out, hipStream_t st);
 // compaction step of the block-level phase on a chain of G groups (one workgroup).  Chains whose
 // state fits LDS (kCompactLds groups) need only the listing in the workspace, longer ones keep

@@ -203,11 +203,12 @@ __device__ __forceinline__ void build_rows(VT tij, VT cj, int rmin, int D, VT RA
 // the value table (a lane's D values are a row of V, so writing them from here would scatter every
 // store instruction over 64 cache lines).  with_times = false: only the fits-in-memory part (rmin,
 // ufit) and level 1 are produced, for searches whose level kernel recomputes the stage times.
+// lds_rmin: the unit's 64 rmin bytes also go there (255 for a lane without a stage).
 template <typename VT, int DP, bool NODIV = false>
 __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *T, const int64_t *P,
                                            const int64_t *A, const int64_t *Cc, int i, int c, int lane,
                                            VT *lds_level1, int ls, int row0, const int64_t *TBp = nullptr,
-                                           const bool with_times = true) {
+                                           const bool with_times = true, uint8_t *lds_rmin = nullptr) {
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int jj = 64 * c + lane;
   const bool valid = (jj >= i) && (jj < N);
@@ -229,6 +230,7 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
   const bool unit_fits = __ballot(fits) != 0ull;
   const int64_t u = unit_index(nch, i, c);
   if (lane == 0) pr.ufit[u] = (uint8_t)unit_fits;
+  if (lds_rmin) lds_rmin[lane] = (uint8_t)(valid ? rmin : 255);  // the caller's copy: every lane, 255 = no stage
   if (!valid) return unit_fits;
   pr.rmin[u * 64 + lane] = (uint8_t)rmin;
   // A unit in which no stage fits for any r is never read (every reader consults ufit or rmin
@@ -492,38 +494,39 @@ __device__ __forceinline__ void direct_consts_init(DirectConsts &k) {
 }
 
 // entry r = ODD << SH and the ones it is the parent of
-template <int DP, int NG, int ODD, int SH>
-__device__ __forceinline__ void direct_chain(uint32_t (&x)[DP], const uint32_t RANNC_GLOBAL *__restrict__ arow,
+template <int DP, int NG, int ODD, int SH, typename AP>
+__device__ __forceinline__ void direct_chain(uint32_t (&x)[DP], AP arow,
                                              uint32_t q_odd, int mlo, int mhi) {
   constexpr int R = ODD << SH, M = R - 1;
   if constexpr (R <= 8 * NG && R <= DP) {
     const uint32_t h = SH == 0 ? q_odd : (q_odd + ((1u << SH) - 1u)) >> SH;
     const uint32_t inf = (uint32_t)__builtin_amdgcn_sbfe(M < 32 ? mlo : mhi, M & 31, 1);  // 0 or 0xFFFFFFFF
     x[DP - 1 - M] = vmax(vmax(arow[DP - 1 - M], h), inf);
-    direct_chain<DP, NG, ODD, SH + 1>(x, arow, q_odd, mlo, mhi);
+    direct_chain<DP, NG, ODD, SH + 1, AP>(x, arow, q_odd, mlo, mhi);
   }
 }
 
-template <int DP, int NG, int K = 0>
-__device__ __forceinline__ void direct_entries(uint32_t (&x)[DP], const uint32_t RANNC_GLOBAL *__restrict__ arow,
-                                               double tf, const DirectConsts &k, int mlo, int mhi) {
+// t = x + (r/2 - 1 + r * 2^-18) for the odd r = 2K + 1; the next odd r adds 1 + 2^-17 (exact: every
+// t is a multiple of 2^-18 below 2^34), so one constant serves all entries
+template <int DP, int NG, typename AP, int K = 0>
+__device__ __forceinline__ void direct_entries(uint32_t (&x)[DP], AP arow,
+                                               double t, const DirectConsts &k, int mlo, int mhi) {
   constexpr int ODD = 2 * K + 1;
   if constexpr (ODD <= 8 * NG && ODD <= DP) {
-    constexpr double add = (double)ODD / 2.0 - 1.0 + (double)ODD * 0x1p-18;
-    const double y = __builtin_fma(tf + add, k.inv[K], k.magic);
-    direct_chain<DP, NG, ODD, 0>(x, arow, (uint32_t)__double_as_longlong(y), mlo, mhi);
-    direct_entries<DP, NG, K + 1>(x, arow, tf, k, mlo, mhi);
+    const double y = __builtin_fma(t, k.inv[K], k.magic);
+    direct_chain<DP, NG, ODD, 0, AP>(x, arow, (uint32_t)__double_as_longlong(y), mlo, mhi);
+    direct_entries<DP, NG, AP, K + 1>(x, arow, t + (1.0 + 0x1p-17), k, mlo, mhi);
   }
 }
 
-template <int DP, int NG>
-__device__ __forceinline__ void row_merge_direct(uint32_t (&x)[DP], const uint32_t RANNC_GLOBAL *__restrict__ arow,
+template <int DP, int NG, typename AP>
+__device__ __forceinline__ void row_merge_direct(uint32_t (&x)[DP], AP arow,
                                                  uint32_t tij, int rmn, const DirectConsts &k) {
   // bit r-1 set for r < rmn: these replica counts do not fit (all of them for rmn = 255)
   const unsigned long long below = rmn > 64 ? ~0ull : ((1ull << (rmn - 1)) - 1ull);
 #pragma unroll
   for (int m = 8 * NG; m < DP; ++m) x[DP - 1 - m] = arow[DP - 1 - m];  // max(a, 0): replica counts not needed
-  direct_entries<DP, NG>(x, arow, (double)tij, k, (int)(uint32_t)below, (int)(uint32_t)(below >> 32));
+  direct_entries<DP, NG, AP>(x, arow, (double)tij + (0x1p-18 - 0.5), k, (int)(uint32_t)below, (int)(uint32_t)(below >> 32));
 #pragma unroll
   for (int h = DP / 2; h >= 1; h >>= 1) {
 #pragma unroll
@@ -576,7 +579,7 @@ __device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], const Pro
     if (__ballot(act) != 0ull) {
       any = true;
       VT x[DP];
-      row_merge_direct<DP, NG>(x, Vprev + (int64_t)i * DP, tij, rmn, k);
+      row_merge_direct<DP, NG, const uint32_t RANNC_GLOBAL *>(x, Vprev + (int64_t)i * DP, tij, rmn, k);
 #pragma unroll
       for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
     }
@@ -750,11 +753,11 @@ constexpr int kSmallWaves = 16;
 __device__ __forceinline__ void select_finish(const ProblemDev &pr, int64_t v, int st, int64_t *d_opt,
                                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status);
 
-template <typename VT, int DP>
+template <typename VT, int DP, bool DIRECT>
 __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
     const ProblemDev *__restrict__ probs, int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est,
     int32_t *d_status) {
-  const ProblemDev pr = probs[blockIdx.x];
+  const ProblemDev &pr = probs[blockIdx.x];
   constexpr VT INF = Lim<VT>::inf;
   constexpr int LS = DP + 1;  // row stride of a level in LDS: lanes (= columns) hit different banks
   constexpr int NT = 64 * kSmallWaves;
@@ -764,6 +767,11 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   __shared__ VT lv[2][(kSmallMaxN + 1) * LS];
   __shared__ VT s_top[64];
   __shared__ int s_flags, s_wlo[2];
+  // DIRECT: the stage times are recomputed from the prefix sums in LDS (as the recomputing level
+  // kernel does), and the fits-in-memory bytes of all units stay in LDS too: no table is written and
+  // the levels read nothing from memory
+  constexpr int kUnits = kSmallMaxN + 64;  // 64 rows of chunk 0, then up to 128 rows of chunk 1
+  __shared__ uint8_t s_rmin[DIRECT ? kUnits * 64 : 64];
   const int N = pr.N, D = pr.D, nch = pr.nch, S_eff = pr.S_eff;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -824,7 +832,8 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   const int R0 = min(64, N), RT = R0 + (nch > 1 ? N : 0);
   for (int f = wave; f < RT; f += kSmallWaves) {
     const int c = f >= R0, i = c ? f - R0 : f;
-    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, pr.o ? sC : nullptr, i, c, lane, lv[0], LS, 0);
+    const bool fits = build_unit<VT, DP>(pr, sT, sP, sA, pr.o ? sC : nullptr, i, c, lane, lv[0], LS, 0, nullptr,
+                                         !DIRECT, DIRECT ? s_rmin + f * 64 : nullptr);
     if (fits && lane == 0) atomicMin(&s_wlo[c], i);
   }
   __syncthreads();
@@ -838,24 +847,52 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
   if (tid == 0) s_top[0] = lv[0][N * LS + D - 1];
 
   // ---- levels 2..S_eff ----
+  [[maybe_unused]] DirectConsts kc;
+  if constexpr (DIRECT) direct_consts_init(kc);
   for (int s = 2; s <= S_eff; ++s) {
     const VT *prev = lv[s & 1];        // level s-1
     VT *cur = lv[(s - 1) & 1];         // level s
     const int rl = D - s + 1;
     for (int e = tid; e < (N + 1) * LS; e += NT) cur[e] = ((e % LS) < D) ? INF : (VT)0;
-    __syncthreads();
+    lds_barrier();  // LDS only: the copy of the previous level to memory stays in flight
     for (int f = wave; f < RT; f += kSmallWaves) {
       const int c = f >= R0, i = c ? f - R0 : f;
       if (i < s - 1 || i < s_wlo[c] || 64 * c + 64 < s) continue;
       if (prev[i * LS + D - 1] == INF) continue;  // no (s-1)-stage plan covers blocks 1..i
       const int jj = 64 * c + lane;
-      const int64_t u = unit_index(nch, i, c);
-      int rmn = 255;
-      if (jj >= i && jj < N) rmn = rmin[u * 64 + lane];
-      const bool act = rmn <= rl;
-      if (__ballot(act) == 0ull) continue;
-      VT x[DP];
-      {
+      if constexpr (DIRECT) {
+        const int rmn = s_rmin[f * 64 + lane];
+        const bool act = rmn <= rl;  // 255 outside the stage's range
+        if (__ballot(act) == 0ull) continue;
+        const uint32_t tij = (uint32_t)(sT[min(jj + 1, N)] - sT[i]);
+        // Narrower merge at late levels.  The first s-2 entries of a[] are INF (s-1 stages need s-1
+        // devices) and only rl = D-s+1 replica counts and device totals are left, so the merge of
+        // a[sig..sig+H-1] with c[1..H] on a network of H >= rl inputs gives every value the level
+        // needs: its t-th output is W[d] for d - 1 = t + 1 + sig (the sig skipped entries are the
+        // sig largest of the full merge).  sig <= s-2 skips only INF, sig <= DP-H stays inside the row.
+#define RANNC_ROW(HH)                                                                                \
+  {                                                                                                  \
+    constexpr int H = (HH) <= DP ? (HH) : DP;                                                        \
+    const int sig = H < DP ? min(s - 2, DP - H) : 0;                                                 \
+    VT x[H];                                                                                         \
+    row_merge_direct<H, (H >= 8 ? H / 8 : 1), const VT *>(x, prev + i * LS + sig, tij, act ? rmn : 255, kc); \
+    if (act && jj + 1 >= s) {                                                                        \
+      /* no test per entry: columns D.. hold 0 and keep it, column DP (t + 1 + sig <= DP) is padding */ \
+      VT *dst = cur + (jj + 1) * LS + 1 + sig;                                                       \
+      _Pragma("unroll") for (int t = 0; t < H; ++t) atomicMin(&dst[t], x[t]);                        \
+    }                                                                                                \
+  }
+        if (rl <= 8) RANNC_ROW(8)
+        else if (rl <= 16) RANNC_ROW(16)
+        else RANNC_ROW(32)
+#undef RANNC_ROW
+      } else {
+        VT x[DP];
+        const int64_t u = unit_index(nch, i, c);
+        int rmn = 255;
+        if (jj >= i && jj < N) rmn = rmin[u * 64 + lane];
+        const bool act = rmn <= rl;
+        if (__ballot(act) == 0ull) continue;
         const int col = act ? lane : __ffsll((long long)__ballot(act)) - 1;
         const VT RANNC_GLOBAL *unit = cost + u * 64 * D + col;
         const VT *arow = prev + i * LS;
@@ -870,15 +907,15 @@ __global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
           default: break;
         }
 #undef RANNC_ROW
-      }
-      if (act && jj + 1 >= s) {
-        // unconditional: folding INF in is a no-op and costs less than testing for it
+        if (act && jj + 1 >= s) {
+          // unconditional: folding INF in is a no-op and costs less than testing for it
 #pragma unroll
-        for (int t = 0; t < DP - 1; ++t)
-          if (t + 1 <= D - 1) atomicMin(&cur[(jj + 1) * LS + t + 1], x[t]);
+          for (int t = 0; t < DP - 1; ++t)
+            if (t + 1 <= D - 1) atomicMin(&cur[(jj + 1) * LS + t + 1], x[t]);
+        }
       }
     }
-    __syncthreads();
+    lds_barrier();
     VT RANNC_GLOBAL *Vs = Vg + (int64_t)(s - 1) * lvl;
     for (int e = tid; e < (N + 1) * DP; e += NT) Vs[e] = cur[(e / DP) * LS + (e % DP)];
     if (tid == 0) s_top[s - 1] = cur[N * LS + D - 1];
@@ -956,7 +993,7 @@ __device__ void traceback_split_body(const ProblemDev &pr, int plan_stride, int3
   const int64_t lvl = (int64_t)(N + 1) * DP;
   const VT *V = (const VT *)pr.V, *VF = (const VT *)pr.VF, *VB = (const VT *)pr.VB;
   const VT *costf = (const VT *)pr.cost, *costb = (const VT *)pr.costb;
-  int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
+  int ns = (*pr.status == 0 && forced >= 0) ? (int)pr.res[1] : 0;  // forced < 0: no plan wanted
   if (forced > 0 && *pr.status == 0)
     ns = (forced <= pr.S_eff && V[(int64_t)(forced - 1) * lvl + (int64_t)N * DP + D - 1] != INF) ? forced : 0;
   for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
@@ -1083,34 +1120,82 @@ __device__ __forceinline__ bool stage_time_completes(uint64_t x, uint64_t C, int
   return __umul64hi(w - 1, (uint64_t)r) == 0 && x > (w - 1) * (uint64_t)r;
 }
 
-template <typename VT, int DP>
+// STAGED: everything the walk reads (the levels of V below the plan's, T, C, the window bounds, the
+// fits-in-memory bytes) is first copied into the workgroup's LDS with one round of independent reads,
+// and the walk then runs out of LDS.  For a search that small the walk is otherwise a chain of one
+// memory round trip per stage out of a cold cache (about 1 us each).  lds: traceback_lds_bytes() bytes.
+template <typename VT, int DP, bool STAGED>
 __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *se, int32_t *rp,
-                               unsigned int *best_key, int forced) {
+                               unsigned int *best_key, int forced, char *lds) {
   constexpr VT INF = Lim<VT>::inf;
   constexpr int KB = 12;  // rows per wave and pass; their reads are independent
   const int N = pr.N, D = pr.D, nch = pr.nch;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nw = blockDim.x >> 6;
   const int64_t lvl = (int64_t)(N + 1) * DP;
-  const VT RANNC_GLOBAL *V = gptr((const VT *)pr.V);
+  const VT RANNC_GLOBAL *Vg = gptr((const VT *)pr.V);
   // forced > 0: the plan of exactly `forced` stages (Algorithm 1's own answer V[S][|B|][D]), if
-  // that level holds one; otherwise the best level chosen by the solve
-  int ns = (*pr.status == 0) ? (int)pr.res[1] : 0;
+  // that level holds one; forced = 0: the best level chosen by the solve; forced < 0: no plan wanted
+  int ns = (*pr.status == 0 && forced >= 0) ? (int)pr.res[1] : 0;
   if (forced > 0 && *pr.status == 0)
-    ns = (forced <= pr.S_eff && V[(int64_t)(forced - 1) * lvl + (int64_t)N * DP + D - 1] != INF) ? forced : 0;
+    ns = (forced <= pr.S_eff && Vg[(int64_t)(forced - 1) * lvl + (int64_t)N * DP + D - 1] != INF) ? forced : 0;
   for (int u = ns + tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
   if (ns == 0) return;
-  const int64_t RANNC_GLOBAL *T = gptr((const int64_t *)pr.T);
-  const uint8_t RANNC_GLOBAL *rmin = gptr((const uint8_t *)pr.rmin);
-  const int32_t RANNC_GLOBAL *wlo = gptr((const int32_t *)pr.wlo);
+  using VP = std::conditional_t<STAGED, const VT *, const VT RANNC_GLOBAL *>;
+  using TP = std::conditional_t<STAGED, const int64_t *, const int64_t RANNC_GLOBAL *>;
+  using RP = std::conditional_t<STAGED, const uint8_t *, const uint8_t RANNC_GLOBAL *>;
+  using WP = std::conditional_t<STAGED, const int32_t *, const int32_t RANNC_GLOBAL *>;
+  VP V;
+  TP T, C = nullptr;
+  RP rmin;
+  WP wlo;
+  if constexpr (STAGED) {
+    const int64_t nT = (((int64_t)(N + 1) * 8 + 31) / 32) * 32;
+    char *w = lds;
+    VT *Vl = (VT *)w; w += (int64_t)pr.S_eff * lvl * (int64_t)sizeof(VT);  // room for every level
+    int64_t *Tl = (int64_t *)w; w += nT;
+    int64_t *Cl = (int64_t *)w; w += nT;
+    int32_t *Wl = (int32_t *)w; w += (((int64_t)nch * 4 + 31) / 32) * 32;
+    uint8_t *Rl = (uint8_t *)w;
+    // 16-byte copies (every array starts on a 256-byte boundary of the workspace; a level of V is
+    // a multiple of 32 bytes)
+    typedef uint32_t Quad __attribute__((ext_vector_type(4)));
+    const Quad RANNC_GLOBAL *src = (const Quad RANNC_GLOBAL *)Vg;
+    // eight reads in flight per lane (index clamped instead of tested, so that no branch separates them)
+    const int64_t nquad = (int64_t)ns * lvl * (int64_t)sizeof(VT) / 16;
+    for (int64_t e0 = tid; e0 < nquad; e0 += 8 * (int64_t)blockDim.x) {
+      Quad r[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) r[k] = src[min(e0 + k * (int64_t)blockDim.x, nquad - 1)];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (e0 + k * (int64_t)blockDim.x < nquad) ((Quad *)Vl)[e0 + k * (int64_t)blockDim.x] = r[k];
+    }
+    for (int e = tid; e <= N; e += blockDim.x) {
+      Tl[e] = pr.T[e];
+      if (pr.C) Cl[e] = pr.C[e];
+    }
+    for (int e = tid; e < nch; e += blockDim.x) Wl[e] = pr.wlo[e];
+    const Quad RANNC_GLOBAL *rsrc = (const Quad RANNC_GLOBAL *)gptr((const uint8_t *)pr.rmin);
+    for (int64_t e = tid; e < units_before(nch, N) * 4; e += blockDim.x) ((Quad *)Rl)[e] = rsrc[e];
+    __syncthreads();
+    V = Vl; T = Tl; rmin = Rl; wlo = Wl;
+    if (pr.C) C = Cl;
+  } else {
+    V = Vg;
+    T = gptr((const int64_t *)pr.T);
+    rmin = gptr((const uint8_t *)pr.rmin);
+    wlo = gptr((const int32_t *)pr.wlo);
+    if (pr.C) C = gptr((const int64_t *)pr.C);
+  }
   int j = N, d = D;
   for (int s = ns; s >= 2; --s) {
-    const VT RANNC_GLOBAL *Vp = V + (int64_t)(s - 2) * lvl;
+    VP Vp = V + (int64_t)(s - 2) * lvl;
     const int jj = j - 1, c = jj >> 6;
     const int64_t Tj = T[j];
-    const uint64_t Cj = pr.C ? (uint64_t)pr.C[j] : 0ull;  // send time of the cut after block j (0 for j = N)
+    const uint64_t Cj = C ? (uint64_t)C[j] : 0ull;  // send time of the cut after block j (0 for j = N)
     if (tid == 0) *best_key = 0xFFFFFFFFu;
-    __syncthreads();
+    lds_barrier();  // the waves meet through LDS only: the reads above and the plan stores stay in flight
     // the cell's value, the window bound and the first pass of rows are read together
     const VT v = V[(int64_t)(s - 1) * lvl + (int64_t)j * DP + d - 1];
     const int first = max(s - 1, min(wlo[c], j));  // earlier rows hold no stage that fits
@@ -1138,9 +1223,17 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
       // checks row k against the stage time
       int my_d = 0;
       VT my_a = INF;
+      // rows of this wave inside the window (they descend with k): the others cost nothing
+      const int low = max(first, s - 1);
+      const int kb = top - wave >= low ? (top - wave - low) / nw + 1 : 0;
 #pragma unroll
       for (int k = 0; k < KB; ++k) {
-        const bool ok = lane + 1 >= s - 1 && lane + 1 <= d - 1 && a[k] <= v;
+        // out of memory a test, not an exit: behind an exit the compiler moves each row's read to
+        // its use, and the reads of a pass no longer overlap; out of LDS the exit is what is cheaper
+        if constexpr (STAGED) {
+          if (k >= kb) break;
+        }
+        const bool ok = k < kb && lane + 1 >= s - 1 && lane + 1 <= d - 1 && a[k] <= v;
         const unsigned long long m = __ballot(ok);
         if (m != 0ull) {
           const int q = __ffsll((long long)m) - 1;
@@ -1156,9 +1249,9 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
       if (top - nw * KB < first) break;  // the remaining rows lie below the window
     }
     if (mine != 0xFFFFFFFFu) atomicMin(best_key, mine);
-    __syncthreads();
+    lds_barrier();
     const unsigned key = *best_key;
-    __syncthreads();
+    lds_barrier();
     if (key == 0xFFFFFFFFu) {  // tables inconsistent: report no plan rather than walk on
       for (int u = tid; u < plan_stride; u += blockDim.x) { se[u] = -1; rp[u] = -1; }
       return;
@@ -1181,17 +1274,39 @@ __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
   const int forced = d_levels ? d_levels[pr.q] : 0;
   int32_t *se = d_stage_end + (int64_t)pr.q * plan_stride;
   int32_t *rp = d_replicas + (int64_t)pr.q * plan_stride;
-#define GO(T)                                                                           \
-  switch (pr.DP) {                                                                      \
-    case 8: traceback_body<T, 8>(pr, plan_stride, se, rp, &best_key, forced); break;            \
-    case 16: traceback_body<T, 16>(pr, plan_stride, se, rp, &best_key, forced); break;          \
-    case 32: traceback_body<T, 32>(pr, plan_stride, se, rp, &best_key, forced); break;          \
-    default: traceback_body<T, 64>(pr, plan_stride, se, rp, &best_key, forced); break;          \
+#define GO(T)                                                                                    \
+  switch (pr.DP) {                                                                               \
+    case 8: traceback_body<T, 8, false>(pr, plan_stride, se, rp, &best_key, forced, nullptr); break;   \
+    case 16: traceback_body<T, 16, false>(pr, plan_stride, se, rp, &best_key, forced, nullptr); break; \
+    case 32: traceback_body<T, 32, false>(pr, plan_stride, se, rp, &best_key, forced, nullptr); break; \
+    default: traceback_body<T, 64, false>(pr, plan_stride, se, rp, &best_key, forced, nullptr); break; \
   }
   if (pr.VF) {  // split objective: first-match over all candidates
     if (pr.bits == 32) traceback_split_body<uint32_t>(pr, plan_stride, se, rp, &best_key, forced);
     else traceback_split_body<uint64_t>(pr, plan_stride, se, rp, &best_key, forced);
     return;
+  }
+  if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
+#undef GO
+}
+
+// Plan recovery out of LDS, for launches of few, small min-max searches (the host checks that every
+// search of the launch fits traceback_lds_bytes() into the dynamic LDS it passes).
+__global__ __launch_bounds__(kTracebackThreads) void traceback_lds_kernel(
+    const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas,
+    const int32_t *__restrict__ d_levels) {
+  __shared__ unsigned int best_key;
+  extern __shared__ __align__(16) char staged[];
+  const ProblemDev pr = probs[blockIdx.x];
+  const int forced = d_levels ? d_levels[pr.q] : 0;
+  int32_t *se = d_stage_end + (int64_t)pr.q * plan_stride;
+  int32_t *rp = d_replicas + (int64_t)pr.q * plan_stride;
+#define GO(T)                                                                                   \
+  switch (pr.DP) {                                                                              \
+    case 8: traceback_body<T, 8, true>(pr, plan_stride, se, rp, &best_key, forced, staged); break;    \
+    case 16: traceback_body<T, 16, true>(pr, plan_stride, se, rp, &best_key, forced, staged); break;  \
+    case 32: traceback_body<T, 32, true>(pr, plan_stride, se, rp, &best_key, forced, staged); break;  \
+    default: traceback_body<T, 64, true>(pr, plan_stride, se, rp, &best_key, forced, staged); break;  \
   }
   if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
@@ -1395,15 +1510,20 @@ hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bi
 }
 
 int small_max_blocks() { return kSmallMaxN; }
+// the one-launch kernel can recompute the stage times for 32-bit values up to the 32-device class
+// (beyond it the reciprocals and the merge do not fit the 128 registers of its sixteen waves)
+bool small_can_recompute(int bits, int DP) { return bits == 32 && DP <= 32; }
 
-hipError_t launch_solve_small(const ProblemDev *p, int Q, int bits, int DP, int64_t *d_opt,
+hipError_t launch_solve_small(const ProblemDev *p, int Q, int bits, int DP, bool direct, int64_t *d_opt,
                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st) {
-#define GO(B, T, W)                                                                              \
-  if (bits == B && DP == W)                                                                      \
-    hipLaunchKernelGGL((solve_small_kernel<T, W>), dim3(Q), dim3(64 * kSmallWaves), 0, st, p, d_opt, \
+  if (direct && !small_can_recompute(bits, DP)) return hipErrorInvalidValue;
+#define GO(B, T, W, X)                                                                                 \
+  if (bits == B && DP == W && direct == X)                                                             \
+    hipLaunchKernelGGL((solve_small_kernel<T, W, X>), dim3(Q), dim3(64 * kSmallWaves), 0, st, p, d_opt, \
                        d_n_stages, d_est, d_status);
-  GO(32, uint32_t, 8) GO(32, uint32_t, 16) GO(32, uint32_t, 32) GO(32, uint32_t, 64)
-  GO(64, uint64_t, 8) GO(64, uint64_t, 16) GO(64, uint64_t, 32) GO(64, uint64_t, 64)
+  GO(32, uint32_t, 8, false) GO(32, uint32_t, 16, false) GO(32, uint32_t, 32, false) GO(32, uint32_t, 64, false)
+  GO(64, uint64_t, 8, false) GO(64, uint64_t, 16, false) GO(64, uint64_t, 32, false) GO(64, uint64_t, 64, false)
+  GO(32, uint32_t, 8, true) GO(32, uint32_t, 16, true) GO(32, uint32_t, 32, true)
 #undef GO
   return hipGetLastError();
 }
@@ -1429,10 +1549,27 @@ hipError_t launch_select(const ProblemDev *p, int Q, int64_t *d_opt, int32_t *d_
   return hipGetLastError();
 }
 
+int64_t traceback_lds_bytes(int N, int DP, int S_eff, int bits) {
+  const int nch = (N + 63) / 64;
+  const int64_t nT = (((int64_t)(N + 1) * 8 + 31) / 32) * 32;
+  return (int64_t)S_eff * (N + 1) * DP * (bits / 8) + 2 * nT + (((int64_t)nch * 4 + 31) / 32) * 32 +
+         units_before(nch, N) * 64;
+}
+
 hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t *d_stage_end,
-                            int32_t *d_replicas, const int32_t *d_levels, hipStream_t st) {
-  hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(kTracebackThreads), 0, st, p, plan_stride, d_stage_end,
-                     d_replicas, d_levels);
+                            int32_t *d_replicas, const int32_t *d_levels, int64_t lds_bytes, hipStream_t st) {
+  if (lds_bytes > 0) {
+    // more than the default 64 KiB of dynamic LDS has to be asked for once
+    static const hipError_t attr = hipFuncSetAttribute((const void *)traceback_lds_kernel,
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kTracebackLdsMax);
+    if (attr != hipSuccess) return attr;
+    if (lds_bytes > kTracebackLdsMax) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(traceback_lds_kernel, dim3(Q), dim3(kTracebackThreads), (size_t)lds_bytes, st, p, plan_stride,
+                       d_stage_end, d_replicas, d_levels);
+  } else {
+    hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(kTracebackThreads), 0, st, p, plan_stride, d_stage_end,
+                       d_replicas, d_levels);
+  }
   return hipGetLastError();
 }
 
@@ -1472,7 +1609,7 @@ hipError_t launch_level_values(const ProblemDev *p, int Q, int stride, int64_t *
 // batch order among equals.  One wave: a lane per search of the batch (in rounds of 64), the
 // candidates of one (n, S) reduced with the lexicographic minimum of (estimate, search index).
 // Writes the record {q, S, first bad status or 0, 0, V, estimate} and the forced-level array of
-// the plan recovery (S at the chosen search, 0 elsewhere).  q = -1: infeasible.
+// the plan recovery (S at the chosen search, -1 = no plan wanted elsewhere).  q = -1: infeasible.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void form_stage_select_kernel(
     int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *__restrict__ vals,
@@ -1481,7 +1618,7 @@ __global__ __launch_bounds__(64) void form_stage_select_kernel(
   const int lane = threadIdx.x;
   int bad = 0;
   for (int q = lane; q < Q; q += 64) {
-    levels[q] = 0;
+    levels[q] = -1;  // only the chosen search's plan is recovered
     const int st = status[q];
     if (st != 0 && bad == 0) bad = st;
   }

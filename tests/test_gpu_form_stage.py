@@ -158,6 +158,19 @@ def test_level_values_and_traceback_at(monkeypatch, fused):
             assert (vals[q, len(wv):] == INF).all()
         # every exact stage count in turn (0 = the best one, as rannc_dp_traceback)
         seen_forced_differs = 0
+        # a negative entry asks for no plan: every slot of that search is -1, the others are unaffected
+        lev = torch.zeros(Q, dtype=torch.int32, device="cuda:0")
+        lev[::2] = -1
+        d_se = torch.full((Q, stride), -7, dtype=torch.int32, device="cuda:0")
+        d_rp = torch.full((Q, stride), -7, dtype=torch.int32, device="cuda:0")
+        assert B.rannc_dp_traceback_at(sess.h, sess.stream(), lev, stride, d_se, d_rp) == B.OK
+        torch.cuda.synchronize()
+        se, rp = d_se.cpu().numpy(), d_rp.cpu().numpy()
+        for q in range(Q):
+            if q % 2 == 0:
+                assert (se[q] == -1).all() and (rp[q] == -1).all(), q
+            else:
+                assert np.array_equal(se[q], res["stage_end"][q]) and np.array_equal(rp[q], res["replicas"][q]), q
         for s in range(0, stride + 2):
             lev = torch.full((Q,), s, dtype=torch.int32, device="cuda:0")
             d_se = torch.full((Q, stride), -7, dtype=torch.int32, device="cuda:0")

@@ -188,7 +188,7 @@ def test_recomputed_stage_times_at_the_edges_of_the_value_range():
     g = np.random.default_rng(4242)
     probs = []
     for case in range(24):
-        N = int(g.integers(40, 130))
+        N = int(g.integers(40, 129))
         D = int(g.choice([7, 8, 16, 31, 32, 33, 63, 64]))
         pr = synth.random_small(9100 + case, N, D, int(g.integers(2, 14)), tight=float(g.choice([1.3, 3.0, 60.0])), tmax=9)
         kind = case % 4
@@ -205,13 +205,18 @@ def test_recomputed_stage_times_at_the_edges_of_the_value_range():
             pr["time_ns"] = (1 << g.integers(0, 24, N)).astype(np.int64) + g.integers(-1, 2, N)
         probs.append(pr)
     rm, sm = gpu_run(probs, algo=B.ALGO_MERGE)
-    rr, sr = gpu_run(probs, algo=B.ALGO_RECOMPUTE)
-    with sm, sr:
+    rr, sr = gpu_run(probs, algo=B.ALGO_RECOMPUTE, one_launch_small=1)
+    ro, so = gpu_run(probs, algo=B.ALGO_RECOMPUTE, one_launch_small=2)   # the one-launch kernel's own recomputation
+    with sm, sr, so:
+        rc, info = B.rannc_dp_solve_info(so.h)
+        assert [info.level_kernel[k] for k in range(3)] == [B.KERNEL_ONE_LAUNCH_RECOMPUTE] * 3
         for k in rm:
             assert np.array_equal(rm[k], rr[k]), k
+            assert np.array_equal(rm[k], ro[k]), k
         assert (rm["status"] == 0).all()
         for q in range(len(probs)):
             assert np.array_equal(sm.table(B.TABLE_V, q), sr.table(B.TABLE_V, q)), q
+            assert np.array_equal(sm.table(B.TABLE_V, q), so.table(B.TABLE_V, q)), q
         assert_results_match(probs, rr)
         for q in (0, 1, 2, 3, 5, 10, 15, 20):   # every kind of total; the table builder divides the same way
             assert_tables_match(probs[q], sr, q, args=False)
@@ -265,12 +270,47 @@ def test_random_batches_against_oracle(width):
                 assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 80))
 
 
+@pytest.mark.parametrize("width", WIDTHS)
+def test_plan_recovery_from_lds_and_from_memory(width):
+    """Plan recovery of a launch of at most 64 small searches first copies what the walk reads into
+    LDS; larger launches, and searches whose tables do not fit, walk through memory.  The same
+    searches alone, in a batch of 30 and inside a batch of 72: identical plans, all equal to the
+    oracle's, also for a forced exact stage count."""
+    g = np.random.default_rng(77)
+    probs = []
+    for q in range(30):
+        N = int(g.integers(2, 100))
+        D = int(g.choice([3, 8, 12, 16, 25, 32, 40, 64]))
+        probs.append(synth.random_small(7000 + q, N, D, int(g.integers(2, 20)), tight=float(g.choice([1.3, 2.5, 40.0])),
+                                        tmax=int(g.choice([5, 10 ** 5]))))
+        if width > B.NARROW_MAX_TOTAL_TIME:
+            probs[-1]["time_ns"] = probs[-1]["time_ns"] * (1 << 22)
+    more = [synth.random_small(7100 + q, 20, 8, 4, tight=2.0) for q in range(42)]
+    r30, s30 = gpu_run(probs, max_total_time_ns=width)
+    r72, s72 = gpu_run(probs + more, max_total_time_ns=width)
+    with s30, s72:
+        assert_results_match(probs, r30)
+        for k in r30:
+            assert np.array_equal(r30[k], r72[k][:30]), k
+    r1, s1 = gpu_run(probs[:1], max_total_time_ns=width)
+    with s1:
+        for k in r1:
+            if r1[k].ndim == 2:   # plan arrays: the stride is the batch's largest stage count
+                w = r1[k].shape[1]
+                assert np.array_equal(r1[k], r30[k][:1, :w]) and (r30[k][:1, w:] == -1).all(), k
+            else:
+                assert np.array_equal(r1[k], r30[k][:1]), k
+
+
+@pytest.mark.parametrize("algo", [B.ALGO_AUTO, B.ALGO_MERGE])
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("width", WIDTHS)
-def test_small_search_kernel_on_and_off(mode, width):
+def test_small_search_kernel_on_and_off(mode, width, algo):
     """Searches of at most 128 blocks can run as one launch with one workgroup per search (levels
     folded in LDS) or through the per-level launches; the library chooses by batch shape.  Both
-    are forced here (1 = never, 2 = always) on the same inputs: identical tables, optimum, plan."""
+    are forced here (1 = never, 2 = always) on the same inputs: identical tables, optimum, plan.
+    The one-launch kernel recomputes the stage times (32-bit values, up to the 32-device class,
+    unless the handle asks for the table) or reads them from the table it builds: both run here."""
     g = np.random.default_rng(99)
     probs = [synth.named_config(1), synth.named_config(2)]
     for q in range(30):
@@ -280,11 +320,16 @@ def test_small_search_kernel_on_and_off(mode, width):
                                         tight=float(g.choice([0.9, 1.2, 2.0, 50.0])),
                                         tmax=int(g.choice([2, 1000, 10 ** 6])),
                                         zero_time_frac=float(g.choice([0.0, 0.25]))))
-    res, sess = gpu_run(probs, max_total_time_ns=width, one_launch_small=mode)
+    res, sess = gpu_run(probs, max_total_time_ns=width, one_launch_small=mode, algo=algo)
     with sess:
         rc, info = B.rannc_dp_solve_info(sess.h)
-        kinds = {info.level_kernel[k] for k in range(4) if info.n_problems[k]}
-        assert rc == B.OK and (kinds == {B.KERNEL_ONE_LAUNCH} if mode == 2 else B.KERNEL_ONE_LAUNCH not in kinds)
+        assert rc == B.OK and all(info.n_problems[k] for k in range(4))
+        kinds = [info.level_kernel[k] for k in range(4)]
+        if mode == 2:
+            recomputes = width == B.NARROW_MAX_TOTAL_TIME and algo == B.ALGO_AUTO
+            assert kinds == ([B.KERNEL_ONE_LAUNCH_RECOMPUTE] * 3 if recomputes else [B.KERNEL_ONE_LAUNCH] * 3) + [B.KERNEL_ONE_LAUNCH]
+        else:
+            assert not {B.KERNEL_ONE_LAUNCH, B.KERNEL_ONE_LAUNCH_RECOMPUTE} & set(kinds)
         assert_results_match(probs, res)
         for q in range(0, len(probs), 3):
             assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
@@ -435,5 +480,5 @@ def test_environment_overrides_and_automatic_choice_of_the_level_kernel(monkeypa
     res, sess = gpu_run(small, one_launch_small=1)
     with sess:
         rc, info = B.rannc_dp_solve_info(sess.h)
-        assert [info.level_kernel[k] for k in (0, 2)] == [B.KERNEL_ONE_LAUNCH] * 2
+        assert [info.level_kernel[k] for k in (0, 2)] == [B.KERNEL_ONE_LAUNCH_RECOMPUTE] * 2
         assert_results_match(small, res)
