@@ -556,8 +556,10 @@ int rannc_dp_solve_info(rannc_dp_t *h, rannc_dp_solve_info_t *out) {
   return RANNC_DP_OK;
 }
 
-int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels, int32_t plan_stride,
-                          int32_t *d_stage_end, int32_t *d_replicas) {
+// rec: the outer driver's result record on the device (the chosen search's plan is also written
+// behind it), or null
+static int traceback_impl(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels, int32_t plan_stride,
+                          int32_t *d_stage_end, int32_t *d_replicas, int64_t *d_rec) {
   if (!h || !d_stage_end || !d_replicas || plan_stride < 1) return RANNC_DP_INVALID_ARG;
   if (!h->solved) return RANNC_DP_BAD_STATE;
   // A few small min-max searches: the walk runs out of LDS (one round of reads instead of one
@@ -573,12 +575,17 @@ int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_leve
     lds_bytes = std::max(lds_bytes, need);
   }
   if (!staged) lds_bytes = 0;
-  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas, d_levels, lds_bytes,
+  if (rannc::launch_traceback(h->d_probs, h->Q, plan_stride, d_stage_end, d_replicas, d_levels, lds_bytes, d_rec,
                               (hipStream_t)hip_stream) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
   }
   return RANNC_DP_OK;
+}
+
+int rannc_dp_traceback_at(rannc_dp_t *h, void *hip_stream, const int32_t *d_levels, int32_t plan_stride,
+                          int32_t *d_stage_end, int32_t *d_replicas) {
+  return traceback_impl(h, hip_stream, d_levels, plan_stride, d_stage_end, d_replicas, nullptr);
 }
 
 int rannc_dp_traceback(rannc_dp_t *h, void *hip_stream, int32_t plan_stride, int32_t *d_stage_end,
@@ -714,7 +721,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   const size_t o_p = o_t + a_in, o_a = o_t + 2 * a_in, o_o = o_t + 3 * a_in, o_b = o_t + 4 * a_in;
   const size_t o_opt = o_t + 5 * a_in;
   const size_t o_ns = o_opt + align_up((size_t)Q * 8);
-  const size_t o_vals = o_ns + align_up((size_t)Q * 8);
+  const size_t o_vals = o_ns + align_up((size_t)Q * 8);  // (room of an earlier layout; rannc_dp_form_stage_scratch_bytes counts it)
   const size_t o_lev = o_vals + align_up((size_t)Q * stride * 8);
   const size_t o_se = o_lev + align_up((size_t)Q * 4);
   const size_t o_rp = o_se + align_up((size_t)Q * stride * 4);
@@ -763,7 +770,6 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   }
   int64_t *d_opt = (int64_t *)(dev + o_opt);
   int32_t *d_ns = (int32_t *)(dev + o_ns), *d_st = d_ns + Q;
-  int64_t *d_vals = (int64_t *)(dev + o_vals);
   int32_t *d_lev = (int32_t *)(dev + o_lev), *d_se = (int32_t *)(dev + o_se), *d_rp = (int32_t *)(dev + o_rp);
   const int32_t *d_pn = (const int32_t *)(dev + o_pair), *d_pm = d_pn + Q;
   int64_t *d_rec = (int64_t *)(dev + o_rec);
@@ -776,23 +782,19 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
   b.cut_bytes = comm ? (const int64_t *)(dev + o_o) : nullptr;
   b.time_bwd_ns = split ? (const int64_t *)(dev + o_b) : nullptr;
-  // Everything on the device, in stream order: the batched search, V[S][N][D] of every S, Algorithm
-  // 2's loops over those values (first n, then first S with a feasible MB; among those the smallest
-  // (MB + S - 1) * V, the first found among equals), the plan of the chosen (n, MB, S), and the
-  // record with that plan packed behind it.  One copy down, one wait.
+  // Everything on the device, in stream order: the batched search, Algorithm 2's loops over the
+  // values V[S][N][D] of every search and S (first n, then first S with a feasible MB; among those
+  // the smallest (MB + S - 1) * V, the first found among equals), and the plan of the chosen
+  // (n, MB, S), which the plan recovery also writes behind the record.  Three launches behind the
+  // search's own, one copy down, one wait.
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
-  if (rc == RANNC_DP_OK) rc = rannc_dp_level_values(h, hip_stream, stride, d_vals);
   if (rc == RANNC_DP_OK &&
-      rannc::launch_form_stage_select(Q, stride, N, in->n_nodes, in->devices_per_node, d_vals, d_st, d_pn, d_pm,
+      rannc::launch_form_stage_select(h->d_probs, Q, stride, N, in->n_nodes, in->devices_per_node, d_pn, d_pm,
                                       d_lev, d_rec, st) != hipSuccess) {
     (void)hipGetLastError();
     rc = RANNC_DP_HIP_ERROR;
   }
-  if (rc == RANNC_DP_OK) rc = rannc_dp_traceback_at(h, hip_stream, d_lev, stride, d_se, d_rp);
-  if (rc == RANNC_DP_OK && rannc::launch_form_stage_pack(stride, d_se, d_rp, d_rec, st) != hipSuccess) {
-    (void)hipGetLastError();
-    rc = RANNC_DP_HIP_ERROR;
-  }
+  if (rc == RANNC_DP_OK) rc = traceback_impl(h, hip_stream, d_lev, stride, d_se, d_rp, d_rec);
   if (rc != RANNC_DP_OK) {
     (void)hipStreamSynchronize(st);  // the mirror may be refilled by the next call
     return rc;

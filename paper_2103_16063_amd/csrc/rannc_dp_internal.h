@@ -146,8 +146,10 @@ hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t
 // launch must be a min-max search with traceback_lds_bytes(...) <= lds_bytes <= kTracebackLdsMax
 constexpr int kTracebackLdsMax = 150 * 1024;
 int64_t traceback_lds_bytes(int N, int DP, int S_eff, int bits);
+// rec != null: the plan of the search that rec[0] names is also written behind the six words of rec
 hipError_t launch_traceback(const ProblemDev *probs, int Q, int plan_stride, int32_t *d_stage_end,
-                            int32_t *d_replicas, const int32_t *d_levels, int64_t lds_bytes, hipStream_t st);
+                            int32_t *d_replicas, const int32_t *d_levels, int64_t lds_bytes, int64_t *rec,
+                            hipStream_t st);
 hipError_t launch_level_values(const ProblemDev *probs, int Q, int stride, int64_t *d_out, hipStream_t st);
 // compaction step of the block-level phase on a chain of G groups (one workgroup).  Chains whose
 // state fits LDS (kCompactLds groups) need only the listing in the workspace, longer ones keep
@@ -168,11 +170,9 @@ hipError_t launch_compact(int G, int k, int64_t M, int max_walks, const int64_t 
                           int64_t *p_out, int64_t *a_out, int32_t *status, hipStream_t st);
 // outer driver: Algorithm 2's loops over the values of a solved batch, and the chosen plan packed
 // behind the result record (rec: 6 int64 {q, S, bad status, 0, V, estimate}, then 2*stride int32)
-hipError_t launch_form_stage_select(int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *vals,
-                                    const int32_t *status, const int32_t *pair_n, const int32_t *pair_mb,
+hipError_t launch_form_stage_select(const ProblemDev *probs, int Q, int stride, int N, int n_nodes,
+                                    int devices_per_node, const int32_t *pair_n, const int32_t *pair_mb,
                                     int32_t *levels, int64_t *rec, hipStream_t st);
-hipError_t launch_form_stage_pack(int stride, const int32_t *stage_end, const int32_t *replicas, int64_t *rec,
-                                  hipStream_t st);
 hipError_t launch_export(const ProblemDev *prob, int which, int bits, void *d_dst, hipStream_t st);
 
 

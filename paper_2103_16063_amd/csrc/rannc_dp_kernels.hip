@@ -1266,9 +1266,22 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
 
 constexpr int kTracebackThreads = 1024;
 
+// The plan of the search that a record names in its first word, copied behind the record (the outer
+// driver's result: record and plan then reach the host in one copy).
+__device__ __forceinline__ void plan_to_record(const ProblemDev &pr, int plan_stride, const int32_t *se,
+                                               const int32_t *rp, int64_t *rec) {
+  __syncthreads();  // the walk's stores, by this workgroup's first thread, are visible to all of it
+  if ((int)rec[0] != pr.q) return;
+  int32_t *plan = (int32_t *)(rec + 6);
+  for (int u = threadIdx.x; u < plan_stride; u += blockDim.x) {
+    plan[u] = se[u];
+    plan[plan_stride + u] = rp[u];
+  }
+}
+
 __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
     const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas,
-    const int32_t *__restrict__ d_levels) {
+    const int32_t *__restrict__ d_levels, int64_t *rec) {
   __shared__ unsigned int best_key;
   const ProblemDev pr = probs[blockIdx.x];  // by value: no reloads after the plan stores
   const int forced = d_levels ? d_levels[pr.q] : 0;
@@ -1284,17 +1297,16 @@ __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
   if (pr.VF) {  // split objective: first-match over all candidates
     if (pr.bits == 32) traceback_split_body<uint32_t>(pr, plan_stride, se, rp, &best_key, forced);
     else traceback_split_body<uint64_t>(pr, plan_stride, se, rp, &best_key, forced);
-    return;
-  }
-  if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
+  } else if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
+  if (rec) plan_to_record(pr, plan_stride, se, rp, rec);
 }
 
 // Plan recovery out of LDS, for launches of few, small min-max searches (the host checks that every
 // search of the launch fits traceback_lds_bytes() into the dynamic LDS it passes).
 __global__ __launch_bounds__(kTracebackThreads) void traceback_lds_kernel(
     const ProblemDev *__restrict__ probs, int plan_stride, int32_t *d_stage_end, int32_t *d_replicas,
-    const int32_t *__restrict__ d_levels) {
+    const int32_t *__restrict__ d_levels, int64_t *rec) {
   __shared__ unsigned int best_key;
   extern __shared__ __align__(16) char staged[];
   const ProblemDev pr = probs[blockIdx.x];
@@ -1310,6 +1322,7 @@ __global__ __launch_bounds__(kTracebackThreads) void traceback_lds_kernel(
   }
   if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
+  if (rec) plan_to_record(pr, plan_stride, se, rp, rec);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1557,7 +1570,8 @@ int64_t traceback_lds_bytes(int N, int DP, int S_eff, int bits) {
 }
 
 hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t *d_stage_end,
-                            int32_t *d_replicas, const int32_t *d_levels, int64_t lds_bytes, hipStream_t st) {
+                            int32_t *d_replicas, const int32_t *d_levels, int64_t lds_bytes, int64_t *rec,
+                            hipStream_t st) {
   if (lds_bytes > 0) {
     // more than the default 64 KiB of dynamic LDS has to be asked for once
     static const hipError_t attr = hipFuncSetAttribute((const void *)traceback_lds_kernel,
@@ -1565,10 +1579,10 @@ hipError_t launch_traceback(const ProblemDev *p, int Q, int plan_stride, int32_t
     if (attr != hipSuccess) return attr;
     if (lds_bytes > kTracebackLdsMax) return hipErrorInvalidValue;
     hipLaunchKernelGGL(traceback_lds_kernel, dim3(Q), dim3(kTracebackThreads), (size_t)lds_bytes, st, p, plan_stride,
-                       d_stage_end, d_replicas, d_levels);
+                       d_stage_end, d_replicas, d_levels, rec);
   } else {
     hipLaunchKernelGGL(traceback_kernel, dim3(Q), dim3(kTracebackThreads), 0, st, p, plan_stride, d_stage_end,
-                       d_replicas, d_levels);
+                       d_replicas, d_levels, rec);
   }
   return hipGetLastError();
 }
@@ -1606,89 +1620,87 @@ hipError_t launch_level_values(const ProblemDev *p, int Q, int stride, int64_t *
 // counts n = 1, 2, 4, ... in turn, for each the stage counts S ascending over
 // (devices_per_node*(n-1), devices_per_node*n], and for the first S that any search of that n can
 // realise (V[S][N][D] finite), the search with the smallest (MB + S - 1) * V, the first one in
-// batch order among equals.  One wave: a lane per search of the batch (in rounds of 64), the
-// candidates of one (n, S) reduced with the lexicographic minimum of (estimate, search index).
-// Writes the record {q, S, first bad status or 0, 0, V, estimate} and the forced-level array of
-// the plan recovery (S at the chosen search, -1 = no plan wanted elsewhere).  q = -1: infeasible.
+// batch order among equals.  That is the lexicographic minimum of (n, S, estimate, search index)
+// over all feasible (search, S) pairs, S inside the range of the search's n: one wave, a lane per
+// search (in rounds of 64) reads its values straight from the value tables (all reads of a lane
+// are independent), then one reduction over the wave.
+// Writes the record {q, S, first bad status in batch order or 0, 0, V, estimate}, the plan area
+// behind it (-1 everywhere; the plan recovery fills in the chosen search's), and the level array
+// of the plan recovery (S at the chosen search, -1 = no plan wanted elsewhere).  q = -1: infeasible.
 // ---------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void form_stage_select_kernel(
-    int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *__restrict__ vals,
-    const int32_t *__restrict__ status, const int32_t *__restrict__ pair_n, const int32_t *__restrict__ pair_mb,
-    int32_t *__restrict__ levels, int64_t *__restrict__ rec) {
+    const ProblemDev *__restrict__ probs, int Q, int stride, int N, int n_nodes, int devices_per_node,
+    const int32_t *__restrict__ pair_n, const int32_t *__restrict__ pair_mb, int32_t *__restrict__ levels,
+    int64_t *__restrict__ rec) {
+  constexpr int NONE = 0x7fffffff;
+  constexpr int kMaxRange = 64;  // devices_per_node <= RANNC_DP_MAX_DEVICES
   const int lane = threadIdx.x;
-  int bad = 0;
-  for (int q = lane; q < Q; q += 64) {
+  int32_t *plan = (int32_t *)(rec + 6);
+  for (int u = lane; u < 2 * stride; u += 64) plan[u] = -1;
+  int bad_q = NONE, bad_st = 0;
+  int best_k = NONE, best_q = NONE;  // k = n << 16 | S
+  int64_t best_e = INT64_MAX, best_v = 0;
+  for (int p = lane; p < Q; p += 64) {
+    const ProblemDev &pr = probs[p];
+    const int q = pr.q;
     levels[q] = -1;  // only the chosen search's plan is recovered
-    const int st = status[q];
-    if (st != 0 && bad == 0) bad = st;
-  }
-  // first bad status in batch order
-  unsigned long long m = __ballot(bad != 0);
-  int bad_all = 0;
-  if (m != 0ull) bad_all = __shfl(bad, __ffsll((long long)m) - 1);
-  int q_sel = -1, S_sel = 0;
-  int64_t v_sel = 0, est_sel = 0;
-  if (bad_all == 0) {
-    for (int n = 1; n <= n_nodes && q_sel < 0; n *= 2) {
-      const int D = devices_per_node * n;
-      for (int S = devices_per_node * (n - 1) + 1; S <= D && q_sel < 0; ++S) {
-        if (S > min(N, D)) break;  // no search of this n has that many levels
-        int64_t best_e = INT64_MAX, best_v = 0;
-        int best_q = 0x7fffffff;
-        for (int q = lane; q < Q; q += 64) {
-          if (pair_n[q] != n) continue;
-          const int64_t v = vals[(int64_t)q * stride + S - 1];
-          if (v == INT64_MAX) continue;
-          const int64_t f = (int64_t)pair_mb[q] + S - 1;
-          const int64_t e = (v != 0 && f > INT64_MAX / v) ? INT64_MAX : f * v;
-          if (best_q == 0x7fffffff || e < best_e) { best_e = e; best_v = v; best_q = q; }  // q ascends per lane
-        }
-#pragma unroll
-        for (int o = 32; o >= 1; o >>= 1) {
-          const int64_t oe = __shfl_xor(best_e, o), ov = __shfl_xor(best_v, o);
-          const int oq = __shfl_xor(best_q, o);
-          if (oq != 0x7fffffff && (best_q == 0x7fffffff || oe < best_e || (oe == best_e && oq < best_q))) {
-            best_e = oe; best_v = ov; best_q = oq;
-          }
-        }
-        if (best_q != 0x7fffffff) { q_sel = best_q; S_sel = S; v_sel = best_v; est_sel = best_e; }
+    const int st = *pr.status;
+    if (st != 0) {
+      if (q < bad_q) { bad_q = q; bad_st = st; }
+      continue;
+    }
+    const int n = pair_n[q];
+    const int64_t mb = pair_mb[q];
+    const int lo = devices_per_node * (n - 1) + 1;
+    const int hi = min(min(devices_per_node * n, N), pr.S_eff);
+    const int64_t lvl = (int64_t)(pr.N + 1) * pr.DP, cell = (int64_t)pr.N * pr.DP + pr.D - 1;
+    // the first S of the range that this search can realise (a smaller S always wins for one n)
+    for (int S = lo; S <= hi && S < lo + kMaxRange; ++S) {
+      int64_t v;
+      if (pr.bits == 32) {
+        const uint32_t u = ((const uint32_t *)pr.V)[(S - 1) * lvl + cell];
+        v = (u == Lim<uint32_t>::inf) ? INT64_MAX : (int64_t)u;
+      } else {
+        const uint64_t u = ((const uint64_t *)pr.V)[(S - 1) * lvl + cell];
+        v = (u == Lim<uint64_t>::inf) ? INT64_MAX : (int64_t)u;
       }
+      if (v == INT64_MAX) continue;
+      const int64_t f = mb + S - 1;
+      const int64_t e = (v != 0 && f > INT64_MAX / v) ? INT64_MAX : f * v;
+      const int k = n << 16 | S;
+      if (k < best_k || (k == best_k && (e < best_e || (e == best_e && q < best_q)))) {
+        best_k = k; best_e = e; best_v = v; best_q = q;
+      }
+      break;
     }
   }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const int ok = __shfl_xor(best_k, o), oq = __shfl_xor(best_q, o);
+    const int64_t oe = __shfl_xor(best_e, o), ov = __shfl_xor(best_v, o);
+    if (ok < best_k || (ok == best_k && (oe < best_e || (oe == best_e && oq < best_q)))) {
+      best_k = ok; best_e = oe; best_v = ov; best_q = oq;
+    }
+    const int obq = __shfl_xor(bad_q, o), obs = __shfl_xor(bad_st, o);
+    if (obq < bad_q) { bad_q = obq; bad_st = obs; }
+  }
   if (lane == 0) {
-    if (q_sel >= 0) levels[q_sel] = S_sel;
-    rec[0] = q_sel;
-    rec[1] = S_sel;
-    rec[2] = bad_all;
+    const bool found = bad_q == NONE && best_q != NONE;
+    if (found) levels[best_q] = best_k & 0xffff;
+    rec[0] = found ? best_q : -1;
+    rec[1] = found ? (best_k & 0xffff) : 0;
+    rec[2] = bad_q == NONE ? 0 : bad_st;
     rec[3] = 0;
-    rec[4] = v_sel;
-    rec[5] = est_sel;
+    rec[4] = found ? best_v : 0;
+    rec[5] = found ? best_e : 0;
   }
 }
 
-// The chosen search's plan, copied behind the record so that one copy brings everything to the host.
-__global__ __launch_bounds__(64) void form_stage_pack_kernel(int stride, const int32_t *__restrict__ stage_end,
-                                                             const int32_t *__restrict__ replicas,
-                                                             int64_t *__restrict__ rec) {
-  const int q = (int)rec[0];
-  int32_t *plan = (int32_t *)(rec + 6);
-  for (int u = threadIdx.x; u < stride; u += 64) {
-    plan[u] = q >= 0 ? stage_end[(int64_t)q * stride + u] : -1;
-    plan[stride + u] = q >= 0 ? replicas[(int64_t)q * stride + u] : -1;
-  }
-}
-
-hipError_t launch_form_stage_select(int Q, int stride, int N, int n_nodes, int devices_per_node, const int64_t *vals,
-                                    const int32_t *status, const int32_t *pair_n, const int32_t *pair_mb,
+hipError_t launch_form_stage_select(const ProblemDev *probs, int Q, int stride, int N, int n_nodes,
+                                    int devices_per_node, const int32_t *pair_n, const int32_t *pair_mb,
                                     int32_t *levels, int64_t *rec, hipStream_t st) {
-  hipLaunchKernelGGL(form_stage_select_kernel, dim3(1), dim3(64), 0, st, Q, stride, N, n_nodes, devices_per_node, vals,
-                     status, pair_n, pair_mb, levels, rec);
-  return hipGetLastError();
-}
-
-hipError_t launch_form_stage_pack(int stride, const int32_t *stage_end, const int32_t *replicas, int64_t *rec,
-                                  hipStream_t st) {
-  hipLaunchKernelGGL(form_stage_pack_kernel, dim3(1), dim3(64), 0, st, stride, stage_end, replicas, rec);
+  hipLaunchKernelGGL(form_stage_select_kernel, dim3(1), dim3(64), 0, st, probs, Q, stride, N, n_nodes, devices_per_node,
+                     pair_n, pair_mb, levels, rec);
   return hipGetLastError();
 }
 
