@@ -509,7 +509,9 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
              hipSuccess;
       else
         ok = rannc::launch_level_merge(dp + cls_start[k], sh, h->bits, kClasses[k], s, recompute_cls[k], merge_items[k],
-                                       st) == hipSuccess;
+                                       // measured: c4 (64 devices) 0.410 -> 0.401 ms; c3, c2 (32, 16 devices,
+                                       // launches of 4-6 us) 1-2 us slower per solve with the larger argument block
+                                       sh.nprob == 1 && kClasses[k] == 64 ? &probs[cls_start[k]] : nullptr, st) == hipSuccess;
       h->level_launches++;
     }
   }

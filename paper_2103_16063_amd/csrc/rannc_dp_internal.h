@@ -116,8 +116,9 @@ int64_t merge_launch_rows(const LaunchShape &sh);
 // recompute: the level kernel computes the stage times from the prefix sums instead of reading
 // their table (32-bit values only)
 // items: merge_grid_items of the launch, the value launch_runs was given
+// host_one: for a launch over one search, a host copy of its descriptor (passed by value), or null
 hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
-                              bool recompute, int items, hipStream_t st);
+                              bool recompute, int items, const ProblemDev *host_one, hipStream_t st);
 // whole search of problems with N <= small_max_blocks() in one launch, one workgroup each
 int small_max_blocks();
 // direct: the stage times are recomputed from the prefix sums and no table is written (only where

@@ -657,9 +657,7 @@ __device__ __forceinline__ bool merge_rows(VT (&acc)[DP], VT *tile_lane, const P
 }
 
 template <typename VT, int DP, bool DIRECT>
-__global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP, DIRECT>())))
-void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
-  const ProblemDev &pr = probs[blockIdx.z];
+__device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int s) {
   if (s > pr.S_eff) return;
   const int N = pr.N, D = pr.D;
   const int32_t RANNC_GLOBAL *__restrict__ runs = gptr((const int32_t *)pr.runs);
@@ -735,6 +733,21 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
     const int j = 64 * c + row + 1;
     if (t + 1 <= D - 1 && j <= N && j >= s && v != INF) global_min(&Vcur[(int64_t)j * DP + t + 1], v);
   }
+}
+
+template <typename VT, int DP, bool DIRECT>
+__global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP, DIRECT>())))
+void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
+  level_merge_body<VT, DP, DIRECT>(probs[blockIdx.z], s);
+}
+
+// The same for a launch over ONE search, with the descriptor as a kernel argument: a workgroup then
+// starts with its fields in scalar registers instead of fetching them through the descriptor
+// array's pointer, one memory round trip less in a launch that consists of a few of them.
+template <typename VT, int DP, bool DIRECT>
+__global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP, DIRECT>())))
+void level_merge_one_kernel(const ProblemDev pr, const int s) {
+  level_merge_body<VT, DP, DIRECT>(pr, s);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1497,7 +1510,13 @@ hipError_t launch_build(const ProblemDev *p, const LaunchShape &sh, int bits, in
 }
 
 template <typename VT, int DP, bool DIRECT>
-static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, int items, hipStream_t st) {
+static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, int items, const ProblemDev *host_one,
+                     hipStream_t st) {
+  if (host_one && sh.nprob == 1) {
+    hipLaunchKernelGGL((level_merge_one_kernel<VT, DP, DIRECT>), dim3((unsigned)items, 1, 1), dim3(64 * kMergeWaves), 0,
+                       st, *host_one, s);
+    return;
+  }
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
     hipLaunchKernelGGL((level_merge_kernel<VT, DP, DIRECT>), dim3((unsigned)items, 1, nq), dim3(64 * kMergeWaves), 0,
@@ -1506,14 +1525,14 @@ static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, int item
 }
 
 hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s, bool recompute,
-                              int items, hipStream_t st) {
+                              int items, const ProblemDev *host_one, hipStream_t st) {
   if (recompute && bits != 32) return hipErrorInvalidValue;
 #define GO(B, T, X)                                                            \
   if (bits == B && recompute == X) {                                           \
-    if (DP == 8) merge_go<T, 8, X>(p, sh, s, items, st);               \
-    else if (DP == 16) merge_go<T, 16, X>(p, sh, s, items, st);        \
-    else if (DP == 32) merge_go<T, 32, X>(p, sh, s, items, st);        \
-    else merge_go<T, 64, X>(p, sh, s, items, st);                      \
+    if (DP == 8) merge_go<T, 8, X>(p, sh, s, items, host_one, st);               \
+    else if (DP == 16) merge_go<T, 16, X>(p, sh, s, items, host_one, st);        \
+    else if (DP == 32) merge_go<T, 32, X>(p, sh, s, items, host_one, st);        \
+    else merge_go<T, 64, X>(p, sh, s, items, host_one, st);                      \
   }
   GO(32, uint32_t, false)
   GO(32, uint32_t, true)
