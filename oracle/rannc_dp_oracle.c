@@ -186,10 +186,31 @@ int rannc_oracle_dp(int32_t N, int32_t D, int32_t n_levels, const int64_t *cost,
   return ORACLE_OK;
 }
 
+/* A plan for blocks 1..j on d devices as Algorithm 1 with separate forward and backward maxima sees
+ * it: its longest forward and backward stage times, and where its last stage begins (split point i,
+ * devices dp spent before it).  none = no such plan. */
+typedef struct {
+  int64_t fwd, bwd;
+  int32_t i, dp;
+  int none;
+} split_plan_t;
+
+/* Which of two plans for the same cell the algorithm keeps: the smaller sum of the two maxima; among
+ * equal sums the one it meets first, i.e. the smaller split point, then the fewer devices before the
+ * last stage (it walks both upwards and replaces only on a strictly smaller sum). */
+static int split_plan_wins(const split_plan_t *x, const split_plan_t *y) {
+  if (x->none || y->none) return !x->none;
+  const int64_t sx = x->fwd + x->bwd, sy = y->fwd + y->bwd;
+  if (sx != sy) return sx < sy;
+  if (x->i != y->i) return x->i < y->i;
+  return x->dp < y->dp;
+}
+
 /* Algorithm 1 with the forward and backward maxima carried separately (see the header): costf and
  * costb are two stage-time tables in the layout of `cost`, TF and TB have the shape of V and hold
  * the largest forward / backward stage time of the plan behind each cell (0 at level 0's origin,
- * INF where V is). */
+ * INF where V is).  A cell keeps ONE plan (split_plan_wins), and only that plan is extended at the
+ * next level: the heuristic of the printed algorithm, not an exact minimum. */
 int rannc_oracle_dp_split(int32_t N, int32_t D, int32_t n_levels, const int64_t *costf,
                           const int64_t *costb, const uint8_t *fit, int64_t *V, int64_t *TF,
                           int64_t *TB, int32_t *arg_i, int32_t *arg_d, int32_t n_threads) {
@@ -211,25 +232,30 @@ int rannc_oracle_dp_split(int32_t N, int32_t D, int32_t n_levels, const int64_t 
 #endif
     for (int32_t j = s; j <= N; ++j) {
       for (int32_t d = s; d <= D; ++d) {
-        const size_t c = CELL(s, j, d);
-        for (int32_t i = s - 1; i < j; ++i) {       /* split point b', ascending */
-          for (int32_t dp = s - 1; dp < d; ++dp) {  /* devices of the earlier stages d', ascending */
-            const size_t pc = CELL(s - 1, i, dp);
-            if (V[pc] == ORACLE_INF) continue; /* earlier stages infeasible */
-            const int32_t r = d - dp; /* replicas of the stage being formed */
-            size_t e = (size_t)(((int64_t)j * (j - 1) / 2 + i) * D) + (size_t)(r - 1);
-            if (!fit[e]) continue; /* does not fit device memory */
-            int64_t f = TF[pc] > costf[e] ? TF[pc] : costf[e]; /* longest forward pass so far */
-            int64_t b = TB[pc] > costb[e] ? TB[pc] : costb[e]; /* longest backward pass so far */
-            int64_t v = f + b;
-            if (v < V[c]) {
-              V[c] = v;
-              TF[c] = f;
-              TB[c] = b;
-              arg_i[c] = i;
-              arg_d[c] = dp;
-            }
+        split_plan_t kept = {0, 0, -1, -1, 1};
+        /* every way to end at (j, d): the kept plan of s-1 stages for blocks 1..i on dp devices,
+         * followed by the stage (i, j] on the remaining d - dp devices */
+        for (int32_t i = s - 1; i < j; ++i) {
+          for (int32_t dp = s - 1; dp < d; ++dp) {
+            const size_t before = CELL(s - 1, i, dp);
+            const size_t stage = (size_t)(((int64_t)j * (j - 1) / 2 + i) * D) + (size_t)(d - dp - 1);
+            if (V[before] == ORACLE_INF || !fit[stage]) continue; /* nothing to extend / stage too large */
+            split_plan_t cand;
+            cand.fwd = TF[before] > costf[stage] ? TF[before] : costf[stage];
+            cand.bwd = TB[before] > costb[stage] ? TB[before] : costb[stage];
+            cand.i = i;
+            cand.dp = dp;
+            cand.none = 0;
+            if (split_plan_wins(&cand, &kept)) kept = cand;
           }
+        }
+        if (!kept.none) {
+          const size_t c = CELL(s, j, d);
+          V[c] = kept.fwd + kept.bwd;
+          TF[c] = kept.fwd;
+          TB[c] = kept.bwd;
+          arg_i[c] = kept.i;
+          arg_d[c] = kept.dp;
         }
       }
     }
@@ -238,52 +264,58 @@ int rannc_oracle_dp_split(int32_t N, int32_t D, int32_t n_levels, const int64_t 
   return ORACLE_OK;
 }
 
+/* Min-max value of cell (s, b, d) from level s-1 (the recurrence of Sec. III-C over every split
+ * point and device split); *scanned counts the predecessor cells looked at. */
+static int64_t minmax_cell(int32_t D, size_t ND, const int64_t *V, const int64_t *cost, const uint8_t *fit,
+                           int32_t s, int32_t b, int32_t d, int64_t *scanned) {
+  int64_t best = ORACLE_INF;
+  for (int32_t from = s - 1; from < b; ++from) {
+    for (int32_t used = s - 1; used < d; ++used) {
+      ++*scanned;
+      const int64_t earlier = V[(size_t)(s - 1) * ND + (size_t)from * (size_t)(D + 1) + (size_t)used];
+      const size_t stage = (size_t)(((int64_t)b * (b - 1) / 2 + from) * D) + (size_t)(d - used - 1);
+      if (earlier == ORACLE_INF || !fit[stage]) continue;
+      const int64_t slowest = earlier > cost[stage] ? earlier : cost[stage];
+      if (slowest < best) best = slowest;
+    }
+  }
+  return best;
+}
+
 /* Algorithm 1 for EXACTLY S stages with the search-space pruning it prints (a study, not part of
- * the search the HIP path runs): block counts b = s .. N-S+s, device totals d descending from
- * D-(S-s) to max(d_min, s), and the running bound d_min: the first (s, b, d) that ends without a
- * solution sets d_min = d + 1 for everything that follows and ends that d loop.  Min-max
- * objective, candidates scanned as in rannc_oracle_dp.  V has the shape [(S+1)][N+1][D+1]; cells
- * that are never visited stay INF.  stats[0] = cells visited, stats[1] = candidates (b', d')
- * scanned, stats[2] = final d_min. */
+ * the search the HIP path runs).  Level s looks only at block counts that leave a block for each
+ * of the S-s later stages and at device totals that leave a device for each of them; the totals
+ * are tried from the largest down, and the first cell anywhere that has no solution raises a
+ * floor (d_min, kept for the rest of the run) to just above its device total and ends that
+ * descent.  V has the shape [(S+1)][N+1][D+1]; cells that are never visited stay INF.
+ * stats[0] = cells visited, stats[1] = candidates (b', d') scanned, stats[2] = final d_min. */
 int rannc_oracle_dp_pruned(int32_t N, int32_t D, int32_t S, const int64_t *cost, const uint8_t *fit,
                            int64_t *V, int64_t *stats) {
   if (N < 1 || D < 1 || S < 1 || S > N || S > D || !cost || !fit || !V || !stats) return ORACLE_BAD_ARG;
   const size_t ND = (size_t)(N + 1) * (size_t)(D + 1);
-#define CELL(s, j, d) ((size_t)(s) * ND + (size_t)(j) * (size_t)(D + 1) + (size_t)(d))
   for (size_t e = 0; e < ((size_t)S + 1) * ND; ++e) V[e] = ORACLE_INF;
   V[0] = 0; /* cell (0, 0, 0) */
-  int32_t d_min = 1;
+  int32_t floor_d = 1; /* d_min */
   int64_t cells = 0, cands = 0;
   for (int32_t s = 1; s <= S; ++s) {
-    for (int32_t b = s; b <= N - S + s; ++b) {
-      const int32_t d_low = d_min > s ? d_min : s;
-      for (int32_t d = D - (S - s); d >= d_low; --d) {
-        int64_t best = ORACLE_INF;
+    const int32_t later = S - s; /* stages still to come: each needs a block and a device */
+    for (int32_t b = s; b + later <= N; ++b) {
+      int32_t d = D - later;
+      while (d >= s && d >= floor_d) {
         ++cells;
-        for (int32_t bp = s - 1; bp <= b - 1; ++bp) {
-          for (int32_t dq = s - 1; dq <= d - 1; ++dq) {
-            ++cands;
-            const int64_t ante = V[CELL(s - 1, bp, dq)];
-            if (ante == ORACLE_INF) continue;
-            const size_t e = (size_t)(((int64_t)b * (b - 1) / 2 + bp) * D) + (size_t)(d - dq - 1);
-            if (!fit[e]) continue;
-            const int64_t h = cost[e];
-            const int64_t cand = ante > h ? ante : h;
-            if (cand < best) best = cand;
-          }
-        }
-        V[CELL(s, b, d)] = best;
-        if (best == ORACLE_INF) { /* no solution with d: nothing below it is tried any more */
-          d_min = d + 1;
+        const int64_t v = minmax_cell(D, ND, V, cost, fit, s, b, d, &cands);
+        V[(size_t)s * ND + (size_t)b * (size_t)(D + 1) + (size_t)d] = v;
+        if (v == ORACLE_INF) {
+          floor_d = d + 1;
           break;
         }
+        --d;
       }
     }
   }
-#undef CELL
   stats[0] = cells;
   stats[1] = cands;
-  stats[2] = d_min;
+  stats[2] = floor_d;
   return ORACLE_OK;
 }
 

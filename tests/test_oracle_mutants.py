@@ -48,18 +48,18 @@ MUTANTS = {
     "comm_floor_instead_of_ceil": ("h += (int64_t)((num + den - 1) / den);", "h += (int64_t)(num / den);"),
     "comm_wrong_time_unit": ("num = (__int128)1000 * o[j - 1];", "num = (__int128)1024 * o[j - 1];"),
     "comm_replaces_compute": ("h += (int64_t)((num + den - 1) / den);", "h = (int64_t)((num + den - 1) / den);"),
-    "split_max_instead_of_sum": ("int64_t v = f + b;", "int64_t v = f > b ? f : b;"),
-    "split_keeps_last_minimiser": ("if (v < V[c]) {", "if (v <= V[c]) {"),
-    "split_backward_takes_forward_table": ("int64_t b = TB[pc] > costb[e] ? TB[pc] : costb[e];",
-                                           "int64_t b = TB[pc] > costf[e] ? TB[pc] : costf[e];"),
-    "split_forward_ignores_history": ("int64_t f = TF[pc] > costf[e] ? TF[pc] : costf[e];",
-                                      "int64_t f = costf[e];"),
-    "split_stores_wrong_half": ("TB[c] = b;", "TB[c] = f;"),
-    "split_history_from_value": ("int64_t b = TB[pc] > costb[e] ? TB[pc] : costb[e];",
-                                 "int64_t b = V[pc] > costb[e] ? V[pc] : costb[e];"),
+    "split_max_instead_of_sum": ("V[c] = kept.fwd + kept.bwd;", "V[c] = kept.fwd > kept.bwd ? kept.fwd : kept.bwd;"),
+    "split_keeps_last_minimiser": ("if (x->i != y->i) return x->i < y->i;", "if (x->i != y->i) return x->i > y->i;"),
+    "split_backward_takes_forward_table": ("cand.bwd = TB[before] > costb[stage] ? TB[before] : costb[stage];",
+                                           "cand.bwd = TB[before] > costf[stage] ? TB[before] : costf[stage];"),
+    "split_forward_ignores_history": ("cand.fwd = TF[before] > costf[stage] ? TF[before] : costf[stage];",
+                                      "cand.fwd = costf[stage];"),
+    "split_stores_wrong_half": ("TB[c] = kept.bwd;", "TB[c] = kept.fwd;"),
+    "split_history_from_value": ("cand.bwd = TB[before] > costb[stage] ? TB[before] : costb[stage];",
+                                 "cand.bwd = V[before] > costb[stage] ? V[before] : costb[stage];"),
     "split_skips_split_at_s_minus_1": ("for (int32_t i = s - 1; i < j; ++i) {", "for (int32_t i = s; i < j; ++i) {"),
     "split_device_loop_stops_early": ("for (int32_t dp = s - 1; dp < d; ++dp) {", "for (int32_t dp = s - 1; dp < d - 1; ++dp) {"),
-    "split_wrong_replica_index": ("const int32_t r = d - dp;", "const int32_t r = dp + 1;"),
+    "split_wrong_replica_index": ("* D) + (size_t)(d - dp - 1);", "* D) + (size_t)(dp);"),
     "compact_ties_to_the_right": ("else w = ct[r] < ct[l] ? r : l;", "else w = ct[r] <= ct[l] ? r : l;"),
     "compact_takes_the_slower_neighbour": ("else w = ct[r] < ct[l] ? r : l;", "else w = ct[r] > ct[l] ? r : l;"),
     "compact_fit_exclusive": ("if (cm[v] + cm[w] > M) continue;", "if (cm[v] + cm[w] >= M) continue;"),
