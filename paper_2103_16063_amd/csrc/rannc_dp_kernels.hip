@@ -256,9 +256,12 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
 // stage-time table is written (64 row stores per unit keep it busy), several when only the
 // fits-in-memory part is (a unit is then 65 bytes of output, and a launch of one wave per unit is
 // bound by the rate at which waves can be started).
+// (The several-rows variant is held to the registers of four waves per SIMD: its time goes into the
+// latency of many short units, and the 64 quotients of row 0, the only row that needs them there,
+// would otherwise halve the waves in flight at 64 devices.)
 template <typename VT, int DP, int ROWS>
-__global__ __launch_bounds__(64 * kBuildWaves) void build_kernel(const ProblemDev *__restrict__ probs,
-                                                                 const int parts) {
+__global__ __launch_bounds__(64 * kBuildWaves) __attribute__((amdgpu_waves_per_eu(ROWS > 1 ? 4 : 1)))
+void build_kernel(const ProblemDev *__restrict__ probs, const int parts) {
   const ProblemDev &pr = probs[blockIdx.z];
   const int lane = threadIdx.x & 63;
   const int i0 = (blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6)) * ROWS, c = blockIdx.x;
