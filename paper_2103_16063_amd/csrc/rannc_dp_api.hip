@@ -441,27 +441,40 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     if (!sh.nprob) continue;
     const ProblemDev *cp = dp + cls_start[k];
     const hipStream_t st = cs[k];  // this class's stream
-    // Small searches: everything in one launch, one workgroup per search.  Measured on MI355X
-    // (N = 16..128, D = 8..64, 1..512 searches per class): it wins whenever a workgroup has little
-    // to walk through (rows x levels up to about 480: no launch per level, levels folded in LDS),
-    // and for classes of hundreds of searches at D <= 16 or N <= 64, where the launches per level
-    // are throughput-bound as well; otherwise a workgroup's waves work through too many table rows one
-    // after the other and the launch per level, which spreads the rows over the whole device, is
-    // faster (up to 10x at N = 128, D = 64).
+    // Small searches: everything in one launch, one workgroup per search, where that measured
+    // faster than the launches per level (MI355X; N = 16..128, D = 8..64, 1..512 searches per class).
     {
       const int64_t rows = std::min(sh.max_N, 64) + (sh.max_nch > 1 ? sh.max_N : 0);
       const int levels = sh.max_S_eff - 1;
-      const bool batch = sh.nprob >= 256 && (kClasses[k] <= 16 || sh.max_N <= 64);
-      // the one-launch kernel that recomputes the stage times reads nothing from memory in its
-      // levels: a level costs it (rows / 16 waves) passes of 0.75 / 1.25 / 1.7 us (8 / 16 / 32
-      // devices; four waves share a SIMD), a level launch costs 4.5 us and the launches in front of
-      // the levels 27 us (N = 32, D = 32, 31 levels: 111 against 172 us; N = 96, D = 16, 7 levels:
-      // 94 against 49 us)
+      const int cls = kClasses[k];
+      // the launches per level of a few small searches: 14 us in front of the levels, 4.4 us a level
+      const double launches_us = 14.0 + 4.4 * levels;
       const bool direct_ok = can_recompute && h->lim.algo != RANNC_DP_ALGO_MERGE &&
-                             rannc::small_can_recompute(h->bits, kClasses[k]);
-      const double pass_us = kClasses[k] <= 8 ? 0.75 : kClasses[k] <= 16 ? 1.25 : 1.7;
-      const bool tiny = direct_ok ? (double)((rows + 15) / 16) * pass_us * levels <= 4.5 * levels + 27.0
-                                  : rows * levels <= 480;
+                             rannc::small_can_recompute(h->bits, cls);
+      const bool heavy = h->bits / 8 * cls >= 256;  // the variants that run eight waves per search
+      bool tiny;
+      if (direct_ok) {
+        // Stage times recomputed: the levels read nothing from memory, and a level costs
+        // ceil(rows / 16 waves) passes whose price follows the width of the merge it still needs
+        // (0.9 / 1.4 / 2.85 us at 8 / 16 / 32 inputs: one compute unit's vector issue rate, four
+        // waves per SIMD).  N = 32, D = 32: 31 levels 124 against 156 us, 15 levels 98 against 92 us.
+        double us = 0.0;
+        for (int s = 2; s <= sh.max_S_eff; ++s) {
+          const int rl = sh.max_D - s + 1;
+          us += rl <= 8 ? 0.9 : rl <= 16 ? 1.4 : 2.85;
+        }
+        tiny = us * (double)((rows + 15) / 16) <= launches_us;
+      } else if (heavy) {
+        // 64 devices, or 64-bit values from 32 devices on, stage times from the table: a level costs
+        // about 7 us plus 1.7 us per pass of eight rows, more than a launch; only two or three levels
+        // are cheaper in one launch
+        tiny = rows <= (h->bits == 64 ? 16 : 32) && (7.0 + 1.7 * (double)((rows + 7) / 8)) * levels <= launches_us;
+      } else {
+        // stage times from the table, sixteen waves (sweep over N = 8..128, D = 8, 16, S = 2..D)
+        tiny = rows <= 64 && rows * levels <= (h->bits == 64 ? 240 : 480);
+      }
+      // hundreds of searches: the launches per level are throughput-bound as well
+      const bool batch = sh.nprob >= 256 && (cls <= 16 || sh.max_N <= 64) && !(h->bits == 64 && cls == 64);
       fused[k] = !scan && !split && sh.max_N <= rannc::small_max_blocks() &&
                  (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);
       fused_direct[k] = fused[k] && direct_ok;

@@ -764,18 +764,23 @@ void level_merge_one_kernel(const ProblemDev pr, const int s) {
 // form_stage_dp calls of Algorithm 2): one workgroup per search.
 // ---------------------------------------------------------------------------------------
 constexpr int kSmallMaxN = 128;
-constexpr int kSmallWaves = 16;
+// Sixteen waves per search, eight where a lane's value array alone takes 64 registers or more (64
+// devices, or 64-bit values from 32 devices on): with the 128 registers of sixteen waves those
+// kernels spilled up to 1 600 registers per lane.
+constexpr int kSmallWavesMax = 16;
+template <typename VT, int DP> constexpr int small_waves() { return sizeof(VT) * DP >= 256 ? 8 : kSmallWavesMax; }
 
 __device__ __forceinline__ void select_finish(const ProblemDev &pr, int64_t v, int st, int64_t *d_opt,
                                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status);
 
 template <typename VT, int DP, bool DIRECT>
-__global__ __launch_bounds__(64 * kSmallWaves) void solve_small_kernel(
+__global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kernel(
     const ProblemDev *__restrict__ probs, int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est,
     int32_t *d_status) {
   const ProblemDev &pr = probs[blockIdx.x];
   constexpr VT INF = Lim<VT>::inf;
   constexpr int LS = DP + 1;  // row stride of a level in LDS: lanes (= columns) hit different banks
+  constexpr int kSmallWaves = small_waves<VT, DP>();
   constexpr int NT = 64 * kSmallWaves;
   __shared__ int64_t sT[kSmallMaxN + 1], sP[kSmallMaxN + 1], sA[kSmallMaxN + 1], sC[kSmallMaxN + 1];
   __shared__ unsigned long long s_max_cut;
@@ -1554,7 +1559,7 @@ hipError_t launch_solve_small(const ProblemDev *p, int Q, int bits, int DP, bool
   if (direct && !small_can_recompute(bits, DP)) return hipErrorInvalidValue;
 #define GO(B, T, W, X)                                                                                 \
   if (bits == B && DP == W && direct == X)                                                             \
-    hipLaunchKernelGGL((solve_small_kernel<T, W, X>), dim3(Q), dim3(64 * kSmallWaves), 0, st, p, d_opt, \
+    hipLaunchKernelGGL((solve_small_kernel<T, W, X>), dim3(Q), dim3(64 * small_waves<T, W>()), 0, st, p, d_opt, \
                        d_n_stages, d_est, d_status);
   GO(32, uint32_t, 8, false) GO(32, uint32_t, 16, false) GO(32, uint32_t, 32, false) GO(32, uint32_t, 64, false)
   GO(64, uint64_t, 8, false) GO(64, uint64_t, 16, false) GO(64, uint64_t, 32, false) GO(64, uint64_t, 64, false)
