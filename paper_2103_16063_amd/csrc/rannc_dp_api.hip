@@ -486,7 +486,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
     if (split) {
       ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
-      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, 0, st) == hipSuccess;
+      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, 0, false, st) == hipSuccess;
     }
     if (scan || split) continue;
     // Rows per wave of the level kernel: chosen on the device from the size of the windows unless
@@ -494,7 +494,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     merge_items[k] = rannc::merge_grid_items(sh, rannc::merge_rows_per_item(h->tune_spw));
     ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), merge_items[k],
                                   h->n_cus * rannc::merge_workgroups_per_cu(h->bits, kClasses[k], recompute_cls[k]),
-                                  st) == hipSuccess;
+                                  recompute_cls[k], st) == hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;

@@ -107,7 +107,9 @@ hipError_t launch_windows(const ProblemDev *probs, const LaunchShape &sh, hipStr
 // rows_per_item: > 0 fixed, 0 chosen on the device for the split-objective kernel, -1 for the
 // sorted-merge kernel (then the smallest item size whose item count fits max_items)
 // slots: workgroups of the level kernel that the device holds at a time
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, hipStream_t st);
+// paired: the list for the level kernel that recomputes the stage times (diagonal blocks as row pairs)
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, bool paired,
+                       hipStream_t st);
 int merge_workgroups_per_cu(int bits, int DP, bool recompute);
 int merge_rows_per_item(int rows_per_wave);
 int merge_grid_items(const LaunchShape &sh, int rows_per_item);

@@ -333,32 +333,55 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // the round is then as full as it can be, and no compute unit is left with one workgroup more
 // than its neighbours.  One workgroup per problem.
 // ---------------------------------------------------------------------------------------
+// paired (the level kernel that recomputes the stage times): inside the diagonal block of a chunk
+// (rows 64c .. 64c+63, where row 64c+p has work only in the lanes from p on) the list holds the
+// rows p = 0 .. 32 only; the kernel treats row 64c+p as the PAIR of rows 64c+p and 64c+64-p, whose
+// lanes with work add up to exactly one wave.  The rows in front of the block and the listed rows
+// of the block form two segments, and no item crosses from one into the other; the last item of a
+// segment carries the number of rows that are left.
+struct RunSegments { int lo0, n0, lo1, n1; };
+__device__ __forceinline__ RunSegments run_segments(const ProblemDev &pr, int c, int paired) {
+  RunSegments g;
+  const int lo = pr.wlo[c], hi = min(64 * c + 63, pr.N - 1);
+  g.lo0 = lo; g.n0 = lo <= hi ? hi - lo + 1 : 0; g.lo1 = 0; g.n1 = 0;
+  if (paired && lo <= hi && hi >= 64 * c) {
+    const int w = max(lo, 64 * c) - 64 * c, hmax = hi - 64 * c;  // window start and last row inside the block
+    g.n0 = max(64 * c - lo, 0);
+    // pairs p_lo .. p_top: every pair that holds a row of the window (a few more when the window
+    // starts inside the block; their rows have no stage that fits and cost a skipped pass)
+    const int p_lo = w == 0 ? 0 : 1, p_top = w <= 32 ? min(32, hmax) : min(31, 64 - w);
+    g.lo1 = 64 * c + p_lo;
+    g.n1 = max(p_top - p_lo + 1, 0);
+  }
+  return g;
+}
+
 __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict__ probs, int rows, int max_items,
-                                                    int batch, int slots) {
+                                                    int batch, int slots, int paired) {
   const ProblemDev &pr = probs[blockIdx.x];
   __shared__ int start[1025];  // nch <= 1024 (N <= 65535)
+  __shared__ RunSegments seg[1024];  // every chunk's segments, computed once (one read of wlo per chunk)
   constexpr int NC = 16;  // candidate item sizes 4, 8, ..., 64 rows
   __shared__ int total_rows, count[NC];
-  const int nch = pr.nch, N = pr.N, tid = threadIdx.x;
+  const int nch = pr.nch, tid = threadIdx.x;
+  int32_t *const runs = pr.runs;  // (read once: the stores below would make the compiler fetch it again)
+  for (int c = tid; c < nch; c += 256) seg[c] = run_segments(pr, c, paired);
+  __syncthreads();
   if (rows <= 0) {
     if (tid < NC) count[tid] = 0;
     if (tid == 0) total_rows = 0;
     __syncthreads();
-    int mine = 0, cnt[NC];
-#pragma unroll
-    for (int k = 0; k < NC; ++k) cnt[k] = 0;
-    for (int c = tid; c < nch; c += 256) {
-      const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
-      if (lo <= hi) {
-        mine += hi - lo + 1;
-#pragma unroll
-        for (int k = 0; k < NC; ++k) cnt[k] += (hi - lo + 4 * (k + 1)) / (4 * (k + 1));
+    // thread t counts the items of candidate size 4 (t % 16 + 1) over the chunks t / 16, t / 16 + 16, ...
+    {
+      const int k = tid % NC, r = 4 * (k + 1);
+      int mine = 0, cnt = 0;
+      for (int c = tid / NC; c < nch; c += 256 / NC) {
+        const RunSegments g = seg[c];
+        mine += g.n0 + g.n1;
+        cnt += (g.n0 + r - 1) / r + (g.n1 + r - 1) / r;
       }
-    }
-    if (mine) {
-      atomicAdd(&total_rows, mine);
-#pragma unroll
-      for (int k = 0; k < NC; ++k) atomicAdd(&count[k], cnt[k]);
+      if (k == 0 && mine) atomicAdd(&total_rows, mine);
+      if (cnt) atomicAdd(&count[k], cnt);
     }
     __syncthreads();
     if (rows == 0) {
@@ -379,21 +402,42 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
       rows = 4 * (pick + 1);
     }
   }
-  const int tag = (rows - 1) << 26;
+  // per chunk: items of the two segments, and their rows dealt evenly over them (33 rows in items
+  // of up to 16: three items of 11, not 16 + 16 + 1); seg[c] is reused for {items0, per0, lo1, per1}
+  __shared__ int n0_of[1024], n1_of[1024];
   for (int c = tid; c < nch; c += 256) {
-    const int lo = pr.wlo[c], hi = min(64 * c + 63, N - 1);
-    start[c + 1] = lo <= hi ? (hi - lo + rows) / rows : 0;  // items of chunk c
+    const RunSegments g = seg[c];
+    const int items0 = (g.n0 + rows - 1) / rows, items1 = (g.n1 + rows - 1) / rows;
+    start[c + 1] = items0 + items1;  // items of chunk c
+    n0_of[c] = g.n0;
+    n1_of[c] = g.n1;
+    RunSegments h;
+    h.lo0 = g.lo0; h.n0 = items0; h.lo1 = g.lo1;
+    h.n1 = ((items0 ? (g.n0 + items0 - 1) / items0 : 0) << 8) | (items1 ? (g.n1 + items1 - 1) / items1 : 0);  // per0, per1 <= 64
+    seg[c] = h;
   }
   __syncthreads();
   if (tid == 0) {
     start[0] = 0;
     for (int c = 0; c < nch; ++c) start[c + 1] += start[c];
-    pr.runs[0] = start[nch];
+    runs[0] = start[nch];
   }
   __syncthreads();
-  for (int c = 0; c < nch; ++c) {
-    const int lo = pr.wlo[c], n = start[c + 1] - start[c];
-    for (int k = tid; k < n; k += 256) pr.runs[1 + start[c] + k] = tag | (c << 16) | (lo + k * rows);
+  const int total = start[nch];
+  for (int e = tid; e < total; e += 256) {
+    int lo = 0, hi = nch - 1;  // the chunk whose items contain e: start[c] <= e < start[c + 1]
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (start[mid + 1] <= e) lo = mid + 1;
+      else hi = mid;
+    }
+    const int c = lo, k = e - start[c];
+    const RunSegments h = seg[c];
+    const int items0 = h.n0, per0 = h.n1 >> 8, per1 = h.n1 & 255;
+    const int first = k < items0 ? h.lo0 + k * per0 : h.lo1 + (k - items0) * per1;
+    const int left = k < items0 ? n0_of[c] - k * per0 : n1_of[c] - (k - items0) * per1;
+    const int take = max(min(k < items0 ? per0 : per1, left), 1);  // (never below one row: the word stays well-formed)
+    runs[1 + e] = ((take - 1) << 26) | (c << 16) | first;
   }
 }
 
@@ -496,6 +540,9 @@ __device__ __forceinline__ void direct_consts_init(DirectConsts &k) {
   asm("" : "+v"(k.magic));
 }
 
+// AP of the helpers below: x[] already holds the lane's own a[] row (read per lane, not wave-uniform)
+struct InPlaceRow {};
+
 // entry r = ODD << SH and the ones it is the parent of
 template <int DP, int NG, int ODD, int SH, typename AP>
 __device__ __forceinline__ void direct_chain(uint32_t (&x)[DP], AP arow,
@@ -504,7 +551,8 @@ __device__ __forceinline__ void direct_chain(uint32_t (&x)[DP], AP arow,
   if constexpr (R <= 8 * NG && R <= DP) {
     const uint32_t h = SH == 0 ? q_odd : (q_odd + ((1u << SH) - 1u)) >> SH;
     const uint32_t inf = (uint32_t)__builtin_amdgcn_sbfe(M < 32 ? mlo : mhi, M & 31, 1);  // 0 or 0xFFFFFFFF
-    x[DP - 1 - M] = vmax(vmax(arow[DP - 1 - M], h), inf);
+    if constexpr (std::is_same<AP, InPlaceRow>::value) x[DP - 1 - M] = vmax(vmax(x[DP - 1 - M], h), inf);
+    else x[DP - 1 - M] = vmax(vmax(arow[DP - 1 - M], h), inf);
     direct_chain<DP, NG, ODD, SH + 1, AP>(x, arow, q_odd, mlo, mhi);
   }
 }
@@ -527,8 +575,10 @@ __device__ __forceinline__ void row_merge_direct(uint32_t (&x)[DP], AP arow,
                                                  uint32_t tij, int rmn, const DirectConsts &k) {
   // bit r-1 set for r < rmn: these replica counts do not fit (all of them for rmn = 255)
   const unsigned long long below = rmn > 64 ? ~0ull : ((1ull << (rmn - 1)) - 1ull);
+  if constexpr (!std::is_same<AP, InPlaceRow>::value) {
 #pragma unroll
-  for (int m = 8 * NG; m < DP; ++m) x[DP - 1 - m] = arow[DP - 1 - m];  // max(a, 0): replica counts not needed
+    for (int m = 8 * NG; m < DP; ++m) x[DP - 1 - m] = arow[DP - 1 - m];  // max(a, 0): replica counts not needed
+  }
   direct_entries<DP, NG, AP>(x, arow, (double)tij + (0x1p-18 - 0.5), k, (int)(uint32_t)below, (int)(uint32_t)(below >> 32));
 #pragma unroll
   for (int h = DP / 2; h >= 1; h >>= 1) {
@@ -547,9 +597,9 @@ __device__ __forceinline__ void row_merge_direct(uint32_t (&x)[DP], AP arow,
 // merge_rows for the recomputing level kernel: no table reads; per row one scalar read of T[i], the
 // lane's rmin byte and the a[] row.
 template <int DP, int NG>
-__device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], const ProblemDev &pr, const int s, const int c,
-                                                  const int i0, const int i_hi, const int lane, const int wave,
-                                                  const DirectConsts &k) {
+__device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], uint32_t *tile, const ProblemDev &pr, const int s,
+                                                  const int c, const int i0, const int i_hi, const int lane,
+                                                  const int wave, const DirectConsts &k) {
   using VT = uint32_t;
   constexpr VT INF = Lim<VT>::inf;
   const int N = pr.N, D = pr.D, nch = pr.nch;
@@ -572,6 +622,59 @@ __device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], const Pro
     return r;
   };
   bool any = false;
+  if (i0 >= 64 * c) {
+    // Diagonal block: the listed row 64c+p stands for the pair of rows 64c+p (lanes p.. with their
+    // own columns) and 64c+64-p (the p columns from 64-p on, on the lanes below p): one pass of a
+    // full wave instead of two half-empty ones.  Every lane reads its own row of V[s-1] (straight
+    // into the registers it is merged in), prefix sum and rmin byte.  The lanes of the second row
+    // do not own their column, so their merge goes straight into the workgroup's tile.
+    typedef uint32_t Quad __attribute__((ext_vector_type(4)));
+    struct Pair { VT alast; int rmn; int64_t Ti, Tc; int row, col; };
+    auto load_pair = [&](int p) -> Pair {
+      const int pc = min(max(p, 0), 32);
+      const bool second = lane < pc && pc < 32;  // rows 64c and 64c+32 have no partner
+      Pair r;
+      r.col = second ? lane + 64 - pc : lane;
+      r.row = lane >= pc ? 64 * c + pc : second ? 64 * c + 64 - pc : -1;
+      const int rc = min(max(r.row, s - 1), N - 1);  // in range for the reads; the row itself decides below
+      r.alast = Vprev[(int64_t)rc * DP + D - 1];
+      r.Ti = T[rc];
+      r.Tc = T[min(64 * c + r.col + 1, N)];
+      r.rmn = rmin[unit_index(nch, rc, c) * 64 + r.col];
+      return r;
+    };
+    int p = i0 - 64 * c + wave;
+    const int p_hi = i_hi - 64 * c;
+    Pair cur = load_pair(p);
+    while (p <= p_hi) {  // wave-uniform
+      const int row = cur.row, col = cur.col;
+      const bool act = row >= s - 1 && row < N && 64 * c + col < N && cur.alast != INF && cur.rmn <= rl;
+      const uint32_t tij = (uint32_t)(cur.Tc - cur.Ti);
+      const int rmn = act ? cur.rmn : 255;
+      const int rc = min(max(row, s - 1), N - 1);
+      cur = load_pair(p + kMergeWaves);
+      if (__ballot(act) != 0ull) {
+        any = true;
+        VT x[DP];
+        const Quad RANNC_GLOBAL *ap = (const Quad RANNC_GLOBAL *)(Vprev + (int64_t)rc * DP);
+#pragma unroll
+        for (int g = 0; g < DP / 4; ++g) {
+          const Quad v = ap[g];
+          x[4 * g] = v.x; x[4 * g + 1] = v.y; x[4 * g + 2] = v.z; x[4 * g + 3] = v.w;
+        }
+        row_merge_direct<DP, NG, InPlaceRow>(x, InPlaceRow(), tij, rmn, k);
+        if (col == lane) {
+#pragma unroll
+          for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
+        } else if (act) {
+#pragma unroll
+          for (int t = 0; t < DP; ++t) atomicMin(&tile[col * (DP + 1) + t], x[t]);
+        }
+      }
+      p += kMergeWaves;
+    }
+    return any;
+  }
   int i = i0 + wave;
   Row cur = load_flags(i);
   while (i <= i_hi) {  // wave-uniform
@@ -595,7 +698,7 @@ __device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], const Pro
 // fit the 168 registers of three waves per SIMD (the compiler left alone takes one more); the
 // recomputing kernel also keeps 32 reciprocals in registers and runs two waves per SIMD.
 template <typename VT, int DP, bool DIRECT> constexpr int merge_waves_per_simd() {
-  return DP == 64 ? (sizeof(VT) == 4 ? (DIRECT ? 2 : 3) : 2) : 1;
+  return DP == 64 ? (sizeof(VT) == 4 ? (DIRECT ? 2 : 3) : 2) : (DP == 32 && DIRECT) ? 4 : 1;
 }
 
 // The rows i0+wave, i0+wave+4, ... <= i_hi of one work item, folded into acc (running minimum of the
@@ -669,7 +772,9 @@ __device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int
   const int c = (int)((desc >> 16) & 0x3ffu), i0 = (int)(desc & 0xffffu), rows = (int)(desc >> 26) + 1;
   if (64 * c + 64 < s) return;  // no column j >= s in this chunk
   const int i_hi = min(min(i0 + rows - 1, 64 * c + 63), N - 1);
-  if (i_hi < s - 1) return;
+  // (an item of the diagonal block of the recomputing kernel also stands for the partner rows
+  // 64c+64-p of its rows 64c+p, which lie above them)
+  if (i_hi < s - 1 && !(DIRECT && i0 >= 64 * c)) return;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   constexpr VT INF = Lim<VT>::inf;
@@ -677,12 +782,14 @@ __device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int
 
   // acc[t] = running minimum over this wave's rows of the sorted merge
   constexpr bool ROWFOLD = sizeof(VT) == 8 && DP == 64;
+  constexpr bool EARLY_TILE = ROWFOLD || DIRECT;  // rows fold into the tile while the row loop runs
   __shared__ VT tile[64 * (DP + 1)];
   [[maybe_unused]] VT acc[DP];
-  if constexpr (ROWFOLD) {
+  if constexpr (EARLY_TILE) {
     for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
     __syncthreads();
-  } else {
+  }
+  if constexpr (!ROWFOLD) {
 #pragma unroll
     for (int t = 0; t < DP; ++t) acc[t] = INF;
   }
@@ -695,7 +802,7 @@ __device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int
 #define RANNC_ROWS(K)                                                                              \
   case K:                                                                                          \
     if constexpr (8 * K <= DP || (K == 1 && DP == 8))                                              \
-      any = merge_rows_direct<DP, (8 * K <= DP ? K : 1)>(acc, pr, s, c, i0, i_hi, lane, wave, k);  \
+      any = merge_rows_direct<DP, (8 * K <= DP ? K : 1)>(acc, tile, pr, s, c, i0, i_hi, lane, wave, k);  \
     break;
     switch (DP == 8 ? 1 : ((ng + 1) & ~1)) {
       RANNC_ROWS(1) RANNC_ROWS(2) RANNC_ROWS(4) RANNC_ROWS(6) RANNC_ROWS(8)
@@ -721,7 +828,8 @@ __device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int
   if constexpr (ROWFOLD) {
     if (__syncthreads_or(any) == 0) return;
   } else {
-    for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
+    if constexpr (!EARLY_TILE)
+      for (int e = threadIdx.x; e < 64 * (DP + 1); e += 64 * kMergeWaves) tile[e] = INF;
     if (__syncthreads_or(any) == 0) return;
     if (any) {
 #pragma unroll
@@ -1465,8 +1573,9 @@ int merge_grid_items(const LaunchShape &sh, int rows_per_item) {
   return (int)std::max<int64_t>(1, items);
 }
 
-hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, hipStream_t st) {
-  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, max_items, Q, slots);
+hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, bool paired,
+                       hipStream_t st) {
+  hipLaunchKernelGGL(runs_kernel, dim3(Q), dim3(256), 0, st, probs, rows_per_item, max_items, Q, slots, paired ? 1 : 0);
   return hipGetLastError();
 }
 
