@@ -978,22 +978,54 @@ __global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kern
   // ---- levels 2..S_eff ----
   [[maybe_unused]] DirectConsts kc;
   if constexpr (DIRECT) direct_consts_init(kc);
+  // passes of the recomputing form (see the level loop): P0 for the triangle of chunk 0, then F1 for
+  // the rectangle and P1 for the triangle of chunk 1
+  const int W0 = R0, W1 = nch > 1 ? N - 64 : 1;
+  const int lg0 = W0 > 1 ? 32 - __builtin_clz(W0 - 1) : 0, lg1 = W1 > 1 ? 32 - __builtin_clz(W1 - 1) : 0;
+  const int P0 = (W0 / 2 + (64 >> lg0)) >> (6 - lg0);
+  const int F1 = nch > 1 ? 64 >> (6 - lg1) : 0;
+  const int P1 = nch > 1 ? (W1 / 2 + (64 >> lg1)) >> (6 - lg1) : 0;
+  [[maybe_unused]] const int RTP = P0 + F1 + P1;
   for (int s = 2; s <= S_eff; ++s) {
     const VT *prev = lv[s & 1];        // level s-1
     VT *cur = lv[(s - 1) & 1];         // level s
     const int rl = D - s + 1;
     for (int e = tid; e < (N + 1) * LS; e += NT) cur[e] = ((e % LS) < D) ? INF : (VT)0;
     lds_barrier();  // LDS only: the copy of the previous level to memory stays in flight
-    for (int f = wave; f < RT; f += kSmallWaves) {
-      const int c = f >= R0, i = c ? f - R0 : f;
-      if (i < s - 1 || i < s_wlo[c] || 64 * c + 64 < s) continue;
-      if (prev[i * LS + D - 1] == INF) continue;  // no (s-1)-stage plan covers blocks 1..i
-      const int jj = 64 * c + lane;
-      if constexpr (DIRECT) {
-        const int rmn = s_rmin[f * 64 + lane];
-        const bool act = rmn <= rl;  // 255 outside the stage's range
+    if constexpr (DIRECT) {
+      // One pass of a wave = 64 (row, column) pairs, one per lane, so that no lane idles on the
+      // triangular blocks.  A diagonal block of W columns (rows base..base+W-1) is cut into groups of
+      // LG = 2^lg >= W lanes, G = 64 / LG groups to a pass; group number p (0..W/2) covers row base+p on
+      // the lanes l >= p (columns l) and, for 0 < p < W-p, row base+W-p on the lanes l < p (columns
+      // l+W-p): W lanes of work where a row alone has W-p.  The rectangular block of chunk 1 (rows
+      // 0..63, W1 columns) runs G1 rows to a pass the same way.  Every lane reads its own a[] row
+      // from LDS and folds its own column in, so a pass may mix rows freely.
+      for (int f = wave; f < RTP; f += kSmallWaves) {
+        const int c = f >= P0;
+        if (64 * c + 64 < s) continue;
+        int row, col;
+        bool valid;
+        if (c && f < P0 + F1) {
+          const int l = lane & ((1 << lg1) - 1);
+          row = ((f - P0) << (6 - lg1)) + (lane >> lg1);
+          col = l;
+          valid = l < W1;
+        } else {
+          const int W = c ? W1 : W0, lg = c ? lg1 : lg0;
+          const int l = lane & ((1 << lg) - 1);
+          const int p = ((c ? f - P0 - F1 : f) << (6 - lg)) + (lane >> lg);
+          const bool second = l < p;
+          valid = l < W && 2 * p <= W && (!second || 2 * p < W);
+          row = 64 * c + (second ? W - p : p);
+          col = second ? l + W - p : l;
+        }
+        if (!valid) { row = 64 * c; col = 0; }
+        const int jj = 64 * c + col;
+        const int rmn = s_rmin[((c ? R0 : 0) + row) * 64 + col];  // 255 outside the stage's range
+        // the row must be able to end s-1 stages: i >= s-1, and some (s-1)-stage plan covers blocks 1..i
+        const bool act = valid && rmn <= rl && row >= s - 1 && row >= s_wlo[c] && prev[row * LS + D - 1] != INF;
         if (__ballot(act) == 0ull) continue;
-        const uint32_t tij = (uint32_t)(sT[min(jj + 1, N)] - sT[i]);
+        const uint32_t tij = (uint32_t)(sT[min(jj + 1, N)] - sT[row]);
         // Narrower merge at late levels.  The first s-2 entries of a[] are INF (s-1 stages need s-1
         // devices) and only rl = D-s+1 replica counts and device totals are left, so the merge of
         // a[sig..sig+H-1] with c[1..H] on a network of H >= rl inputs gives every value the level
@@ -1004,7 +1036,7 @@ __global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kern
     constexpr int H = (HH) <= DP ? (HH) : DP;                                                        \
     const int sig = H < DP ? min(s - 2, DP - H) : 0;                                                 \
     VT x[H];                                                                                         \
-    row_merge_direct<H, (H >= 8 ? H / 8 : 1), const VT *>(x, prev + i * LS + sig, tij, act ? rmn : 255, kc); \
+    row_merge_direct<H, (H >= 8 ? H / 8 : 1), const VT *>(x, prev + row * LS + sig, tij, act ? rmn : 255, kc); \
     if (act && jj + 1 >= s) {                                                                        \
       /* no test per entry: columns D.. hold 0 and keep it, column DP (t + 1 + sig <= DP) is padding */ \
       VT *dst = cur + (jj + 1) * LS + 1 + sig;                                                       \
@@ -1015,7 +1047,13 @@ __global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kern
         else if (rl <= 16) RANNC_ROW(16)
         else RANNC_ROW(32)
 #undef RANNC_ROW
-      } else {
+      }
+    } else {
+      for (int f = wave; f < RT; f += kSmallWaves) {
+        const int c = f >= R0, i = c ? f - R0 : f;
+        if (i < s - 1 || i < s_wlo[c] || 64 * c + 64 < s) continue;
+        if (prev[i * LS + D - 1] == INF) continue;  // no (s-1)-stage plan covers blocks 1..i
+        const int jj = 64 * c + lane;
         VT x[DP];
         const int64_t u = unit_index(nch, i, c);
         int rmn = 255;
