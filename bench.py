@@ -276,7 +276,7 @@ def run_workload(name, steps, warmup, wide=False, algo="auto"):
             "phase": phase, "launches": launches, "res": res, "roofline": roof}
 
 
-def run_form_stage(name, steps, warmup, cpu_baseline):
+def run_form_stage(name, steps, warmup, cpu_baseline, wide=False):
     """Outer driver (Algorithm 2) end to end: host arrays in, chosen plan on the host, at the
     paper's cluster shape (4 nodes x 8 devices, batch 256, Sec. IV-A).  A step is one call:
     24 searches in three device-count classes plus the host's loops over their results."""
@@ -292,7 +292,8 @@ def run_form_stage(name, steps, warmup, cpu_baseline):
     if split:
         kw["time_bwd_per_sample_ns"] = synth.with_backward_times(
             {"time_ns": c["time_per_sample_ns"], "name": c["name"]}, 5)["time_bwd_ns"]
-    fs = B.FormStageSession(N, nn, dn, BS, split=split)
+    fs = B.FormStageSession(N, nn, dn, BS, split=split,
+                            max_total_time_ns=(1 << 60) if wide else B.NARROW_MAX_TOTAL_TIME)
     args = (c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], c["mem_capacity"])
     for _ in range(warmup):
         fs.run(*args, **kw)
@@ -316,7 +317,7 @@ def run_form_stage(name, steps, warmup, cpu_baseline):
         "metric": "DP cell-updates/sec (definitional count, outer driver end to end, host arrays in, plan out)",
         "value": U / (ms * 1e-3) / 1e9, "unit": "G cell-updates/s", "n_gpus": 1, "steps": steps,
         "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "u64" if wide else "u32", "data": "synthetic",
         "config": {"workload": f"outer driver: {nn} nodes x {dn} devices, batch {BS}, N={N} blocks"
                                + (", split fwd/bwd objective" if split else ""),
                    "n_problems": Q, "cell_updates": U},
@@ -377,7 +378,7 @@ def main():
         del src, dst
 
     if args.workload.startswith("formstage"):
-        print(json.dumps(run_form_stage(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)),
+        print(json.dumps(run_form_stage(args.workload, args.steps, args.warmup, not args.no_cpu_baseline, args.wide)),
               flush=True)
         return
     m = run_workload(args.workload, args.steps, args.warmup, args.wide, args.algo)

@@ -454,16 +454,31 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       const bool heavy = h->bits / 8 * cls >= 256;  // the variants that run eight waves per search
       bool tiny;
       if (direct_ok) {
-        // Stage times recomputed: the levels read nothing from memory, and a level costs
-        // ceil(rows / 16 waves) passes whose price follows the width of the merge it still needs
-        // (0.9 / 1.4 / 2.85 us at 8 / 16 / 32 inputs: one compute unit's vector issue rate, four
-        // waves per SIMD).  N = 32, D = 32: 31 levels 124 against 156 us, 15 levels 98 against 92 us.
-        double us = 0.0;
+        // Stage times recomputed: the levels read nothing from memory.  The kernel runs a level as
+        // passes of 64 (row, column) pairs packed from the triangular and rectangular blocks, sixteen
+        // waves at a time.  Least-squares fit over a sweep (N = 8..128, D = 8, 16, 32, S = 2..D, 1 and
+        // 8 searches; rms 3.7 us): 12 us + 0.04 us per table row in front, then per level a constant
+        // and a price per pass that follow the width of the merge the level still needs (32 / 16 / 8
+        // inputs), the passes of the first round of sixteen dearer than the later ones.  The launches
+        // per level on the same sweep: 21 us + 4.4 us per level + 0.05 us per block.
+        auto tri = [](int W) {
+          int lg = 0;
+          while ((1 << lg) < W) ++lg;
+          return (W / 2 + (64 >> lg)) >> (6 - lg);
+        };
+        int passes = tri(std::min(sh.max_N, 64));
+        if (sh.max_N > 64) {
+          int lg = 0;
+          while ((1 << lg) < sh.max_N - 64) ++lg;
+          passes += (64 >> (6 - lg)) + tri(sh.max_N - 64);
+        }
+        const double work = 0.17 * std::min(passes, 16) + 0.105 * std::max(passes - 16, 0);
+        double us = 12.0 + 0.04 * (double)rows;
         for (int s = 2; s <= sh.max_S_eff; ++s) {
           const int rl = sh.max_D - s + 1;
-          us += rl <= 8 ? 0.9 : rl <= 16 ? 1.4 : 2.85;
+          us += rl <= 8 ? 0.43 + 0.45 * work : rl <= 16 ? 0.68 + 0.61 * work : 1.5 + 0.91 * work;
         }
-        tiny = us * (double)((rows + 15) / 16) <= launches_us;
+        tiny = us <= 21.0 + 4.4 * levels + 0.05 * sh.max_N;
       } else if (heavy) {
         // 64 devices, or 64-bit values from 32 devices on, stage times from the table: a level costs
         // about 7 us plus 1.7 us per pass of eight rows, more than a launch; only two or three levels

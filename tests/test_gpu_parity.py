@@ -335,6 +335,28 @@ def test_small_search_kernel_on_and_off(mode, width, algo):
             assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
 
 
+def test_one_launch_recompute_block_shapes():
+    """The recomputing one-launch kernel packs row pairs of the triangular blocks and short rows of
+    the rectangular block into passes of 64 lanes; the packing depends on the widths min(64, N) and
+    N - 64.  Every kind of width (one column, odd, a power of two, one more or less than one, the
+    full 64) in both chunks, at 8 and 32 devices: tables, optimum and plan against the oracle."""
+    probs = []
+    for q, N in enumerate([1, 2, 3, 5, 8, 15, 16, 17, 31, 32, 33, 47, 63, 64, 65, 66, 67, 72, 80, 81,
+                           95, 96, 97, 111, 127, 128]):
+        for D in (8, 32):
+            probs.append(synth.random_small(7000 + 2 * q + (D == 32), N, D, min(D, 12),
+                                            tight=1.2 if q % 3 else 50.0, tmax=10 ** 6,
+                                            zero_time_frac=0.25 if q % 4 == 0 else 0.0))
+    res, sess = gpu_run(probs, one_launch_small=2)
+    with sess:
+        rc, info = B.rannc_dp_solve_info(sess.h)
+        assert rc == B.OK
+        assert [info.level_kernel[k] for k in range(4) if info.n_problems[k]] == [B.KERNEL_ONE_LAUNCH_RECOMPUTE] * 2
+        assert_results_match(probs, res)
+        for q in range(len(probs)):
+            assert_tables_match(probs[q], sess, q, args=False)
+
+
 @pytest.mark.parametrize("N,M_gib,width", [(4096, 64, B.NARROW_MAX_TOTAL_TIME), (3000, 48, 1 << 50)])
 def test_large_search_prefix_parity_and_properties(N, M_gib, width):
     """A search four times config 4's length (64 column chunks, a ragged one at N = 3000, 2 GB of
