@@ -76,7 +76,10 @@ typedef enum {
                                      table, and the stage-time table is built when rannc_dp_read_table
                                      asks for it.  Applies to 32-bit handles (max_total_time_ns up to
                                      4294967294) and batches without a communication term; elsewhere
-                                     this value behaves as RANNC_DP_ALGO_MERGE.  Same results. */
+                                     this value behaves as RANNC_DP_ALGO_MERGE.  Same results.  (The
+                                     one-launch kernel of small searches, see one_launch_small, also
+                                     recomputes on 64-bit handles whose max_total_time_ns is at most
+                                     2^40, under AUTO and RECOMPUTE.) */
 
 /* Handle flag: run Algorithm 1 as printed, with separate forward and backward block times.  A
  * cell of the search then keeps, besides its value, the largest forward and the largest backward
@@ -101,7 +104,9 @@ typedef struct {
   int32_t max_stages;        /* largest S of any problem (values above it are clamped by N, D) */
   int64_t max_total_time_ns; /* bound on the sum of a problem's block times.  Up to
                                 4294967294 the tables hold 32-bit values (half the memory
-                                traffic); above it 64-bit.  Results are the same int64. */
+                                traffic); above it 64-bit.  Results are the same int64.  A tight
+                                bound helps: up to 2^40 (18 minutes) small searches on 64-bit
+                                tables can take the kernel that recomputes the stage times. */
   int32_t algo;              /* RANNC_DP_ALGO_* */
   int32_t flags;             /* RANNC_DP_FLAG_* or 0 */
   /* Tuning; 0 everywhere = the library's own choices.  None of them changes a result. */

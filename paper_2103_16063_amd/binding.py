@@ -27,6 +27,7 @@ TABLE_COST_BWD, TABLE_MAX_FWD, TABLE_MAX_BWD = 5, 6, 7
 FLAG_SPLIT_OBJECTIVE = 1
 MAX_DEVICES = 64
 NARROW_MAX_TOTAL_TIME = 4294967294
+WIDE_RECOMPUTE_MAX_TOTAL_TIME = 1 << 40   # 64-bit handles up to this bound can recompute stage times
 
 EXPORTS = ["rannc_dp_workspace_bytes", "rannc_dp_workspace_bytes_for", "rannc_dp_create",
            "rannc_dp_solve", "rannc_dp_traceback", "rannc_dp_read_table", "rannc_dp_destroy",

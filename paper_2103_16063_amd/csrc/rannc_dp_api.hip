@@ -132,6 +132,7 @@ struct rannc_dp {
   int tune_spw;  // > 0: override of the rows-per-wave heuristic (RANNC_DP_ROWS_PER_WAVE)
   int fused_small;  // one-launch kernel for classes of small searches: 1 = where it pays (default),
                     // 0 = never, 2 = whenever N <= 128 (RANNC_DP_FUSED_SMALL)
+  int64_t call_total_bound;  // > 0 during the outer driver's solve: no search's total time exceeds it
 };
 
 extern "C" {
@@ -195,6 +196,7 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   h->level_launches = 0;
   h->tune_spw = l->rows_per_wave;
   for (int k = 0; k < 4; ++k) h->no_times[k] = false;
+  h->call_total_bound = 0;
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
@@ -433,6 +435,10 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       for (int a = 0; a < n_aux && ok; ++a) ok = hipStreamWaitEvent(h->aux[a], h->fork_ev, 0) == hipSuccess;
     }
   }
+  // what the host knows about the total time of a search of this batch: the handle's bound, or the
+  // outer driver's own sum over the inputs it has just scaled
+  const int64_t total_bound = h->call_total_bound > 0 ? std::min(h->call_total_bound, h->lim.max_total_time_ns)
+                                                      : h->lim.max_total_time_ns;
   bool fused[4] = {false, false, false, false};
   bool fused_direct[4] = {false, false, false, false};  // one-launch kernel that recomputes the stage times
   int merge_items[4] = {1, 1, 1, 1};
@@ -449,8 +455,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       const int cls = kClasses[k];
       // the launches per level of a few small searches: 14 us in front of the levels, 4.4 us a level
       const double launches_us = 14.0 + 4.4 * levels;
-      const bool direct_ok = can_recompute && h->lim.algo != RANNC_DP_ALGO_MERGE &&
-                             rannc::small_can_recompute(h->bits, cls);
+      const bool direct_ok = !scan && !split && !b->cut_bytes && h->lim.algo != RANNC_DP_ALGO_MERGE &&
+                             rannc::small_can_recompute(h->bits, cls, total_bound);
       const bool heavy = h->bits / 8 * cls >= 256;  // the variants that run eight waves per search
       bool tiny;
       if (direct_ok) {
@@ -473,12 +479,14 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
           passes += (64 >> (6 - lg)) + tri(sh.max_N - 64);
         }
         const double work = 0.17 * std::min(passes, 16) + 0.105 * std::max(passes - 16, 0);
-        double us = 12.0 + 0.04 * (double)rows;
+        const bool w64 = h->bits == 64;  // the same fit on 64-bit values (rms 5.7 us; eight waves at 32 devices)
+        double us = w64 ? 13.0 + 0.02 * (double)rows : 12.0 + 0.04 * (double)rows;
         for (int s = 2; s <= sh.max_S_eff; ++s) {
           const int rl = sh.max_D - s + 1;
-          us += rl <= 8 ? 0.43 + 0.45 * work : rl <= 16 ? 0.68 + 0.61 * work : 1.5 + 0.91 * work;
+          if (w64) us += rl <= 8 ? 0.33 + 0.63 * work : rl <= 16 ? 1.1 + 0.9 * work : 1.45 + 1.62 * work;
+          else us += rl <= 8 ? 0.43 + 0.45 * work : rl <= 16 ? 0.68 + 0.61 * work : 1.5 + 0.91 * work;
         }
-        tiny = us <= 21.0 + 4.4 * levels + 0.05 * sh.max_N;
+        tiny = us <= (w64 ? 22.0 + 5.5 * levels + 0.06 * sh.max_N : 21.0 + 4.4 * levels + 0.05 * sh.max_N);
       } else if (heavy) {
         // 64 devices, or 64-bit values from 32 devices on, stage times from the table: a level costs
         // about 7 us plus 1.7 us per pass of eight rows, more than a launch; only two or three levels
@@ -763,7 +771,10 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   int32_t *hpn = (int32_t *)(pin + o_pair), *hpm = hpn + Q;
   // per-microbatch inputs of every (n, MB): b samples on one pipeline replica
   const __int128 lim = (__int128)1 << 62;
+  __int128 max_total = 0;  // largest total time of a search (forward, no communication term: what the
+                           // kernels that care about it are restricted to)
   for (int q = 0; q < Q; ++q) {
+    __int128 total = 0;
     hD[q] = in->devices_per_node * pairs[q].n;
     hS[q] = hD[q];
     hMB[q] = pairs[q].MB;
@@ -775,6 +786,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
       if (ts < 0 || as < 0 || in->param_bytes[k] < 0) return RANNC_DP_INVALID_ARG;
       if ((__int128)ts * pairs[q].b >= lim || (__int128)as * pairs[q].b >= lim) return RANNC_DP_OVERFLOW;
       ht[(size_t)q * N + k] = ts * pairs[q].b;
+      total += (__int128)ts * pairs[q].b;
       ha[(size_t)q * N + k] = as * pairs[q].b;
       hp[(size_t)q * N + k] = in->param_bytes[k];
       if (split) {
@@ -790,6 +802,7 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
         ho[(size_t)q * N + k] = os * pairs[q].b;
       }
     }
+    max_total = std::max(max_total, total);
   }
   hoff[Q] = (int64_t)Q * N;
   // one copy up: the (n, MB) of every search and the block arrays in use are contiguous
@@ -817,7 +830,9 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   // the smallest (MB + S - 1) * V, the first found among equals), and the plan of the chosen
   // (n, MB, S), which the plan recovery also writes behind the record.  Three launches behind the
   // search's own, one copy down, one wait.
+  h->call_total_bound = max_total < lim ? (int64_t)max_total : 0;
   int rc = rannc_dp_solve(h, &b, hip_stream, d_opt, d_ns, nullptr, d_st);
+  h->call_total_bound = 0;
   if (rc == RANNC_DP_OK &&
       rannc::launch_form_stage_select(h->d_probs, Q, stride, N, in->n_nodes, in->devices_per_node, d_pn, d_pm,
                                       d_lev, d_rec, st) != hipSuccess) {

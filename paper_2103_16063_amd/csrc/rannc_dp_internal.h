@@ -124,8 +124,9 @@ hipError_t launch_level_merge(const ProblemDev *probs, const LaunchShape &sh, in
 // whole search of problems with N <= small_max_blocks() in one launch, one workgroup each
 int small_max_blocks();
 // direct: the stage times are recomputed from the prefix sums and no table is written (only where
-// small_can_recompute says so, and only for searches without a communication term)
-bool small_can_recompute(int bits, int DP);
+// small_can_recompute says so, and only for searches without a communication term);
+// max_total_time: the largest total time a search of the launch can have without being flagged
+bool small_can_recompute(int bits, int DP, int64_t max_total_time);
 hipError_t launch_solve_small(const ProblemDev *probs, int Q, int bits, int DP, bool direct, int64_t *d_opt,
                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st);
 hipError_t launch_level_scan(const ProblemDev *probs, const LaunchShape &sh, int bits, int s,

@@ -540,53 +540,78 @@ __device__ __forceinline__ void direct_consts_init(DirectConsts &k) {
   asm("" : "+v"(k.magic));
 }
 
+// The same with 64-bit values, for stage times below 2^40 (the caller's bound on a search's total
+// time guarantees it): the offset is 2^-8 instead of 2^-18, so that t stays exact (a multiple of 2^-8
+// below 2^41: 49 bits) while the rounded reciprocal moves the product by less than 2^41 * 2^-53 =
+// 2^-12, far inside both margins (2^-8 below, 1/63 - 2^-8 above).  The quotient, below 2^40, sits in
+// the low 51 bits of the sum; the even counts are a 64-bit add and shift.
+template <typename VT> struct DirectArith;
+template <> struct DirectArith<uint32_t> {
+  static constexpr double kOffset = 0x1p-18;
+  static __device__ __forceinline__ uint32_t quotient(double y) { return (uint32_t)__double_as_longlong(y); }
+  // 0 or INF from bit (m & 31) of the mask word
+  static __device__ __forceinline__ uint32_t inf_if(int word, int m) {
+    return (uint32_t)__builtin_amdgcn_sbfe(word, m & 31, 1);
+  }
+};
+template <> struct DirectArith<uint64_t> {
+  static constexpr double kOffset = 0x1p-8;
+  static __device__ __forceinline__ uint64_t quotient(double y) {
+    return (uint64_t)__double_as_longlong(y) & ((1ull << 51) - 1ull);
+  }
+  static __device__ __forceinline__ uint64_t inf_if(int word, int m) {
+    return (uint64_t)((uint32_t)__builtin_amdgcn_sbfe(word, m & 31, 1) & (uint32_t)(Lim<uint64_t>::inf >> 32)) << 32;
+  }
+};
+// largest stage time the 64-bit form is exact for
+constexpr int64_t kDirectWideMaxTime = (int64_t)1 << 40;
+
 // AP of the helpers below: x[] already holds the lane's own a[] row (read per lane, not wave-uniform)
 struct InPlaceRow {};
 
 // entry r = ODD << SH and the ones it is the parent of
-template <int DP, int NG, int ODD, int SH, typename AP>
-__device__ __forceinline__ void direct_chain(uint32_t (&x)[DP], AP arow,
-                                             uint32_t q_odd, int mlo, int mhi) {
+template <typename VT, int DP, int NG, int ODD, int SH, typename AP>
+__device__ __forceinline__ void direct_chain(VT (&x)[DP], AP arow, VT q_odd, int mlo, int mhi) {
   constexpr int R = ODD << SH, M = R - 1;
   if constexpr (R <= 8 * NG && R <= DP) {
-    const uint32_t h = SH == 0 ? q_odd : (q_odd + ((1u << SH) - 1u)) >> SH;
-    const uint32_t inf = (uint32_t)__builtin_amdgcn_sbfe(M < 32 ? mlo : mhi, M & 31, 1);  // 0 or 0xFFFFFFFF
+    const VT h = SH == 0 ? q_odd : (q_odd + (VT)((1u << SH) - 1u)) >> SH;
+    const VT inf = DirectArith<VT>::inf_if(M < 32 ? mlo : mhi, M);
     if constexpr (std::is_same<AP, InPlaceRow>::value) x[DP - 1 - M] = vmax(vmax(x[DP - 1 - M], h), inf);
-    else x[DP - 1 - M] = vmax(vmax(arow[DP - 1 - M], h), inf);
-    direct_chain<DP, NG, ODD, SH + 1, AP>(x, arow, q_odd, mlo, mhi);
+    else x[DP - 1 - M] = vmax(vmax((VT)arow[DP - 1 - M], h), inf);
+    direct_chain<VT, DP, NG, ODD, SH + 1, AP>(x, arow, q_odd, mlo, mhi);
   }
 }
 
-// t = x + (r/2 - 1 + r * 2^-18) for the odd r = 2K + 1; the next odd r adds 1 + 2^-17 (exact: every
-// t is a multiple of 2^-18 below 2^34), so one constant serves all entries
-template <int DP, int NG, typename AP, int K = 0>
-__device__ __forceinline__ void direct_entries(uint32_t (&x)[DP], AP arow,
-                                               double t, const DirectConsts &k, int mlo, int mhi) {
+// t = x + (r/2 - 1 + r * offset) for the odd r = 2K + 1; the next odd r adds 1 + 2 * offset (exact:
+// every t is a multiple of the offset inside the 53 bits), so one constant serves all entries
+template <typename VT, int DP, int NG, typename AP, int K = 0>
+__device__ __forceinline__ void direct_entries(VT (&x)[DP], AP arow, double t, const DirectConsts &k, int mlo,
+                                               int mhi) {
   constexpr int ODD = 2 * K + 1;
   if constexpr (ODD <= 8 * NG && ODD <= DP) {
     const double y = __builtin_fma(t, k.inv[K], k.magic);
-    direct_chain<DP, NG, ODD, 0, AP>(x, arow, (uint32_t)__double_as_longlong(y), mlo, mhi);
-    direct_entries<DP, NG, AP, K + 1>(x, arow, t + (1.0 + 0x1p-17), k, mlo, mhi);
+    direct_chain<VT, DP, NG, ODD, 0, AP>(x, arow, DirectArith<VT>::quotient(y), mlo, mhi);
+    direct_entries<VT, DP, NG, AP, K + 1>(x, arow, t + (1.0 + 2.0 * DirectArith<VT>::kOffset), k, mlo, mhi);
   }
 }
 
-template <int DP, int NG, typename AP>
-__device__ __forceinline__ void row_merge_direct(uint32_t (&x)[DP], AP arow,
-                                                 uint32_t tij, int rmn, const DirectConsts &k) {
+template <typename VT, int DP, int NG, typename AP>
+__device__ __forceinline__ void row_merge_direct(VT (&x)[DP], AP arow, VT tij, int rmn, const DirectConsts &k) {
   // bit r-1 set for r < rmn: these replica counts do not fit (all of them for rmn = 255)
   const unsigned long long below = rmn > 64 ? ~0ull : ((1ull << (rmn - 1)) - 1ull);
   if constexpr (!std::is_same<AP, InPlaceRow>::value) {
 #pragma unroll
     for (int m = 8 * NG; m < DP; ++m) x[DP - 1 - m] = arow[DP - 1 - m];  // max(a, 0): replica counts not needed
   }
-  direct_entries<DP, NG, AP>(x, arow, (double)tij + (0x1p-18 - 0.5), k, (int)(uint32_t)below, (int)(uint32_t)(below >> 32));
+  direct_entries<VT, DP, NG, AP>(x, arow, (double)tij + (DirectArith<VT>::kOffset - 0.5), k, (int)(uint32_t)below,
+                                 (int)(uint32_t)(below >> 32));
 #pragma unroll
   for (int h = DP / 2; h >= 1; h >>= 1) {
 #pragma unroll
     for (int q = 0; q < DP; ++q) {
       if ((q & h) == 0) {
-        const uint32_t hi = vmax(x[q], x[q + h]);
-        const uint32_t lo = vmin(x[q], x[q + h]);
+        const VT hi = vmax(x[q], x[q + h]);
+        const VT lo = vmin(x[q], x[q + h]);
         x[q] = hi;
         x[q + h] = lo;
       }
@@ -662,7 +687,7 @@ __device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], uint32_t 
           const Quad v = ap[g];
           x[4 * g] = v.x; x[4 * g + 1] = v.y; x[4 * g + 2] = v.z; x[4 * g + 3] = v.w;
         }
-        row_merge_direct<DP, NG, InPlaceRow>(x, InPlaceRow(), tij, rmn, k);
+        row_merge_direct<uint32_t, DP, NG, InPlaceRow>(x, InPlaceRow(), tij, rmn, k);
         if (col == lane) {
 #pragma unroll
           for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
@@ -685,7 +710,7 @@ __device__ __forceinline__ bool merge_rows_direct(uint32_t (&acc)[DP], uint32_t 
     if (__ballot(act) != 0ull) {
       any = true;
       VT x[DP];
-      row_merge_direct<DP, NG, const uint32_t RANNC_GLOBAL *>(x, Vprev + (int64_t)i * DP, tij, rmn, k);
+      row_merge_direct<uint32_t, DP, NG, const uint32_t RANNC_GLOBAL *>(x, Vprev + (int64_t)i * DP, tij, rmn, k);
 #pragma unroll
       for (int t = 0; t < DP; ++t) acc[t] = vmin(acc[t], x[t]);
     }
@@ -1025,7 +1050,7 @@ __global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kern
         // the row must be able to end s-1 stages: i >= s-1, and some (s-1)-stage plan covers blocks 1..i
         const bool act = valid && rmn <= rl && row >= s - 1 && row >= s_wlo[c] && prev[row * LS + D - 1] != INF;
         if (__ballot(act) == 0ull) continue;
-        const uint32_t tij = (uint32_t)(sT[min(jj + 1, N)] - sT[row]);
+        const VT tij = (VT)(sT[min(jj + 1, N)] - sT[row]);
         // Narrower merge at late levels.  The first s-2 entries of a[] are INF (s-1 stages need s-1
         // devices) and only rl = D-s+1 replica counts and device totals are left, so the merge of
         // a[sig..sig+H-1] with c[1..H] on a network of H >= rl inputs gives every value the level
@@ -1036,7 +1061,7 @@ __global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kern
     constexpr int H = (HH) <= DP ? (HH) : DP;                                                        \
     const int sig = H < DP ? min(s - 2, DP - H) : 0;                                                 \
     VT x[H];                                                                                         \
-    row_merge_direct<H, (H >= 8 ? H / 8 : 1), const VT *>(x, prev + row * LS + sig, tij, act ? rmn : 255, kc); \
+    row_merge_direct<VT, H, (H >= 8 ? H / 8 : 1), const VT *>(x, prev + row * LS + sig, tij, act ? rmn : 255, kc); \
     if (act && jj + 1 >= s) {                                                                        \
       /* no test per entry: columns D.. hold 0 and keep it, column DP (t + 1 + sig <= DP) is padding */ \
       VT *dst = cur + (jj + 1) * LS + 1 + sig;                                                       \
@@ -1697,13 +1722,17 @@ hipError_t launch_level_merge(const ProblemDev *p, const LaunchShape &sh, int bi
 }
 
 int small_max_blocks() { return kSmallMaxN; }
-// the one-launch kernel can recompute the stage times for 32-bit values up to the 32-device class
-// (beyond it the reciprocals and the merge do not fit the 128 registers of its sixteen waves)
-bool small_can_recompute(int bits, int DP) { return bits == 32 && DP <= 32; }
+// the one-launch kernel can recompute the stage times up to the 32-device class (beyond it the
+// reciprocals and the merge do not fit the 128 registers of its sixteen waves): 32-bit values, or
+// 64-bit values where the caller's bound on a search's total time keeps every stage time in the
+// range the double-precision quotient is exact for
+bool small_can_recompute(int bits, int DP, int64_t max_total_time) {
+  return DP <= 32 && (bits == 32 || max_total_time <= kDirectWideMaxTime);
+}
 
 hipError_t launch_solve_small(const ProblemDev *p, int Q, int bits, int DP, bool direct, int64_t *d_opt,
                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status, hipStream_t st) {
-  if (direct && !small_can_recompute(bits, DP)) return hipErrorInvalidValue;
+  if (direct && DP > 32) return hipErrorInvalidValue;
 #define GO(B, T, W, X)                                                                                 \
   if (bits == B && DP == W && direct == X)                                                             \
     hipLaunchKernelGGL((solve_small_kernel<T, W, X>), dim3(Q), dim3(64 * small_waves<T, W>()), 0, st, p, d_opt, \
@@ -1711,6 +1740,7 @@ hipError_t launch_solve_small(const ProblemDev *p, int Q, int bits, int DP, bool
   GO(32, uint32_t, 8, false) GO(32, uint32_t, 16, false) GO(32, uint32_t, 32, false) GO(32, uint32_t, 64, false)
   GO(64, uint64_t, 8, false) GO(64, uint64_t, 16, false) GO(64, uint64_t, 32, false) GO(64, uint64_t, 64, false)
   GO(32, uint32_t, 8, true) GO(32, uint32_t, 16, true) GO(32, uint32_t, 32, true)
+  GO(64, uint64_t, 8, true) GO(64, uint64_t, 16, true) GO(64, uint64_t, 32, true)
 #undef GO
   return hipGetLastError();
 }

@@ -91,6 +91,27 @@ def test_form_stage_cluster_shapes(N, n_nodes, d_node, BS, tight, wide):
     _assert_same(c, got, _oracle_form_stage(c), stride)
 
 
+@pytest.mark.parametrize("tmax,recomputes", [(2000, True), (2_000_000_000, False)])
+def test_form_stage_on_a_64_bit_handle_uses_the_totals_it_computes(tmax, recomputes):
+    """A caller that cannot bound the times creates a 64-bit handle.  The outer driver scales the
+    inputs on the host and so knows the largest total of its searches: where that is at most 2^40 ns
+    the one-launch kernel recomputes the stage times (as on a handle created with that bound),
+    beyond it the searches read the table.  Same answer as the oracle either way."""
+    c = synth.form_stage_case(7, 32, 4, 8, 256, tight=1.3, tmax=tmax, layered=True)
+    fs = B.FormStageSession(32, 4, 8, 256, max_total_time_ns=1 << 60)
+    try:
+        got = fs.run(c["time_per_sample_ns"], c["act_bytes_per_sample"], c["param_bytes"], c["mem_capacity"])
+        rc, info = B.rannc_dp_solve_info(fs.h)
+        assert rc == B.OK
+        kinds = [info.level_kernel[k] for k in range(4) if info.n_problems[k]]
+        assert len(kinds) == 3
+        assert all((k == B.KERNEL_ONE_LAUNCH_RECOMPUTE) == recomputes for k in kinds), kinds
+        assert (int(c["time_per_sample_ns"].sum()) * 64 <= B.WIDE_RECOMPUTE_MAX_TOTAL_TIME) == recomputes
+        _assert_same(c, got, _oracle_form_stage(c), fs.plan_stride)
+    finally:
+        fs.close()
+
+
 def test_form_stage_narrow_handle_reports_overflow():
     c = synth.form_stage_case(7, 96, 4, 8, 256, tight=2.0, tmax=20_000_000, layered=True)
     (rc, out, se, rp), _ = _gpu_form_stage(c)  # 32-bit tables cannot hold these totals

@@ -223,6 +223,51 @@ def test_recomputed_stage_times_at_the_edges_of_the_value_range():
             assert_tables_match(probs[q], sm, q, args=False)
 
 
+def test_recomputed_stage_times_64_bit_values_at_the_edges_of_their_range():
+    """The one-launch kernel's recomputation on 64-bit values is exact for stage times up to 2^40 ns
+    (the handle's bound says so).  Chains whose total is exactly 2^40, whose stage totals are
+    multiples of many r at once (and one off them) far above the 32-bit range, and powers of two
+    with their neighbours: identical tables with the stage times read from the table on a handle
+    of a larger bound, and equal to the oracle's."""
+    g = np.random.default_rng(777)
+    top = B.WIDE_RECOMPUTE_MAX_TOTAL_TIME
+    probs = []
+    for case in range(24):
+        N = int(g.integers(20, 129))
+        D = int(g.choice([7, 8, 16, 31, 32]))
+        pr = synth.random_small(9300 + case, N, D, int(g.integers(2, 14)), tight=float(g.choice([1.3, 3.0, 60.0])), tmax=9)
+        kind = case % 4
+        unit = 720720 * 11 * 13 * 17   # lcm(1..17) * ... : exact quotients for many r, about 2^31
+        if kind == 0:
+            pr["time_ns"] = np.full(N, unit, dtype=np.int64) * g.integers(0, 3, N)
+        elif kind == 1:
+            pr["time_ns"] = np.maximum(np.full(N, unit, dtype=np.int64) * g.integers(0, 3, N)
+                                       + g.integers(-1, 2, N) * (g.random(N) < 0.2), 0)
+        elif kind == 2:    # the whole chain is exactly the bound
+            t = g.integers(0, 1 << 32, N).astype(np.int64)
+            t[int(g.integers(0, N))] += top - int(t.sum())
+            pr["time_ns"] = t
+        else:
+            pr["time_ns"] = (1 << g.integers(0, 33, N)).astype(np.int64) + g.integers(-1, 2, N)
+        assert 0 <= int(pr["time_ns"].min()) and int(pr["time_ns"].sum()) <= top
+        probs.append(pr)
+    rt, st = gpu_run(probs, max_total_time_ns=1 << 50, one_launch_small=1)
+    ro, so = gpu_run(probs, max_total_time_ns=top, one_launch_small=2)
+    with st, so:
+        rc, info = B.rannc_dp_solve_info(so.h)
+        assert [info.level_kernel[k] for k in range(3)] == [B.KERNEL_ONE_LAUNCH_RECOMPUTE] * 3
+        rc, info = B.rannc_dp_solve_info(st.h)
+        assert B.KERNEL_ONE_LAUNCH_RECOMPUTE not in [info.level_kernel[k] for k in range(3)]
+        assert (rt["status"] == 0).all()
+        for k in rt:
+            assert np.array_equal(rt[k], ro[k]), k
+        for q in range(len(probs)):
+            assert np.array_equal(st.table(B.TABLE_V, q), so.table(B.TABLE_V, q)), q
+        assert_results_match(probs, ro)
+        for q in (0, 1, 2, 3, 6, 11, 18, 23):
+            assert_tables_match(probs[q], so, q, args=False)
+
+
 @pytest.mark.parametrize("algo", [B.ALGO_MERGE, B.ALGO_RECOMPUTE])
 @pytest.mark.parametrize("rows", [1, 2, 4, 8])
 def test_rows_per_wave_variants(rows, algo):
@@ -304,13 +349,14 @@ def test_plan_recovery_from_lds_and_from_memory(width):
 
 @pytest.mark.parametrize("algo", [B.ALGO_AUTO, B.ALGO_MERGE])
 @pytest.mark.parametrize("mode", [1, 2])
-@pytest.mark.parametrize("width", WIDTHS)
+@pytest.mark.parametrize("width", [B.NARROW_MAX_TOTAL_TIME, B.WIDE_RECOMPUTE_MAX_TOTAL_TIME, 1 << 50])
 def test_small_search_kernel_on_and_off(mode, width, algo):
     """Searches of at most 128 blocks can run as one launch with one workgroup per search (levels
     folded in LDS) or through the per-level launches; the library chooses by batch shape.  Both
     are forced here (1 = never, 2 = always) on the same inputs: identical tables, optimum, plan.
-    The one-launch kernel recomputes the stage times (32-bit values, up to the 32-device class,
-    unless the handle asks for the table) or reads them from the table it builds: both run here."""
+    The one-launch kernel recomputes the stage times (up to the 32-device class, 32-bit values or
+    64-bit values on a handle whose time bound is at most 2^40 ns, unless the handle asks for the
+    table) or reads them from the table it builds: all of these run here."""
     g = np.random.default_rng(99)
     probs = [synth.named_config(1), synth.named_config(2)]
     for q in range(30):
@@ -326,7 +372,7 @@ def test_small_search_kernel_on_and_off(mode, width, algo):
         assert rc == B.OK and all(info.n_problems[k] for k in range(4))
         kinds = [info.level_kernel[k] for k in range(4)]
         if mode == 2:
-            recomputes = width == B.NARROW_MAX_TOTAL_TIME and algo == B.ALGO_AUTO
+            recomputes = width <= B.WIDE_RECOMPUTE_MAX_TOTAL_TIME and algo == B.ALGO_AUTO
             assert kinds == ([B.KERNEL_ONE_LAUNCH_RECOMPUTE] * 3 if recomputes else [B.KERNEL_ONE_LAUNCH] * 3) + [B.KERNEL_ONE_LAUNCH]
         else:
             assert not {B.KERNEL_ONE_LAUNCH, B.KERNEL_ONE_LAUNCH_RECOMPUTE} & set(kinds)
@@ -335,7 +381,8 @@ def test_small_search_kernel_on_and_off(mode, width, algo):
             assert_tables_match(probs[q], sess, q, args=(probs[q]["time_ns"].shape[0] <= 100))
 
 
-def test_one_launch_recompute_block_shapes():
+@pytest.mark.parametrize("width", [B.NARROW_MAX_TOTAL_TIME, B.WIDE_RECOMPUTE_MAX_TOTAL_TIME])
+def test_one_launch_recompute_block_shapes(width):
     """The recomputing one-launch kernel packs row pairs of the triangular blocks and short rows of
     the rectangular block into passes of 64 lanes; the packing depends on the widths min(64, N) and
     N - 64.  Every kind of width (one column, odd, a power of two, one more or less than one, the
@@ -347,7 +394,7 @@ def test_one_launch_recompute_block_shapes():
             probs.append(synth.random_small(7000 + 2 * q + (D == 32), N, D, min(D, 12),
                                             tight=1.2 if q % 3 else 50.0, tmax=10 ** 6,
                                             zero_time_frac=0.25 if q % 4 == 0 else 0.0))
-    res, sess = gpu_run(probs, one_launch_small=2)
+    res, sess = gpu_run(probs, one_launch_small=2, max_total_time_ns=width)
     with sess:
         rc, info = B.rannc_dp_solve_info(sess.h)
         assert rc == B.OK
