@@ -38,12 +38,12 @@ ESIZE = 4  # bytes per table entry in the 32-bit mode all benchmark configuratio
 # one of the 32 launches of the level phase (15 levels of the D = 32 and D = 64 classes, the two
 # one-launch kernels of the D = 8 and D = 16 classes, tables included): their bytes summed, over 32.
 PMC_TRAFFIC = {
-    ("c4", False, False): (29.46e6, "profiles/level_merge_config4.md"),
-    ("c4", True, False): (48.34e6, "profiles/level_merge_config4_wide.md"),
-    ("c4dense", False, False): (113.64e6, "profiles/level_merge_config4_dense.md"),
-    ("c4dense", False, True): (9.29e6, "profiles/level_merge_config4_dense_recompute.md"),
-    ("c5", False, True): (87.2e6, "profiles/level_merge_config5_batched.md"),
-    ("c5", False, False): (799.6e6, "profiles/level_merge_config5_batched_table.md"),
+    ("c4", False, False): (29.44e6, "profiles/level_merge_config4.md"),
+    ("c4", True, False): (48.32e6, "profiles/level_merge_config4_wide.md"),
+    ("c4dense", False, False): (113.63e6, "profiles/level_merge_config4_dense.md"),
+    ("c4dense", False, True): (9.22e6, "profiles/level_merge_config4_dense_recompute.md"),
+    ("c5", False, True): (82.3e6, "profiles/level_merge_config5_batched.md"),
+    ("c5", False, False): (800.1e6, "profiles/level_merge_config5_batched_table.md"),
 }
 # useful vector instructions of the sorted-merge level kernel per (i, j) stage: DP maxima that form
 # the bitonic sequence, then log2(DP) compare-exchange stages of DP/2 (max, min) pairs
