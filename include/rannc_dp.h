@@ -111,8 +111,8 @@ typedef struct {
   int32_t flags;             /* RANNC_DP_FLAG_* or 0 */
   /* Tuning; 0 everywhere = the library's own choices.  None of them changes a result. */
   int32_t rows_per_wave;     /* sorted-merge level kernel: predecessor rows a wave takes one after the
-                                other before the workgroup folds (1, 2, 4 or 8); 0 = by the size of the
-                                launch.  Environment override: RANNC_DP_ROWS_PER_WAVE */
+                                other before the workgroup folds (1, 2, 4, 8, 12 or 16; values between
+                                round up); 0 = by the size of the launch.  Environment override: RANNC_DP_ROWS_PER_WAVE */
   int32_t one_launch_small;  /* searches of at most 128 blocks can run as ONE launch with one workgroup
                                 per search: 0 = where it measured faster (few rows x levels, or
                                 classes of >= 256 searches with D <= 16 or N <= 64), 1 = never,

@@ -58,7 +58,7 @@ bool limits_ok(const rannc_dp_limits_t *l) {
   return l && l->max_problems >= 1 && l->max_blocks >= 1 && l->max_blocks <= 65535 &&
          l->max_devices >= 1 && l->max_devices <= RANNC_DP_MAX_DEVICES && l->max_stages >= 1 &&
          l->max_total_time_ns >= 0 && (l->flags & ~RANNC_DP_FLAG_SPLIT_OBJECTIVE) == 0 && l->algo >= RANNC_DP_ALGO_AUTO &&
-         l->algo <= RANNC_DP_ALGO_RECOMPUTE && l->rows_per_wave >= 0 && l->rows_per_wave <= 8 &&
+         l->algo <= RANNC_DP_ALGO_RECOMPUTE && l->rows_per_wave >= 0 && l->rows_per_wave <= 16 &&
          l->one_launch_small >= 0 && l->one_launch_small <= 2 && l->single_stream >= 0 && l->single_stream <= 1 &&
          l->reserved == 0;
 }
@@ -514,10 +514,11 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     if (scan || split) continue;
     // Rows per wave of the level kernel: chosen on the device from the size of the windows unless
     // the handle fixes it (1, 2 or 4).
-    merge_items[k] = rannc::merge_grid_items(sh, rannc::merge_rows_per_item(h->tune_spw));
-    ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::merge_rows_per_item(h->tune_spw), merge_items[k],
-                                  h->n_cus * rannc::merge_workgroups_per_cu(h->bits, kClasses[k], recompute_cls[k]),
-                                  recompute_cls[k], st) == hipSuccess;
+    const int slots = h->n_cus * rannc::merge_workgroups_per_cu(h->bits, kClasses[k], recompute_cls[k]);
+    int rows_for_list = -1;
+    merge_items[k] = rannc::merge_grid_items(sh, rannc::merge_rows_per_item(h->tune_spw), slots, recompute_cls[k],
+                                             &rows_for_list);
+    ok = ok && rannc::launch_runs(cp, sh.nprob, rows_for_list, merge_items[k], slots, recompute_cls[k], st) == hipSuccess;
   }
   if (timing) ok = ok && hipEventRecord(h->ev[1], st) == hipSuccess;
   int max_levels = 0;

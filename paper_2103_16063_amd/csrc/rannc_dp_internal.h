@@ -112,7 +112,8 @@ hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int ma
                        hipStream_t st);
 int merge_workgroups_per_cu(int bits, int DP, bool recompute);
 int merge_rows_per_item(int rows_per_wave);
-int merge_grid_items(const LaunchShape &sh, int rows_per_item);
+// rows_for_list: what launch_runs is to be given as rows_per_item (the size the host fixed, or -1)
+int merge_grid_items(const LaunchShape &sh, int rows_per_item, int slots, bool paired, int *rows_for_list);
 // rows of the searches of a launch if nothing is pruned (every chunk c holds rows 0 .. 64c+63)
 int64_t merge_launch_rows(const LaunchShape &sh);
 // recompute: the level kernel computes the stage times from the prefix sums instead of reading

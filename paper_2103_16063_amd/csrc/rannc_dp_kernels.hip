@@ -331,7 +331,8 @@ __global__ __launch_bounds__(256) void windows_kernel(const ProblemDev *__restri
 // workgroups (`slots` run at a time, `batch` searches in the launch), the smallest item size that
 // brings it down to one round is taken instead, provided the round still fills half the device:
 // the round is then as full as it can be, and no compute unit is left with one workgroup more
-// than its neighbours.  One workgroup per problem.
+// than its neighbours.  (For a launch of many rounds, hundreds of searches, the host fixes the item
+// size for all of them: merge_grid_items.)  One workgroup per problem.
 // ---------------------------------------------------------------------------------------
 // paired (the level kernel that recomputes the stage times): inside the diagonal block of a chunk
 // (rows 64c .. 64c+63, where row 64c+p has work only in the lanes from p on) the list holds the
@@ -788,12 +789,12 @@ __device__ __forceinline__ bool merge_rows(VT (&acc)[DP], VT *tile_lane, const P
 }
 
 template <typename VT, int DP, bool DIRECT>
-__device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int s) {
+__device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int s, const int item) {
   if (s > pr.S_eff) return;
   const int N = pr.N, D = pr.D;
   const int32_t RANNC_GLOBAL *__restrict__ runs = gptr((const int32_t *)pr.runs);
-  if ((int)blockIdx.x >= runs[0]) return;
-  const unsigned desc = (unsigned)runs[1 + blockIdx.x];
+  if (item >= runs[0]) return;
+  const unsigned desc = (unsigned)runs[1 + item];
   const int c = (int)((desc >> 16) & 0x3ffu), i0 = (int)(desc & 0xffffu), rows = (int)(desc >> 26) + 1;
   if (64 * c + 64 < s) return;  // no column j >= s in this chunk
   const int i_hi = min(min(i0 + rows - 1, 64 * c + 63), N - 1);
@@ -873,8 +874,14 @@ __device__ __forceinline__ void level_merge_body(const ProblemDev &pr, const int
 
 template <typename VT, int DP, bool DIRECT>
 __global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP, DIRECT>())))
-void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
-  level_merge_body<VT, DP, DIRECT>(probs[blockIdx.z], s);
+void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s, const int search_major) {
+  // Workgroups go to the eight XCDs round-robin in the order of their linear index.  With the items
+  // of a search next to each other (search_major) and, say, four items per search, item k of every
+  // search lands on XCDs k and k + 4: the XCDs with the long items finish last and those with the
+  // empty ones idle (config 5: 176 against 121 us per level).  In a launch over several searches
+  // the search index therefore runs fastest: every XCD gets every kind of item.
+  if (search_major) level_merge_body<VT, DP, DIRECT>(probs[blockIdx.z], s, (int)blockIdx.x);
+  else level_merge_body<VT, DP, DIRECT>(probs[blockIdx.x], s, (int)blockIdx.z);
 }
 
 // The same for a launch over ONE search, with the descriptor as a kernel argument: a workgroup then
@@ -883,7 +890,7 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s) {
 template <typename VT, int DP, bool DIRECT>
 __global__ __launch_bounds__(64 * kMergeWaves) __attribute__((amdgpu_waves_per_eu(merge_waves_per_simd<VT, DP, DIRECT>())))
 void level_merge_one_kernel(const ProblemDev pr, const int s) {
-  level_merge_body<VT, DP, DIRECT>(pr, s);
+  level_merge_body<VT, DP, DIRECT>(pr, s, (int)blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1611,7 +1618,7 @@ hipError_t launch_fill(const ProblemDev *probs, int Q, hipStream_t st) {
 
 int merge_rows_per_item(int rows_per_wave) {
   if (rows_per_wave <= 0) return -1;  // chosen on the device
-  return kMergeWaves * (rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : rows_per_wave <= 4 ? 4 : 8);
+  return kMergeWaves * (rows_per_wave <= 1 ? 1 : rows_per_wave <= 2 ? 2 : rows_per_wave <= 4 ? 4 : rows_per_wave <= 8 ? 8 : rows_per_wave <= 12 ? 12 : 16);
 }
 
 // Grid of the sorted-merge level kernel = items of the largest search of the launch if nothing is
@@ -1625,15 +1632,34 @@ int64_t merge_launch_rows(const LaunchShape &sh) {
   return all_rows * sh.nprob;
 }
 
-int merge_grid_items(const LaunchShape &sh, int rows_per_item) {
+int merge_grid_items(const LaunchShape &sh, int rows_per_item, int slots, bool paired, int *rows_for_list) {
+  // items of the largest search of the launch if nothing is pruned, in items of `rows` rows: the
+  // segments of run_segments for windows that start at row 0 (a pruned window has no more rows in
+  // either segment, so no more items at any size)
+  auto items_at = [&](int rows) {
+    int64_t items = 0;
+    for (int c = 0; c < sh.max_nch; ++c) {
+      const int hi = min(64 * c + 63, sh.max_N - 1);
+      int n0 = hi + 1, n1 = 0;
+      if (paired && hi >= 64 * c) { n0 = 64 * c; n1 = min(32, hi - 64 * c) + 1; }
+      items += (n0 + rows - 1) / rows + (n1 + rows - 1) / rows;
+    }
+    return std::max<int64_t>(1, items);
+  };
   int rows = rows_per_item;
+  *rows_for_list = rows_per_item;
   if (rows <= 0) {
     const int64_t launch_rows = merge_launch_rows(sh);
     rows = launch_rows >= kMergeRows16From ? 16 : launch_rows >= kMergeRows8From ? 8 : kMergeMinRows;
+    // A launch of many rounds of workgroups (hundreds of searches): the largest items that still
+    // leave four rounds if nothing is pruned, the same size for every search of the launch.
+    // Clearing the tile, the fold and the atomics are paid per item, and with four rounds the
+    // partly filled last one costs little (config 5: 16 -> 60 rows, 157 -> 121 us per level).
+    if (items_at(rows) * sh.nprob > slots)
+      for (int r = 64; r > rows; r -= 4)
+        if (items_at(r) * sh.nprob >= 4ll * slots) { rows = r; *rows_for_list = r; break; }
   }
-  int64_t items = 0;
-  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + rows - 1) / rows;
-  return (int)std::max<int64_t>(1, items);
+  return (int)items_at(rows);
 }
 
 hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int max_items, int slots, bool paired,
@@ -1699,8 +1725,12 @@ static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, int item
   }
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    hipLaunchKernelGGL((level_merge_kernel<VT, DP, DIRECT>), dim3((unsigned)items, 1, nq), dim3(64 * kMergeWaves), 0,
-                       st, p + q0, s);
+    if (nq > 1 && items <= 65535)
+      hipLaunchKernelGGL((level_merge_kernel<VT, DP, DIRECT>), dim3(nq, 1, (unsigned)items), dim3(64 * kMergeWaves), 0,
+                         st, p + q0, s, 0);
+    else
+      hipLaunchKernelGGL((level_merge_kernel<VT, DP, DIRECT>), dim3((unsigned)items, 1, nq), dim3(64 * kMergeWaves), 0,
+                         st, p + q0, s, 1);
   }
 }
 

@@ -269,10 +269,10 @@ def test_recomputed_stage_times_64_bit_values_at_the_edges_of_their_range():
 
 
 @pytest.mark.parametrize("algo", [B.ALGO_MERGE, B.ALGO_RECOMPUTE])
-@pytest.mark.parametrize("rows", [1, 2, 4, 8])
+@pytest.mark.parametrize("rows", [1, 2, 4, 8, 12, 16])
 def test_rows_per_wave_variants(rows, algo):
-    """A wave of the merge level kernel takes 1, 2, 4 or 8 predecessor rows one after the other
-    (work items of 4, 8, 16 or 32 rows); the handle's limits fix the choice.  All must give the
+    """A wave of the merge level kernel takes 1, 2, 4, 8, 12 or 16 predecessor rows one after the other
+    (work items of 4 to 64 rows); the handle's limits fix the choice.  All must give the
     oracle's tables, with the stage times read from their table and recomputed."""
     probs = [synth.enlarged_transformer_chain(seed=21, N=333, D=64, S=12, M=24 * synth.GiB),
              synth.random_small(77, 150, 40, 9, tight=1.3, tmax=5000),
