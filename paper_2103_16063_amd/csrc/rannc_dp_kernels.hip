@@ -261,10 +261,16 @@ __device__ __forceinline__ bool build_unit(const ProblemDev &pr, const int64_t *
 // would otherwise halve the waves in flight at 64 devices.)
 template <typename VT, int DP, int ROWS>
 __global__ __launch_bounds__(64 * kBuildWaves) __attribute__((amdgpu_waves_per_eu(ROWS > 1 ? 4 : 1)))
-void build_kernel(const ProblemDev *__restrict__ probs, const int parts) {
-  const ProblemDev &pr = probs[blockIdx.z];
+void build_kernel(const ProblemDev *__restrict__ probs, const int parts, const int pr_many) {
+  // Workgroups go to the eight XCDs round-robin in the order of their linear index.  A launch over
+  // several searches has grid = (searches, row groups, chunks): the search runs fastest and every
+  // XCD gets rows of every chunk (with the chunk fastest and two chunks per search, the XCDs with
+  // even numbers would get the triangle of chunk 0 and the others the three times larger chunk 1:
+  // config 5, fits-in-memory part, 59 -> 39 us).  One search: grid = (chunks, row groups, 1).
+  const bool many = pr_many != 0;
+  const ProblemDev &pr = probs[many ? blockIdx.x : 0];
   const int lane = threadIdx.x & 63;
-  const int i0 = (blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6)) * ROWS, c = blockIdx.x;
+  const int i0 = (blockIdx.y * kBuildWaves + (int)(threadIdx.x >> 6)) * ROWS, c = many ? blockIdx.z : blockIdx.x;
   __shared__ VT tile[64 * (DP + 1)];  // level 1 of this chunk (only the wave that holds row 0 uses it)
   if (c >= pr.nch) return;
   auto one_row = [&](const int i) {
@@ -878,8 +884,8 @@ void level_merge_kernel(const ProblemDev *__restrict__ probs, const int s, const
   // Workgroups go to the eight XCDs round-robin in the order of their linear index.  With the items
   // of a search next to each other (search_major) and, say, four items per search, item k of every
   // search lands on XCDs k and k + 4: the XCDs with the long items finish last and those with the
-  // empty ones idle (config 5: 176 against 121 us per level).  In a launch over several searches
-  // the search index therefore runs fastest: every XCD gets every kind of item.
+  // empty ones idle (config 5: 176 against 121 us per level).  In a launch of the recomputing form
+  // over several searches the search index therefore runs fastest: every XCD gets every kind of item.
   if (search_major) level_merge_body<VT, DP, DIRECT>(probs[blockIdx.z], s, (int)blockIdx.x);
   else level_merge_body<VT, DP, DIRECT>(probs[blockIdx.x], s, (int)blockIdx.z);
 }
@@ -1651,11 +1657,12 @@ int merge_grid_items(const LaunchShape &sh, int rows_per_item, int slots, bool p
   if (rows <= 0) {
     const int64_t launch_rows = merge_launch_rows(sh);
     rows = launch_rows >= kMergeRows16From ? 16 : launch_rows >= kMergeRows8From ? 8 : kMergeMinRows;
-    // A launch of many rounds of workgroups (hundreds of searches): the largest items that still
-    // leave four rounds if nothing is pruned, the same size for every search of the launch.
-    // Clearing the tile, the fold and the atomics are paid per item, and with four rounds the
-    // partly filled last one costs little (config 5: 16 -> 60 rows, 157 -> 121 us per level).
-    if (items_at(rows) * sh.nprob > slots)
+    // A launch of the recomputing form with many rounds of workgroups (hundreds of searches): the
+    // largest items that still leave four rounds if nothing is pruned, the same size for every
+    // search of the launch.  Clearing the tile, the fold and the atomics are paid per item, and with
+    // four rounds the partly filled last one costs little (config 5: 16 -> 60 rows, 157 -> 121 us
+    // per level; the table form, bound by its reads, gains nothing: 100 -> 107 us at 32 devices).
+    if (paired && items_at(rows) * sh.nprob > slots)
       for (int r = 64; r > rows; r -= 4)
         if (items_at(r) * sh.nprob >= 4ll * slots) { rows = r; *rows_for_list = r; break; }
   }
@@ -1694,9 +1701,10 @@ static void build_go(const ProblemDev *p, const LaunchShape &sh, int parts, hipS
   const int per_group = kBuildWaves * rows;
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    const dim3 grid(sh.max_nch, (sh.max_N + per_group - 1) / per_group, nq), block(64 * kBuildWaves);
-    if (rows == 1) hipLaunchKernelGGL((build_kernel<VT, DP, 1>), grid, block, 0, st, p + q0, parts);
-    else hipLaunchKernelGGL((build_kernel<VT, DP, kBuildRowsFitOnly>), grid, block, 0, st, p + q0, parts);
+    const int groups = (sh.max_N + per_group - 1) / per_group, many = nq > 1;
+    const dim3 grid = many ? dim3(nq, groups, sh.max_nch) : dim3(sh.max_nch, groups, 1), block(64 * kBuildWaves);
+    if (rows == 1) hipLaunchKernelGGL((build_kernel<VT, DP, 1>), grid, block, 0, st, p + q0, parts, many);
+    else hipLaunchKernelGGL((build_kernel<VT, DP, kBuildRowsFitOnly>), grid, block, 0, st, p + q0, parts, many);
   }
 }
 
@@ -1725,7 +1733,10 @@ static void merge_go(const ProblemDev *p, const LaunchShape &sh, int s, int item
   }
   for (int q0 = 0; q0 < sh.nprob; q0 += 65535) {
     const int nq = min(65535, sh.nprob - q0);
-    if (nq > 1 && items <= 65535)
+    // (the table form keeps the items of a search together: workgroups that run at the same time
+    // then read neighbouring units of few tables instead of one unit each of hundreds of tables,
+    // which measured 10 % slower on config 5)
+    if (DIRECT && nq > 1 && items <= 65535)
       hipLaunchKernelGGL((level_merge_kernel<VT, DP, DIRECT>), dim3(nq, 1, (unsigned)items), dim3(64 * kMergeWaves), 0,
                          st, p + q0, s, 0);
     else

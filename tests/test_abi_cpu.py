@@ -43,7 +43,7 @@ def test_workspace_query_validates():
     assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, max_total_time_ns=-1)) == 0
     assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, algo=7)) == 0
     assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, algo=B.ALGO_RECOMPUTE)) > 0
-    assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, rows_per_wave=9)) == 0      # tuning out of range
+    assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, rows_per_wave=17)) == 0     # tuning out of range
     assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, one_launch_small=3)) == 0
     assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, single_stream=2)) == 0
     assert B.rannc_dp_workspace_bytes(B.make_limits(1, 16, 4, 4, rows_per_wave=8, one_launch_small=2, single_stream=1)) > 0
