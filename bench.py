@@ -42,8 +42,8 @@ PMC_TRAFFIC = {
     ("c4", True, False): (48.32e6, "profiles/level_merge_config4_wide.md"),
     ("c4dense", False, False): (113.63e6, "profiles/level_merge_config4_dense.md"),
     ("c4dense", False, True): (9.22e6, "profiles/level_merge_config4_dense_recompute.md"),
-    ("c5", False, True): (82.3e6, "profiles/level_merge_config5_batched.md"),
-    ("c5", False, False): (800.1e6, "profiles/level_merge_config5_batched_table.md"),
+    ("c5", False, True): (48.2e6, "profiles/level_merge_config5_batched.md"),
+    ("c5", False, False): (811.8e6, "profiles/level_merge_config5_batched_table.md"),
 }
 # useful vector instructions of the sorted-merge level kernel per (i, j) stage: DP maxima that form
 # the bitonic sequence, then log2(DP) compare-exchange stages of DP/2 (max, min) pairs
