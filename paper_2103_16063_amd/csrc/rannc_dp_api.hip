@@ -512,8 +512,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, 0, false, st) == hipSuccess;
     }
     if (scan || split) continue;
-    // Rows per wave of the level kernel: chosen on the device from the size of the windows unless
-    // the handle fixes it (1, 2 or 4).
+    // Rows per item of the level kernel: chosen on the device from the size of the windows unless
+    // the handle fixes it, or the host does for a launch of many rounds (merge_grid_items).
     const int slots = h->n_cus * rannc::merge_workgroups_per_cu(h->bits, kClasses[k], recompute_cls[k]);
     int rows_for_list = -1;
     merge_items[k] = rannc::merge_grid_items(sh, rannc::merge_rows_per_item(h->tune_spw), slots, recompute_cls[k],

@@ -398,13 +398,20 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
       for (int k = NC - 1; k >= 0; --k)
         if (count[k] <= max_items) pick = k;
       if ((long long)count[pick] * batch > slots) {
+        bool one_round = false;
         for (int k = pick + 1; k < NC; ++k) {
           const long long then = (long long)count[k] * batch;
           if (then <= slots) {
-            if (2 * then >= slots) pick = k;
+            if (2 * then >= slots) { pick = k; one_round = true; }
             break;
           }
         }
+        // one large search of the recomputing form with many rounds: the largest items that still
+        // leave four rounds, by the rows that are really there (the host, which fixes the size for
+        // a launch over many searches, cannot see the pruning of a single one)
+        if (!one_round && paired && batch == 1)
+          for (int k = NC - 1; k > pick; --k)
+            if (count[k] >= 4 * slots) { pick = k; break; }
       }
       rows = 4 * (pick + 1);
     }
@@ -466,7 +473,7 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
 // Only replica counts r <= D-s+1 can occur at level s (s-1 devices are spent on the earlier
 // stages); the larger ones rank below position D-1 of the merge, so they are not read.
 //
-// Work item (one workgroup of four waves) = 4, 8 or 16 consecutive rows of one chunk's window,
+// Work item (one workgroup of four waves) = 4 to 64 consecutive rows of one chunk's window,
 // taken from the work list; wave w takes rows i0+w, i0+w+4, ... one after the other and keeps the
 // running minimum over them in registers (one value array for the row in flight, one for the
 // minimum: three waves per SIMD, i.e. three workgroups per compute unit, whose memory, merge and
@@ -1657,12 +1664,12 @@ int merge_grid_items(const LaunchShape &sh, int rows_per_item, int slots, bool p
   if (rows <= 0) {
     const int64_t launch_rows = merge_launch_rows(sh);
     rows = launch_rows >= kMergeRows16From ? 16 : launch_rows >= kMergeRows8From ? 8 : kMergeMinRows;
-    // A launch of the recomputing form with many rounds of workgroups (hundreds of searches): the
+    // A launch of the recomputing form over several searches with many rounds of workgroups: the
     // largest items that still leave four rounds if nothing is pruned, the same size for every
     // search of the launch.  Clearing the tile, the fold and the atomics are paid per item, and with
     // four rounds the partly filled last one costs little (config 5: 16 -> 60 rows, 157 -> 121 us
     // per level; the table form, bound by its reads, gains nothing: 100 -> 107 us at 32 devices).
-    if (paired && items_at(rows) * sh.nprob > slots)
+    if (paired && sh.nprob > 1 && items_at(rows) * sh.nprob > slots)
       for (int r = 64; r > rows; r -= 4)
         if (items_at(r) * sh.nprob >= 4ll * slots) { rows = r; *rows_for_list = r; break; }
   }
