@@ -509,7 +509,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
     ok = ok && rannc::launch_windows(cp, sh, st) == hipSuccess;  // also used by traceback
     if (split) {
       ok = ok && rannc::launch_split_level1(cp, sh, h->bits, st) == hipSuccess;
-      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(), 0, 0, false, st) == hipSuccess;
+      if (split_fast) ok = ok && rannc::launch_runs(cp, sh.nprob, rannc::split_rows_per_item(sh, h->n_cus), 0, 0, false, st) == hipSuccess;
     }
     if (scan || split) continue;
     // Rows per item of the level kernel: chosen on the device from the size of the windows unless
@@ -537,7 +537,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       if (!sh.nprob || sh.max_S_eff < s || fused[k]) continue;
       const hipStream_t st = cs[k];
       if (split_fast)
-        ok = rannc::launch_level_split_fast(dp + cls_start[k], sh, h->bits, kClasses[k], s, st) == hipSuccess;
+        ok = rannc::launch_level_split_fast(dp + cls_start[k], sh, h->bits, kClasses[k], s,
+                                            rannc::split_rows_per_item(sh, h->n_cus), st) == hipSuccess;
       else if (split)
         ok = rannc::launch_level_split(dp + cls_start[k], sh, h->bits, s, 1, nullptr, nullptr, st) ==
              hipSuccess;

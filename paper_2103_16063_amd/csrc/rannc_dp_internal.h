@@ -39,8 +39,14 @@ __host__ __device__ inline int64_t unit_index(int nch, int i, int c) {
 }
 
 // upper bound on the number of work items ("runs") of one level: every chunk's rows cut into
-// groups of at least 4 rows (chunk c has at most 64(c+1) rows)
-__host__ __device__ inline int64_t max_runs(int nch) { return 8LL * nch * (nch + 1); }
+// groups of at least 4 rows (chunk c has at most 64(c+1) rows), or, for a search of at most
+// kSplitSmallRows rows, into items of one or two rows (split_rows_per_item)
+constexpr int kSplitSmallRows = 1024;
+__host__ __device__ inline int64_t max_runs(int nch) {
+  const int64_t by4 = 8LL * nch * (nch + 1), rows = 32LL * nch * (nch + 1);
+  const int64_t small = rows < kSplitSmallRows + nch ? rows : kSplitSmallRows + nch;
+  return by4 > small ? by4 : small;
+}
 
 // Sorted-merge level kernel: waves per work item; a wave takes 1, 2, 4, ... of the item's rows.  The
 // host sizes the grid for items of 16 rows when the searches of a launch together hold at least
@@ -141,9 +147,12 @@ hipError_t launch_level_split(const ProblemDev *probs, const LaunchShape &sh, in
 // needs the key table and the work list made by launch_runs(..., split_rows_per_item(), ...); with
 // 64-bit tables only for time bounds up to kSplitPackedMax (the packed winner holds 42 value bits)
 constexpr int64_t kSplitPackedMax = (1LL << 42) - 2;
-int split_rows_per_item();
+// rows per work item: 1 or 2 for a launch whose rows (unpruned) then still fit one round of workgroups
+// (a short chain of rows per workgroup: the launch is bound by latency), else 0 = chosen on the
+// device from the size of the windows (4, 8 or 16); the level launcher is given the same value
+int split_rows_per_item(const LaunchShape &sh, int n_cus);
 hipError_t launch_level_split_fast(const ProblemDev *probs, const LaunchShape &sh, int bits, int DP, int s,
-                                   hipStream_t st);
+                                   int rows_per_item, hipStream_t st);
 hipError_t launch_select(const ProblemDev *probs, int Q, int64_t *d_opt, int32_t *d_n_stages,
                          int64_t *d_est, int32_t *d_status, hipStream_t st);
 // d_levels: per problem (caller's order) the exact stage count to recover, 0 = the best one; or null

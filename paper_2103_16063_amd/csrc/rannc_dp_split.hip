@@ -284,7 +284,11 @@ hipError_t launch_level_split(const ProblemDev *p, const LaunchShape &sh, int bi
   return hipGetLastError();
 }
 
-int split_rows_per_item() { return 0; }  // 0 = chosen on the device from the size of the windows
+int split_rows_per_item(const LaunchShape &sh, int n_cus) {
+  // two workgroups of eight waves per compute unit; the work list has room for kSplitSmallRows such items
+  const int64_t rows = merge_launch_rows(sh), slots = std::min<int64_t>(2ll * n_cus, kSplitSmallRows / 2);
+  return rows <= slots ? 1 : rows <= 2 * slots ? 2 : 0;
+}
 
 template <typename VT>
 static void split_fast_go(const ProblemDev *p, const LaunchShape &sh, int DP, int s, int64_t items, hipStream_t st) {
@@ -301,9 +305,10 @@ static void split_fast_go(const ProblemDev *p, const LaunchShape &sh, int DP, in
 }
 
 hipError_t launch_level_split_fast(const ProblemDev *p, const LaunchShape &sh, int bits, int DP, int s,
-                                   hipStream_t st) {
+                                   int rows_per_item, hipStream_t st) {
+  const int per = rows_per_item > 0 ? rows_per_item : kSplitMinRows;
   int64_t items = 0;  // upper bound on the items of any problem of the launch
-  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + kSplitMinRows - 1) / kSplitMinRows;
+  for (int c = 0; c < sh.max_nch; ++c) items += (min(64 * c + 64, sh.max_N) + per - 1) / per;
   if (bits == 32) split_fast_go<uint32_t>(p, sh, DP, s, items, st);
   else split_fast_go<uint64_t>(p, sh, DP, s, items, st);
   return hipGetLastError();
