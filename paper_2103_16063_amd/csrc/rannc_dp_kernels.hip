@@ -407,11 +407,11 @@ __global__ __launch_bounds__(256) void runs_kernel(const ProblemDev *__restrict_
           }
         }
         // one large search of the recomputing form with many rounds: the largest items that still
-        // leave four rounds, by the rows that are really there (the host, which fixes the size for
+        // leave three rounds, by the rows that are really there (the host, which fixes the size for
         // a launch over many searches, cannot see the pruning of a single one)
         if (!one_round && paired && batch == 1)
           for (int k = NC - 1; k > pick; --k)
-            if (count[k] >= 4 * slots) { pick = k; break; }
+            if (count[k] >= 3 * slots) { pick = k; break; }
       }
       rows = 4 * (pick + 1);
     }
@@ -1665,13 +1665,13 @@ int merge_grid_items(const LaunchShape &sh, int rows_per_item, int slots, bool p
     const int64_t launch_rows = merge_launch_rows(sh);
     rows = launch_rows >= kMergeRows16From ? 16 : launch_rows >= kMergeRows8From ? 8 : kMergeMinRows;
     // A launch of the recomputing form over several searches with many rounds of workgroups: the
-    // largest items that still leave four rounds if nothing is pruned, the same size for every
+    // largest items that still leave three rounds if nothing is pruned, the same size for every
     // search of the launch.  Clearing the tile, the fold and the atomics are paid per item, and with
-    // four rounds the partly filled last one costs little (config 5: 16 -> 60 rows, 157 -> 121 us
+    // three rounds the partly filled last one costs little (config 5: 16 -> 64 rows, 157 -> 115 us
     // per level; the table form, bound by its reads, gains nothing: 100 -> 107 us at 32 devices).
     if (paired && sh.nprob > 1 && items_at(rows) * sh.nprob > slots)
       for (int r = 64; r > rows; r -= 4)
-        if (items_at(r) * sh.nprob >= 4ll * slots) { rows = r; *rows_for_list = r; break; }
+        if (items_at(r) * sh.nprob >= 3ll * slots) { rows = r; *rows_for_list = r; break; }
   }
   return (int)items_at(rows);
 }
@@ -1686,7 +1686,7 @@ hipError_t launch_runs(const ProblemDev *probs, int Q, int rows_per_item, int ma
 // registers of its four waves, one per SIMD; see the kernel's resource usage).
 int merge_workgroups_per_cu(int bits, int DP, bool recompute) {
   if (bits == 32) {
-    if (recompute) return DP == 64 ? 2 : DP == 32 ? 3 : DP == 16 ? 5 : 8;
+    if (recompute) return DP == 64 ? 2 : DP == 32 ? 4 : DP == 16 ? 5 : 8;
     return DP == 64 ? 3 : DP == 32 ? 4 : DP == 16 ? 6 : 8;
   }
   return DP == 64 ? 2 : DP == 32 ? 3 : DP == 16 ? 4 : 8;
