@@ -1,6 +1,7 @@
 """GPU parity on random batches with the options of the search drawn together: send times on or
 off, split objective on or off, 32-bit / packed 64-bit / full 64-bit handles, merge or literal level
-kernel, one-launch kernel forced on / off / by rule, device-count classes on one stream or several.
+kernel, one-launch kernel forced on / off / by rule, work items of the level kernel of a fixed size or
+by rule, device-count classes on one stream or several.
 Every problem against the oracle (optimum, stage count, canonical plan); one small problem per
 batch also table by table.  Integers: bit-exact."""
 import os
@@ -52,7 +53,8 @@ def test_random_batches_with_mixed_options(group):
                 else:
                     os.environ.pop(k, None)
             probs = _random_batch(g)
-            res, sess = gpu_run(probs, algo=algo, max_total_time_ns=width)
+            rows_per_wave = int(g.choice([0, 0, 1, 4, 8, 12, 16]))  # work-item size of the level kernel
+            res, sess = gpu_run(probs, algo=algo, max_total_time_ns=width, rows_per_wave=rows_per_wave)
             with sess:
                 assert_results_match(probs, res, threads=0)
                 small = [q for q, p in enumerate(probs) if p["time_ns"].shape[0] <= 66]
