@@ -926,8 +926,16 @@ template <typename VT, int DP> constexpr int small_waves() { return sizeof(VT) *
 __device__ __forceinline__ void select_finish(const ProblemDev &pr, int64_t v, int st, int64_t *d_opt,
                                               int32_t *d_n_stages, int64_t *d_est, int32_t *d_status);
 
+// Waves per SIMD the one-launch kernel is compiled for.  The recomputing form on 32-bit values at 16
+// devices needs 70 registers left alone, one wave per SIMD short of TWO workgroups per compute unit
+// (16 waves each); held to 64 registers the two rounds of a batch of 512 searches run side by side.
+template <typename VT, int DP, bool DIRECT> constexpr int small_waves_per_simd() {
+  return (DIRECT && sizeof(VT) == 4 && DP == 16) ? 8 : small_waves<VT, DP>() / 4;
+}
+
 template <typename VT, int DP, bool DIRECT>
-__global__ __launch_bounds__((64 * small_waves<VT, DP>())) void solve_small_kernel(
+__global__ __launch_bounds__((64 * small_waves<VT, DP>())) __attribute__((amdgpu_waves_per_eu((small_waves_per_simd<VT, DP, DIRECT>()))))
+void solve_small_kernel(
     const ProblemDev *__restrict__ probs, int64_t *d_opt, int32_t *d_n_stages, int64_t *d_est,
     int32_t *d_status) {
   const ProblemDev &pr = probs[blockIdx.x];
