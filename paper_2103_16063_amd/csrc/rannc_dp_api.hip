@@ -122,6 +122,7 @@ struct rannc_dp {
   // caller's stream with events.  Off while per-phase timing is on (the phases are timed on the
   // caller's stream) and with RANNC_DP_STREAMS=0.
   char *fs_pin;          // pinned host mirror of the outer driver's device scratch (grown on demand)
+  char *fs_pin_dev;      // the address the device reads and writes the mirror through, or null
   size_t fs_pin_bytes;
   hipStream_t aux[3];
   hipEvent_t fork_ev, join_ev[3];
@@ -211,6 +212,7 @@ int rannc_dp_create(const rannc_dp_limits_t *l, void *d_workspace, size_t worksp
   if (const char *e = std::getenv("RANNC_DP_FUSED_SMALL")) h->fused_small = std::atoi(e);
   h->d_probs = (ProblemDev *)h->ws;
   h->fs_pin = nullptr;
+  h->fs_pin_dev = nullptr;
   h->fs_pin_bytes = 0;
   h->multi_stream = l->single_stream == 0;
   if (const char *e = std::getenv("RANNC_DP_STREAMS")) h->multi_stream = std::atoi(e) != 0;
@@ -420,33 +422,15 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   h->ev_valid = false;
   h->level_launches = 0;
   if (timing) ok = ok && hipEventRecord(h->ev[0], st) == hipSuccess;
-  // one stream per device-count class: the largest class stays on the caller's stream
-  hipStream_t cs[4] = {st, st, st, st};
-  int n_aux = 0;
-  if (h->multi_stream && !timing) {
-    bool first = true;
-    for (int k = 3; k >= 0; --k) {
-      if (!shape[k].nprob) continue;
-      if (first) { first = false; continue; }
-      cs[k] = h->aux[n_aux++];
-    }
-    if (n_aux > 0) {
-      ok = ok && hipEventRecord(h->fork_ev, st) == hipSuccess;  // descriptors are on the device
-      for (int a = 0; a < n_aux && ok; ++a) ok = hipStreamWaitEvent(h->aux[a], h->fork_ev, 0) == hipSuccess;
-    }
-  }
   // what the host knows about the total time of a search of this batch: the handle's bound, or the
   // outer driver's own sum over the inputs it has just scaled
   const int64_t total_bound = h->call_total_bound > 0 ? std::min(h->call_total_bound, h->lim.max_total_time_ns)
                                                       : h->lim.max_total_time_ns;
   bool fused[4] = {false, false, false, false};
   bool fused_direct[4] = {false, false, false, false};  // one-launch kernel that recomputes the stage times
-  int merge_items[4] = {1, 1, 1, 1};
-  for (int k = 0; k < 4 && ok; ++k) {
+  for (int k = 0; k < 4; ++k) {
     const LaunchShape &sh = shape[k];
     if (!sh.nprob) continue;
-    const ProblemDev *cp = dp + cls_start[k];
-    const hipStream_t st = cs[k];  // this class's stream
     // Small searches: everything in one launch, one workgroup per search, where that measured
     // faster than the launches per level (MI355X; N = 16..128, D = 8..64, 1..512 searches per class).
     {
@@ -502,6 +486,36 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
                  (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);
       fused_direct[k] = fused[k] && direct_ok;
     }
+  }
+  // one stream per device-count class: the largest class stays on the caller's stream
+  hipStream_t cs[4] = {st, st, st, st};
+  int n_aux = 0;
+  if (h->multi_stream && !timing) {
+    // (the other classes that run as ONE launch each share a stream: they are short, and every
+    // stream costs a wait on the fork event and one on its join event, 10 us of host time each)
+    bool first = true;
+    int shared = -1;
+    for (int k = 3; k >= 0; --k) {
+      if (!shape[k].nprob) continue;
+      if (first) { first = false; continue; }
+      if (fused[k]) {
+        if (shared < 0) shared = n_aux++;
+        cs[k] = h->aux[shared];
+      } else {
+        cs[k] = h->aux[n_aux++];
+      }
+    }
+    if (n_aux > 0) {
+      ok = ok && hipEventRecord(h->fork_ev, st) == hipSuccess;  // descriptors are on the device
+      for (int a = 0; a < n_aux && ok; ++a) ok = hipStreamWaitEvent(h->aux[a], h->fork_ev, 0) == hipSuccess;
+    }
+  }
+  int merge_items[4] = {1, 1, 1, 1};
+  for (int k = 0; k < 4 && ok; ++k) {
+    const LaunchShape &sh = shape[k];
+    if (!sh.nprob) continue;
+    const ProblemDev *cp = dp + cls_start[k];
+    const hipStream_t st = cs[k];  // this class's stream
     if (fused[k]) continue;
     ok = rannc::launch_prefix(cp, sh.nprob, st) == hipSuccess;
     ok = ok && rannc::launch_fill(cp, sh.nprob, st) == hipSuccess;
@@ -588,6 +602,8 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
 }
 
 constexpr int kTracebackStagedMaxProblems = 64;
+// outer driver: inputs of up to this many bytes are read by the kernels out of the pinned host mirror
+constexpr size_t kFsReadInPlaceMax = 32 << 10;
 
 int rannc_dp_solve_info(rannc_dp_t *h, rannc_dp_solve_info_t *out) {
   if (!h || !out) return RANNC_DP_INVALID_ARG;
@@ -739,14 +755,20 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
       if (hipStreamSynchronize(st) != hipSuccess) return RANNC_DP_HIP_ERROR;  // an earlier call's copies
       (void)hipHostFree(h->fs_pin);
       h->fs_pin = nullptr;
+      h->fs_pin_dev = nullptr;
       h->fs_pin_bytes = 0;
     }
-    if (hipHostMalloc((void **)&h->fs_pin, need, hipHostMallocDefault) != hipSuccess) {
+    if (hipHostMalloc((void **)&h->fs_pin, need, hipHostMallocMapped | hipHostMallocPortable) != hipSuccess) {
       (void)hipGetLastError();
       h->fs_pin = nullptr;
       return RANNC_DP_NO_HOST_MEMORY;
     }
     h->fs_pin_bytes = need;
+    // the device's view of the mirror; without one the call copies in both directions
+    if (hipHostGetDevicePointer((void **)&h->fs_pin_dev, h->fs_pin, 0) != hipSuccess) {
+      (void)hipGetLastError();
+      h->fs_pin_dev = nullptr;
+    }
   }
   try {
     if (comm) hbw.assign(Q, in->bandwidth_bytes_per_us);
@@ -766,7 +788,6 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
   const size_t o_se = o_lev + align_up((size_t)Q * 4);
   const size_t o_rp = o_se + align_up((size_t)Q * stride * 4);
   const size_t o_rec = o_rp + align_up((size_t)Q * stride * 4);
-  const size_t rec_bytes = 6 * 8 + (size_t)stride * 8;
   char *dev = (char *)d_scratch, *pin = h->fs_pin;
   int64_t *ht = (int64_t *)(pin + o_t), *hp = (int64_t *)(pin + o_p), *ha = (int64_t *)(pin + o_a);
   int64_t *ho = (int64_t *)(pin + o_o), *hb = (int64_t *)(pin + o_b);
@@ -807,26 +828,34 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
     max_total = std::max(max_total, total);
   }
   hoff[Q] = (int64_t)Q * N;
-  // one copy up: the (n, MB) of every search and the block arrays in use are contiguous
+  // The (n, MB) of every search and the block arrays in use are contiguous: one copy up.  Small
+  // inputs (the paper's 32 blocks: 18 KB) are not copied at all: the mirror is pinned host memory
+  // that the device reads through the same address, every word once, which costs the kernels a
+  // bus round trip and saves the call a copy in front of its first kernel.
   const size_t in_bytes = o_t + (split ? 5 : comm ? 4 : 3) * a_in;
-  if (hipMemcpyAsync(dev, pin, in_bytes, hipMemcpyHostToDevice, st) != hipSuccess) {
+  char *pin_dev = h->fs_pin_dev;
+  const bool in_place = pin_dev && in_bytes <= kFsReadInPlaceMax;
+  if (!in_place && hipMemcpyAsync(dev, pin, in_bytes, hipMemcpyHostToDevice, st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;
   }
+  const char *src = in_place ? pin_dev : dev;
   int64_t *d_opt = (int64_t *)(dev + o_opt);
   int32_t *d_ns = (int32_t *)(dev + o_ns), *d_st = d_ns + Q;
   int32_t *d_lev = (int32_t *)(dev + o_lev), *d_se = (int32_t *)(dev + o_se), *d_rp = (int32_t *)(dev + o_rp);
-  const int32_t *d_pn = (const int32_t *)(dev + o_pair), *d_pm = d_pn + Q;
-  int64_t *d_rec = (int64_t *)(dev + o_rec);
+  const int32_t *d_pn = (const int32_t *)(src + o_pair), *d_pm = d_pn + Q;
+  // the result record and the chosen plan behind it are written by the kernels straight into the
+  // mirror (they only write it): no copy down, the wait for the stream is all that is left
+  int64_t *d_rec = (int64_t *)((pin_dev ? pin_dev : dev) + o_rec);
   rannc_dp_batch_t b;
   b.n_problems = Q;
   b.n_blocks = hN.data(); b.n_devices = hD.data(); b.max_stages = hS.data();
   b.n_microbatches = hMB.data(); b.mem_capacity = hM.data(); b.block_offset = hoff.data();
-  b.time_ns = (const int64_t *)(dev + o_t); b.param_bytes = (const int64_t *)(dev + o_p);
-  b.act_bytes = (const int64_t *)(dev + o_a);
+  b.time_ns = (const int64_t *)(src + o_t); b.param_bytes = (const int64_t *)(src + o_p);
+  b.act_bytes = (const int64_t *)(src + o_a);
   b.bandwidth_bytes_per_us = comm ? hbw.data() : nullptr;
-  b.cut_bytes = comm ? (const int64_t *)(dev + o_o) : nullptr;
-  b.time_bwd_ns = split ? (const int64_t *)(dev + o_b) : nullptr;
+  b.cut_bytes = comm ? (const int64_t *)(src + o_o) : nullptr;
+  b.time_bwd_ns = split ? (const int64_t *)(src + o_b) : nullptr;
   // Everything on the device, in stream order: the batched search, Algorithm 2's loops over the
   // values V[S][N][D] of every search and S (first n, then first S with a feasible MB; among those
   // the smallest (MB + S - 1) * V, the first found among equals), and the plan of the chosen
@@ -846,7 +875,8 @@ int rannc_dp_form_stage(rannc_dp_t *h, const rannc_dp_form_stage_in_t *in, void 
     (void)hipStreamSynchronize(st);  // the mirror may be refilled by the next call
     return rc;
   }
-  if (hipMemcpyAsync(pin + o_rec, dev + o_rec, rec_bytes, hipMemcpyDeviceToHost, st) != hipSuccess ||
+  if ((!pin_dev && hipMemcpyAsync(pin + o_rec, dev + o_rec, 6 * 8 + (size_t)stride * 8, hipMemcpyDeviceToHost, st) !=
+                       hipSuccess) ||
       hipStreamSynchronize(st) != hipSuccess) {
     (void)hipGetLastError();
     return RANNC_DP_HIP_ERROR;

@@ -1486,12 +1486,11 @@ __device__ void traceback_body(const ProblemDev &pr, int plan_stride, int32_t *s
 
 constexpr int kTracebackThreads = 1024;
 
-// The plan of the search that a record names in its first word, copied behind the record (the outer
-// driver's result: record and plan then reach the host in one copy).
-__device__ __forceinline__ void plan_to_record(const ProblemDev &pr, int plan_stride, const int32_t *se,
-                                               const int32_t *rp, int64_t *rec) {
+// The plan of the one search the outer driver chose (the only one whose entry of the level array is
+// not negative), copied behind its result record.  The record may live in host memory: it is only
+// written here.
+__device__ __forceinline__ void plan_to_record(int plan_stride, const int32_t *se, const int32_t *rp, int64_t *rec) {
   __syncthreads();  // the walk's stores, by this workgroup's first thread, are visible to all of it
-  if ((int)rec[0] != pr.q) return;
   int32_t *plan = (int32_t *)(rec + 6);
   for (int u = threadIdx.x; u < plan_stride; u += blockDim.x) {
     plan[u] = se[u];
@@ -1519,7 +1518,7 @@ __global__ __launch_bounds__(kTracebackThreads) void traceback_kernel(
     else traceback_split_body<uint64_t>(pr, plan_stride, se, rp, &best_key, forced);
   } else if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
-  if (rec) plan_to_record(pr, plan_stride, se, rp, rec);
+  if (rec && d_levels && forced >= 0) plan_to_record(plan_stride, se, rp, rec);
 }
 
 // Plan recovery out of LDS, for launches of few, small min-max searches (the host checks that every
@@ -1542,7 +1541,7 @@ __global__ __launch_bounds__(kTracebackThreads) void traceback_lds_kernel(
   }
   if (pr.bits == 32) { GO(uint32_t) } else { GO(uint64_t) }
 #undef GO
-  if (rec) plan_to_record(pr, plan_stride, se, rp, rec);
+  if (rec && d_levels && forced >= 0) plan_to_record(plan_stride, se, rp, rec);
 }
 
 // ---------------------------------------------------------------------------------------
