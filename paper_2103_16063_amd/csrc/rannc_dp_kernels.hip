@@ -946,7 +946,10 @@ void solve_small_kernel(
   __shared__ int64_t sT[kSmallMaxN + 1], sP[kSmallMaxN + 1], sA[kSmallMaxN + 1], sC[kSmallMaxN + 1];
   __shared__ unsigned long long s_max_cut;
   __shared__ uint64_t scan[3][kSmallMaxN];
-  __shared__ VT lv[2][(kSmallMaxN + 1) * LS];
+  // levels of V in LDS: the one being read and the one being folded into; the recomputing form keeps
+  // a third, cleared while a level runs, so that a level costs one workgroup barrier instead of two
+  constexpr int kLevelBufs = DIRECT ? 3 : 2;
+  __shared__ VT lv[kLevelBufs][(kSmallMaxN + 1) * LS];
   __shared__ VT s_top[64];
   __shared__ int s_flags, s_wlo[2];
   // DIRECT: the stage times are recomputed from the prefix sums in LDS (as the recomputing level
@@ -1003,6 +1006,8 @@ void solve_small_kernel(
   if (myflags) atomicOr(&s_flags, myflags);
   // level 1 buffer: "no plan" everywhere, padding columns 0
   for (int e = tid; e < (N + 1) * LS; e += NT) lv[0][e] = ((e % LS) < D) ? INF : (VT)0;
+  if constexpr (DIRECT)  // level 2's buffer as well
+    for (int e = tid; e < (N + 1) * LS; e += NT) lv[1][e] = ((e % LS) < D) ? INF : (VT)0;
   __syncthreads();
   int st = RANNC_DP_PROBLEM_OK;
   if (s_flags & 1) st = RANNC_DP_PROBLEM_NEGATIVE_INPUT;
@@ -1040,11 +1045,14 @@ void solve_small_kernel(
   const int P1 = nch > 1 ? (W1 / 2 + (64 >> lg1)) >> (6 - lg1) : 0;
   [[maybe_unused]] const int RTP = P0 + F1 + P1;
   for (int s = 2; s <= S_eff; ++s) {
-    const VT *prev = lv[s & 1];        // level s-1
-    VT *cur = lv[(s - 1) & 1];         // level s
+    // level s lives in buffer (s-1) mod kLevelBufs
+    const VT *prev = lv[(s - 2) % kLevelBufs];  // level s-1
+    VT *cur = lv[(s - 1) % kLevelBufs];         // level s
     const int rl = D - s + 1;
-    for (int e = tid; e < (N + 1) * LS; e += NT) cur[e] = ((e % LS) < D) ? INF : (VT)0;
-    lds_barrier();  // LDS only: the copy of the previous level to memory stays in flight
+    if constexpr (!DIRECT) {
+      for (int e = tid; e < (N + 1) * LS; e += NT) cur[e] = ((e % LS) < D) ? INF : (VT)0;
+      lds_barrier();  // LDS only: the copy of the previous level to memory stays in flight
+    }
     if constexpr (DIRECT) {
       // One pass of a wave = 64 (row, column) pairs, one per lane, so that no lane idles on the
       // triangular blocks.  A diagonal block of W columns (rows base..base+W-1) is cut into groups of
@@ -1133,6 +1141,15 @@ void solve_small_kernel(
           for (int t = 0; t < DP - 1; ++t)
             if (t + 1 <= D - 1) atomicMin(&cur[(jj + 1) * LS + t + 1], x[t]);
         }
+      }
+    }
+    if constexpr (DIRECT) {
+      // The next level's buffer held level s-2: its last readers were the passes of level s-1, which
+      // the barrier before this level's passes closed, and its copy to memory was issued by these
+      // same threads before their passes of level s-1.
+      if (s < S_eff) {
+        VT *next = lv[s % kLevelBufs];
+        for (int e = tid; e < (N + 1) * LS; e += NT) next[e] = ((e % LS) < D) ? INF : (VT)0;
       }
     }
     lds_barrier();
