@@ -428,6 +428,9 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
                                                       : h->lim.max_total_time_ns;
   bool fused[4] = {false, false, false, false};
   bool fused_direct[4] = {false, false, false, false};  // one-launch kernel that recomputes the stage times
+  // estimated time of a class of few small searches (us): as one launch with recomputed stage times
+  // (< 0: that kernel does not apply) and as launches per level
+  double est_one[4] = {-1.0, -1.0, -1.0, -1.0}, est_levels[4] = {0.0, 0.0, 0.0, 0.0};
   for (int k = 0; k < 4; ++k) {
     const LaunchShape &sh = shape[k];
     if (!sh.nprob) continue;
@@ -470,6 +473,7 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
           if (w64) us += rl <= 8 ? 0.33 + 0.63 * work : rl <= 16 ? 1.1 + 0.9 * work : 1.45 + 1.62 * work;
           else us += rl <= 8 ? 0.43 + 0.45 * work : rl <= 16 ? 0.68 + 0.61 * work : 1.5 + 0.91 * work;
         }
+        est_one[k] = us;
         tiny = us <= (w64 ? 22.0 + 5.5 * levels + 0.06 * sh.max_N : 21.0 + 4.4 * levels + 0.05 * sh.max_N);
       } else if (heavy) {
         // 64 devices, or 64-bit values from 32 devices on, stage times from the table: a level costs
@@ -485,20 +489,46 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
       fused[k] = !scan && !split && sh.max_N <= rannc::small_max_blocks() &&
                  (h->fused_small == 1 ? (batch || tiny) : h->fused_small == 2);
       fused_direct[k] = fused[k] && direct_ok;
+      est_levels[k] = h->bits == 64 ? 22.0 + 5.5 * levels + 0.06 * sh.max_N : 21.0 + 4.4 * levels + 0.05 * sh.max_N;
     }
+  }
+  // Classes in the shadow of the longest one.  The classes of a batch run side by side on streams
+  // of their own, so the call takes as long as its longest class -- or as long as the host needs to
+  // enqueue everything: a class of launches per level costs the host some 3 us per launch (outer
+  // driver at 128 blocks: 118 launches, 0.385 ms per call for 0.27 ms of device time).  A class of
+  // few searches that is not the longest and would finish as ONE launch within the longest class's
+  // time takes the one-launch kernel even where its own launches per level would be faster.
+  bool share_stream = true;  // the one-launch classes besides the first share one stream
+  if (h->fused_small == 1 && h->multi_stream && !timing) {
+    double longest = 0.0;
+    int crit = -1;
+    for (int k = 0; k < 4; ++k) {
+      if (!shape[k].nprob) continue;
+      const double t = fused[k] && est_one[k] >= 0.0 ? est_one[k] : est_levels[k];
+      if (t > longest) { longest = t; crit = k; }
+    }
+    for (int k = 0; k < 4; ++k)
+      if (shape[k].nprob && k != crit && !fused[k] && est_one[k] >= 0.0 && est_one[k] <= longest &&
+          shape[k].nprob <= 64 && shape[k].max_N <= rannc::small_max_blocks())
+        fused[k] = fused_direct[k] = true;
+    double sum = 0.0;
+    for (int k = 0; k < 4; ++k)
+      if (shape[k].nprob && fused[k] && k != crit && est_one[k] >= 0.0) sum += est_one[k];
+    share_stream = sum <= longest;
   }
   // one stream per device-count class: the largest class stays on the caller's stream
   hipStream_t cs[4] = {st, st, st, st};
   int n_aux = 0;
   if (h->multi_stream && !timing) {
-    // (the other classes that run as ONE launch each share a stream: they are short, and every
-    // stream costs a wait on the fork event and one on its join event, 10 us of host time each)
+    // (the other classes that run as ONE launch each share a stream where together they stay within
+    // the longest class's time: every stream costs a wait on the fork event and one on its join
+    // event, 10 us of host time each)
     bool first = true;
     int shared = -1;
     for (int k = 3; k >= 0; --k) {
       if (!shape[k].nprob) continue;
       if (first) { first = false; continue; }
-      if (fused[k]) {
+      if (fused[k] && share_stream) {
         if (shared < 0) shared = n_aux++;
         cs[k] = h->aux[shared];
       } else {
