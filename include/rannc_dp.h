@@ -114,8 +114,10 @@ typedef struct {
                                 other before the workgroup folds (1, 2, 4, 8, 12 or 16; values between
                                 round up); 0 = by the size of the launch.  Environment override: RANNC_DP_ROWS_PER_WAVE */
   int32_t one_launch_small;  /* searches of at most 128 blocks can run as ONE launch with one workgroup
-                                per search: 0 = where it measured faster (few rows x levels, or
-                                classes of >= 256 searches with D <= 16 or N <= 64), 1 = never,
+                                per search: 0 = where it measured faster (few rows x levels,
+                                classes of >= 256 searches with D <= 16 or N <= 64, or a class of
+                                few searches that finishes within the time of the batch's longest
+                                class anyway), 1 = never,
                                 2 = whenever N <= 128.  Environment override: RANNC_DP_FUSED_SMALL
                                 (0 = never, 1 = where faster, 2 = always) */
   int32_t single_stream;     /* 0 = the device-count classes of a batch run on streams of the handle,
