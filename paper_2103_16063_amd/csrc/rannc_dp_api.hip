@@ -416,7 +416,9 @@ int rannc_dp_solve(rannc_dp_t *h, const rannc_dp_batch_t *b, void *hip_stream, i
   for (int k = 0; k < 4; ++k)
     recompute_cls[k] = can_recompute && (h->lim.algo == RANNC_DP_ALGO_RECOMPUTE ||
                                          (h->lim.algo == RANNC_DP_ALGO_AUTO &&
-                                          rannc::merge_launch_rows(shape[k]) >= rannc::kRecomputeRowsFrom));
+                                          rannc::merge_launch_rows(shape[k]) >=
+                                              (shape[k].nprob > 1 ? rannc::kRecomputeRowsFromMany
+                                                                  : rannc::kRecomputeRowsFrom)));
   bool ok = true;
   const bool timing = h->timing;
   h->ev_valid = false;

@@ -60,6 +60,11 @@ constexpr int kMergeRows16From = 16384;
 // workgroups and is bound by throughput, where recomputing beats reading the table; below, the
 // level is a single round bound by latency, where the shorter table kernel wins.
 constexpr int kRecomputeRowsFrom = 32768;
+// A launch over SEVERAL searches recomputes from far fewer rows on: it needs no stage-time table
+// built in front, and measured ahead of the table form from 2 700 rows (outer driver at 192 blocks)
+// upwards at every memory tightness, by 1 to 14 %; below (two or three small searches) the table form
+// keeps its edge.
+constexpr int kRecomputeRowsFromMany = 2048;
 
 __host__ __device__ inline int dp_class(int D) { return D <= 8 ? 8 : D <= 16 ? 16 : D <= 32 ? 32 : 64; }
 
